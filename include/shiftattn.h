@@ -1,0 +1,187 @@
+/*
+ * shiftattn.h - C ABI of one GPU's share of an attention layer under Shift Parallelism
+ * (arXiv 2509.16495), for AMD MI355X (gfx950).
+ *
+ * The library covers what a rank does between the QKV projection and the O projection
+ * (Algorithm 1, the two SP all-to-all lines and the boxed attention line):
+ *
+ *   shiftattn_pack_seq2head     send side of the sequence->head all-to-all (SP mode only)
+ *   shiftattn_kv_write          append new K/V rows to the paged KV cache
+ *   shiftattn_prefill           causal attention of new-token chunks over the cache (fused KV append)
+ *   shiftattn_decode            one-token-per-sequence attention, split over the context (fused KV append)
+ *   shiftattn_unpack_head2seq   receive side of the head->sequence all-to-all (SP mode only)
+ *
+ * In TP mode (the shift configuration, SP=1) a rank calls only kv_write/prefill/decode on the
+ * fused rows its own QKV projection produced; in SP mode it packs, exchanges, attends,
+ * exchanges, unpacks.  Both modes drive the same attention kernels over the same cache: that
+ * is the KV-cache invariance of Sec. 3.1 / 3.3.1.  The exchange itself (the wire transfer) is
+ * not part of this library.
+ *
+ * Conventions for every entry point
+ *   - Pointers named in "device" positions are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or synchronises: each call validates its arguments on the host,
+ *     then only enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream).  No host-side read of device memory, so calls can be captured into a HIP graph.
+ *   - Return value: SHIFTATTN_OK or a negative error code.  Arguments are validated before any
+ *     launch; on error nothing has been enqueued.  shiftattn_last_error() returns a
+ *     thread-local description of the last failure.  No C++ exception crosses this boundary.
+ *   - Element types: SHIFTATTN_BF16 (bfloat16, 2 bytes) or SHIFTATTN_F32 (4 bytes); all
+ *     tensors of one call share the type.  head_dim * element size must be a multiple of 16 and
+ *     all tensor base pointers and row strides must be 16-byte aligned.
+ *   - Contents of device-side index arrays (slots, block ids, lengths) are trusted: an
+ *     out-of-range block id or slot is undefined behaviour.
+ *
+ * Paged KV cache (layout is a convention of this library; the paper only requires that it is
+ * the same in SP and TP mode):
+ *     kv_cache[num_blocks][num_kv_heads][2][block_size * head_dim]
+ *   part 0 holds K token-major,      K[offset][d]
+ *   part 1 holds V dimension-major,  V[d][offset]
+ *   with offset = token position % block_size.  Slot id = block * block_size + offset.
+ *   block_size is 16.  block_table[s][i] is the cache block of tokens [16 i, 16 i + 16) of
+ *   sequence s; entries past the sequence's last block are never read.
+ */
+#ifndef SHIFTATTN_H
+#define SHIFTATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SHIFTATTN_OK = 0,
+    SHIFTATTN_EINVAL = -1,       /* null pointer, negative size, inconsistent arguments          */
+    SHIFTATTN_EUNSUPPORTED = -2, /* well-formed but not built (head_dim, block_size, head ratio)  */
+    SHIFTATTN_EWORKSPACE = -3,   /* workspace missing or smaller than *_workspace_bytes() says    */
+    SHIFTATTN_EHIP = -4          /* the HIP runtime refused a launch                               */
+};
+
+enum { SHIFTATTN_BF16 = 0, SHIFTATTN_F32 = 1 };
+
+/* One sequence<->head exchange among P ranks (Algorithm 1: P is the SP degree of the base
+ * configuration; h and h_kv are the heads a source rank holds, i.e. model heads / TP). */
+typedef struct shiftattn_xchg {
+    int32_t P;            /* members of the exchange group, >= 1                                  */
+    int32_t num_q_heads;  /* h: query heads per source row; must be a multiple of P                */
+    int32_t num_kv_heads; /* h_kv: K (and V) heads per source row; 0 = query-only rows.  Either a
+                             multiple of P (each destination gets h_kv/P heads) or a divisor of P
+                             (each head is replicated to P/h_kv consecutive destinations,
+                             Sec. 3.2.1 "KV Cache Replication")                                    */
+    int32_t head_dim;     /* D                                                                     */
+    int32_t dtype;        /* SHIFTATTN_BF16 | SHIFTATTN_F32                                        */
+} shiftattn_xchg;
+
+/* The local head shard and its cache (Algorithm 1, boxed line: h/(SP*TP) heads over all n tokens). */
+typedef struct shiftattn_attn {
+    int32_t num_q_heads;        /* hq_l: local query heads                                         */
+    int32_t num_kv_heads;       /* hkv_l: local KV heads; hq_l must be a multiple of it (GQA)      */
+    int32_t head_dim;           /* D: 64 or 128 are tuned; any multiple of 8 up to 256 is accepted */
+    int32_t dtype;              /* SHIFTATTN_BF16 | SHIFTATTN_F32                                  */
+    int32_t block_size;         /* tokens per cache block; must be 16                              */
+    int32_t num_blocks;         /* blocks in kv_cache                                              */
+    int32_t max_blocks_per_seq; /* row length of block_table                                       */
+    float softmax_scale;        /* multiplies q.k before the softmax (the paper leaves it implicit;
+                                   1/sqrt(D) is customary)                                         */
+    int64_t q_stride;           /* elements between consecutive tokens of q;   0 = hq_l*D (dense)  */
+    int64_t kv_stride;          /* same for k_new and v_new;                   0 = hkv_l*D         */
+    int64_t out_stride;         /* same for out;                               0 = hq_l*D          */
+} shiftattn_attn;
+/* Strides let q, k_new and v_new be views into one fused receive buffer
+ * [n_pad][hq_l + 2*hkv_l][D]: q = buf, k_new = buf + hq_l*D, v_new = buf + (hq_l+hkv_l)*D,
+ * q_stride = kv_stride = (hq_l + 2*hkv_l)*D. */
+
+/* ---- Algorithm 1, first SP all-to-all, send side ("fused" q|k|v exchange, Sec. 3.2.1) ----------
+ * qkv  (device, in) : [T][h + 2*h_kv][D]   this rank's rows; per row: q heads, then k heads, then
+ *                                          v heads, each D contiguous elements.
+ * send (device, out): [P][T_pad][hq_l + 2*hkv_l][D], hq_l = h/P, hkv_l = max(1, h_kv/P)
+ *                     (hkv_l = 0 when h_kv = 0).  Buffer p holds query heads [p*hq_l, (p+1)*hq_l)
+ *                     followed by the K then V heads that GQA assigns to them, starting at KV head
+ *                     floor(p*h_kv/P).  Rows T..T_pad-1 (padding of the batch to a multiple of the
+ *                     SP degree, Sec. 3.2.1 "Load Imbalance") are written as zeros.
+ * After the exchange, destination p's receive buffer is the concatenation over source ranks of
+ * their send[p] and needs no further transform.
+ * Errors: EINVAL for null pointers (unless the tensor is empty), T<0, T_pad<T, P<1, h%P != 0,
+ * h_kv neither multiple nor divisor of P; EUNSUPPORTED for D*elem_size % 16 != 0 or more than
+ * 2^31-1 16-byte vectors per tensor. */
+int shiftattn_pack_seq2head(const void *qkv, void *send, int32_t T, int32_t T_pad, const shiftattn_xchg *x,
+                            void *stream);
+
+/* ---- Algorithm 1, second SP all-to-all, receive side -------------------------------------------
+ * recv (device, in) : [P][T_pad][hq_l][D]  buffer p = the attention output rows this rank owns,
+ *                                          computed by the rank holding head block p.
+ * out  (device, out): [T][h][D] with out[t][p*hq_l + j] = recv[p][t][j]; padding rows dropped.
+ * x->num_kv_heads is ignored.  Errors as for pack. */
+int shiftattn_unpack_head2seq(const void *recv, void *out, int32_t T, int32_t T_pad, const shiftattn_xchg *x,
+                              void *stream);
+
+/* ---- KV-cache append (Sec. 2.2: prefill initialises the cache, decoding appends to it) --------
+ * k_new, v_new (device, in): [n_tokens][hkv_l][D] with row stride a->kv_stride.
+ * slot_mapping (device, in): int64 [n_tokens]; token i goes to slot slot_mapping[i];
+ *                            a negative slot (padding row) writes nothing.
+ * kv_cache (device, in/out): see the layout above.  Untouched slots keep their bytes. */
+int shiftattn_kv_write(const void *k_new, const void *v_new, const int64_t *slot_mapping, int32_t n_tokens,
+                       void *kv_cache, const shiftattn_attn *a, void *stream);
+
+/* ---- Algorithm 1, boxed line: attention of prefill chunks ---------------------------------------
+ * Sequence s has q_len_s = cu_seqlens_q[s+1]-cu_seqlens_q[s] new tokens and seq_lens[s] tokens in
+ * total (cached + new).  New token i sits at position pos = seq_lens[s] - q_len_s + i and attends
+ * to positions 0..pos of its own sequence (causal, aligned to the end of the context, which is
+ * what chunked prefill needs).  Query head j uses KV head j / (hq_l/hkv_l).
+ *
+ * q (device, in)            : [total_q][hq_l][D], row stride a->q_stride
+ * k_new, v_new, slot_mapping: as in shiftattn_kv_write with n_tokens = total_q.  All three NULL =
+ *                             the cache already holds the new tokens.  Otherwise they are written
+ *                             first and the result equals "write, then attend".
+ * block_table (device, in)  : int32 [num_seqs][max_blocks_per_seq]
+ * cu_seqlens_q (device, in) : int32 [num_seqs + 1], cu_seqlens_q[0] = 0, non-decreasing
+ * seq_lens (device, in)     : int32 [num_seqs], seq_lens[s] >= q_len_s
+ * total_q, max_q_len, max_seq_len (host): total_q = cu_seqlens_q[num_seqs]; upper bounds on
+ *                             q_len_s and seq_lens[s] (they size the launch; exceeding them
+ *                             silently drops work)
+ * out (device, out)         : [total_q][hq_l][D], row stride a->out_stride
+ * workspace (device)        : at least shiftattn_prefill_workspace_bytes(...) bytes, 16-byte
+ *                             aligned; may be NULL when that is 0.  Contents are scratch.
+ * num_seqs == 0 or total_q == 0 is a valid no-op. */
+int shiftattn_prefill(const void *q, const void *k_new, const void *v_new, const int64_t *slot_mapping,
+                      void *kv_cache, const int32_t *block_table, const int32_t *cu_seqlens_q,
+                      const int32_t *seq_lens, int32_t num_seqs, int32_t total_q, int32_t max_q_len,
+                      int32_t max_seq_len, void *out, void *workspace, size_t workspace_bytes,
+                      const shiftattn_attn *a, void *stream);
+
+/* ---- Algorithm 1, boxed line: attention of decode rows (one new token per sequence) -------------
+ * Same definition with q_len_s = 1, pos = seq_lens[s] - 1.  The context of every sequence is cut
+ * into fixed-size chunks processed in parallel; partial results are merged in a fixed order, so
+ * results are bitwise reproducible from run to run.
+ * q, out: [num_seqs][hq_l][D]; k_new/v_new/slot_mapping: n_tokens = num_seqs (or all NULL). */
+int shiftattn_decode(const void *q, const void *k_new, const void *v_new, const int64_t *slot_mapping,
+                     void *kv_cache, const int32_t *block_table, const int32_t *seq_lens, int32_t num_seqs,
+                     int32_t max_seq_len, void *out, void *workspace, size_t workspace_bytes,
+                     const shiftattn_attn *a, void *stream);
+
+/* Workspace sizes (host only, no GPU work).  Return 0 when no workspace is needed; SIZE_MAX on
+ * invalid arguments. */
+size_t shiftattn_prefill_workspace_bytes(int32_t num_seqs, int32_t total_q, int32_t max_q_len,
+                                         int32_t max_seq_len, const shiftattn_attn *a);
+size_t shiftattn_decode_workspace_bytes(int32_t num_seqs, int32_t max_seq_len, const shiftattn_attn *a);
+
+/* ---- Host-side index helpers (no GPU work) -------------------------------------------------------
+ * Head block held by global rank `rank` in base configuration (SP=sp, TP=tp): TP groups are runs
+ * of consecutive ranks, SP groups take every tp-th rank, so the block is (rank % tp)*sp + rank/tp.
+ * The shift configuration (1, sp*tp) must shard its weights in this order to keep the cache valid
+ * (Sec. 3.3.1; for (3,2) the ranks in block order are 0,2,4,1,3,5).  Returns -1 on bad arguments. */
+int32_t shiftattn_head_block(int32_t sp, int32_t tp, int32_t rank);
+/* First KV head that head block `block` of `P` uses when the source holds h_kv KV heads:
+ * floor(block*h_kv/P).  Returns -1 on bad arguments. */
+int32_t shiftattn_kv_head_of_block(int32_t block, int32_t P, int32_t h_kv);
+/* Batch size padded up to a multiple of the SP degree (Sec. 3.2.1).  Returns -1 on bad arguments. */
+int32_t shiftattn_padded_tokens(int32_t n, int32_t sp);
+
+/* Thread-local text of the last error returned on this thread ("" if none). */
+const char *shiftattn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHIFTATTN_H */

@@ -1,0 +1,232 @@
+"""Thin Python binding of the C ABI in include/shiftattn.h.
+
+Argument marshalling only: every function takes torch tensors that already live on the GPU,
+checks shapes, and passes raw device pointers plus the current HIP stream to libshiftattn.so.
+All of the path's work happens in the library's kernels; there is no Python or CPU fallback.
+If the library has not been built (python -m paper_2509_16495_amd.build, or
+__graft_entry__.build()), loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libshiftattn.so")
+
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+BF16, F32 = 0, 1
+BLOCK_SIZE = 16
+
+
+class ShiftAttnError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"shiftattn error {code}: {msg}")
+        self.code = code
+
+
+class Xchg(ctypes.Structure):
+    _fields_ = [("P", ctypes.c_int32), ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class Attn(ctypes.Structure):
+    _fields_ = [("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("block_size", ctypes.c_int32), ("num_blocks", ctypes.c_int32),
+                ("max_blocks_per_seq", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("q_stride", ctypes.c_int64), ("kv_stride", ctypes.c_int64), ("out_stride", ctypes.c_int64)]
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C library.  Raises if it was never built: there is no other implementation."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_16495_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64p, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
+        xp, ap = ctypes.POINTER(Xchg), ctypes.POINTER(Attn)
+        L.shiftattn_pack_seq2head.argtypes = [vp, vp, i32, i32, xp, vp]
+        L.shiftattn_unpack_head2seq.argtypes = [vp, vp, i32, i32, xp, vp]
+        L.shiftattn_kv_write.argtypes = [vp, vp, i64p, i32, vp, ap, vp]
+        L.shiftattn_prefill.argtypes = [vp, vp, vp, i64p, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, ap, vp]
+        L.shiftattn_decode.argtypes = [vp, vp, vp, i64p, vp, vp, vp, i32, i32, vp, vp, sz, ap, vp]
+        L.shiftattn_prefill_workspace_bytes.argtypes = [i32, i32, i32, i32, ap]
+        L.shiftattn_prefill_workspace_bytes.restype = sz
+        L.shiftattn_decode_workspace_bytes.argtypes = [i32, i32, ap]
+        L.shiftattn_decode_workspace_bytes.restype = sz
+        L.shiftattn_head_block.argtypes = [i32, i32, i32]
+        L.shiftattn_head_block.restype = i32
+        L.shiftattn_kv_head_of_block.argtypes = [i32, i32, i32]
+        L.shiftattn_kv_head_of_block.restype = i32
+        L.shiftattn_padded_tokens.argtypes = [i32, i32]
+        L.shiftattn_padded_tokens.restype = i32
+        L.shiftattn_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().shiftattn_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != OK:
+        raise ShiftAttnError(rc, last_error())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _row_stride(t: torch.Tensor) -> int:
+    """Elements between consecutive tokens of a [tokens, heads, D] view whose inner two dims are dense."""
+    assert t.dim() == 3 and t.stride(2) == 1 and (t.shape[1] == 1 or t.stride(1) == t.shape[2]), "inner dims must be dense"
+    return int(t.stride(0)) if t.shape[0] > 1 else int(t.shape[1] * t.shape[2])
+
+
+# ---- host-only helpers --------------------------------------------------------------------------
+def head_block(sp: int, tp: int, rank: int) -> int:
+    return int(lib().shiftattn_head_block(sp, tp, rank))
+
+
+def kv_head_of_block(block: int, P: int, h_kv: int) -> int:
+    return int(lib().shiftattn_kv_head_of_block(block, P, h_kv))
+
+
+def padded_tokens(n: int, sp: int) -> int:
+    return int(lib().shiftattn_padded_tokens(n, sp))
+
+
+def local_kv_heads(P: int, h_kv: int) -> int:
+    return 0 if h_kv == 0 else (h_kv // P if h_kv >= P else 1)
+
+
+# ---- exchange pack / unpack -----------------------------------------------------------------------
+def pack_seq2head(qkv: torch.Tensor, send: torch.Tensor, P: int, h: int, h_kv: int) -> None:
+    """qkv [T, h+2*h_kv, D] -> send [P, T_pad, h/P + 2*hkv_l, D] (pad rows zeroed)."""
+    T, w, D = qkv.shape
+    assert w == h + 2 * h_kv and qkv.is_contiguous() and send.is_contiguous() and send.dtype == qkv.dtype
+    T_pad = send.shape[1]
+    assert send.shape[0] == P and send.shape[3] == D
+    x = Xchg(P, h, h_kv, D, _dtype_code(qkv))
+    _check(lib().shiftattn_pack_seq2head(_ptr(qkv), _ptr(send), T, T_pad, ctypes.byref(x), _stream()))
+
+
+def unpack_head2seq(recv: torch.Tensor, out: torch.Tensor) -> None:
+    """recv [P, T_pad, h/P, D] -> out [T, h, D]."""
+    P, T_pad, hq_l, D = recv.shape
+    T, h, D2 = out.shape
+    assert D2 == D and h == P * hq_l and recv.is_contiguous() and out.is_contiguous() and out.dtype == recv.dtype
+    x = Xchg(P, h, 0, D, _dtype_code(recv))
+    _check(lib().shiftattn_unpack_head2seq(_ptr(recv), _ptr(out), T, T_pad, ctypes.byref(x), _stream()))
+
+
+# ---- KV cache and attention -------------------------------------------------------------------------
+def attn_desc(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, softmax_scale: float,
+              k_new: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> Attn:
+    """Descriptor from tensor shapes.  kv_cache is [num_blocks, hkv_l, 2, 16*D]."""
+    hq_l, D = q.shape[1], q.shape[2]
+    num_blocks, hkv_l, two, bd = kv_cache.shape
+    assert two == 2 and bd == BLOCK_SIZE * D and kv_cache.is_contiguous() and kv_cache.dtype == q.dtype
+    assert block_table.dtype == torch.int32 and block_table.dim() == 2 and block_table.is_contiguous()
+    a = Attn(hq_l, hkv_l, D, _dtype_code(q), BLOCK_SIZE, num_blocks, block_table.shape[1], float(softmax_scale),
+             _row_stride(q), 0, 0)
+    if k_new is not None:
+        a.kv_stride = _row_stride(k_new)
+    if out is not None:
+        a.out_stride = _row_stride(out)
+    return a
+
+
+def kv_write(k_new: torch.Tensor, v_new: torch.Tensor, slot_mapping: torch.Tensor, kv_cache: torch.Tensor) -> None:
+    n, hkv_l, D = k_new.shape
+    assert v_new.shape == k_new.shape and slot_mapping.dtype == torch.int64 and slot_mapping.shape[0] == n
+    assert _row_stride(v_new) == _row_stride(k_new)
+    num_blocks = kv_cache.shape[0]
+    assert kv_cache.shape[1:] == (hkv_l, 2, BLOCK_SIZE * D) and kv_cache.is_contiguous()
+    a = Attn(hkv_l, hkv_l, D, _dtype_code(k_new), BLOCK_SIZE, num_blocks, 0, 1.0, 0, _row_stride(k_new), 0)
+    _check(lib().shiftattn_kv_write(_ptr(k_new), _ptr(v_new), _ptr(slot_mapping), n, _ptr(kv_cache), ctypes.byref(a),
+                                    _stream()))
+
+
+def prefill_workspace_bytes(num_seqs: int, total_q: int, max_q_len: int, max_seq_len: int, a: Attn) -> int:
+    return int(lib().shiftattn_prefill_workspace_bytes(num_seqs, total_q, max_q_len, max_seq_len, ctypes.byref(a)))
+
+
+def decode_workspace_bytes(num_seqs: int, max_seq_len: int, a: Attn) -> int:
+    return int(lib().shiftattn_decode_workspace_bytes(num_seqs, max_seq_len, ctypes.byref(a)))
+
+
+def prefill(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, cu_seqlens_q: torch.Tensor,
+            seq_lens: torch.Tensor, max_q_len: int, max_seq_len: int, out: torch.Tensor, softmax_scale: float,
+            k_new: Optional[torch.Tensor] = None, v_new: Optional[torch.Tensor] = None,
+            slot_mapping: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> None:
+    """Causal attention of prefill chunks; q/out [total_q, hq_l, D] (row-strided views allowed)."""
+    total_q = q.shape[0]
+    num_seqs = seq_lens.shape[0]
+    assert cu_seqlens_q.dtype == torch.int32 and seq_lens.dtype == torch.int32 and cu_seqlens_q.shape[0] == num_seqs + 1
+    assert out.shape == q.shape and out.dtype == q.dtype
+    a = attn_desc(q, kv_cache, block_table, softmax_scale, k_new, out)
+    need = prefill_workspace_bytes(num_seqs, total_q, max_q_len, max_seq_len, a)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().shiftattn_prefill(_ptr(q), _ptr(k_new), _ptr(v_new), _ptr(slot_mapping), _ptr(kv_cache),
+                                   _ptr(block_table), _ptr(cu_seqlens_q), _ptr(seq_lens), num_seqs, total_q,
+                                   max_q_len, max_seq_len, _ptr(out), _ptr(workspace), ws_bytes, ctypes.byref(a),
+                                   _stream()))
+
+
+def decode(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, seq_lens: torch.Tensor,
+           max_seq_len: int, out: torch.Tensor, softmax_scale: float, k_new: Optional[torch.Tensor] = None,
+           v_new: Optional[torch.Tensor] = None, slot_mapping: Optional[torch.Tensor] = None,
+           workspace: Optional[torch.Tensor] = None) -> None:
+    """One new token per sequence; q/out [num_seqs, hq_l, D]."""
+    num_seqs = q.shape[0]
+    assert seq_lens.dtype == torch.int32 and seq_lens.shape[0] == num_seqs
+    assert out.shape == q.shape and out.dtype == q.dtype
+    a = attn_desc(q, kv_cache, block_table, softmax_scale, k_new, out)
+    need = decode_workspace_bytes(num_seqs, max_seq_len, a)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().shiftattn_decode(_ptr(q), _ptr(k_new), _ptr(v_new), _ptr(slot_mapping), _ptr(kv_cache),
+                                  _ptr(block_table), _ptr(seq_lens), num_seqs, max_seq_len, _ptr(out),
+                                  _ptr(workspace), ws_bytes, ctypes.byref(a), _stream()))
+
+
+# ---- numpy <-> device helpers for tests and benchmarks (storage only) ------------------------------------
+def to_device(a, dtype: str, device: str = "cuda:0") -> torch.Tensor:
+    """numpy array in the workloads storage convention (uint16 bit patterns for bf16) -> GPU tensor."""
+    import numpy as np
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(device)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+def to_host(t: torch.Tensor):
+    """GPU tensor -> numpy array in the workloads storage convention."""
+    import numpy as np
+    t = t.detach().contiguous().cpu()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()

@@ -1,0 +1,271 @@
+// C-ABI front end: argument validation on the host, then kernel launches on the caller's stream.
+// Nothing here allocates, frees, synchronises or reads device memory.
+#include "../../include/shiftattn.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+
+#include "internal.h"
+
+using namespace shiftattn;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+    return fail(SHIFTATTN_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int elem_size(int dtype) { return dtype == SHIFTATTN_BF16 ? 2 : (dtype == SHIFTATTN_F32 ? 4 : 0); }
+
+bool force_generic() {
+    static const bool v = [] {
+        const char* e = getenv("SHIFTATTN_FORCE_GENERIC");
+        return e && e[0] == '1';
+    }();
+    return v;
+}
+
+// Fills `s` from the public struct; returns 0 or an error code.
+int check_xchg(const shiftattn_xchg* x, int32_t T, int32_t T_pad, bool with_kv, XchgShape* s) {
+    if (!x) return fail(SHIFTATTN_EINVAL, "exchange descriptor is NULL");
+    const int e = elem_size(x->dtype);
+    if (!e) return fail(SHIFTATTN_EINVAL, "unknown dtype %d", x->dtype);
+    if (x->P < 1) return fail(SHIFTATTN_EINVAL, "P = %d must be >= 1", x->P);
+    if (x->num_q_heads < 1 || x->num_q_heads % x->P)
+        return fail(SHIFTATTN_EINVAL, "num_q_heads = %d must be a positive multiple of P = %d", x->num_q_heads, x->P);
+    const int h_kv = with_kv ? x->num_kv_heads : 0;
+    if (h_kv < 0) return fail(SHIFTATTN_EINVAL, "num_kv_heads = %d is negative", h_kv);
+    if (h_kv > 0 && h_kv % x->P && x->P % h_kv)
+        return fail(SHIFTATTN_EINVAL, "num_kv_heads = %d is neither a multiple nor a divisor of P = %d", h_kv, x->P);
+    if (h_kv > 0 && x->num_q_heads % h_kv)
+        return fail(SHIFTATTN_EINVAL, "num_q_heads = %d is not a multiple of num_kv_heads = %d", x->num_q_heads, h_kv);
+    if (T < 0 || T_pad < T) return fail(SHIFTATTN_EINVAL, "need 0 <= T (%d) <= T_pad (%d)", T, T_pad);
+    if (x->head_dim < 1) return fail(SHIFTATTN_EINVAL, "head_dim = %d", x->head_dim);
+    if ((x->head_dim * e) % 16)
+        return fail(SHIFTATTN_EUNSUPPORTED, "head_dim * element size = %d bytes is not a multiple of 16", x->head_dim * e);
+    s->P = x->P;
+    s->h = x->num_q_heads;
+    s->h_kv = h_kv;
+    s->hq_l = x->num_q_heads / x->P;
+    s->hkv_l = h_kv == 0 ? 0 : (h_kv >= x->P ? h_kv / x->P : 1);
+    if (h_kv > 0) {
+        // the q heads of one destination must sit inside the GQA groups of the KV heads it receives
+        const int group = x->num_q_heads / h_kv;
+        if (s->hq_l % group && group % s->hq_l)
+            return fail(SHIFTATTN_EINVAL, "h/P = %d neither divides nor is a multiple of the GQA group h/h_kv = %d",
+                        s->hq_l, group);
+    }
+    s->vec_per_head = x->head_dim * e / 16;
+    s->T = T;
+    s->T_pad = T_pad;
+    const uint64_t in_vecs = static_cast<uint64_t>(T) * (s->h + 2 * s->h_kv) * s->vec_per_head;
+    const uint64_t out_vecs = static_cast<uint64_t>(T_pad) * (s->hq_l + 2 * s->hkv_l) * s->vec_per_head;
+    if (in_vecs > 0x7FFFFFFFull || out_vecs > 0x7FFFFFFFull)
+        return fail(SHIFTATTN_EUNSUPPORTED, "more than 2^31-1 16-byte vectors per buffer");
+    return 0;
+}
+
+int check_attn(const shiftattn_attn* a, AttnShape* s) {
+    if (!a) return fail(SHIFTATTN_EINVAL, "attention descriptor is NULL");
+    const int e = elem_size(a->dtype);
+    if (!e) return fail(SHIFTATTN_EINVAL, "unknown dtype %d", a->dtype);
+    if (a->num_q_heads < 1 || a->num_kv_heads < 1 || a->num_q_heads % a->num_kv_heads)
+        return fail(SHIFTATTN_EINVAL, "num_q_heads = %d must be a positive multiple of num_kv_heads = %d",
+                    a->num_q_heads, a->num_kv_heads);
+    if (a->head_dim < 1) return fail(SHIFTATTN_EINVAL, "head_dim = %d", a->head_dim);
+    if (a->head_dim % 8 || a->head_dim > 256)
+        return fail(SHIFTATTN_EUNSUPPORTED, "head_dim = %d: need a multiple of 8 up to 256", a->head_dim);
+    if (a->block_size != kBlockSize) return fail(SHIFTATTN_EUNSUPPORTED, "block_size = %d: only 16 is built", a->block_size);
+    if (a->num_blocks < 0 || a->max_blocks_per_seq < 0)
+        return fail(SHIFTATTN_EINVAL, "num_blocks = %d, max_blocks_per_seq = %d", a->num_blocks, a->max_blocks_per_seq);
+    if (!(a->softmax_scale > 0.f) || a->softmax_scale > 3.0e38f)
+        return fail(SHIFTATTN_EINVAL, "softmax_scale must be positive and finite");
+    s->hq_l = a->num_q_heads;
+    s->hkv_l = a->num_kv_heads;
+    s->D = a->head_dim;
+    s->elem = e;
+    s->num_blocks = a->num_blocks;
+    s->max_blocks = a->max_blocks_per_seq;
+    s->scale = a->softmax_scale;
+    s->q_stride = a->q_stride ? a->q_stride : static_cast<int64_t>(s->hq_l) * s->D;
+    s->kv_stride = a->kv_stride ? a->kv_stride : static_cast<int64_t>(s->hkv_l) * s->D;
+    s->out_stride = a->out_stride ? a->out_stride : static_cast<int64_t>(s->hq_l) * s->D;
+    if (s->q_stride < static_cast<int64_t>(s->hq_l) * s->D || s->out_stride < static_cast<int64_t>(s->hq_l) * s->D ||
+        s->kv_stride < static_cast<int64_t>(s->hkv_l) * s->D)
+        return fail(SHIFTATTN_EINVAL, "a row stride is smaller than the row it strides over");
+    if ((s->q_stride * e) % 16 || (s->kv_stride * e) % 16 || (s->out_stride * e) % 16)
+        return fail(SHIFTATTN_EINVAL, "row strides must be multiples of 16 bytes");
+    return 0;
+}
+
+int check_new_kv(const void* k_new, const void* v_new, const int64_t* slots, bool* present) {
+    const int n = (k_new != nullptr) + (v_new != nullptr) + (slots != nullptr);
+    if (n != 0 && n != 3) return fail(SHIFTATTN_EINVAL, "k_new, v_new and slot_mapping must be all NULL or all set");
+    if (n == 3 && (!aligned16(k_new) || !aligned16(v_new)))
+        return fail(SHIFTATTN_EINVAL, "k_new / v_new must be 16-byte aligned");
+    *present = n == 3;
+    return 0;
+}
+
+bool use_prefill_mfma(const AttnShape& s) { return !force_generic() && prefill_mfma_supported(s); }
+bool use_decode_mfma(const AttnShape& s, int num_seqs) {
+    return !force_generic() && decode_mfma_supported(s) && num_seqs <= 65535;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* shiftattn_last_error(void) { return g_err; }
+
+int32_t shiftattn_head_block(int32_t sp, int32_t tp, int32_t rank) {
+    if (sp < 1 || tp < 1 || rank < 0 || rank >= sp * tp) return -1;
+    return (rank % tp) * sp + rank / tp;
+}
+
+int32_t shiftattn_kv_head_of_block(int32_t block, int32_t P, int32_t h_kv) {
+    if (P < 1 || h_kv < 1 || block < 0 || block >= P) return -1;
+    return static_cast<int32_t>((static_cast<int64_t>(block) * h_kv) / P);
+}
+
+int32_t shiftattn_padded_tokens(int32_t n, int32_t sp) {
+    if (n < 0 || sp < 1) return -1;
+    const int64_t padded = (static_cast<int64_t>(n) + sp - 1) / sp * sp;
+    return padded > 0x7FFFFFFF ? -1 : static_cast<int32_t>(padded);
+}
+
+int shiftattn_pack_seq2head(const void* qkv, void* send, int32_t T, int32_t T_pad, const shiftattn_xchg* x,
+                            void* stream) {
+    XchgShape s;
+    if (int rc = check_xchg(x, T, T_pad, true, &s)) return rc;
+    if (T_pad == 0) return SHIFTATTN_OK;
+    if (!send || (T > 0 && !qkv)) return fail(SHIFTATTN_EINVAL, "qkv or send is NULL");
+    if (!aligned16(qkv) || !aligned16(send)) return fail(SHIFTATTN_EINVAL, "qkv / send must be 16-byte aligned");
+    hipError_t e = launch_pack(qkv, send, s, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "pack_seq2head launch");
+}
+
+int shiftattn_unpack_head2seq(const void* recv, void* out, int32_t T, int32_t T_pad, const shiftattn_xchg* x,
+                              void* stream) {
+    XchgShape s;
+    if (int rc = check_xchg(x, T, T_pad, false, &s)) return rc;
+    if (T == 0) return SHIFTATTN_OK;
+    if (!recv || !out) return fail(SHIFTATTN_EINVAL, "recv or out is NULL");
+    if (!aligned16(recv) || !aligned16(out)) return fail(SHIFTATTN_EINVAL, "recv / out must be 16-byte aligned");
+    hipError_t e = launch_unpack(recv, out, s, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_head2seq launch");
+}
+
+int shiftattn_kv_write(const void* k_new, const void* v_new, const int64_t* slot_mapping, int32_t n_tokens,
+                       void* kv_cache, const shiftattn_attn* a, void* stream) {
+    AttnShape s;
+    if (int rc = check_attn(a, &s)) return rc;
+    if (n_tokens < 0) return fail(SHIFTATTN_EINVAL, "n_tokens = %d", n_tokens);
+    if (n_tokens == 0) return SHIFTATTN_OK;
+    if (!k_new || !v_new || !slot_mapping || !kv_cache) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(kv_cache))
+        return fail(SHIFTATTN_EINVAL, "k_new / v_new / kv_cache must be 16-byte aligned");
+    hipError_t e = launch_kv_write(k_new, v_new, slot_mapping, n_tokens, kv_cache, s, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "kv_write launch");
+}
+
+size_t shiftattn_prefill_workspace_bytes(int32_t num_seqs, int32_t total_q, int32_t max_q_len, int32_t max_seq_len,
+                                         const shiftattn_attn* a) {
+    AttnShape s;
+    if (check_attn(a, &s) || num_seqs < 0 || total_q < 0 || max_q_len < 0 || max_seq_len < 0) return SIZE_MAX;
+    if (!use_prefill_mfma(s) || num_seqs == 0 || total_q == 0) return 0;
+    return prefill_mfma_workspace(num_seqs, total_q, max_q_len, max_seq_len, s);
+}
+
+size_t shiftattn_decode_workspace_bytes(int32_t num_seqs, int32_t max_seq_len, const shiftattn_attn* a) {
+    AttnShape s;
+    if (check_attn(a, &s) || num_seqs < 0 || max_seq_len < 0) return SIZE_MAX;
+    if (!use_decode_mfma(s, num_seqs) || num_seqs == 0) return 0;
+    return decode_mfma_workspace(num_seqs, max_seq_len, s);
+}
+
+int shiftattn_prefill(const void* q, const void* k_new, const void* v_new, const int64_t* slot_mapping, void* kv_cache,
+                      const int32_t* block_table, const int32_t* cu_seqlens_q, const int32_t* seq_lens,
+                      int32_t num_seqs, int32_t total_q, int32_t max_q_len, int32_t max_seq_len, void* out,
+                      void* workspace, size_t workspace_bytes, const shiftattn_attn* a, void* stream) {
+    AttnShape s;
+    if (int rc = check_attn(a, &s)) return rc;
+    if (num_seqs < 0 || total_q < 0 || max_q_len < 0 || max_seq_len < 0)
+        return fail(SHIFTATTN_EINVAL, "negative size argument");
+    if (max_q_len > total_q || max_q_len > max_seq_len)
+        return fail(SHIFTATTN_EINVAL, "max_q_len = %d exceeds total_q = %d or max_seq_len = %d", max_q_len, total_q,
+                    max_seq_len);
+    bool new_kv;
+    if (int rc = check_new_kv(k_new, v_new, slot_mapping, &new_kv)) return rc;
+    if (num_seqs == 0 || total_q == 0) return SHIFTATTN_OK;
+    if (!q || !kv_cache || !block_table || !cu_seqlens_q || !seq_lens || !out)
+        return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(q) || !aligned16(out) || !aligned16(kv_cache))
+        return fail(SHIFTATTN_EINVAL, "q / out / kv_cache must be 16-byte aligned");
+    if (static_cast<int64_t>(s.max_blocks) * kBlockSize < max_seq_len)
+        return fail(SHIFTATTN_EINVAL, "max_blocks_per_seq = %d cannot hold max_seq_len = %d", s.max_blocks, max_seq_len);
+    const bool mfma = use_prefill_mfma(s);
+    const size_t need = mfma ? prefill_mfma_workspace(num_seqs, total_q, max_q_len, max_seq_len, s) : 0;
+    if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace)))
+        return fail(SHIFTATTN_EWORKSPACE, "prefill needs %zu workspace bytes, got %zu", need,
+                    workspace ? workspace_bytes : static_cast<size_t>(0));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (new_kv) {
+        e = launch_kv_write(k_new, v_new, slot_mapping, total_q, kv_cache, s, st);
+        if (e != hipSuccess) return hip_fail(e, "kv_write launch");
+    }
+    if (mfma)
+        e = launch_prefill_mfma(q, kv_cache, block_table, cu_seqlens_q, seq_lens, num_seqs, total_q, max_q_len,
+                                max_seq_len, out, workspace, s, st);
+    else
+        e = launch_attn_generic(q, kv_cache, block_table, cu_seqlens_q, seq_lens, num_seqs, total_q, out, s, st);
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "prefill launch");
+}
+
+int shiftattn_decode(const void* q, const void* k_new, const void* v_new, const int64_t* slot_mapping, void* kv_cache,
+                     const int32_t* block_table, const int32_t* seq_lens, int32_t num_seqs, int32_t max_seq_len,
+                     void* out, void* workspace, size_t workspace_bytes, const shiftattn_attn* a, void* stream) {
+    AttnShape s;
+    if (int rc = check_attn(a, &s)) return rc;
+    if (num_seqs < 0 || max_seq_len < 0) return fail(SHIFTATTN_EINVAL, "negative size argument");
+    bool new_kv;
+    if (int rc = check_new_kv(k_new, v_new, slot_mapping, &new_kv)) return rc;
+    if (num_seqs == 0) return SHIFTATTN_OK;
+    if (!q || !kv_cache || !block_table || !seq_lens || !out) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(q) || !aligned16(out) || !aligned16(kv_cache))
+        return fail(SHIFTATTN_EINVAL, "q / out / kv_cache must be 16-byte aligned");
+    if (static_cast<int64_t>(s.max_blocks) * kBlockSize < max_seq_len)
+        return fail(SHIFTATTN_EINVAL, "max_blocks_per_seq = %d cannot hold max_seq_len = %d", s.max_blocks, max_seq_len);
+    const bool mfma = use_decode_mfma(s, num_seqs);
+    const size_t need = mfma ? decode_mfma_workspace(num_seqs, max_seq_len, s) : 0;
+    if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace)))
+        return fail(SHIFTATTN_EWORKSPACE, "decode needs %zu workspace bytes, got %zu", need,
+                    workspace ? workspace_bytes : static_cast<size_t>(0));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (new_kv) {
+        e = launch_kv_write(k_new, v_new, slot_mapping, num_seqs, kv_cache, s, st);
+        if (e != hipSuccess) return hip_fail(e, "kv_write launch");
+    }
+    if (mfma)
+        e = launch_decode_mfma(q, kv_cache, block_table, seq_lens, num_seqs, max_seq_len, out, workspace, s, st);
+    else
+        e = launch_attn_generic(q, kv_cache, block_table, nullptr, seq_lens, num_seqs, num_seqs, out, s, st);
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "decode launch");
+}
+
+}  // extern "C"

@@ -1,0 +1,203 @@
+// General attention kernel and the merge of split-context partial results.
+//
+// attn_rows_kernel covers every element type, head_dim (multiple of 8, <= 256) and GQA ratio the
+// boundary accepts, for prefill chunks and decode rows alike: one wavefront per (token, query head)
+// row, lanes spread over 64 keys for q.k, then over the head dimension for p.V, online softmax in
+// fp32 (Algorithm 1, boxed attention line; Sec. 2.2).  It is the reference-grade path for shapes
+// the MFMA kernels do not take (fp32 tensors, head_dim != 128) and is not tuned for speed.
+#include "internal.h"
+
+namespace shiftattn {
+
+namespace {
+
+__device__ inline float to_float(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+__device__ inline float to_float(float f) { return f; }
+
+__device__ inline uint16_t bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if (f != f) return 0x7FC0;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+__device__ inline void store_elem(uint16_t* p, float f) { *p = bf16_rne(f); }
+__device__ inline void store_elem(float* p, float f) { *p = f; }
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+constexpr int kWaves = 4;
+constexpr int kMaxD = 256;
+
+template <typename Elem>
+__global__ __launch_bounds__(kWaves * 64) void attn_rows_kernel(
+    const Elem* __restrict__ q, const Elem* __restrict__ cache, const int32_t* __restrict__ block_table,
+    const int32_t* __restrict__ cu_seqlens_q, const int32_t* __restrict__ seq_lens, int num_seqs, int total_q,
+    Elem* __restrict__ out, AttnShape a) {
+    constexpr int kPer = 16 / sizeof(Elem);  // elements per 16-byte vector
+    __shared__ float q_s[kWaves][kMaxD];
+    __shared__ float p_s[kWaves][64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + wave;
+    if (row >= static_cast<int64_t>(total_q) * a.hq_l) return;  // whole wavefront leaves together
+    const int tok = static_cast<int>(row / a.hq_l);
+    const int j = static_cast<int>(row % a.hq_l);
+    const int g = j / (a.hq_l / a.hkv_l);
+
+    int s, pos;
+    if (cu_seqlens_q == nullptr) {
+        s = tok;
+        pos = seq_lens[s] - 1;
+    } else {
+        int lo = 0, hi = num_seqs;  // last s with cu[s] <= tok
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (cu_seqlens_q[mid] <= tok) lo = mid; else hi = mid;
+        }
+        s = lo;
+        const int q_len = cu_seqlens_q[s + 1] - cu_seqlens_q[s];
+        pos = seq_lens[s] - q_len + (tok - cu_seqlens_q[s]);
+    }
+    const int32_t* table = block_table + static_cast<size_t>(s) * a.max_blocks;
+    const int D = a.D;
+
+    const Elem* q_row = q + static_cast<size_t>(tok) * a.q_stride + static_cast<size_t>(j) * D;
+    for (int d = lane; d < D; d += 64) q_s[wave][d] = to_float(q_row[d]);
+    __builtin_amdgcn_wave_barrier();
+
+    float m_run = -INFINITY, l_run = 0.f;
+    float o[kMaxD / 64] = {0.f, 0.f, 0.f, 0.f};
+
+    for (int t0 = 0; t0 <= pos; t0 += 64) {
+        const int t = t0 + lane;
+        float logit = -INFINITY;
+        if (t <= pos) {
+            const int64_t blk = table[t / kBlockSize];
+            const Elem* k_row = cache + cache_part_offset(blk, g, 0, a.hkv_l, D) + static_cast<size_t>(t % kBlockSize) * D;
+            float dot = 0.f;
+            for (int dv = 0; dv < D / kPer; ++dv) {
+                union { u32x4 v; Elem e[kPer]; } u;
+                u.v = *reinterpret_cast<const u32x4*>(k_row + dv * kPer);
+#pragma unroll
+                for (int x = 0; x < kPer; ++x) dot = fmaf(q_s[wave][dv * kPer + x], to_float(u.e[x]), dot);
+            }
+            logit = dot * a.scale;
+        }
+        const float m_new = fmaxf(m_run, wave_max(logit));  // finite: key t0 is always visible
+        const float p = (t <= pos) ? expf(logit - m_new) : 0.f;
+        const float alpha = expf(m_run - m_new);             // exp(-inf) = 0 on the first chunk
+        l_run = l_run * alpha + wave_sum(p);
+        m_run = m_new;
+        p_s[wave][lane] = p;
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int x = 0; x < kMaxD / 64; ++x) o[x] *= alpha;
+        for (int b = 0; b < 4 && t0 + b * kBlockSize <= pos; ++b) {
+            const int64_t blk = table[(t0 + b * kBlockSize) / kBlockSize];
+            const Elem* v_part = cache + cache_part_offset(blk, g, 1, a.hkv_l, D);
+#pragma unroll
+            for (int x = 0; x < kMaxD / 64; ++x) {
+                const int d = lane + 64 * x;
+                if (d < D) {
+                    const Elem* v_row = v_part + static_cast<size_t>(d) * kBlockSize;
+#pragma unroll
+                    for (int vv = 0; vv < kBlockSize / kPer; ++vv) {
+                        union { u32x4 v; Elem e[kPer]; } u;
+                        u.v = *reinterpret_cast<const u32x4*>(v_row + vv * kPer);
+#pragma unroll
+                        for (int y = 0; y < kPer; ++y) {
+                            const int off = vv * kPer + y;
+                            // slots past the context may hold anything (also NaN): select, do not multiply
+                            const float val = (t0 + b * kBlockSize + off <= pos) ? to_float(u.e[y]) : 0.f;
+                            o[x] = fmaf(p_s[wave][b * kBlockSize + off], val, o[x]);
+                        }
+                    }
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    Elem* o_row = out + static_cast<size_t>(tok) * a.out_stride + static_cast<size_t>(j) * D;
+    const float inv = 1.f / l_run;
+#pragma unroll
+    for (int x = 0; x < kMaxD / 64; ++x) {
+        const int d = lane + 64 * x;
+        if (d < D) store_elem(o_row + d, o[x] * inv);
+    }
+}
+
+// One workgroup per output row (token, head); thread d merges the row's partials in part order.
+template <typename Elem>
+__global__ __launch_bounds__(128) void combine_kernel(const float* __restrict__ o_part, const float* __restrict__ ml_part,
+                                                      int n_rows, int hq_l, int D, int n_parts, int mode,
+                                                      const int32_t* __restrict__ seq_lens, int chunk,
+                                                      Elem* __restrict__ out, int64_t out_stride) {
+    const int row = blockIdx.x;           // token * hq_l + head
+    const int tok = row / hq_l, head = row % hq_l;
+    int np = n_parts;
+    if (mode == 1) np = (seq_lens[tok] + chunk - 1) / chunk;
+    const size_t part_rows = static_cast<size_t>(n_rows) * hq_l;
+    float m_star = -INFINITY;
+    for (int c = 0; c < np; ++c) m_star = fmaxf(m_star, ml_part[(c * part_rows + row) * 2]);
+    float l_star = 0.f;
+    for (int c = 0; c < np; ++c) {
+        const float m_c = ml_part[(c * part_rows + row) * 2];
+        const float w = (m_c == -INFINITY) ? 0.f : exp2f(m_c - m_star);
+        l_star += ml_part[(c * part_rows + row) * 2 + 1] * w;
+    }
+    const float inv = l_star > 0.f ? 1.f / l_star : 0.f;
+    for (int d = threadIdx.x; d < D; d += blockDim.x) {
+        float acc = 0.f;
+        for (int c = 0; c < np; ++c) {
+            const float m_c = ml_part[(c * part_rows + row) * 2];
+            const float w = (m_c == -INFINITY) ? 0.f : exp2f(m_c - m_star);
+            acc += o_part[(c * part_rows + row) * D + d] * w;
+        }
+        store_elem(out + static_cast<size_t>(tok) * out_stride + static_cast<size_t>(head) * D + d, acc * inv);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_attn_generic(const void* q, const void* cache, const int32_t* block_table,
+                               const int32_t* cu_seqlens_q, const int32_t* seq_lens, int num_seqs, int total_q,
+                               void* out, const AttnShape& a, hipStream_t st) {
+    const int64_t rows = static_cast<int64_t>(total_q) * a.hq_l;
+    if (rows == 0) return hipSuccess;
+    const unsigned grid = static_cast<unsigned>((rows + kWaves - 1) / kWaves);
+    if (a.elem == 2)
+        attn_rows_kernel<uint16_t><<<grid, kWaves * 64, 0, st>>>(
+            static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(cache), block_table, cu_seqlens_q, seq_lens,
+            num_seqs, total_q, static_cast<uint16_t*>(out), a);
+    else
+        attn_rows_kernel<float><<<grid, kWaves * 64, 0, st>>>(static_cast<const float*>(q),
+                                                            static_cast<const float*>(cache), block_table,
+                                                            cu_seqlens_q, seq_lens, num_seqs, total_q,
+                                                            static_cast<float*>(out), a);
+    return hipGetLastError();
+}
+
+hipError_t launch_combine(const float* o_part, const float* ml_part, int n_rows, int hq_l, int D, int n_parts,
+                          int mode, const int32_t* seq_lens, int chunk, void* out, int64_t out_stride, int elem,
+                          hipStream_t st) {
+    const int64_t rows = static_cast<int64_t>(n_rows) * hq_l;
+    if (rows == 0) return hipSuccess;
+    if (elem == 2)
+        combine_kernel<uint16_t><<<static_cast<unsigned>(rows), 128, 0, st>>>(
+            o_part, ml_part, n_rows, hq_l, D, n_parts, mode, seq_lens, chunk, static_cast<uint16_t*>(out), out_stride);
+    else
+        combine_kernel<float><<<static_cast<unsigned>(rows), 128, 0, st>>>(o_part, ml_part, n_rows, hq_l, D, n_parts,
+                                                                          mode, seq_lens, chunk,
+                                                                          static_cast<float*>(out), out_stride);
+    return hipGetLastError();
+}
+
+}  // namespace shiftattn

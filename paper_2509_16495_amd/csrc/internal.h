@@ -1,0 +1,69 @@
+// Internal launch interface between the C-ABI front end (api.hip) and the kernel files.
+// Every launcher only enqueues on the given stream and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace shiftattn {
+
+constexpr int kBlockSize = 16;         // tokens per KV-cache block
+constexpr int kDecodeChunk = 512;      // context tokens per decode workgroup
+constexpr int kPrefillKvTile = 64;     // keys per prefill inner-loop step
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte vector
+
+struct XchgShape {
+    int P, h, h_kv, hq_l, hkv_l;  // heads in elements of one head vector
+    int vec_per_head;             // 16-byte vectors per head vector (D * elem_size / 16)
+    int T, T_pad;
+};
+
+struct AttnShape {
+    int hq_l, hkv_l, D, elem;     // elem: bytes per element (2 = bf16, 4 = f32)
+    int num_blocks, max_blocks;
+    float scale;
+    int64_t q_stride, kv_stride, out_stride;  // in elements
+};
+
+// layout_kernels.hip
+hipError_t launch_pack(const void* qkv, void* send, const XchgShape& s, hipStream_t st);
+hipError_t launch_unpack(const void* recv, void* out, const XchgShape& s, hipStream_t st);
+hipError_t launch_kv_write(const void* k_new, const void* v_new, const int64_t* slots, int n_tokens,
+                           void* cache, const AttnShape& a, hipStream_t st);
+
+// attn_generic.hip : any dtype / head_dim / head ratio, one wavefront per (token, head) row
+hipError_t launch_attn_generic(const void* q, const void* cache, const int32_t* block_table,
+                               const int32_t* cu_seqlens_q /*null: one token per sequence*/,
+                               const int32_t* seq_lens, int num_seqs, int total_q, void* out,
+                               const AttnShape& a, hipStream_t st);
+
+// Merge of split-context partial results (shared by decode and split prefill).
+// Partials: o[part][row][D] fp32 un-normalised, ml[part][row][2] = (max logit * log2e*scale, sum).
+// mode 0: every row has n_parts parts.  mode 1 (decode): row = (sequence, head), the number of
+// parts of a row is ceil(seq_lens[sequence] / chunk).
+hipError_t launch_combine(const float* o_part, const float* ml_part, int n_rows, int hq_l, int D,
+                          int n_parts, int mode, const int32_t* seq_lens, int chunk, void* out,
+                          int64_t out_stride, int elem, hipStream_t st);
+
+// decode_mfma.hip : bf16, D = 128, hq_l/hkv_l <= 16
+bool decode_mfma_supported(const AttnShape& a);
+size_t decode_mfma_workspace(int num_seqs, int max_seq_len, const AttnShape& a);
+hipError_t launch_decode_mfma(const void* q, const void* cache, const int32_t* block_table,
+                              const int32_t* seq_lens, int num_seqs, int max_seq_len, void* out,
+                              void* workspace, const AttnShape& a, hipStream_t st);
+
+// prefill_mfma.hip : bf16, D = 128
+bool prefill_mfma_supported(const AttnShape& a);
+size_t prefill_mfma_workspace(int num_seqs, int total_q, int max_q_len, int max_seq_len, const AttnShape& a);
+hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* block_table,
+                               const int32_t* cu_seqlens_q, const int32_t* seq_lens, int num_seqs,
+                               int total_q, int max_q_len, int max_seq_len, void* out, void* workspace,
+                               const AttnShape& a, hipStream_t st);
+
+// element offsets inside the cache: kv_cache[block][kv head][2][16*D]
+__host__ __device__ inline size_t cache_part_offset(int64_t block, int g, int part, int hkv_l, int D) {
+    return ((static_cast<size_t>(block) * hkv_l + g) * 2 + part) * static_cast<size_t>(kBlockSize) * D;
+}
+
+}  // namespace shiftattn

@@ -1,0 +1,151 @@
+// Data-movement kernels of the path: send-side pack and receive-side unpack of the two SP
+// all-to-alls (Algorithm 1), and the KV-cache append (Sec. 2.2).  All three are pure byte moves
+// bound by HBM bandwidth: every thread moves whole 16-byte vectors, each workgroup issues four
+// independent loads per thread before its stores, and consecutive lanes touch consecutive
+// vectors of the output so that stores are fully coalesced and loads come in runs of at least one
+// head vector (D * elem_size bytes).
+#include "internal.h"
+
+namespace shiftattn {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;
+
+// One workgroup writes kThreads*kUnroll consecutive vectors of send[p]; blockIdx.y = p.
+__global__ __launch_bounds__(kThreads) void pack_seq2head_kernel(const u32x4* __restrict__ in,
+                                                                 u32x4* __restrict__ out, XchgShape s,
+                                                                 uint32_t row_vecs, uint32_t dest_vecs) {
+    const int p = blockIdx.y;
+    const int kv0 = s.h_kv ? static_cast<int>((static_cast<int64_t>(p) * s.h_kv) / s.P) : 0;
+    const uint32_t in_row_heads = s.h + 2 * s.h_kv;
+    const uint32_t first = blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+    u32x4 v[kUnroll];
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) {
+        const uint32_t idx = first + k * kThreads;
+        v[k] = u32x4{0u, 0u, 0u, 0u};
+        if (idx < dest_vecs) {
+            const uint32_t t = idx / row_vecs;
+            const uint32_t c = idx - t * row_vecs;
+            const uint32_t head = c / s.vec_per_head;
+            const uint32_t dv = c - head * s.vec_per_head;
+            uint32_t src_head;
+            if (head < static_cast<uint32_t>(s.hq_l)) src_head = p * s.hq_l + head;
+            else if (head < static_cast<uint32_t>(s.hq_l + s.hkv_l)) src_head = s.h + kv0 + (head - s.hq_l);
+            else src_head = s.h + s.h_kv + kv0 + (head - s.hq_l - s.hkv_l);
+            if (t < static_cast<uint32_t>(s.T))
+                v[k] = __builtin_nontemporal_load(
+                    in + (static_cast<size_t>(t) * in_row_heads + src_head) * s.vec_per_head + dv);
+        }
+    }
+    u32x4* dst = out + static_cast<size_t>(p) * dest_vecs;
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) {
+        const uint32_t idx = first + k * kThreads;
+        if (idx < dest_vecs) __builtin_nontemporal_store(v[k], dst + idx);
+    }
+}
+
+// One workgroup writes kThreads*kUnroll consecutive vectors of out[T][h][D].
+__global__ __launch_bounds__(kThreads) void unpack_head2seq_kernel(const u32x4* __restrict__ in,
+                                                                   u32x4* __restrict__ out, XchgShape s,
+                                                                   uint32_t row_vecs, uint32_t out_vecs) {
+    const uint32_t first = blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+    u32x4 v[kUnroll];
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) {
+        const uint32_t idx = first + k * kThreads;
+        if (idx < out_vecs) {
+            const uint32_t t = idx / row_vecs;
+            const uint32_t c = idx - t * row_vecs;
+            const uint32_t head = c / s.vec_per_head;
+            const uint32_t dv = c - head * s.vec_per_head;
+            const uint32_t p = head / s.hq_l;
+            const uint32_t j = head - p * s.hq_l;
+            v[k] = __builtin_nontemporal_load(
+                in + ((static_cast<size_t>(p) * s.T_pad + t) * s.hq_l + j) * s.vec_per_head + dv);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) {
+        const uint32_t idx = first + k * kThreads;
+        if (idx < out_vecs) __builtin_nontemporal_store(v[k], out + idx);
+    }
+}
+
+// One thread moves one 16-byte piece of a new K row and the matching piece of the V row.
+// K keeps its row shape (one vector store); V is stored dimension-major inside the block, so its
+// elements are scattered with a stride of one block row.
+template <typename Elem>
+__global__ __launch_bounds__(kThreads) void kv_write_kernel(const Elem* __restrict__ k_new,
+                                                            const Elem* __restrict__ v_new,
+                                                            const int64_t* __restrict__ slots, int n_tokens,
+                                                            Elem* __restrict__ cache, int hkv_l, int D,
+                                                            int64_t kv_stride) {
+    constexpr int kPer = 16 / sizeof(Elem);
+    const int vec_per_head = D / kPer;
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    const int64_t total = static_cast<int64_t>(n_tokens) * hkv_l * vec_per_head;
+    if (id >= total) return;
+    const int dv = static_cast<int>(id % vec_per_head);
+    const int g = static_cast<int>((id / vec_per_head) % hkv_l);
+    const int64_t i = id / (static_cast<int64_t>(vec_per_head) * hkv_l);
+    const int64_t slot = slots[i];
+    if (slot < 0) return;
+    const int64_t blk = slot / kBlockSize;
+    const int off = static_cast<int>(slot % kBlockSize);
+    const size_t src = static_cast<size_t>(i) * kv_stride + static_cast<size_t>(g) * D + dv * kPer;
+    const u32x4 kvec = *reinterpret_cast<const u32x4*>(k_new + src);
+    *reinterpret_cast<u32x4*>(cache + cache_part_offset(blk, g, 0, hkv_l, D) + static_cast<size_t>(off) * D +
+                              dv * kPer) = kvec;
+    union {
+        u32x4 v;
+        Elem e[kPer];
+    } u;
+    u.v = *reinterpret_cast<const u32x4*>(v_new + src);
+    Elem* vdst = cache + cache_part_offset(blk, g, 1, hkv_l, D) + static_cast<size_t>(dv * kPer) * kBlockSize + off;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) vdst[j * kBlockSize] = u.e[j];
+}
+
+}  // namespace
+
+hipError_t launch_pack(const void* qkv, void* send, const XchgShape& s, hipStream_t st) {
+    const uint32_t row_vecs = static_cast<uint32_t>(s.hq_l + 2 * s.hkv_l) * s.vec_per_head;
+    const uint32_t dest_vecs = static_cast<uint32_t>(s.T_pad) * row_vecs;
+    if (dest_vecs == 0) return hipSuccess;
+    dim3 grid((dest_vecs + kThreads * kUnroll - 1) / (kThreads * kUnroll), s.P);
+    pack_seq2head_kernel<<<grid, kThreads, 0, st>>>(static_cast<const u32x4*>(qkv), static_cast<u32x4*>(send), s,
+                                                    row_vecs, dest_vecs);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack(const void* recv, void* out, const XchgShape& s, hipStream_t st) {
+    const uint32_t row_vecs = static_cast<uint32_t>(s.h) * s.vec_per_head;
+    const uint32_t out_vecs = static_cast<uint32_t>(s.T) * row_vecs;
+    if (out_vecs == 0) return hipSuccess;
+    dim3 grid((out_vecs + kThreads * kUnroll - 1) / (kThreads * kUnroll));
+    unpack_head2seq_kernel<<<grid, kThreads, 0, st>>>(static_cast<const u32x4*>(recv), static_cast<u32x4*>(out), s,
+                                                      row_vecs, out_vecs);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_write(const void* k_new, const void* v_new, const int64_t* slots, int n_tokens, void* cache,
+                           const AttnShape& a, hipStream_t st) {
+    const int64_t total = static_cast<int64_t>(n_tokens) * a.hkv_l * (a.D * a.elem / 16);
+    if (total == 0) return hipSuccess;
+    const unsigned grid = static_cast<unsigned>((total + kThreads - 1) / kThreads);
+    if (a.elem == 2)
+        kv_write_kernel<uint16_t><<<grid, kThreads, 0, st>>>(static_cast<const uint16_t*>(k_new),
+                                                            static_cast<const uint16_t*>(v_new), slots, n_tokens,
+                                                            static_cast<uint16_t*>(cache), a.hkv_l, a.D, a.kv_stride);
+    else
+        kv_write_kernel<uint32_t><<<grid, kThreads, 0, st>>>(static_cast<const uint32_t*>(k_new),
+                                                            static_cast<const uint32_t*>(v_new), slots, n_tokens,
+                                                            static_cast<uint32_t*>(cache), a.hkv_l, a.D, a.kv_stride);
+    return hipGetLastError();
+}
+
+}  // namespace shiftattn

@@ -1,0 +1,155 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every function the header
+declares, its index helpers reproduce the paper's worked examples, and every invalid-argument
+path returns an error code before anything could be launched."""
+import ast
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "shiftattn.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2509_16495_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2509_16495_amd import build
+        build.build_library()
+    binding.lib()
+    return binding
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(shiftattn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(B):
+    names = _declared_functions()
+    assert {"shiftattn_pack_seq2head", "shiftattn_prefill", "shiftattn_decode", "shiftattn_unpack_head2seq",
+            "shiftattn_kv_write", "shiftattn_last_error"} <= set(names)
+    for n in names:
+        assert hasattr(B.lib(), n), n
+
+
+def test_struct_layouts_match_header(B):
+    assert ctypes.sizeof(B.Xchg) == 20
+    assert ctypes.sizeof(B.Attn) == 56 and B.Attn.q_stride.offset == 32
+
+
+def test_head_block_matches_paper_example(B):
+    gold = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "process_groups_sp3_tp2.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split("=", 1)
+            gold[k.strip()] = ast.literal_eval(v.strip())
+    sp, tp = gold["SP"], gold["TP"]
+    blocks = [B.head_block(sp, tp, r) for r in range(sp * tp)]
+    for rank, head in gold["HEAD_OF_RANK"].items():
+        assert blocks[rank] == head
+    assert [blocks.index(b) for b in range(sp * tp)] == gold["SP_TP_GROUP"][0]
+    assert B.head_block(3, 2, 6) == -1 and B.head_block(0, 2, 0) == -1 and B.head_block(3, 2, -1) == -1
+
+
+def test_replication_and_padding_helpers(B):
+    assert [B.kv_head_of_block(p, 8, 4) for p in range(8)] == [0, 0, 1, 1, 2, 2, 3, 3]
+    assert [B.kv_head_of_block(p, 4, 8) for p in range(4)] == [0, 2, 4, 6]
+    assert B.kv_head_of_block(8, 8, 4) == -1
+    assert B.padded_tokens(9, 8) == 16 and B.padded_tokens(16, 8) == 16 and B.padded_tokens(0, 8) == 0
+    assert B.padded_tokens(-1, 8) == -1 and B.padded_tokens(5, 0) == -1
+
+
+def _xchg(B, **kw):
+    d = dict(P=2, num_q_heads=8, num_kv_heads=0, head_dim=64, dtype=B.F32)
+    d.update(kw)
+    return B.Xchg(d["P"], d["num_q_heads"], d["num_kv_heads"], d["head_dim"], d["dtype"])
+
+
+def _attn(B, **kw):
+    d = dict(num_q_heads=8, num_kv_heads=1, head_dim=128, dtype=B.BF16, block_size=16, num_blocks=64,
+             max_blocks_per_seq=8, softmax_scale=0.1, q_stride=0, kv_stride=0, out_stride=0)
+    d.update(kw)
+    return B.Attn(*[d[f[0]] for f in B.Attn._fields_])
+
+
+FAKE = ctypes.c_void_p(0x1000)  # aligned, never dereferenced: every case below fails validation first
+
+
+def test_pack_unpack_reject_bad_arguments(B):
+    L = B.lib()
+    cases = [
+        (dict(P=0), 4, 4, B.EINVAL), (dict(P=3), 4, 4, B.EINVAL), (dict(num_kv_heads=3, P=2), 4, 4, B.EINVAL),
+        (dict(dtype=7), 4, 4, B.EINVAL), (dict(), 5, 4, B.EINVAL), (dict(), -1, 4, B.EINVAL),
+        (dict(head_dim=6), 4, 4, B.EUNSUPPORTED), (dict(head_dim=0), 4, 4, B.EINVAL),
+        (dict(num_q_heads=12, num_kv_heads=6, P=4), 4, 4, B.EINVAL),
+    ]
+    for kw, T, T_pad, code in cases:
+        x = _xchg(B, **kw)
+        assert L.shiftattn_pack_seq2head(FAKE, FAKE, T, T_pad, ctypes.byref(x), None) == code, kw
+        assert B.last_error()
+    x = _xchg(B)
+    assert L.shiftattn_pack_seq2head(None, FAKE, 4, 4, ctypes.byref(x), None) == B.EINVAL
+    assert L.shiftattn_pack_seq2head(FAKE, None, 4, 4, ctypes.byref(x), None) == B.EINVAL
+    assert L.shiftattn_pack_seq2head(ctypes.c_void_p(0x1008), FAKE, 4, 4, ctypes.byref(x), None) == B.EINVAL
+    assert L.shiftattn_pack_seq2head(FAKE, FAKE, 4, 4, None, None) == B.EINVAL
+    assert L.shiftattn_unpack_head2seq(None, FAKE, 4, 4, ctypes.byref(x), None) == B.EINVAL
+    assert L.shiftattn_unpack_head2seq(FAKE, FAKE, 4, 3, ctypes.byref(x), None) == B.EINVAL
+    # empty problems are valid no-ops and touch nothing
+    assert L.shiftattn_pack_seq2head(None, None, 0, 0, ctypes.byref(x), None) == B.OK
+    assert L.shiftattn_unpack_head2seq(None, None, 0, 4, ctypes.byref(x), None) == B.OK
+    big = _xchg(B, num_q_heads=1 << 20, P=1, head_dim=256)
+    assert L.shiftattn_pack_seq2head(FAKE, FAKE, 1 << 20, 1 << 20, ctypes.byref(big), None) == B.EUNSUPPORTED
+
+
+def test_attention_entry_points_reject_bad_arguments(B):
+    L = B.lib()
+
+    def prefill(a, q=FAKE, k=None, v=None, slots=None, cache=FAKE, table=FAKE, cu=FAKE, sl=FAKE, S=1, tq=32, mq=32,
+                ms=64, out=FAKE, ws=None, wsb=0):
+        return L.shiftattn_prefill(q, k, v, slots, cache, table, cu, sl, S, tq, mq, ms, out, ws, wsb,
+                                   None if a is None else ctypes.byref(a), None)
+
+    def decode(a, q=FAKE, k=None, v=None, slots=None, cache=FAKE, table=FAKE, sl=FAKE, S=4, ms=64, out=FAKE, ws=None,
+               wsb=0):
+        return L.shiftattn_decode(q, k, v, slots, cache, table, sl, S, ms, out, ws, wsb,
+                                  None if a is None else ctypes.byref(a), None)
+
+    ok = _attn(B)
+    assert prefill(None) == B.EINVAL and decode(None) == B.EINVAL
+    for kw, code in [(dict(num_kv_heads=3), B.EINVAL), (dict(num_kv_heads=0), B.EINVAL), (dict(dtype=5), B.EINVAL),
+                     (dict(head_dim=100), B.EUNSUPPORTED), (dict(head_dim=512), B.EUNSUPPORTED),
+                     (dict(block_size=32), B.EUNSUPPORTED), (dict(softmax_scale=0.0), B.EINVAL),
+                     (dict(softmax_scale=-1.0), B.EINVAL), (dict(softmax_scale=float("nan")), B.EINVAL),
+                     (dict(q_stride=100), B.EINVAL), (dict(kv_stride=8), B.EINVAL), (dict(out_stride=1028), B.EINVAL),
+                     (dict(max_blocks_per_seq=2), B.EINVAL)]:
+        assert prefill(_attn(B, **kw)) == code, kw
+        assert decode(_attn(B, **kw)) == code, kw
+    for kw in (dict(q=None), dict(cache=None), dict(table=None), dict(sl=None), dict(out=None)):
+        assert prefill(ok, **kw) == B.EINVAL and decode(ok, **kw) == B.EINVAL
+    assert prefill(ok, cu=None) == B.EINVAL
+    assert prefill(ok, k=FAKE) == B.EINVAL and decode(ok, v=FAKE, slots=FAKE) == B.EINVAL
+    assert prefill(ok, q=ctypes.c_void_p(0x1002)) == B.EINVAL
+    assert prefill(ok, S=-1) == B.EINVAL and prefill(ok, mq=64, tq=32) == B.EINVAL and prefill(ok, mq=128, tq=128, ms=64) == B.EINVAL
+    assert decode(ok, S=-1) == B.EINVAL
+    # decode always needs a workspace on the tuned path; a missing or short one is reported, not used
+    need = B.decode_workspace_bytes(4, 64, ok)
+    assert need > 0
+    assert decode(ok) == B.EWORKSPACE and decode(ok, ws=FAKE, wsb=need - 1) == B.EWORKSPACE
+    # split prefill (short chunk on a long context) needs one too
+    long_ctx = _attn(B, max_blocks_per_seq=8320)
+    need = B.prefill_workspace_bytes(1, 2048, 2048, 133120, long_ctx)
+    assert need > 0
+    assert prefill(long_ctx, tq=2048, mq=2048, ms=133120) == B.EWORKSPACE
+    assert B.prefill_workspace_bytes(4, 16384, 4096, 4096, _attn(B, num_q_heads=4, max_blocks_per_seq=256)) == 0
+    # empty batches are valid no-ops
+    assert prefill(ok, q=None, cache=None, table=None, cu=None, sl=None, out=None, S=0, tq=0, mq=0, ms=0) == B.OK
+    assert decode(ok, q=None, cache=None, table=None, sl=None, out=None, S=0, ms=0) == B.OK
+    kvw = L.shiftattn_kv_write
+    assert kvw(None, FAKE, FAKE, 4, FAKE, ctypes.byref(ok), None) == B.EINVAL
+    assert kvw(FAKE, FAKE, FAKE, -1, FAKE, ctypes.byref(ok), None) == B.EINVAL
+    assert kvw(None, None, None, 0, None, ctypes.byref(ok), None) == B.OK
+    assert B.lib().shiftattn_decode_workspace_bytes(-1, 64, ctypes.byref(ok)) == ctypes.c_size_t(-1).value

@@ -1,0 +1,199 @@
+"""GPU parity of prefill and decode attention against the CPU fp64 oracle, through the C ABI.
+
+Tolerances (absolute, on outputs of O(1) magnitude):
+  bf16 tensors, fp32 accumulation : max |err| <= 2e-2 and mean |err| <= 1e-3
+  fp32 tensors                    : max |err| <= 1e-5
+and, where outputs are tiny (values pre-scaled by 1/sqrt(128)), additionally max |err| <= 2e-2 * max |ref|.
+Small cases are compared element by element; the benchmark-sized configurations on sampled rows
+(all heads of every sampled token) that the oracle can afford.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from paper_2509_16495_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+BF16_MAX, BF16_MEAN, F32_MAX = 2e-2, 1e-3, 1e-5
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_backend
+    return gpu_backend
+
+
+def _check(got_bits, want, dtype, relative=False):
+    got = W.to_f64(got_bits, dtype)
+    assert got.shape == want.shape
+    assert np.all(np.isfinite(got))
+    err = np.abs(got - want)
+    if dtype == "f32":
+        assert err.max() <= F32_MAX, err.max()
+    else:
+        assert err.max() <= BF16_MAX and err.mean() <= BF16_MEAN, (err.max(), err.mean())
+        if relative:
+            assert err.max() <= BF16_MAX * np.abs(want).max(), (err.max(), np.abs(want).max())
+
+
+def _sample_rows(case, n_random, seed, edge=32):
+    """Sampled query tokens: the first and last `edge` tokens of every sequence plus random ones."""
+    rng = np.random.default_rng(seed)
+    rows = []
+    for s in range(case.num_seqs):
+        a, b = int(case.cu_seqlens_q[s]), int(case.cu_seqlens_q[s + 1])
+        rows += list(range(a, min(a + edge, b))) + list(range(max(a, b - edge), b))
+    rows += list(rng.integers(0, case.total_q, size=n_random))
+    return np.unique(np.array(rows, dtype=np.int64))
+
+
+# ------------------------------------------------------------------------------------------------------
+# small cases, element by element
+# ------------------------------------------------------------------------------------------------------
+def test_config1_tiny_fp32_prefill(oracle, G):
+    case = W.config1_attn()
+    want = oracle.attention_case(case, oracle.cache_for_case(case))
+    got = G.prefill_case(case, G.cache_for_case(case))
+    _check(got, want, "f32")
+
+
+PREFILL_SMALL = [
+    # seqs (q_len, ctx), hq_l, hkv_l  - bf16, D=128 (MFMA path)
+    ([(200, 200), (77, 300), (1, 50), (130, 130)], 8, 1),   # several tiles, ragged tails, chunked, one decode-like row
+    ([(64, 64), (33, 33), (16, 16)], 4, 1),
+    ([(150, 150), (5, 260)], 8, 2),                          # two KV heads
+    ([(100, 100)], 4, 4),                                    # no GQA sharing
+    ([(90, 190)], 6, 2),                                     # three query heads per KV head (not a power of two)
+    ([(300, 300)], 16, 1),
+    ([(0, 10), (40, 40), (0, 0)], 4, 1),                     # empty chunks in the batch
+]
+
+
+@pytest.mark.parametrize("seqs,hq_l,hkv_l", PREFILL_SMALL)
+def test_prefill_bf16_small(oracle, G, seqs, hq_l, hkv_l):
+    case = W.make_attn_case("t", 51, "bf16", seqs, hq_l, hkv_l, 128)
+    want = oracle.attention_case(case, oracle.cache_for_case(case))
+    got = G.prefill_case(case, G.cache_for_case(case))
+    _check(got, want, "bf16")
+
+
+def test_prefill_fused_kv_write_from_strided_views(oracle, G):
+    """New tokens' K/V arrive with the call as views into a fused receive buffer; the cache afterwards
+    and the attention output both match 'write, then attend'."""
+    from paper_2509_16495_amd import binding as B
+    case = W.make_attn_case("t", 52, "bf16", [(70, 170), (128, 128), (1, 40)], 8, 1, 128)
+    want = oracle.attention_case(case, oracle.cache_for_case(case))
+    cache = G.cache_for_case(case, only_cached=True)
+    got = G.prefill_case(case, cache, fused_new_kv=True)
+    _check(got, want, "bf16")
+    assert B.to_host(cache).tobytes() == oracle.cache_for_case(case).tobytes()
+
+
+def test_prefill_split_over_keys(oracle, G):
+    """A short chunk on a long cached context is split into key ranges and merged."""
+    from paper_2509_16495_amd import binding as B
+    case = W.make_attn_case("t", 53, "bf16", [(48, 9000)], 8, 1, 128)
+    a = B.Attn(8, 1, 128, B.BF16, 16, case.num_blocks, case.max_blocks_per_seq, case.softmax_scale, 0, 0, 0)
+    assert B.prefill_workspace_bytes(1, 48, 48, 9000, a) > 0
+    want = oracle.attention_case(case, oracle.cache_for_case(case))
+    got = G.prefill_case(case, G.cache_for_case(case))
+    _check(got, want, "bf16")
+
+
+def test_generic_kernel_bf16_and_other_head_dims(oracle, G):
+    for dtype, D, hq_l, hkv_l in [("bf16", 64, 4, 2), ("f32", 128, 8, 1), ("f32", 32, 2, 2), ("bf16", 256, 2, 1)]:
+        case = W.make_attn_case("t", 54, dtype, [(37, 150), (80, 80), (1, 9)], hq_l, hkv_l, D)
+        want = oracle.attention_case(case, oracle.cache_for_case(case))
+        got = G.prefill_case(case, G.cache_for_case(case))
+        _check(got, want, dtype)
+
+
+DECODE_LENS = [1, 15, 16, 17, 31, 32, 33, 100, 511, 512, 513, 1023, 1500, 3000]
+
+
+@pytest.mark.parametrize("hq_l,hkv_l", [(8, 1), (4, 1), (4, 4), (16, 1), (6, 2), (16, 2)])
+def test_decode_bf16_small(oracle, G, hq_l, hkv_l):
+    case = W.make_attn_case("t", 55, "bf16", [(1, c) for c in DECODE_LENS], hq_l, hkv_l, 128, pool_factor=1.3)
+    want = oracle.attention_case(case, oracle.cache_for_case(case))
+    got = G.decode_case(case, G.cache_for_case(case))
+    _check(got, want, "bf16")
+
+
+def test_decode_fused_kv_write_and_fp32(oracle, G):
+    from paper_2509_16495_amd import binding as B
+    case = W.make_attn_case("t", 56, "bf16", [(1, c) for c in (1, 16, 17, 700, 64)], 8, 1, 128)
+    want = oracle.attention_case(case, oracle.cache_for_case(case))
+    cache = G.cache_for_case(case, only_cached=True)
+    got = G.decode_case(case, cache, fused_new_kv=True)
+    _check(got, want, "bf16")
+    assert B.to_host(cache).tobytes() == oracle.cache_for_case(case).tobytes()
+    case = W.make_attn_case("t", 57, "f32", [(1, c) for c in (1, 33, 200)], 4, 1, 64)
+    want = oracle.attention_case(case, oracle.cache_for_case(case))
+    _check(G.decode_case(case, G.cache_for_case(case)), want, "f32")
+
+
+def test_unwritten_cache_slots_may_hold_nan(oracle, G):
+    """Slots past a sequence's context are never written; whatever they hold must not leak."""
+    case = W.make_attn_case("t", 58, "bf16", [(1, 5), (1, 41), (1, 530)], 8, 1, 128)
+    want = oracle.attention_case(case, oracle.cache_for_case(case))
+    got = G.decode_case(case, G.cache_for_case(case, fill_byte=0xFF))       # 0xFFFF = bf16 NaN
+    _check(got, want, "bf16")
+    case = W.make_attn_case("t", 59, "bf16", [(37, 37), (5, 70)], 8, 1, 128)
+    want = oracle.attention_case(case, oracle.cache_for_case(case))
+    got = G.prefill_case(case, G.cache_for_case(case, fill_byte=0xFF))
+    _check(got, want, "bf16")
+
+
+def test_results_are_bitwise_reproducible(G):
+    case = W.make_attn_case("t", 60, "bf16", [(1, c) for c in (900, 2100, 40)], 8, 1, 128)
+    cache = G.cache_for_case(case)
+    assert G.decode_case(case, cache).tobytes() == G.decode_case(case, cache).tobytes()
+    case = W.make_attn_case("t", 61, "bf16", [(48, 9000), (200, 200)], 8, 1, 128)
+    cache = G.cache_for_case(case)
+    assert G.prefill_case(case, cache).tobytes() == G.prefill_case(case, cache).tobytes()
+
+
+# ------------------------------------------------------------------------------------------------------
+# benchmark-sized configurations, in the launch configuration the benchmark times
+# ------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("data_scaled", [False, True])
+def test_config2_8b_prefill_sampled(oracle, G, data_scaled):
+    case = W.config2_attn(data_scaled=data_scaled)
+    rows = _sample_rows(case, 24, 2)
+    want = oracle.attention_case(case, oracle.cache_for_case(case), rows)
+    got = G.prefill_case(case, G.cache_for_case(case))
+    _check(got[rows], want, "bf16", relative=data_scaled)
+
+
+def test_config3_70b_prefill_sampled(oracle, G):
+    case = W.config3_attn()
+    rows = _sample_rows(case, 40, 3)
+    want = oracle.attention_case(case, oracle.cache_for_case(case), rows)
+    got = G.prefill_case(case, G.cache_for_case(case))
+    _check(got[rows], want, "bf16")
+
+
+def test_config4_batch_decode_full(oracle, G):
+    case = W.config4_attn()
+    want = oracle.attention_case(case, oracle.cache_for_case(case))
+    got = G.decode_case(case, G.cache_for_case(case, only_cached=True), fused_new_kv=True)
+    _check(got, want, "bf16")
+
+
+def test_config5_mixed_step(oracle, G):
+    """One 2048-token chunk on a 131072-token cached context plus 64 decodes in one block pool; the new
+    tokens' K/V are written by the calls themselves."""
+    from paper_2509_16495_amd import binding as B
+    case, n_prefill = W.config5_attn()
+    ocache = oracle.cache_for_case(case)
+    cache = G.cache_for_case(case, only_cached=True)
+    pre = W.sub_case(case, range(n_prefill))
+    dec = W.sub_case(case, range(n_prefill, case.num_seqs))
+    got_pre = G.prefill_case(pre, cache, fused_new_kv=True)
+    got_dec = G.decode_case(dec, cache, fused_new_kv=True)
+    assert B.to_host(cache).tobytes() == ocache.tobytes()
+    rows = _sample_rows(pre, 8, 5, edge=8)
+    _check(got_pre[rows], oracle.attention_case(pre, ocache, rows), "bf16")
+    _check(got_dec, oracle.attention_case(dec, ocache), "bf16")
