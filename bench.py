@@ -1,0 +1,282 @@
+#!/usr/bin/env python3
+"""Benchmark of one GPU's share of a Shift-Parallelism attention layer on MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic batch, with every input already in
+HBM: send-side pack of this rank's fused QKV rows, causal prefill with fused KV-cache append,
+receive-side unpack, and one decode step (with its KV append) for the same sequences.  The batch is
+the Llama-3.1-8B-shaped shard at P=8 (4 query heads / 1 KV head, head_dim 128, 4 sequences of 4096
+tokens, 16-token cache blocks in a random block-table permutation).  The wire exchange between the
+ranks is not part of the path: the buffers it would deliver are staged in HBM beforehand.
+
+One JSON line goes to stdout.  `value` is attention TFLOP/s of the whole step (4*D flops per
+(query, visible key) pair per query head, masked pairs and softmax not counted, divided by the
+wall time of the step).  `roofline` prices the dominant kernel (the MFMA prefill kernel) against
+the chip's dense bf16 MFMA peak using HIP-event timing of that kernel alone.  `cpu_baseline` is the
+fp64 CPU oracle timed on a stated sample of the same batch.  Further objects report the
+HBM-bound kernels on the configurations that are large enough to measure bandwidth (batch decode of
+256 sequences, exchange of a [16384, 64, 128] hidden state) and the 70B-shaped prefill.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
+METRIC = "prefill attn TFLOP/s + decode KV-read GB/s per MI355X (head shard, % roofline)"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the decode / exchange / 70B-prefill configurations")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build covers one GPU's share of the layer and runs on exactly one GPU; "
+              f"--gpus {args.gpus} is not supported (no collectives are part of the path).", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2509_16495_amd import binding as B
+    from paper_2509_16495_amd import workloads as W
+
+    B.lib()  # fail loudly if the HIP library was not built
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    bf = torch.bfloat16
+
+    def ti(a, dt):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=dt)).to(dev)
+
+    def time_events(fn, reps, warm=3):
+        """Average duration (ms) of fn over `reps` back-to-back calls, HIP events on the launch stream."""
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    # ------------------------------------------------------------------------------------------------
+    # the step's batch: 8B-shaped shard at P=8
+    # ------------------------------------------------------------------------------------------------
+    P, H, H_kv, D = 8, 32, 8, 128
+    case = W.config2_attn()
+    hq_l, hkv_l = case.hq_l, case.hkv_l
+    n = case.total_q
+    T = n // P
+    log(f"[bench] step batch: {case.name}: {case.num_seqs} x {int(case.q_lens[0])} tokens, {hq_l}q/{hkv_l}kv heads, D={D}, "
+        f"{case.num_blocks} cache blocks; flops/step = {case.flops() / 1e9:.2f} GFLOP (prefill)")
+
+    rng = np.random.Generator(np.random.PCG64(1002))
+    qkv_local = B.to_device(W.f32_to_bf16_bits(rng.standard_normal((T, H + 2 * H_kv, D), dtype=np.float32)), "bf16", dev)
+    send = torch.empty((P, T, hq_l + 2 * hkv_l, D), dtype=bf, device=dev)
+    new = case.new_token_index
+    recv1 = B.to_device(np.concatenate([case.q, case.k_ctx[new], case.v_ctx[new]], axis=1), "bf16", dev)  # after a2a #1
+    q_v, k_v, v_v = recv1[:, :hq_l], recv1[:, hq_l:hq_l + hkv_l], recv1[:, hq_l + hkv_l:]
+    slots = ti(case.slots[new], np.int64)
+    cache = torch.zeros((case.num_blocks, hkv_l, 2, 16 * D), dtype=bf, device=dev)
+    table, cu, sl = ti(case.block_table, np.int32), ti(case.cu_seqlens_q, np.int32), ti(case.ctx_lens, np.int32)
+    max_q, max_ctx = int(case.q_lens.max()), int(case.ctx_lens.max())
+    attn_o = torch.empty((n, hq_l, D), dtype=bf, device=dev)
+    recv2 = B.to_device(W.f32_to_bf16_bits(rng.standard_normal((P, T, hq_l, D), dtype=np.float32)), "bf16", dev)  # after a2a #2
+    out_seq = torch.empty((T, H, D), dtype=bf, device=dev)
+    # the decode step that follows for the same sequences (context 4097 each)
+    dcase = W.make_attn_case("cfg2_decode_step", 1003, "bf16", [(1, int(c) + 1) for c in case.ctx_lens], hq_l, hkv_l, D,
+                             pool_factor=2.0)
+    dnew = dcase.new_token_index
+    drecv = B.to_device(np.concatenate([dcase.q, dcase.k_ctx[dnew], dcase.v_ctx[dnew]], axis=1), "bf16", dev)
+    dq, dk, dv = drecv[:, :hq_l], drecv[:, hq_l:hq_l + hkv_l], drecv[:, hq_l + hkv_l:]
+    dslots = ti(dcase.slots[dnew], np.int64)
+    dcache = torch.zeros((dcase.num_blocks, hkv_l, 2, 16 * D), dtype=bf, device=dev)
+    dslots_all = dcase.slots.copy()
+    dslots_all[dnew] = -1
+    B.kv_write(B.to_device(dcase.k_ctx, "bf16", dev), B.to_device(dcase.v_ctx, "bf16", dev), ti(dslots_all, np.int64), dcache)
+    dtable, dsl = ti(dcase.block_table, np.int32), ti(dcase.ctx_lens, np.int32)
+    dmax = int(dcase.ctx_lens.max())
+    dout = torch.empty((dcase.num_seqs, hq_l, D), dtype=bf, device=dev)
+    a_dec = B.attn_desc(dq, dcache, dtable, dcase.softmax_scale, dk, dout)
+    dws = torch.empty(max(B.decode_workspace_bytes(dcase.num_seqs, dmax, a_dec), 16), dtype=torch.uint8, device=dev)
+    a_pre = B.attn_desc(q_v, cache, table, case.softmax_scale, k_v, attn_o)
+    pws = torch.empty(max(B.prefill_workspace_bytes(case.num_seqs, n, max_q, max_ctx, a_pre), 16), dtype=torch.uint8, device=dev)
+
+    def do_pack():
+        B.pack_seq2head(qkv_local, send, P, H, H_kv)
+
+    def do_prefill():
+        B.prefill(q_v, cache, table, cu, sl, max_q, max_ctx, attn_o, case.softmax_scale, k_new=k_v, v_new=v_v,
+                  slot_mapping=slots, workspace=pws)
+
+    def do_prefill_kernel_only():
+        B.prefill(q_v, cache, table, cu, sl, max_q, max_ctx, attn_o, case.softmax_scale, workspace=pws)
+
+    def do_unpack():
+        B.unpack_head2seq(recv2, out_seq)
+
+    def do_decode():
+        B.decode(dq, dcache, dtable, dsl, dmax, dout, dcase.softmax_scale, k_new=dk, v_new=dv, slot_mapping=dslots,
+                 workspace=dws)
+
+    def step():
+        do_pack()
+        do_prefill()
+        do_unpack()
+        do_decode()
+
+    # ---- the timed region: W warm-up steps, then exactly K steps between synchronisations -----------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    step_flops = case.flops() + dcase.flops()
+    value = step_flops / (ms_per_step * 1e-3) / 1e12
+    log(f"[bench] step: {ms_per_step:.4f} ms -> {value:.1f} TFLOP/s of attention")
+
+    # ---- per-phase HIP-event timings, same stream ------------------------------------------------------------
+    reps = max(args.steps, 10)
+    phases = {}
+    e = 2
+    pack_bytes = T * (H + 2 * H_kv) * D * e + P * T * (hq_l + 2 * hkv_l) * D * e
+    unpack_bytes = 2 * T * H * D * e
+    for name, fn, work, unit in [("pack_seq2head", do_pack, pack_bytes / 1e9, "GB/s"),
+                                 ("prefill_with_kv_write", do_prefill, case.flops() / 1e12, "TFLOP/s"),
+                                 ("prefill_kernel", do_prefill_kernel_only, case.flops() / 1e12, "TFLOP/s"),
+                                 ("unpack_head2seq", do_unpack, unpack_bytes / 1e9, "GB/s"),
+                                 ("decode_with_kv_write", do_decode, dcase.kv_bytes() / 1e9, "GB/s")]:
+        ms = time_events(fn, reps)
+        phases[name] = {"ms": round(ms, 5), "rate": round(work / (ms * 1e-3), 2), "unit": unit}
+        log(f"[bench]   {name:24s} {ms * 1e3:9.1f} us  {phases[name]['rate']:10.1f} {unit}")
+    pk_ms = phases["prefill_kernel"]["ms"]
+    achieved = case.flops() / (pk_ms * 1e-3) / 1e12
+    roofline = {"kernel": "prefill_kernel (bf16 MFMA causal prefill)", "bound": "mfma", "achieved": round(achieved, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": None, "flops_per_launch": case.flops(), "avg_launch_ms": round(pk_ms, 5)}
+
+    result = {
+        "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: Llama-3.1-8B-shaped shard at P=8, bf16, 4q/1kv heads, head_dim 128, "
+                               "4 x 4096-token causal prefill, paged KV (16-token blocks, seeded random block table); "
+                               "step = pack + prefill(+KV write) + unpack + one decode step",
+                   "flop_convention": "4*D per (query, visible key) pair per query head",
+                   "step_flops": step_flops},
+        "roofline": roofline,
+        "phases": phases,
+    }
+
+    # ---- the HBM-bound kernels and the 70B-shaped prefill on their own configurations ------------------------
+    if not args.no_extras:
+        # batch decode, 256 sequences (configs[3])
+        c4 = W.config4_attn()
+        cache4 = torch.zeros((c4.num_blocks, 1, 2, 16 * D), dtype=bf, device=dev)
+        B.kv_write(B.to_device(c4.k_ctx, "bf16", dev), B.to_device(c4.v_ctx, "bf16", dev), ti(c4.slots, np.int64), cache4)
+        q4 = B.to_device(c4.q, "bf16", dev)
+        t4, s4 = ti(c4.block_table, np.int32), ti(c4.ctx_lens, np.int32)
+        o4 = torch.empty_like(q4)
+        m4 = int(c4.ctx_lens.max())
+        a4 = B.attn_desc(q4, cache4, t4, c4.softmax_scale, None, o4)
+        w4 = torch.empty(B.decode_workspace_bytes(c4.num_seqs, m4, a4), dtype=torch.uint8, device=dev)
+        ms = time_events(lambda: B.decode(q4, cache4, t4, s4, m4, o4, c4.softmax_scale, workspace=w4), reps)
+        gbps = c4.kv_bytes() / (ms * 1e-3) / 1e9
+        result["decode_kv_read"] = {"workload": f"configs[3]: 256 decode sequences, contexts U[512,8192], realised sum "
+                                                f"{int(c4.ctx_lens.sum())} tokens, 8q/1kv, D=128, bf16 paged KV",
+                                    "kv_bytes": c4.kv_bytes(), "ms": round(ms, 5),
+                                    "roofline": {"kernel": "decode_splitk_kernel + combine_kernel", "bound": "hbm",
+                                                 "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                                 "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": None}}
+        log(f"[bench] decode cfg4: {ms * 1e3:.1f} us, {gbps:.0f} GB/s of KV ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
+        del cache4, w4
+        # exchange of the 70B hidden state (configs[2])
+        x3 = W.config3_xchg()
+        copies = 3
+        xin = [B.to_device(x3.x, "bf16", dev) for _ in range(copies)]
+        xsend = [torch.empty((x3.P, x3.T_pad, x3.h // x3.P, D), dtype=bf, device=dev) for _ in range(copies)]
+        xout = [torch.empty((x3.T, x3.h, D), dtype=bf, device=dev) for _ in range(copies)]
+        it = [0]
+
+        def pack3():
+            i = it[0] = (it[0] + 1) % copies
+            B.pack_seq2head(xin[i], xsend[i], x3.P, x3.h, 0)
+
+        def unpack3():
+            i = it[0] = (it[0] + 1) % copies
+            B.unpack_head2seq(xsend[i], xout[i])
+
+        for nm, fn in (("pack_seq2head", pack3), ("unpack_head2seq", unpack3)):
+            ms = time_events(fn, reps)
+            gbps = x3.bytes_moved() / (ms * 1e-3) / 1e9
+            result[nm] = {"workload": "configs[2]: hidden [16384, 64 heads, 128] bf16 <-> 8 buffers, 3 rotating copies",
+                          "bytes": x3.bytes_moved(), "ms": round(ms, 5),
+                          "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                       "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": None}}
+            log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {gbps:.0f} GB/s ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
+        del xin, xsend, xout
+        # 70B-shaped prefill (configs[2])
+        c3 = W.config3_attn()
+        cache3 = torch.zeros((c3.num_blocks, 1, 2, 16 * D), dtype=bf, device=dev)
+        B.kv_write(B.to_device(c3.k_ctx, "bf16", dev), B.to_device(c3.v_ctx, "bf16", dev), ti(c3.slots, np.int64), cache3)
+        q3 = B.to_device(c3.q, "bf16", dev)
+        t3, cu3, s3 = ti(c3.block_table, np.int32), ti(c3.cu_seqlens_q, np.int32), ti(c3.ctx_lens, np.int32)
+        o3 = torch.empty_like(q3)
+        ms = time_events(lambda: B.prefill(q3, cache3, t3, cu3, s3, c3.total_q, c3.total_q, o3, c3.softmax_scale), reps)
+        tf = c3.flops() / (ms * 1e-3) / 1e12
+        result["prefill_70b"] = {"workload": "configs[2]: 8q/1kv, D=128, one 16384-token causal prefill", "flops": c3.flops(),
+                                 "ms": round(ms, 5),
+                                 "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_BF16_TFLOPS,
+                                              "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}}
+        log(f"[bench] prefill cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%} of bf16 MFMA peak)")
+        del cache3
+
+    # ---- CPU oracle on a bounded sample of the step's batch --------------------------------------------------
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        rows = np.arange(0, n, dtype=np.int64)                         # the whole prefill batch of the step
+        ocache = O.cache_for_case(case)
+        t0 = time.perf_counter()
+        want = O.attention_case(case, ocache, rows)
+        dt = time.perf_counter() - t0
+        pos = np.concatenate([case.ctx_lens[s] - case.q_lens[s] + np.arange(case.q_lens[s]) for s in range(case.num_seqs)])
+        sample_flops = 4 * D * hq_l * int((pos[rows] + 1).sum())
+        do_prefill()
+        torch.cuda.synchronize()
+        got = W.to_f64(B.to_host(attn_o)[rows], "bf16")
+        err = np.abs(got - want)
+        result["cpu_baseline"] = {"value": round(sample_flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": O.num_threads(),
+                                  "kind": "oracle", "seconds": round(dt, 2),
+                                  "sample": f"fp64 oracle on every query token and head of the step's prefill batch "
+                                            f"({sample_flops / 1e9:.1f} of {case.flops() / 1e9:.1f} GFLOP)"}
+        result["parity_on_sample"] = {"max_abs_err": float(err.max()), "mean_abs_err": float(err.mean())}
+        log(f"[bench] oracle: {dt:.1f} s on {O.num_threads()} threads, {sample_flops / dt / 1e9:.2f} GFLOP/s; "
+            f"GPU vs oracle max|err|={err.max():.2e} mean|err|={err.mean():.2e}")
+
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
