@@ -134,33 +134,54 @@ __global__ __launch_bounds__(kWaves * 64) void attn_rows_kernel(
     }
 }
 
-// One workgroup per output row (token, head); thread d merges the row's partials in part order.
+// One workgroup per output row (token, head).  The row's (max, sum) pairs are fetched in parallel
+// and turned into weights in LDS; then every thread owns head-dim elements and sums the weighted
+// partials in part order with independent loads.
+constexpr int kCombineThreads = 128;
+constexpr int kCombineMaxParts = kMaxParts;
+
 template <typename Elem>
-__global__ __launch_bounds__(128) void combine_kernel(const float* __restrict__ o_part, const float* __restrict__ ml_part,
-                                                      int n_rows, int hq_l, int D, int n_parts, int mode,
-                                                      const int32_t* __restrict__ seq_lens, int chunk,
-                                                      Elem* __restrict__ out, int64_t out_stride) {
-    const int row = blockIdx.x;           // token * hq_l + head
+__global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* __restrict__ o_part,
+                                                                  const float* __restrict__ ml_part, int n_rows,
+                                                                  int hq_l, int D, int n_parts, int mode,
+                                                                  const int32_t* __restrict__ seq_lens, int chunk,
+                                                                  Elem* __restrict__ out, int64_t out_stride) {
+    __shared__ float w_s[kCombineMaxParts];
+    __shared__ float l_s[kCombineMaxParts];
+    __shared__ float red_s[kCombineThreads / 64];
+    const int row = blockIdx.x;  // token * hq_l + head
     const int tok = row / hq_l, head = row % hq_l;
     int np = n_parts;
     if (mode == 1) np = (seq_lens[tok] + chunk - 1) / chunk;
+    np = min(np, kCombineMaxParts);
     const size_t part_rows = static_cast<size_t>(n_rows) * hq_l;
-    float m_star = -INFINITY;
-    for (int c = 0; c < np; ++c) m_star = fmaxf(m_star, ml_part[(c * part_rows + row) * 2]);
-    float l_star = 0.f;
-    for (int c = 0; c < np; ++c) {
+    const int tid = threadIdx.x;
+    float m_loc = -INFINITY;
+    for (int c = tid; c < np; c += kCombineThreads) {
         const float m_c = ml_part[(c * part_rows + row) * 2];
-        const float w = (m_c == -INFINITY) ? 0.f : exp2f(m_c - m_star);
-        l_star += ml_part[(c * part_rows + row) * 2 + 1] * w;
+        w_s[c] = m_c;
+        l_s[c] = ml_part[(c * part_rows + row) * 2 + 1];
+        m_loc = fmaxf(m_loc, m_c);
     }
+    m_loc = wave_max(m_loc);
+    if ((tid & 63) == 0) red_s[tid >> 6] = m_loc;
+    __syncthreads();
+    float m_star = red_s[0];
+#pragma unroll
+    for (int w = 1; w < kCombineThreads / 64; ++w) m_star = fmaxf(m_star, red_s[w]);
+    for (int c = tid; c < np; c += kCombineThreads) {
+        const float m_c = w_s[c];  // each slot is read and rewritten by the same thread
+        w_s[c] = (m_c == -INFINITY) ? 0.f : exp2f(m_c - m_star);
+    }
+    __syncthreads();
+    float l_star = 0.f;  // every thread sums in part order: same value everywhere, no atomics
+    for (int c = 0; c < np; ++c) l_star = fmaf(l_s[c], w_s[c], l_star);
     const float inv = l_star > 0.f ? 1.f / l_star : 0.f;
-    for (int d = threadIdx.x; d < D; d += blockDim.x) {
+    for (int d = tid; d < D; d += kCombineThreads) {
         float acc = 0.f;
-        for (int c = 0; c < np; ++c) {
-            const float m_c = ml_part[(c * part_rows + row) * 2];
-            const float w = (m_c == -INFINITY) ? 0.f : exp2f(m_c - m_star);
-            acc += o_part[(c * part_rows + row) * D + d] * w;
-        }
+        const float* src = o_part + static_cast<size_t>(row) * D + d;
+#pragma unroll 4
+        for (int c = 0; c < np; ++c) acc = fmaf(src[c * part_rows * D], w_s[c], acc);
         store_elem(out + static_cast<size_t>(tok) * out_stride + static_cast<size_t>(head) * D + d, acc * inv);
     }
 }

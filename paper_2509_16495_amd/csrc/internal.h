@@ -10,6 +10,7 @@ namespace shiftattn {
 constexpr int kBlockSize = 16;         // tokens per KV-cache block
 constexpr int kDecodeChunk = 512;      // context tokens per decode workgroup
 constexpr int kPrefillKvTile = 64;     // keys per prefill inner-loop step
+constexpr int kMaxParts = 1024;        // most partial results the merge kernel takes per output row
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte vector
 
