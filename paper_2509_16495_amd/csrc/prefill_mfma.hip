@@ -2,27 +2,42 @@
 // attention line, prefill rows; chunked prefill continues a cached context).  bf16 tensors, fp32
 // accumulation, head_dim 128.
 //
-// Tiling.  A workgroup of four wavefronts owns a tile of 128*NQB "columns"; a column is one
-// (new token, query head) pair.  The query heads that share a KV head are stacked next to each
-// other in the column index (GS heads per token), so one K/V tile in LDS serves the whole GQA group
-// and the causal diagonal of a tile spans only 128*NQB/GS tokens.  Each wavefront owns NQB blocks
-// of 32 columns and walks the keys in tiles of 64 tokens (four cache blocks):
+// Tiling.  A workgroup owns a tile of 128 "columns"; a column is one (new token, query head) pair.
+// The query heads that share a KV head are stacked next to each other in the column index (GS heads
+// per token), so one K/V tile serves the whole GQA group and the causal diagonal of a tile spans
+// only 128/GS tokens.  The workgroup has eight wavefronts in two groups of four: a wavefront owns 32
+// columns, and the two groups split the key tiles (64 keys = four cache blocks each) of the column
+// tile between them - group 0 takes the even tiles, group 1 the odd ones - and merge their
+// partial results through LDS at the end.  That puts two wavefronts of the same workgroup on every
+// SIMD (the matrix pipe and the vector ALUs only overlap across wavefronts: a lone wavefront hides
+// about six vector instructions under one MFMA, measured) while the tile stays small enough that a
+// 4 x 4096-token batch still yields one equal-work workgroup per compute unit.
 //
-//   S^T[key][col]  = K[key][:] . Q^T[:][col]          32x32x16 bf16 MFMA, A = K rows from LDS,
-//                                                      B = Q^T held in registers for the whole tile
-//   online softmax down each column: a lane holds 32 keys of one column in its accumulator
-//   registers, the other 32 sit in lane+32, so the column max costs one cross-lane exchange
-//   O^T[d][col]   += V^T[d][key] . P^T[key][col]       A = V^T rows from LDS, B = P^T taken straight
-//                                                      from the softmax registers
+// Math per key tile, transposed so that P never leaves registers:
+//   S^T[key][col]  = K[key][:] . Q^T[:][col]     32x32x16 bf16 MFMA, A = K rows from LDS,
+//                                                 B = Q^T held in registers for the whole tile
+//   softmax down each column: a lane holds 32 keys of one column, the other 32 sit in lane+32, so
+//   the column max costs one v_permlane32_swap
+//   O^T[d][col]   += V^T[d][key] . P^T[key][col]  A = V^T rows from LDS, B = P^T straight from the
+//                                                 softmax registers
+// K rows are assigned to MFMA rows with bits 2 and 3 of the row index swapped; with that
+// assignment the keys a lane holds are runs of eight consecutive tokens, matching one 16-byte piece
+// of a dimension-major V row in the cache.
 //
-// Computing the transposed products keeps P in registers: the accumulator layout of S^T (a lane
-// owns one column and several keys) is, after packing to bf16, already the B-operand layout of
-// the second product.  K rows are assigned to MFMA rows with bits 2 and 3 of the row index
-// swapped; with that assignment the keys a lane holds are runs of eight consecutive tokens,
-// matching one 16-byte piece of a dimension-major V row in the cache.
+// Pipeline.  In iteration i a wavefront issues, interleaved in one instruction stream,
+//   A(i+1): S^T of its next tile (16 MFMAs), B(i): softmax of the current tile (vector ALU),
+//   C(i-1): O^T += V^T P^T of the previous tile (16 MFMAs),
+// one MFMA, the LDS read of the operand two MFMAs ahead and a few softmax instructions at a time.
+// Rescaling of O is lazy: a column's reference maximum only moves when the tile maximum exceeds it
+// by more than 2^8 (in exp2 units), so `O *= alpha` is a rare wavefront-uniform branch; P then ranges
+// up to 2^8, which bf16 and the fp32 sums hold without loss.
 //
-// K and V^T tiles are double-buffered in LDS: the global loads of tile i+1 are issued before the
-// math of tile i and written to the other buffer afterwards (one barrier per tile).
+// Memory.  K and V^T tiles go from the cache to LDS with direct-to-LDS loads (no registers, no
+// LDS store instructions), issued one iteration ahead of their use; a wavefront loads "its" cache
+// block of the tile with eight 1-KiB loads that are contiguous in HBM.  LDS is not padded; bank
+// conflicts are avoided by XOR-swizzling 16-byte pieces, applied on the global-address side of
+// the load.  Stage `par` of a group is filled during an iteration of parity `par` and read during
+// the next one; one barrier per iteration.
 //
 // Scheduling.  Tiles of a sequence are processed in pairs (heaviest with lightest) by one
 // workgroup so every workgroup of a causal prefill does the same amount of work; the long
@@ -32,36 +47,50 @@
 
 #include <stdlib.h>
 
+#include <utility>
+
 namespace shiftattn {
 
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kD = 128;
-constexpr int kThreads = 256;
-constexpr int kKvTile = kPrefillKvTile;           // 64 keys
-constexpr int kKPitch = kD * 2 + 16;              // bytes per K row in LDS (padded)
-constexpr int kVPitch = kKvTile * 2 + 16;         // bytes per V^T row in LDS (padded)
-constexpr int kKBytes = kKvTile * kKPitch;        // 17408
-constexpr int kVBytes = kD * kVPitch;             // 18432
-constexpr int kStageBytes = kKBytes + kVBytes;    // 35840
-constexpr int kLdsBytes = 2 * kStageBytes;        // 71680
+constexpr int kThreads = 512;
+constexpr int kKvTile = kPrefillKvTile;        // 64 keys
+constexpr int kKBytes = kKvTile * kD * 2;      // 16384: K tile, 64 rows of 256 B
+constexpr int kVBytes = kD * kKvTile * 2;      // 16384: V^T tile, 4 blocks of [128 rows][32 B]
+constexpr int kStageBytes = kKBytes + kVBytes; // 32768
+constexpr int kGroupBytes = 2 * kStageBytes;   // two stages per wavefront group
+constexpr int kLdsBytes = 2 * kGroupBytes;     // 131072
+constexpr int kBlockBytes = kBlockSize * kD * 2;  // 4096: K (or V^T) of one cache block and head
 
 __device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+template <int kV>
+struct IC {
+    static constexpr int value = kV;
+};
+
+#define SHIFTATTN_INLINE __attribute__((always_inline))
+
+// s_waitcnt vmcnt(0) with the other counters left alone (gfx9 encoding)
+__device__ inline void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 struct PrefillParams {
-    const uint16_t* q;
-    const uint16_t* cache;
-    const int32_t* block_table;
-    const int32_t* cu_seqlens_q;
-    const int32_t* seq_lens;
-    uint16_t* out;
-    float* o_part;
-    float* ml_part;
+    const uint16_t* __restrict__ q;
+    const uint16_t* __restrict__ cache;
+    const int32_t* __restrict__ block_table;
+    const int32_t* __restrict__ cu_seqlens_q;
+    const int32_t* __restrict__ seq_lens;
+    uint16_t* __restrict__ out;
+    float* __restrict__ o_part;
+    float* __restrict__ ml_part;
     int64_t q_stride, out_stride;
     int num_seqs, total_q, hq_l, hkv_l, G;
     int gs_log2;      // log2 of heads stacked per token in the column index
@@ -71,12 +100,13 @@ struct PrefillParams {
     float c;          // softmax_scale * log2(e)
 };
 
-template <int NQB>
-__global__ __launch_bounds__(kThreads, NQB == 1 ? 2 : 1) void prefill_kernel(PrefillParams p) {
+__global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    constexpr int kCols = 128 * NQB;  // columns per workgroup tile
+    constexpr int kCols = 128;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int grp = wave >> 2;  // key-tile parity this wavefront works on
+    const int wg = wave & 3;    // column block of the wavefront; also the cache block of a tile it loads
     const int l32 = lane & 31, half = lane >> 5;
 
     // ---- which (pair rank, key split, sequence, head slot) is this workgroup -----------------------
@@ -99,219 +129,387 @@ __global__ __launch_bounds__(kThreads, NQB == 1 ? 2 : 1) void prefill_kernel(Pre
     const int n_pass = (hi_tile == rank) ? 1 : 2;
     const int gs_mask = (1 << p.gs_log2) - 1;
     const int g = (hs << p.gs_log2) / p.G;  // KV head of every column of this workgroup
-    const int32_t* table = p.block_table + static_cast<size_t>(s) * p.max_blocks;
+    const int32_t* __restrict__ table = p.block_table + static_cast<size_t>(s) * p.max_blocks;
     const int last_block = (ctx - 1) / kBlockSize;
 
-    // ---- global -> LDS mapping of this thread (one 16-byte piece of K and of V^T per cache block) --
-    const int k_row = tid >> 4, k_piece = tid & 15;   // K block: 16 rows x 16 pieces
-    const int v_row = tid >> 1, v_piece = tid & 1;    // V^T block: 128 rows x 2 pieces
-    // ---- LDS -> MFMA operand mapping ------------------------------------------------------------------
-    // K row feeding MFMA row l32: swap bits 2 and 3
+    // ---- LDS addressing ---------------------------------------------------------------------------------
+    unsigned char* gbase = lds + grp * kGroupBytes;  // this group's two stages
+    // K operand of MFMA row l32 is K row tau (bits 2 and 3 swapped); piece c of row r sits at c ^ (r & 15)
     const int tau = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
-    const int k_rd = tau * kKPitch + half * 16;       // + sub*32*kKPitch + ks*32
-    const int v_rd = l32 * kVPitch + half * 16;       // + mt*32*kVPitch + ks2*32
+    int k_rd[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) k_rd[ks] = tau * 256 + (((2 * ks + half) ^ (tau & 15)) << 4);
+    // V^T operand: block-major [4][128 rows][32 B]; the two 16-byte halves of a row are swapped in
+    // every other run of eight rows
+    const int v_rd = kKBytes + l32 * 32 + ((half ^ ((l32 >> 3) & 1)) << 4);
+    // direct-to-LDS loads: this wavefront fills cache block `wg` of a tile, 1 KiB per instruction
+    // (LDS side contiguous in lane order; the swizzle is applied to the global address)
+    int k_ld[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = 4 * j + (lane >> 4);
+        k_ld[j] = row * 256 + (((lane & 15) ^ row) << 4);
+    }
+    const int v_ld = kBlockBytes + (lane >> 1) * 32 + (((lane & 1) ^ ((lane >> 4) & 1)) << 4);
+    const size_t blk_bytes = static_cast<size_t>(p.hkv_l) * 2 * kBlockBytes;
+    const unsigned char* cache_g = reinterpret_cast<const unsigned char*>(p.cache) + static_cast<size_t>(g) * 2 * kBlockBytes;
 
-    int buf = 0;
+    typedef __attribute__((address_space(3))) void* lds_ptr;
+    typedef const __attribute__((address_space(1))) void* glb_ptr;
+
+    bf16x2 ones;
+    ones[0] = static_cast<__bf16>(1.0f);
+    ones[1] = static_cast<__bf16>(1.0f);
+    const float thr = 8.0f / p.c;
+
     for (int pass = 0; pass < n_pass; ++pass) {
         const int tile = pass == 0 ? hi_tile : rank;
         const int tok0 = tile * tile_tokens;
-        // ---- this lane's columns ------------------------------------------------------------------------
-        int pos_col[NQB];     // position of the column's token in its sequence, -1 for padding columns
-        int row_col[NQB];     // global row index (token) of the column
-        int head_col[NQB];
-        bf16x8 qf[NQB][8];
-#pragma unroll
-        for (int nb = 0; nb < NQB; ++nb) {
-            const int cw = (wave * NQB + nb) * 32 + l32;
-            const int tok = tok0 + (cw >> p.gs_log2);
-            const bool valid = tok < q_len;
-            head_col[nb] = (hs << p.gs_log2) + (cw & gs_mask);
-            row_col[nb] = q_begin + tok;
-            pos_col[nb] = valid ? ctx - q_len + tok : -1;
-            const uint16_t* qp = p.q + static_cast<size_t>(row_col[nb]) * p.q_stride + head_col[nb] * kD + half * 8;
+        const int cw = wg * 32 + l32;
+        const int tok = tok0 + (cw >> p.gs_log2);
+        const bool valid = tok < q_len;
+        const int head_col = (hs << p.gs_log2) + (cw & gs_mask);
+        const int row_col = q_begin + tok;
+        const int pos_col = valid ? ctx - q_len + tok : -1;
+        bf16x8 qf[8];
+        {
+            const uint16_t* qp = p.q + static_cast<size_t>(row_col) * p.q_stride + head_col * kD + half * 8;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
                 u32x4 v = {0u, 0u, 0u, 0u};
                 if (valid) v = *reinterpret_cast<const u32x4*>(qp + ks * 16);
-                qf[nb][ks] = as_bf16x8(v);
+                qf[ks] = as_bf16x8(v);
             }
         }
-        // wavefront-uniform bounds of the wavefront's columns
-        const int w_tok_first = tok0 + ((wave * NQB * 32) >> p.gs_log2);
-        const int w_tok_last = min(tok0 + ((wave * NQB * 32 + NQB * 32 - 1) >> p.gs_log2), q_len - 1);
-        const bool w_active = w_tok_first < q_len;
-        const int w_pos_min = ctx - q_len + w_tok_first;
-        const int w_pos_max = ctx - q_len + w_tok_last;
+        const int w_tok_first = tok0 + ((wg * 32) >> p.gs_log2);
+        const int w_pos_min = w_tok_first < q_len ? ctx - q_len + w_tok_first : -1;
 
-        // ---- key range of this (tile, split) ----------------------------------------------------------
+        // ---- key tiles of this (column tile, split), dealt alternately to the two groups ------------------
         const int tile_pos_max = ctx - q_len + min(tok0 + tile_tokens, q_len) - 1;
         const int kv_tiles = tile_pos_max / kKvTile + 1;
         const int per_split = (kv_tiles + p.n_splits - 1) / p.n_splits;
         const int kt_begin = split * per_split;
         const int kt_end = min(kv_tiles, kt_begin + per_split);
+        const int n_all = max(kt_end - kt_begin, 0);
+        const int n = (n_all + 1 - grp) >> 1;        // tiles of this group: kt(j) = kt_begin + grp + 2 j
+        const int n_other = (n_all + grp) >> 1;
+        // The tile that reaches past the context (if any) holds unwritten V slots; its owner clears them
+        // in LDS before use, which costs one extra barrier that the other group mirrors.
+        const bool pass_ragged = n_all > 0 && kt_end * kKvTile > ctx;
+        const bool own_ragged = pass_ragged && (((n_all - 1) & 1) == grp);
 
-        f32x16 oacc[NQB][4];
-        float m_run[NQB], l_run[NQB];
+        f32x16 oacc[4];
 #pragma unroll
-        for (int nb = 0; nb < NQB; ++nb) {
-            m_run[nb] = -INFINITY;
-            l_run[nb] = 0.f;
+        for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[nb][mt][r] = 0.f;
-        }
+            for (int r = 0; r < 16; ++r) oacc[mt][r] = 0.f;
+        f32x16 sbuf[2][2];
+        uint32_t pw[2][4][4];
+        float m_used = -INFINITY, l_run = 0.f, alpha_pending = 1.f;
 
-        u32x4 kreg[4], vreg[4];
-        auto fetch = [&](int kt) {
-#pragma unroll
-            for (int bi = 0; bi < 4; ++bi) {
-                const int64_t blk = table[min(kt * 4 + bi, last_block)];
-                kreg[bi] = *reinterpret_cast<const u32x4*>(p.cache + cache_part_offset(blk, g, 0, p.hkv_l, kD) + tid * 8);
-                vreg[bi] = *reinterpret_cast<const u32x4*>(p.cache + cache_part_offset(blk, g, 1, p.hkv_l, kD) + tid * 8);
-            }
+        auto kt_of = [&](int j) SHIFTATTN_INLINE { return kt_begin + grp + 2 * j; };
+        // cache block `wg` of key tile kt (block ids are fetched before any direct-to-LDS load of the
+        // iteration is issued: loads return in order, so waiting for an id behind them would wait for them)
+        auto block_base = [&](int kt) SHIFTATTN_INLINE -> const unsigned char* {
+            const int64_t blk = __builtin_amdgcn_readfirstlane(table[min(kt * 4 + wg, last_block)]);
+            return cache_g + blk * blk_bytes;
         };
-        auto stash = [&](int kt, unsigned char* stage) {
-            const bool ragged = (kt + 1) * kKvTile > ctx;  // tile reaches past the context: uniform
+        auto load_k = [&](const unsigned char* src, int stage) SHIFTATTN_INLINE {
+            unsigned char* dst = gbase + stage * kStageBytes + wg * kBlockBytes;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                __builtin_amdgcn_global_load_lds((glb_ptr)(src + k_ld[j]), (lds_ptr)(dst + j * 1024), 16, 0, 0);
+        };
+        auto load_v = [&](const unsigned char* src, int stage) SHIFTATTN_INLINE {
+            unsigned char* dst = gbase + stage * kStageBytes + kKBytes + wg * kBlockBytes;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                __builtin_amdgcn_global_load_lds((glb_ptr)(src + v_ld + j * 1024), (lds_ptr)(dst + j * 1024), 16, 0, 0);
+        };
+        // zero the V^T entries of keys at or past the context in the given stage (tile kt)
+        auto clear_ragged_v = [&](int kt, int stage) SHIFTATTN_INLINE {
+            const int t4 = tid & 255;  // thread within the group
+            const int d = t4 >> 1, h = t4 & 1;
 #pragma unroll
             for (int bi = 0; bi < 4; ++bi) {
-                u32x4 v = vreg[bi];
-                if (ragged) {
-                    // keys at or past ctx were never written; clear their V so that 0 * x stays 0
-                    const int n_valid = ctx - (kt * kKvTile + bi * 16 + v_piece * 8);
+                const int n_valid = ctx - (kt * kKvTile + bi * 16 + h * 8);
+                if (n_valid < 8) {
+                    u32x4* ptr = reinterpret_cast<u32x4*>(gbase + stage * kStageBytes + kKBytes + bi * kBlockBytes + d * 32 +
+                                                          ((h ^ ((d >> 3) & 1)) << 4));
+                    u32x4 v = *ptr;
 #pragma unroll
                     for (int w = 0; w < 4; ++w)
                         v[w] &= n_valid > 2 * w + 1 ? 0xFFFFFFFFu : (n_valid > 2 * w ? 0x0000FFFFu : 0u);
+                    *ptr = v;
                 }
-                *reinterpret_cast<u32x4*>(stage + (bi * 16 + k_row) * kKPitch + k_piece * 16) = kreg[bi];
-                *reinterpret_cast<u32x4*>(stage + kKBytes + v_row * kVPitch + bi * 32 + v_piece * 16) = v;
             }
         };
+        auto apply_pending = [&]() SHIFTATTN_INLINE {
+            if (__builtin_amdgcn_ballot_w64(alpha_pending != 1.f)) {
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha_pending;
+            }
+            alpha_pending = 1.f;
+        };
 
-        if (kt_begin < kt_end) fetch(kt_begin);
-        for (int kt = kt_begin; kt < kt_end; ++kt) {
-            unsigned char* stage = lds + buf * kStageBytes;
-            stash(kt, stage);
-            __syncthreads();
-            if (kt + 1 < kt_end) fetch(kt + 1);
-            buf ^= 1;
+        // One iteration on the group's tile j.  PAR = parity of j: selects register sets and LDS stages
+        // at compile time (stage PAR is filled in this iteration, stage 1-PAR is read).
+        auto body = [&](auto par_c, auto has_a_c, auto has_c_c, int j) SHIFTATTN_INLINE {
+            constexpr int PAR = decltype(par_c)::value;
+            constexpr bool HAS_A = decltype(has_a_c)::value != 0;
+            constexpr bool HAS_C = decltype(has_c_c)::value != 0;
+            constexpr int RD = 1 - PAR;
+            f32x16(&s_cur)[2] = sbuf[PAR];
+            f32x16(&s_nxt)[2] = sbuf[1 - PAR];
+            uint32_t(&p_cur)[4][4] = pw[PAR];
+            uint32_t(&p_prv)[4][4] = pw[1 - PAR];
+            const int kt = kt_of(j);
             const int key0 = kt * kKvTile;
-            if (!w_active || key0 > w_pos_max) continue;  // nothing visible for this wavefront (uniform)
 
-            // ---- S^T = K Q^T ------------------------------------------------------------------------------
-            f32x16 sacc[NQB][2];
-#pragma unroll
-            for (int nb = 0; nb < NQB; ++nb)
-#pragma unroll
-                for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sacc[nb][sub][r] = 0.f;
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(stage + k_rd + sub * 32 * kKPitch + ks * 32));
-#pragma unroll
-                    for (int nb = 0; nb < NQB; ++nb)
-                        sacc[nb][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][ks], sacc[nb][sub], 0, 0, 0);
-                }
-            // accumulator register r of sub-tile sub holds key  key0 + 32*sub + 16*(r/8) + 8*half + r%8
-            const bool need_mask = key0 + kKvTile - 1 > w_pos_min;
-            bf16x8 pf[NQB][4];
-#pragma unroll
-            for (int nb = 0; nb < NQB; ++nb) {
-                if (need_mask) {
-#pragma unroll
-                    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int key = key0 + 32 * sub + 16 * (r >> 3) + 8 * half + (r & 7);
-                            if (key > pos_col[nb]) sacc[nb][sub][r] = -INFINITY;
-                        }
-                }
-                float mx = -INFINITY;
-#pragma unroll
-                for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[nb][sub][r]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run[nb], mx);
-                const float m_safe = m_new == -INFINITY ? 0.f : m_new;  // column with no visible key so far
-                const float alpha = __builtin_amdgcn_exp2f((m_run[nb] - m_safe) * p.c);
-                const float mc = m_safe * p.c;
-                float psum = 0.f;
+            __syncthreads();
+            // fill stage PAR for the next iteration: K of tile j+2, V^T of tile j
+            {
+                const bool more_k = j + 2 < n;
+                const unsigned char* src_k = block_base(more_k ? kt + 4 : kt);
+                const unsigned char* src_v = block_base(kt);
+                if (more_k) load_k(src_k, PAR);
+                load_v(src_v, PAR);
+            }
+            if (HAS_C) apply_pending();
+            if (key0 + kKvTile - 1 > w_pos_min) {  // tile crosses the diagonal of this wavefront: uniform
 #pragma unroll
                 for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const float e = __builtin_amdgcn_exp2f(fmaf(sacc[nb][sub][r], p.c, -mc));
-                        psum += e;
-                        pf[nb][sub * 2 + (r >> 3)][r & 7] = static_cast<__bf16>(e);
+                        const int key = key0 + 32 * sub + 16 * (r >> 3) + 8 * half + (r & 7);
+                        if (key > pos_col) s_cur[sub][r] = -INFINITY;
                     }
-                l_run[nb] = l_run[nb] * alpha + psum;
-                m_run[nb] = m_new;
-                if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {  // skip the rescale when no max moved
+            }
+
+            // ---- interleaved block ------------------------------------------------------------------
+            constexpr int NOPS = (HAS_A ? 16 : 0) + (HAS_C ? 16 : 0);
+            float mx = -INFINITY, mc = 0.f, alpha = 1.f, psum = 0.f;
+            auto chunk = [&](auto cc) SHIFTATTN_INLINE {
+                constexpr int c = decltype(cc)::value;
+                if constexpr (c < 8) {
+                    constexpr int sub = (4 * c) / 16, r = (4 * c) % 16;
+                    mx = fmaxf(fmaxf(mx, s_cur[sub][r]), s_cur[sub][r + 1]);
+                    mx = fmaxf(fmaxf(mx, s_cur[sub][r + 2]), s_cur[sub][r + 3]);
+                } else if constexpr (c == 8) {
+                    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                    mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                    const bool grow = mx > m_used + thr;
+                    const float m_new = grow ? mx : m_used;
+                    alpha = grow ? __builtin_amdgcn_exp2f((m_used - m_new) * p.c) : 1.f;
+                    m_used = m_new;
+                    mc = (m_new == -INFINITY ? 0.f : m_new) * p.c;
+                    alpha_pending = alpha;
+                    // the empty asm statements pin each result to its slot: without them the optimiser
+                    // sinks the softmax below the MFMA sequence, next to its first use
+                    asm volatile("" : "+v"(mc), "+v"(alpha), "+v"(m_used));
+                } else if constexpr (c < 25) {
+                    constexpr int v = 2 * (c - 9), sub = v / 16, r = v % 16;
+                    const float e0 = __builtin_amdgcn_exp2f(fmaf(s_cur[sub][r], p.c, -mc));
+                    const float e1 = __builtin_amdgcn_exp2f(fmaf(s_cur[sub][r + 1], p.c, -mc));
+                    bf16x2 t;
+                    t[0] = static_cast<__bf16>(e0);
+                    t[1] = static_cast<__bf16>(e1);
+                    psum = __builtin_amdgcn_fdot2_f32_bf16(t, ones, psum, false);
+                    uint32_t w = __builtin_bit_cast(uint32_t, t);
+                    asm volatile("" : "+v"(w), "+v"(psum));
+                    p_cur[sub * 2 + (r >> 3)][(r & 7) >> 1] = w;
+                } else {
+                    l_run = l_run * alpha + psum;
+                    asm volatile("" : "+v"(l_run));
+                }
+            };
+            auto op_read = [&](auto tc) SHIFTATTN_INLINE -> u32x4 {
+                constexpr int t = decltype(tc)::value;
+                constexpr bool is_a = HAS_A && (!HAS_C || (t % 2 == 0));
+                constexpr int o = (HAS_A && HAS_C) ? t / 2 : t;
+                if constexpr (is_a)
+                    return *reinterpret_cast<const u32x4*>(gbase + RD * kStageBytes + (o / 8) * 8192 + k_rd[o % 8]);
+                else
+                    return *reinterpret_cast<const u32x4*>(gbase + RD * kStageBytes + v_rd + (o / 4) * kBlockBytes + (o % 4) * 1024);
+            };
+            auto op_mfma = [&](auto tc, u32x4 a) SHIFTATTN_INLINE {
+                constexpr int t = decltype(tc)::value;
+                constexpr bool is_a = HAS_A && (!HAS_C || (t % 2 == 0));
+                constexpr int o = (HAS_A && HAS_C) ? t / 2 : t;
+                if constexpr (is_a) {
+                    constexpr int sub = o / 8, ks = o % 8;
+                    if constexpr (ks == 0) {
+                        f32x16 z;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) z[r] = 0.f;
+                        s_nxt[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), qf[ks], z, 0, 0, 0);
+                    } else {
+                        s_nxt[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), qf[ks], s_nxt[sub], 0, 0, 0);
+                    }
+                } else {
+                    constexpr int ks2 = o / 4, mt = o % 4;
+                    u32x4 pv = {p_prv[ks2][0], p_prv[ks2][1], p_prv[ks2][2], p_prv[ks2][3]};
+                    oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(pv), oacc[mt], 0, 0, 0);
+                }
+            };
+
+            if constexpr (NOPS == 0) {
+                [&]<int... C>(std::integer_sequence<int, C...>) SHIFTATTN_INLINE { (chunk(IC<C>{}), ...); }
+                (std::make_integer_sequence<int, 26>{});
+            } else {
+                u32x4 opnd[NOPS];
+                opnd[0] = op_read(IC<0>{});
+                opnd[1] = op_read(IC<1>{});
+                [&]<int... T>(std::integer_sequence<int, T...>) SHIFTATTN_INLINE {
+                    (([&]() SHIFTATTN_INLINE {
+                         if constexpr (T + 2 < NOPS) opnd[T + 2] = op_read(IC<T + 2>{});
+                         op_mfma(IC<T>{}, opnd[T]);
+                         if constexpr (NOPS == 32) {
+                             if constexpr (T < 26) chunk(IC<T>{});
+                         } else {
+                             if constexpr (2 * T < 26) chunk(IC<2 * T>{});
+                             if constexpr (2 * T + 1 < 26) chunk(IC<2 * T + 1>{});
+                         }
+                         __builtin_amdgcn_sched_barrier(0);
+                     }()),
+                     ...);
+                }
+                (std::make_integer_sequence<int, NOPS>{});
+            }
+            wait_vm0();  // this wavefront's loads have landed before it reaches the next barrier
+        };
+
+        int barriers = 0;  // barriers this group executes in the pass; both groups must end up equal
+        if (n > 0) {
+            // prologue: K of the first two tiles, S^T of the first
+            {
+                const unsigned char* src0 = block_base(kt_of(0));
+                const unsigned char* src1 = block_base(kt_of(n > 1 ? 1 : 0));
+                load_k(src0, 0);
+                if (n > 1) load_k(src1, 1);
+            }
+            wait_vm0();
+            __syncthreads();
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sbuf[0][sub][r] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    const u32x4 a = *reinterpret_cast<const u32x4*>(gbase + sub * 8192 + k_rd[ks]);
+                    sbuf[0][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), qf[ks], sbuf[0][sub], 0, 0, 0);
+                }
+            }
+            if (n == 1) {
+                body(IC<0>{}, IC<0>{}, IC<0>{}, 0);
+            } else {
+                body(IC<0>{}, IC<1>{}, IC<0>{}, 0);
+                int j = 1;  // stays odd: the steady-state loop takes two tiles per trip so that the
+                            // register sets of even and odd tiles are fixed at compile time
+                for (; j + 2 < n; j += 2) {
+                    body(IC<1>{}, IC<1>{}, IC<1>{}, j);
+                    body(IC<0>{}, IC<1>{}, IC<1>{}, j + 1);
+                }
+                if (j + 1 < n) {
+                    body(IC<1>{}, IC<1>{}, IC<1>{}, j);
+                    body(IC<0>{}, IC<0>{}, IC<1>{}, j + 1);
+                } else {
+                    body(IC<1>{}, IC<0>{}, IC<1>{}, j);
+                }
+            }
+            // epilogue: C of the last tile
+            __syncthreads();
+            const int lp = (n - 1) & 1;
+            if (own_ragged) {
+                clear_ragged_v(kt_of(n - 1), lp);
+                __syncthreads();
+            }
+            apply_pending();
+            auto last_c = [&](auto par_c) SHIFTATTN_INLINE {
+                constexpr int PAR = decltype(par_c)::value;
+#pragma unroll
+                for (int ks2 = 0; ks2 < 4; ++ks2)
+#pragma unroll
+                    for (int mt = 0; mt < 4; ++mt) {
+                        const u32x4 a = *reinterpret_cast<const u32x4*>(gbase + PAR * kStageBytes + v_rd + ks2 * kBlockBytes + mt * 1024);
+                        u32x4 pv = {pw[PAR][ks2][0], pw[PAR][ks2][1], pw[PAR][ks2][2], pw[PAR][ks2][3]};
+                        oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(pv), oacc[mt], 0, 0, 0);
+                    }
+            };
+            if (lp) last_c(IC<1>{});
+            else last_c(IC<0>{});
+            barriers = n + 2 + (own_ragged ? 1 : 0);
+        }
+        // even out the barrier count of the two groups (their LDS regions are disjoint, only the count matters)
+        const int other_barriers = n_other > 0 ? n_other + 2 + ((pass_ragged && !own_ragged) ? 1 : 0) : 0;
+        for (int b = barriers; b < other_barriers; ++b) __syncthreads();
+
+        // ---- merge the two groups: group 1 parks (m, l, O) in LDS, group 0 folds it in --------------------
+        float l_tot = l_run + __shfl_xor(l_run, 32);
+        __syncthreads();  // every wavefront is done with the tile stages
+        float* x_o = reinterpret_cast<float*>(lds);                   // [64 values][256 lanes of a group]
+        float* x_ml = x_o + 64 * 256;                                  // [2][256]
+        const int t4 = tid & 255;
+        if (grp == 1) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) x_o[(mt * 16 + r) * 256 + t4] = oacc[mt][r];
+            x_ml[t4] = m_used;
+            x_ml[256 + t4] = l_tot;
+        }
+        __syncthreads();
+        if (grp == 0) {
+            const float m1 = x_ml[t4], l1 = x_ml[256 + t4];
+            const float m_star = fmaxf(m_used, m1);
+            const float w0 = m_used == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_used - m_star) * p.c);
+            const float w1 = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m1 - m_star) * p.c);
+            l_tot = l_tot * w0 + l1 * w1;
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[mt][r] = oacc[mt][r] * w0 + x_o[(mt * 16 + r) * 256 + t4] * w1;
+            // ---- output: accumulator register r of row tile mt is head-dim 32*mt + 8*(r/4) + 4*half + r%4 ----
+            if (pos_col >= 0) {
+                if (p.n_splits == 1) {
+                    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+                    uint16_t* op = p.out + static_cast<size_t>(row_col) * p.out_stride + head_col * kD + 4 * half;
 #pragma unroll
                     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) oacc[nb][mt][r] *= alpha;
-                }
-            }
-            // ---- O^T += V^T P^T ---------------------------------------------------------------------------
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            bf16x4 v;
 #pragma unroll
-            for (int ks2 = 0; ks2 < 4; ++ks2)
+                            for (int x = 0; x < 4; ++x) v[x] = static_cast<__bf16>(oacc[mt][r4 * 4 + x] * inv);
+                            *reinterpret_cast<u32x2*>(op + 32 * mt + 8 * r4) = __builtin_bit_cast(u32x2, v);
+                        }
+                } else {
+                    const size_t prow = (static_cast<size_t>(split) * p.total_q + row_col) * p.hq_l + head_col;
+                    float* op = p.o_part + prow * kD + 4 * half;
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt) {
-                    const bf16x8 a = as_bf16x8(
-                        *reinterpret_cast<const u32x4*>(stage + kKBytes + v_rd + mt * 32 * kVPitch + ks2 * 32));
+                    for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-                    for (int nb = 0; nb < NQB; ++nb)
-                        oacc[nb][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nb][ks2], oacc[nb][mt], 0, 0, 0);
-                }
-        }
-
-        // ---- epilogue: accumulator register r of row tile mt is head-dim  32*mt + 8*(r/4) + 4*half + r%4 ----
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            f32x4 v;
 #pragma unroll
-        for (int nb = 0; nb < NQB; ++nb) {
-            const float l_tot = l_run[nb] + __shfl_xor(l_run[nb], 32);
-            if (pos_col[nb] < 0) continue;
-            if (p.n_splits == 1) {
-                const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-                uint16_t* op = p.out + static_cast<size_t>(row_col[nb]) * p.out_stride + head_col[nb] * kD + 4 * half;
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-                        bf16x4 v;
-#pragma unroll
-                        for (int x = 0; x < 4; ++x) v[x] = static_cast<__bf16>(oacc[nb][mt][r4 * 4 + x] * inv);
-                        *reinterpret_cast<u32x2*>(op + 32 * mt + 8 * r4) = __builtin_bit_cast(u32x2, v);
+                            for (int x = 0; x < 4; ++x) v[x] = oacc[mt][r4 * 4 + x];
+                            *reinterpret_cast<f32x4*>(op + 32 * mt + 8 * r4) = v;
+                        }
+                    if (half == 0) {
+                        p.ml_part[prow * 2] = m_star * p.c;  // -inf when this key range held no visible key
+                        p.ml_part[prow * 2 + 1] = l_tot;
                     }
-            } else {
-                const size_t prow = (static_cast<size_t>(split) * p.total_q + row_col[nb]) * p.hq_l + head_col[nb];
-                float* op = p.o_part + prow * kD + 4 * half;
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        f32x4 v;
-#pragma unroll
-                        for (int x = 0; x < 4; ++x) v[x] = oacc[nb][mt][r4 * 4 + x];
-                        *reinterpret_cast<f32x4*>(op + 32 * mt + 8 * r4) = v;
-                    }
-                if (half == 0) {
-                    p.ml_part[prow * 2] = m_run[nb] * p.c;  // -inf when this key range held no visible key
-                    p.ml_part[prow * 2 + 1] = l_tot;
                 }
             }
         }
-        __syncthreads();  // the next pass reuses both LDS buffers
+        __syncthreads();  // the next pass reuses LDS
     }
 }
 
 struct Plan {
-    int nqb, gs_log2, head_slots, tile_tokens, pair_ranks, n_splits;
+    int gs_log2, head_slots, tile_tokens, pair_ranks, n_splits;
 };
 
 int env_int(const char* name, int dflt) {
@@ -326,8 +524,7 @@ Plan make_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const 
     pl.gs_log2 = 0;
     if (pow2) while ((1 << pl.gs_log2) < G) ++pl.gs_log2;
     pl.head_slots = a.hq_l >> pl.gs_log2;
-    pl.nqb = env_int("SHIFTATTN_PREFILL_NQB", 1) == 2 ? 2 : 1;
-    pl.tile_tokens = (128 * pl.nqb) >> pl.gs_log2;
+    pl.tile_tokens = 128 >> pl.gs_log2;
     const int tiles = (max_q_len + pl.tile_tokens - 1) / pl.tile_tokens;
     pl.pair_ranks = (tiles + 1) / 2;
     // Split the keys when the tiles alone cannot fill the chip (long cached context, short chunk).
@@ -337,7 +534,7 @@ Plan make_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const 
     if (forced > 0) splits = forced;
     else if (wgs < 192) {
         const int by_fill = static_cast<int>((512 + wgs - 1) / wgs);
-        const int by_len = max_seq_len / (8 * kKvTile);  // at least 8 key tiles per range
+        const int by_len = max_seq_len / (16 * kKvTile);  // at least 16 key tiles per range
         splits = by_fill < by_len ? by_fill : by_len;
     }
     if (splits < 1) splits = 1;
@@ -386,26 +583,15 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
     p.c = a.scale * 1.4426950408889634f;
 
     const unsigned grid = static_cast<unsigned>(pl.pair_ranks) * pl.n_splits * num_seqs * pl.head_slots;
+    static bool attr_done = false;
     hipError_t e;
-    if (pl.nqb == 2) {
-        static bool attr_done2 = false;
-        if (!attr_done2) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<2>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-            if (e != hipSuccess) return e;
-            attr_done2 = true;
-        }
-        prefill_kernel<2><<<grid, kThreads, kLdsBytes, st>>>(p);
-    } else {
-        static bool attr_done1 = false;
-        if (!attr_done1) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<1>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-            if (e != hipSuccess) return e;
-            attr_done1 = true;
-        }
-        prefill_kernel<1><<<grid, kThreads, kLdsBytes, st>>>(p);
+    if (!attr_done) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_done = true;
     }
+    prefill_kernel<<<grid, kThreads, kLdsBytes, st>>>(p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (pl.n_splits > 1)
