@@ -208,12 +208,16 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
         float m_used = -INFINITY, l_run = 0.f, alpha_pending = 1.f;
 
         auto kt_of = [&](int j) SHIFTATTN_INLINE { return kt_begin + grp + 2 * j; };
-        // cache block `wg` of key tile kt (block ids are fetched before any direct-to-LDS load of the
-        // iteration is issued: loads return in order, so waiting for an id behind them would wait for them)
-        auto block_base = [&](int kt) SHIFTATTN_INLINE -> const unsigned char* {
-            const int64_t blk = __builtin_amdgcn_readfirstlane(table[min(kt * 4 + wg, last_block)]);
-            return cache_g + blk * blk_bytes;
+        // Cache block `wg` of the group's tile j.  Ids are fetched three tiles ahead and waited for a
+        // whole iteration later: loads return in order, so a wait right behind the direct-to-LDS loads
+        // (or right after the barrier) would stall for a full memory round trip every iteration.
+        auto fetch_id = [&](int j) SHIFTATTN_INLINE -> int {
+            return table[min((kt_begin + grp + 2 * min(j, max(n - 1, 0))) * 4 + wg, last_block)];
         };
+        auto block_base = [&](int id) SHIFTATTN_INLINE -> const unsigned char* {
+            return cache_g + static_cast<int64_t>(id) * blk_bytes;
+        };
+        int id0 = 0, id1 = 0, id2 = 0;  // ids of tiles j, j+1, j+2 at the top of iteration j (uniform)
         auto load_k = [&](const unsigned char* src, int stage) SHIFTATTN_INLINE {
             unsigned char* dst = gbase + stage * kStageBytes + wg * kBlockBytes;
 #pragma unroll
@@ -270,13 +274,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
 
             __syncthreads();
             // fill stage PAR for the next iteration: K of tile j+2, V^T of tile j
-            {
-                const bool more_k = j + 2 < n;
-                const unsigned char* src_k = block_base(more_k ? kt + 4 : kt);
-                const unsigned char* src_v = block_base(kt);
-                if (more_k) load_k(src_k, PAR);
-                load_v(src_v, PAR);
-            }
+            const int id3_v = fetch_id(j + 3);  // consumed at the bottom of this iteration
+            if (j + 2 < n) load_k(block_base(id2), PAR);
+            load_v(block_base(id0), PAR);
             if (HAS_C) apply_pending();
             if (key0 + kKvTile - 1 > w_pos_min) {  // tile crosses the diagonal of this wavefront: uniform
 #pragma unroll
@@ -379,16 +379,21 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
                 (std::make_integer_sequence<int, NOPS>{});
             }
             wait_vm0();  // this wavefront's loads have landed before it reaches the next barrier
+            id0 = id1;
+            id1 = id2;
+            id2 = __builtin_amdgcn_readfirstlane(id3_v);
         };
 
         int barriers = 0;  // barriers this group executes in the pass; both groups must end up equal
         if (n > 0) {
             // prologue: K of the first two tiles, S^T of the first
             {
-                const unsigned char* src0 = block_base(kt_of(0));
-                const unsigned char* src1 = block_base(kt_of(n > 1 ? 1 : 0));
-                load_k(src0, 0);
-                if (n > 1) load_k(src1, 1);
+                const int a0 = fetch_id(0), a1 = fetch_id(1), a2 = fetch_id(2);
+                id0 = __builtin_amdgcn_readfirstlane(a0);
+                id1 = __builtin_amdgcn_readfirstlane(a1);
+                id2 = __builtin_amdgcn_readfirstlane(a2);
+                load_k(block_base(id0), 0);
+                if (n > 1) load_k(block_base(id1), 1);
             }
             wait_vm0();
             __syncthreads();
