@@ -44,6 +44,7 @@ int check_xchg(const shiftattn_xchg* x, int32_t T, int32_t T_pad, bool with_kv, 
     const int e = elem_size(x->dtype);
     if (!e) return fail(SHIFTATTN_EINVAL, "unknown dtype %d", x->dtype);
     if (x->P < 1) return fail(SHIFTATTN_EINVAL, "P = %d must be >= 1", x->P);
+    if (x->P > 1024) return fail(SHIFTATTN_EUNSUPPORTED, "P = %d: at most 1024 exchange members are supported", x->P);
     if (x->num_q_heads < 1 || x->num_q_heads % x->P)
         return fail(SHIFTATTN_EINVAL, "num_q_heads = %d must be a positive multiple of P = %d", x->num_q_heads, x->P);
     const int h_kv = with_kv ? x->num_kv_heads : 0;

@@ -13,14 +13,17 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
 
-// One workgroup writes kThreads*kUnroll consecutive vectors of send[p]; blockIdx.y = p.
+// One workgroup writes kThreads*kUnroll consecutive vectors of send[p].  The destination index is
+// the fastest-varying part of the workgroup id, so the P workgroups that read the same input rows run
+// together and the input is streamed once, front to back, while the P outputs advance in step.
 __global__ __launch_bounds__(kThreads) void pack_seq2head_kernel(const u32x4* __restrict__ in,
                                                                  u32x4* __restrict__ out, XchgShape s,
                                                                  uint32_t row_vecs, uint32_t dest_vecs) {
-    const int p = blockIdx.y;
+    const int p = blockIdx.x % s.P;
+    const uint32_t chunk = blockIdx.x / s.P;
     const int kv0 = s.h_kv ? static_cast<int>((static_cast<int64_t>(p) * s.h_kv) / s.P) : 0;
     const uint32_t in_row_heads = s.h + 2 * s.h_kv;
-    const uint32_t first = blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+    const uint32_t first = chunk * (kThreads * kUnroll) + threadIdx.x;
     u32x4 v[kUnroll];
 #pragma unroll
     for (int k = 0; k < kUnroll; ++k) {
@@ -116,7 +119,8 @@ hipError_t launch_pack(const void* qkv, void* send, const XchgShape& s, hipStrea
     const uint32_t row_vecs = static_cast<uint32_t>(s.hq_l + 2 * s.hkv_l) * s.vec_per_head;
     const uint32_t dest_vecs = static_cast<uint32_t>(s.T_pad) * row_vecs;
     if (dest_vecs == 0) return hipSuccess;
-    dim3 grid((dest_vecs + kThreads * kUnroll - 1) / (kThreads * kUnroll), s.P);
+    const uint64_t chunks = (dest_vecs + kThreads * kUnroll - 1) / (kThreads * kUnroll);
+    const unsigned grid = static_cast<unsigned>(chunks * s.P);  // < 2^31: dest_vecs * P is bounded by the caller
     pack_seq2head_kernel<<<grid, kThreads, 0, st>>>(static_cast<const u32x4*>(qkv), static_cast<u32x4*>(send), s,
                                                     row_vecs, dest_vecs);
     return hipGetLastError();
