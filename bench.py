@@ -30,6 +30,26 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+
+
+def load_traffic():
+    """HBM bytes per launch measured with rocprofv3 counters, from the committed summary table.
+
+    Rows look like `| key | kernel | fetch bytes | write bytes | ...`; returns {key: fetch + write}."""
+    out = {}
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                cells = [c.strip() for c in line.strip().strip("|").split("|")]
+                if len(cells) >= 4 and cells[0] and cells[0][0].isalpha():
+                    try:
+                        out[cells[0]] = int(float(cells[2])) + int(float(cells[3]))
+                    except ValueError:
+                        pass
+    except OSError:
+        pass
+    return out
 METRIC = "prefill attn TFLOP/s + decode KV-read GB/s per MI355X (head shard, % roofline)"
 
 
@@ -44,6 +64,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the decode / exchange / 70B-prefill configurations")
+    ap.add_argument("--pmc-calibrate", action="store_true",
+                    help="also run a plain 1-GiB elementwise copy a few times (reference for scaling FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build covers one GPU's share of the layer and runs on exactly one GPU; "
@@ -57,6 +79,7 @@ def main() -> int:
     from paper_2509_16495_amd import workloads as W
 
     B.lib()  # fail loudly if the HIP library was not built
+    traffic = load_traffic()
     dev = "cuda:0"
     torch.cuda.set_device(0)
     bf = torch.bfloat16
@@ -174,7 +197,7 @@ def main() -> int:
     achieved = case.flops() / (pk_ms * 1e-3) / 1e12
     roofline = {"kernel": "prefill_kernel (bf16 MFMA causal prefill)", "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": None, "flops_per_launch": case.flops(), "avg_launch_ms": round(pk_ms, 5)}
+                "traffic": traffic.get("prefill_8b"), "flops_per_launch": case.flops(), "avg_launch_ms": round(pk_ms, 5)}
 
     result = {
         "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -208,7 +231,7 @@ def main() -> int:
                                     "kv_bytes": c4.kv_bytes(), "ms": round(ms, 5),
                                     "roofline": {"kernel": "decode_splitk_kernel + combine_kernel", "bound": "hbm",
                                                  "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                                                 "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": None}}
+                                                 "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": traffic.get("decode_256seq")}}
         log(f"[bench] decode cfg4: {ms * 1e3:.1f} us, {gbps:.0f} GB/s of KV ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
         del cache4, w4
         # exchange of the 70B hidden state (configs[2])
@@ -233,7 +256,7 @@ def main() -> int:
             result[nm] = {"workload": "configs[2]: hidden [16384, 64 heads, 128] bf16 <-> 8 buffers, 3 rotating copies",
                           "bytes": x3.bytes_moved(), "ms": round(ms, 5),
                           "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                                       "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": None}}
+                                       "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": traffic.get(nm + "_70b")}}
             log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {gbps:.0f} GB/s ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
         del xin, xsend, xout
         # 70B-shaped prefill (configs[2])
@@ -248,9 +271,20 @@ def main() -> int:
         result["prefill_70b"] = {"workload": "configs[2]: 8q/1kv, D=128, one 16384-token causal prefill", "flops": c3.flops(),
                                  "ms": round(ms, 5),
                                  "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_BF16_TFLOPS,
-                                              "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}}
+                                              "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4),
+                                              "traffic": traffic.get("prefill_70b")}}
         log(f"[bench] prefill cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%} of bf16 MFMA peak)")
         del cache3
+
+    if args.pmc_calibrate:
+        # a plain copy of known size, far larger than the caches: 512 Mi bf16 elements (1 GiB) read, as many written
+        src = torch.ones(512 << 20, dtype=bf, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1, out=dst)
+        torch.cuda.synchronize()
+        log(f"[bench] calibration copy: {src.numel() * 2} bytes read and written per launch of torch's elementwise kernel")
+        del src, dst
 
     # ---- CPU oracle on a bounded sample of the step's batch --------------------------------------------------
     if not args.no_cpu_baseline:

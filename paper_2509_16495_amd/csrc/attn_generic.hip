@@ -145,7 +145,8 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* _
                                                                   const float* __restrict__ ml_part, int n_rows,
                                                                   int hq_l, int D, int n_parts, int mode,
                                                                   const int32_t* __restrict__ seq_lens, int chunk,
-                                                                  Elem* __restrict__ out, int64_t out_stride) {
+                                                                  Elem* __restrict__ out, int64_t out_stride,
+                                                                  const int2* __restrict__ plan) {
     __shared__ float w_s[kCombineMaxParts];
     __shared__ float l_s[kCombineMaxParts];
     __shared__ float red_s[kCombineThreads / 64];
@@ -153,14 +154,23 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* _
     const int tok = row / hq_l, head = row % hq_l;
     int np = n_parts;
     if (mode == 1) np = (seq_lens[tok] + chunk - 1) / chunk;
+    // partial row of part c: row0 + c * part_rows
+    size_t part_rows = static_cast<size_t>(n_rows) * hq_l;
+    size_t row0 = row;
+    if (mode == 2) {
+        const int G = chunk;
+        const int2 e = plan[tok * (hq_l / G) + head / G];
+        np = e.y;
+        part_rows = G;
+        row0 = static_cast<size_t>(e.x) * G + head % G;
+    }
     np = min(np, kCombineMaxParts);
-    const size_t part_rows = static_cast<size_t>(n_rows) * hq_l;
     const int tid = threadIdx.x;
     float m_loc = -INFINITY;
     for (int c = tid; c < np; c += kCombineThreads) {
-        const float m_c = ml_part[(c * part_rows + row) * 2];
+        const float m_c = ml_part[(c * part_rows + row0) * 2];
         w_s[c] = m_c;
-        l_s[c] = ml_part[(c * part_rows + row) * 2 + 1];
+        l_s[c] = ml_part[(c * part_rows + row0) * 2 + 1];
         m_loc = fmaxf(m_loc, m_c);
     }
     m_loc = wave_max(m_loc);
@@ -179,7 +189,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* _
     const float inv = l_star > 0.f ? 1.f / l_star : 0.f;
     for (int d = tid; d < D; d += kCombineThreads) {
         float acc = 0.f;
-        const float* src = o_part + static_cast<size_t>(row) * D + d;
+        const float* src = o_part + row0 * D + d;
 #pragma unroll 4
         for (int c = 0; c < np; ++c) acc = fmaf(src[c * part_rows * D], w_s[c], acc);
         store_elem(out + static_cast<size_t>(tok) * out_stride + static_cast<size_t>(head) * D + d, acc * inv);
@@ -208,16 +218,17 @@ hipError_t launch_attn_generic(const void* q, const void* cache, const int32_t* 
 
 hipError_t launch_combine(const float* o_part, const float* ml_part, int n_rows, int hq_l, int D, int n_parts,
                           int mode, const int32_t* seq_lens, int chunk, void* out, int64_t out_stride, int elem,
-                          hipStream_t st) {
+                          hipStream_t st, const int2* plan) {
     const int64_t rows = static_cast<int64_t>(n_rows) * hq_l;
     if (rows == 0) return hipSuccess;
     if (elem == 2)
         combine_kernel<uint16_t><<<static_cast<unsigned>(rows), 128, 0, st>>>(
-            o_part, ml_part, n_rows, hq_l, D, n_parts, mode, seq_lens, chunk, static_cast<uint16_t*>(out), out_stride);
+            o_part, ml_part, n_rows, hq_l, D, n_parts, mode, seq_lens, chunk, static_cast<uint16_t*>(out), out_stride,
+            plan);
     else
         combine_kernel<float><<<static_cast<unsigned>(rows), 128, 0, st>>>(o_part, ml_part, n_rows, hq_l, D, n_parts,
                                                                           mode, seq_lens, chunk,
-                                                                          static_cast<float*>(out), out_stride);
+                                                                          static_cast<float*>(out), out_stride, plan);
     return hipGetLastError();
 }
 

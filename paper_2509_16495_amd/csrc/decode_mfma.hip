@@ -15,6 +15,15 @@
 //
 // Each workgroup writes one un-normalised partial (max, sum, O) per head; launch_combine merges
 // the chunks of a sequence in chunk order, so results do not depend on scheduling.
+//
+// Two decompositions share that arithmetic.  decode_flat_kernel (the default) lays all (sequence, KV
+// head) pairs end to end, each padded to a multiple of 32 tokens, and gives every wavefront of a
+// fixed-size grid the same number of tokens of that line, whatever the mix of context lengths: all
+// wavefronts start and finish together, none waits at a barrier, and a wavefront pays its start-up
+// latency once.  A wavefront emits one partial per sequence its range touches; sorted by position
+// these partials are numbered (wavefront index + pair index), so the parts of a pair are
+// consecutive rows.  decode_splitk_kernel (one workgroup per fixed-size chunk of one sequence) remains
+// for batches with more pairs than the flat kernel indexes in LDS.
 #include "internal.h"
 
 #include <stdlib.h>
@@ -45,6 +54,280 @@ struct GroupFrags {
 // LDS area and the MFMA operands are read back from there without bank conflicts; the next group's
 // loads are already in flight in registers meanwhile.
 constexpr int kStageBytes = 16384;  // per wavefront: K of two blocks (2 x 4 KiB), V^T of two blocks (2 x 4 KiB)
+
+constexpr int kFlatMaxPairs = 2048;                       // (sequence, KV head) pairs indexed in LDS
+constexpr int kFlatWorkgroups = 512;                      // two resident per compute unit
+constexpr int kFlatWorkers = kFlatWorkgroups * kWaves;    // wavefronts, each with its own token range
+
+// The flat kernel: see the file header.  cum[i + 1] holds the padded token count of pairs 0..i in
+// its upper bits and (padded - real) length of pair i in its low five bits.
+__global__ __launch_bounds__(kWaves * 64, 2) void decode_flat_kernel(
+    const uint16_t* __restrict__ q, int64_t q_stride, const uint16_t* __restrict__ cache,
+    const int32_t* __restrict__ block_table, int max_blocks, const int32_t* __restrict__ seq_lens,
+    float* __restrict__ o_part, float* __restrict__ ml_part, int2* __restrict__ plan, int num_seqs, int hq_l, int hkv_l,
+    float c, int r_min) {
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kWaves * kStageBytes];
+    __shared__ int cum[kFlatMaxPairs + 1];
+    __shared__ int wave_sum[kWaves];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int n_pairs = num_seqs * hkv_l;
+    const int G = hq_l / hkv_l;
+
+    // ---- padded prefix sums of the context lengths: thread t owns pairs 8t .. 8t+7 -----------------
+    {
+        constexpr int kPer = kFlatMaxPairs / (kWaves * 64);  // 8
+        int len[kPer], pad[kPer];
+        int mine = 0;
+#pragma unroll
+        for (int x = 0; x < kPer; ++x) {
+            const int i = threadIdx.x * kPer + x;
+            len[x] = i < n_pairs ? max(seq_lens[i / hkv_l], 0) : 0;
+        }
+#pragma unroll
+        for (int x = 0; x < kPer; ++x) {
+            pad[x] = (len[x] + kGroup - 1) & ~(kGroup - 1);
+            mine += pad[x];
+        }
+        int incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int y = __shfl_up(incl, d);
+            if (lane >= d) incl += y;
+        }
+        if (lane == 63) wave_sum[wave] = incl;
+        __syncthreads();
+        int run = incl - mine;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w)
+            if (w < wave) run += wave_sum[w];
+#pragma unroll
+        for (int x = 0; x < kPer; ++x) {
+            const int i = threadIdx.x * kPer + x;
+            run += pad[x];
+            if (i < n_pairs) cum[i + 1] = run | (pad[x] - len[x]);
+        }
+        if (threadIdx.x == 0) cum[0] = 0;
+        __syncthreads();
+    }
+    const int total = __builtin_amdgcn_readfirstlane(cum[n_pairs]) & ~(kGroup - 1);
+    int R = ((total + kFlatWorkers - 1) / kFlatWorkers + kGroup - 1) & ~(kGroup - 1);
+    R = max(R, r_min);
+    if (blockIdx.x == 0) {  // which partial rows belong to which pair, for the merge kernel
+        for (int i = threadIdx.x; i < n_pairs; i += kWaves * 64) {
+            const int a = cum[i] & ~(kGroup - 1), b = cum[i + 1] & ~(kGroup - 1);
+            int2 e = {0, 0};
+            if (b > a) {
+                const int w0 = a / R, w1 = (b - 1) / R;
+                e.x = w0 + i;
+                e.y = w1 - w0 + 1;
+            }
+            plan[i] = e;
+        }
+    }
+    const int wk = blockIdx.x * kWaves + wave;
+    const int64_t start64 = static_cast<int64_t>(wk) * R;
+    if (start64 >= total) return;  // no barrier below this line
+    const int start = static_cast<int>(start64);
+    const int end = min(start + R, total);
+
+    const int col = lane & 15;
+    const int grp = lane >> 4;
+    unsigned char* my = smem + wave * kStageBytes;
+    // LDS positions (see decode_splitk_kernel for the layout), folded so that four bases serve the K
+    // writes, four the K reads and one each the V^T writes and reads; the rest are immediate offsets.
+    //   K write, block b, load j   : kw[j ^ b] + 4096 b + 1024 j
+    //   K read, tile a / b, step kk: kr[kk] / kr[kk ^ 1] + 1024
+    int kw[4], kr[4];
+    {
+        const int r0 = lane >> 4, p = lane & 15;
+        const int base = r0 * 256 + ((p ^ r0) << 4);
+        const int tau_a = ((col >> 2) << 3) + (col & 3);
+        const int k_sel = tau_a >> 4, k_off_a = tau_a & 15;
+        const int rbase = k_sel * 4096 + k_off_a * 256 + ((grp ^ k_off_a ^ (4 * k_sel)) << 4);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            kw[x] = base ^ (64 * x);
+            kr[x] = rbase ^ (64 * x);
+        }
+    }
+    const int vw = 8192 + ((lane ^ ((lane >> 4) & 1)) << 4);
+    const int vr = 8192 + (grp >> 1) * 4096 + (((2 * col + (grp & 1)) ^ ((col >> 3) & 1)) << 4);
+
+    // ---- a position on the line: pair index, its padded token range, its real length (all scalar) --
+    int pos = start, pair, seg_begin, seg_end, ctx;
+    auto seg_of = [&](int pr, int& sb, int& se, int& cx) {
+        const int lo = __builtin_amdgcn_readfirstlane(cum[pr]);
+        const int hi = __builtin_amdgcn_readfirstlane(cum[pr + 1]);
+        sb = lo & ~(kGroup - 1);
+        se = hi & ~(kGroup - 1);
+        cx = se - sb - (hi & (kGroup - 1));
+    };
+    {
+        int lo = 0, hi = n_pairs;  // first pair whose padded range ends beyond `start`
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if ((__builtin_amdgcn_readfirstlane(cum[mid + 1]) & ~(kGroup - 1)) > start) hi = mid;
+            else lo = mid + 1;
+        }
+        pair = lo;
+        seg_of(pair, seg_begin, seg_end, ctx);
+    }
+    // block ids of the group at (pr, ps); scalar loads
+    auto fetch_ids = [&](int pr, int ps, int sb, int cx, int& blk0, int& blk1) {
+        const int s = pr / hkv_l;
+        const int b0 = (ps - sb) / kBlockSize;
+        const int last_block = (cx - 1) / kBlockSize;
+        const int32_t* table = block_table + static_cast<size_t>(s) * max_blocks;
+        blk0 = table[b0];
+        blk1 = table[min(b0 + 1, last_block)];
+    };
+    GroupFrags f;
+    auto load_group = [&](int pr, int blk0, int blk1) {
+        const int g = pr % hkv_l;
+        const u32x4* k0 = reinterpret_cast<const u32x4*>(cache + cache_part_offset(blk0, g, 0, hkv_l, kD)) + lane;
+        const u32x4* k1 = reinterpret_cast<const u32x4*>(cache + cache_part_offset(blk1, g, 0, hkv_l, kD)) + lane;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            f.k[j] = __builtin_nontemporal_load(k0 + 64 * j);
+            f.k[4 + j] = __builtin_nontemporal_load(k1 + 64 * j);
+            f.v[j] = __builtin_nontemporal_load(k0 + 256 + 64 * j);
+            f.v[4 + j] = __builtin_nontemporal_load(k1 + 256 + 64 * j);
+        }
+    };
+    bf16x8 qf[4];
+    auto load_q = [&](int pr) {
+        const int s = pr / hkv_l, g = pr % hkv_l;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (col < G)
+                v = *reinterpret_cast<const u32x4*>(q + static_cast<size_t>(s) * q_stride +
+                                                    static_cast<size_t>(g * G + col) * kD + 8 * (grp + 4 * kk));
+            qf[kk] = as_bf16x8(v);
+        }
+    };
+
+    f32x4 o[8];
+    float m_run, l_run;
+    auto reset = [&]() {
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) o[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m_run = -INFINITY;
+        l_run = 0.f;
+    };
+    auto flush = [&](int pr) {  // this wavefront's partial of pair `pr`: row (wavefront + pair)
+        float l = l_run + __shfl_xor(l_run, 16);
+        l += __shfl_xor(l, 32);
+        if (col < G) {
+            const size_t prow = (static_cast<size_t>(wk) + pr) * G + col;
+            float* dst = o_part + prow * kD + 4 * grp;
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) *reinterpret_cast<f32x4*>(dst + 16 * mt) = o[mt];
+            if (grp == 0) {
+                ml_part[prow * 2] = m_run * c;
+                ml_part[prow * 2 + 1] = l;
+            }
+        }
+    };
+
+    // ---- pipeline: while group i is computed from LDS, the loads of group i+1 are in flight (into the
+    // registers group i has just left) and so are the block ids of group i+2 ---------------------------
+    int blk0, blk1;
+    fetch_ids(pair, pos, seg_begin, ctx, blk0, blk1);
+    load_group(pair, blk0, blk1);
+    load_q(pair);
+    reset();
+    // position and ids of the next group
+    int n_pos = pos + kGroup, n_pair = pair, n_begin = seg_begin, n_end = seg_end, n_ctx = ctx;
+    bool n_valid_grp = n_pos < end;
+    if (n_valid_grp) {
+        while (n_pos >= n_end) seg_of(++n_pair, n_begin, n_end, n_ctx);
+        fetch_ids(n_pair, n_pos, n_begin, n_ctx, blk0, blk1);
+    }
+    while (true) {
+        // group (pair, pos) has arrived in f: park it in LDS, then reuse f for the next group
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            *reinterpret_cast<u32x4*>(my + kw[j] + 1024 * j) = f.k[j];
+            *reinterpret_cast<u32x4*>(my + kw[j ^ 1] + 4096 + 1024 * j) = f.k[4 + j];
+            *reinterpret_cast<u32x4*>(my + vw + 1024 * j) = f.v[j];
+            *reinterpret_cast<u32x4*>(my + vw + 4096 + 1024 * j) = f.v[4 + j];
+        }
+        int nn_pos = n_pos + kGroup, nn_pair = n_pair, nn_begin = n_begin, nn_end = n_end, nn_ctx = n_ctx;
+        bool nn_valid = false;
+        if (n_valid_grp) {
+            load_group(n_pair, blk0, blk1);
+            nn_valid = nn_pos < end;
+            if (nn_valid) {
+                while (nn_pos >= nn_end) seg_of(++nn_pair, nn_begin, nn_end, nn_ctx);
+                fetch_ids(nn_pair, nn_pos, nn_begin, nn_ctx, blk0, blk1);
+            }
+        }
+
+        f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const bf16x8 ka = as_bf16x8(*reinterpret_cast<const u32x4*>(my + kr[kk]));
+            const bf16x8 kb = as_bf16x8(*reinterpret_cast<const u32x4*>(my + kr[kk ^ 1] + 1024));
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[kk], sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb, qf[kk], sb, 0, 0, 0);
+        }
+        u32x4 vf[8];
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) vf[mt] = *reinterpret_cast<const u32x4*>(my + vr + 512 * mt);
+
+        const int off = pos - seg_begin;
+        const int n_valid = ctx - (off + 8 * grp);
+        if (off + kGroup > ctx) {  // last, partial group of the context: uniform branch
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (r >= n_valid) sa[r] = -INFINITY;
+                if (4 + r >= n_valid) sb[r] = -INFINITY;
+            }
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const uint32_t mask = n_valid > 2 * w + 1 ? 0xFFFFFFFFu : (n_valid > 2 * w ? 0x0000FFFFu : 0u);
+#pragma unroll
+                for (int mt = 0; mt < 8; ++mt) vf[mt][w] &= mask;
+            }
+        }
+        float mx = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])), fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+        const float mc = m_new * c;
+        float pa[4], pb[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            pa[r] = __builtin_amdgcn_exp2f(fmaf(sa[r], c, -mc));
+            pb[r] = __builtin_amdgcn_exp2f(fmaf(sb[r], c, -mc));
+        }
+        l_run = l_run * alpha + ((pa[0] + pa[1]) + (pa[2] + pa[3])) + ((pb[0] + pb[1]) + (pb[2] + pb[3]));
+        m_run = m_new;
+        bf16x8 pf;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            pf[r] = static_cast<__bf16>(pa[r]);
+            pf[4 + r] = static_cast<__bf16>(pb[r]);
+        }
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) {
+            o[mt] *= alpha;
+            o[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vf[mt]), pf, o[mt], 0, 0, 0);
+        }
+        if (!n_valid_grp) break;
+        if (n_pair != pair) {  // the next group starts another pair: emit this one's partial, fetch its queries
+            flush(pair);
+            reset();
+            load_q(n_pair);
+        }
+        pos = n_pos, pair = n_pair, seg_begin = n_begin, seg_end = n_end, ctx = n_ctx;
+        n_pos = nn_pos, n_pair = nn_pair, n_begin = nn_begin, n_end = nn_end, n_ctx = nn_ctx;
+        n_valid_grp = nn_valid;
+    }
+    flush(pair);
+}
 
 template <bool kPrefetch>
 __global__ __launch_bounds__(kWaves * 64, 2) void decode_splitk_kernel(
@@ -269,7 +552,21 @@ bool decode_mfma_supported(const AttnShape& a) {
     return a.elem == 2 && a.D == kD && a.hq_l % a.hkv_l == 0 && a.hq_l / a.hkv_l <= 16;
 }
 
+namespace {
+
+inline bool use_flat(int num_seqs, const AttnShape& a) {
+    return static_cast<int64_t>(num_seqs) * a.hkv_l <= kFlatMaxPairs && env_int("SHIFTATTN_DECODE_FLAT", 1) != 0;
+}
+// partial rows of the flat kernel: one per (wavefront, pair) whose ranges meet, numbered wavefront + pair
+inline size_t flat_rows(int num_seqs, const AttnShape& a) {
+    return (static_cast<size_t>(kFlatWorkers) + static_cast<size_t>(num_seqs) * a.hkv_l) * (a.hq_l / a.hkv_l);
+}
+
+}  // namespace
+
 size_t decode_mfma_workspace(int num_seqs, int max_seq_len, const AttnShape& a) {
+    if (use_flat(num_seqs, a))
+        return flat_rows(num_seqs, a) * (kD + 2) * sizeof(float) + static_cast<size_t>(num_seqs) * a.hkv_l * sizeof(int2);
     const size_t rows = static_cast<size_t>(max_chunks_of(num_seqs, a.hkv_l, max_seq_len)) * num_seqs * a.hq_l;
     return rows * (kD + 2) * sizeof(float);
 }
@@ -278,12 +575,30 @@ hipError_t launch_decode_mfma(const void* q, const void* cache, const int32_t* b
                               int num_seqs, int max_seq_len, void* out, void* workspace, const AttnShape& a,
                               hipStream_t st) {
     if (num_seqs == 0 || max_seq_len <= 0) return hipSuccess;
+    const float c = a.scale * 1.4426950408889634f;
+    if (use_flat(num_seqs, a)) {
+        const size_t rows = flat_rows(num_seqs, a);
+        float* o_part = static_cast<float*>(workspace);
+        float* ml_part = o_part + rows * kD;
+        int2* plan = reinterpret_cast<int2*>(ml_part + rows * 2);
+        // tokens per wavefront never fall below this, so that no output row has more parts than the
+        // merge kernel holds (and tiny batches are not shredded into one-group partials)
+        const int padded_max = (max_seq_len + kGroup - 1) / kGroup * kGroup;
+        int r_min = (padded_max / (kMaxParts - 24) + kGroup) / kGroup * kGroup;
+        if (r_min < 2 * kGroup) r_min = 2 * kGroup;
+        decode_flat_kernel<<<kFlatWorkgroups, kWaves * 64, 0, st>>>(
+            static_cast<const uint16_t*>(q), a.q_stride, static_cast<const uint16_t*>(cache), block_table, a.max_blocks,
+            seq_lens, o_part, ml_part, plan, num_seqs, a.hq_l, a.hkv_l, c, r_min);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        return launch_combine(o_part, ml_part, num_seqs, a.hq_l, kD, 0, 2, seq_lens, a.hq_l / a.hkv_l, out, a.out_stride,
+                              a.elem, st, plan);
+    }
     const int chunk = chunk_tokens(num_seqs, a.hkv_l, max_seq_len);
     const int max_chunks = max_chunks_of(num_seqs, a.hkv_l, max_seq_len);
     const size_t rows = static_cast<size_t>(max_chunks) * num_seqs * a.hq_l;
     float* o_part = static_cast<float*>(workspace);
     float* ml_part = o_part + rows * kD;
-    const float c = a.scale * 1.4426950408889634f;
     dim3 grid(max_chunks, num_seqs, a.hkv_l);
     decode_splitk_kernel<true><<<grid, kWaves * 64, 0, st>>>(
         static_cast<const uint16_t*>(q), a.q_stride, static_cast<const uint16_t*>(cache), block_table, a.max_blocks,
