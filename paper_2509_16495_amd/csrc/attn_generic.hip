@@ -166,6 +166,15 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* _
     }
     np = min(np, kCombineMaxParts);
     const int tid = threadIdx.x;
+    // the first parts of this thread's output elements are requested before the weights are known,
+    // so their latency overlaps that of the (max, sum) pairs
+    constexpr int kEarly = 8;
+    float early[kEarly];
+    const int d0 = tid;  // D <= kCombineThreads * ceil: the common D = 128 gives one element per thread
+    if (d0 < D) {
+#pragma unroll
+        for (int c = 0; c < kEarly; ++c) early[c] = c < np ? o_part[(row0 + c * part_rows) * D + d0] : 0.f;
+    }
     float m_loc = -INFINITY;
     for (int c = tid; c < np; c += kCombineThreads) {
         const float m_c = ml_part[(c * part_rows + row0) * 2];
@@ -190,8 +199,15 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* _
     for (int d = tid; d < D; d += kCombineThreads) {
         float acc = 0.f;
         const float* src = o_part + row0 * D + d;
+        int c_first = 0;
+        if (d == d0) {
+#pragma unroll
+            for (int c = 0; c < kEarly; ++c)
+                if (c < np) acc = fmaf(early[c], w_s[c], acc);
+            c_first = kEarly;
+        }
 #pragma unroll 4
-        for (int c = 0; c < np; ++c) acc = fmaf(src[c * part_rows * D], w_s[c], acc);
+        for (int c = c_first; c < np; ++c) acc = fmaf(src[c * part_rows * D], w_s[c], acc);
         store_elem(out + static_cast<size_t>(tok) * out_stride + static_cast<size_t>(head) * D + d, acc * inv);
     }
 }

@@ -88,12 +88,14 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_flat_kernel(
             pad[x] = (len[x] + kGroup - 1) & ~(kGroup - 1);
             mine += pad[x];
         }
+        // inclusive scan over the wavefront with cross-lane moves (rows of 16, then row to row)
         int incl = mine;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int y = __shfl_up(incl, d);
-            if (lane >= d) incl += y;
-        }
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x111, 0xf, 0xf, false);  // row_shr:1
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x112, 0xf, 0xf, false);  // row_shr:2
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x114, 0xf, 0xf, false);  // row_shr:4
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x118, 0xf, 0xf, false);  // row_shr:8
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x142, 0xa, 0xf, false);  // lane 15 of a row into rows 1 and 3
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x143, 0xc, 0xf, false);  // lane 31 into rows 2 and 3
         if (lane == 63) wave_sum[wave] = incl;
         __syncthreads();
         int run = incl - mine;
@@ -163,13 +165,22 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_flat_kernel(
         cx = se - sb - (hi & (kGroup - 1));
     };
     {
-        int lo = 0, hi = n_pairs;  // first pair whose padded range ends beyond `start`
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if ((__builtin_amdgcn_readfirstlane(cum[mid + 1]) & ~(kGroup - 1)) > start) hi = mid;
-            else lo = mid + 1;
+        // first pair whose padded range ends beyond `start` (one exists: start < total): every lane
+        // probes one entry, first among 64 evenly spaced ones, then inside the stretch that brackets it
+        const int step = (n_pairs + 63) / 64;
+        const int probe = min((lane + 1) * step, n_pairs);
+        const uint64_t coarse = __builtin_amdgcn_ballot_w64((cum[probe] & ~(kGroup - 1)) > start);
+        const int base = __builtin_ctzll(coarse) * step;  // the answer lies in [base, base + step)
+        int lo = base;
+        for (int b = base; b < base + step; b += 64) {
+            const int i = min(b + lane, n_pairs - 1);
+            const uint64_t fine = __builtin_amdgcn_ballot_w64((cum[i + 1] & ~(kGroup - 1)) > start);
+            if (fine) {
+                lo = b + __builtin_ctzll(fine);
+                break;
+            }
         }
-        pair = lo;
+        pair = __builtin_amdgcn_readfirstlane(lo);
         seg_of(pair, seg_begin, seg_end, ctx);
     }
     // block ids of the group at (pr, ps); scalar loads
