@@ -121,6 +121,25 @@ def test_decode_bf16_small(oracle, G, hq_l, hkv_l):
     _check(got, want, "bf16")
 
 
+def test_decode_many_sequences_and_long_contexts(oracle, G):
+    """The flat decomposition at the edges of its range: as many (sequence, KV head) pairs as it
+    indexes, one more than that (the per-chunk kernel takes over), a context long enough that the
+    minimum range per wavefront is set by the merge kernel's part limit, and a batch so small that
+    most wavefronts get no tokens."""
+    rng = np.random.default_rng(62)
+    for n_seqs, hq_l, hkv_l in [(2048, 4, 1), (2049, 4, 1), (1024, 4, 2), (1025, 4, 2)]:
+        lens = rng.integers(1, 70, size=n_seqs)
+        case = W.make_attn_case("t", 63, "bf16", [(1, int(c)) for c in lens], hq_l, hkv_l, 128, pool_factor=1.2)
+        want = oracle.attention_case(case, oracle.cache_for_case(case))
+        _check(G.decode_case(case, G.cache_for_case(case)), want, "bf16")
+    case = W.make_attn_case("t", 64, "bf16", [(1, 150001), (1, 3), (1, 40000)], 8, 1, 128, pool_factor=1.05)
+    want = oracle.attention_case(case, oracle.cache_for_case(case))
+    _check(G.decode_case(case, G.cache_for_case(case)), want, "bf16")
+    case = W.make_attn_case("t", 65, "bf16", [(1, 2)], 8, 1, 128)
+    want = oracle.attention_case(case, oracle.cache_for_case(case))
+    _check(G.decode_case(case, G.cache_for_case(case)), want, "bf16")
+
+
 def test_decode_fused_kv_write_and_fp32(oracle, G):
     from paper_2509_16495_amd import binding as B
     case = W.make_attn_case("t", 56, "bf16", [(1, c) for c in (1, 16, 17, 700, 64)], 8, 1, 128)
