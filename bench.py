@@ -276,6 +276,34 @@ def main() -> int:
         log(f"[bench] prefill cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%} of bf16 MFMA peak)")
         del cache3
 
+    # ---- what the chip attains on the two priced resources (context for the roofline fractions) -------------
+    if not args.no_extras:
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        ops = B.to_device(W.f32_to_bf16_bits(rng.standard_normal((128, 8), dtype=np.float32)), "bf16", dev)
+        flops = [0]
+
+        def mfma_probe():
+            flops[0] = B.ceiling_mfma_bf16(ops, sink, 2000)
+
+        ms = time_events(mfma_probe, 10)
+        mfma_tf = flops[0] / (ms * 1e-3) / 1e12
+        big = torch.empty(3 << 30, dtype=torch.uint8, device=dev)
+        big.fill_(1)
+        nbytes = [0]
+
+        def read_probe():
+            nbytes[0] = B.ceiling_hbm_read(big, sink)
+
+        ms = time_events(read_probe, 5)
+        rd_gbps = nbytes[0] / (ms * 1e-3) / 1e9
+        result["attainable"] = {
+            "mfma_bf16_random_operands": {"value": round(mfma_tf, 1), "unit": "TFLOP/s",
+                                          "note": "MFMA-only loop, 32x32x16 bf16, N(0,1) operands, two wavefronts per SIMD"},
+            "hbm_streaming_read": {"value": round(rd_gbps, 1), "unit": "GB/s",
+                                   "note": "3 GiB read once by 2048 wavefronts, 16 KiB per wavefront in flight"}}
+        log(f"[bench] attainable: MFMA-only loop {mfma_tf:.0f} TFLOP/s, streaming read {rd_gbps:.0f} GB/s")
+        del big
+
     if args.pmc_calibrate:
         # a plain copy of known size, far larger than the caches: 512 Mi bf16 elements (1 GiB) read, as many written
         src = torch.ones(512 << 20, dtype=bf, device=dev)

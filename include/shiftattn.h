@@ -151,9 +151,9 @@ int shiftattn_prefill(const void *q, const void *k_new, const void *v_new, const
                       const shiftattn_attn *a, void *stream);
 
 /* ---- Algorithm 1, boxed line: attention of decode rows (one new token per sequence) -------------
- * Same definition with q_len_s = 1, pos = seq_lens[s] - 1.  The context of every sequence is cut
- * into fixed-size chunks processed in parallel; partial results are merged in a fixed order, so
- * results are bitwise reproducible from run to run.
+ * Same definition with q_len_s = 1, pos = seq_lens[s] - 1.  The contexts of the batch are cut into
+ * pieces processed in parallel (equal shares of all tokens per wavefront); partial results are
+ * merged in a fixed order, so results are bitwise reproducible from run to run.
  * q, out: [num_seqs][hq_l][D]; k_new/v_new/slot_mapping: n_tokens = num_seqs (or all NULL). */
 int shiftattn_decode(const void *q, const void *k_new, const void *v_new, const int64_t *slot_mapping,
                      void *kv_cache, const int32_t *block_table, const int32_t *seq_lens, int32_t num_seqs,
@@ -177,6 +177,24 @@ int32_t shiftattn_head_block(int32_t sp, int32_t tp, int32_t rank);
 int32_t shiftattn_kv_head_of_block(int32_t block, int32_t P, int32_t h_kv);
 /* Batch size padded up to a multiple of the SP degree (Sec. 3.2.1).  Returns -1 on bad arguments. */
 int32_t shiftattn_padded_tokens(int32_t n, int32_t sp);
+
+/* Algorithm 2 (the shift dispatcher): 1 when a batch of n_tokens runs in the base configuration
+ * (SP, TP), i.e. n_tokens > threshold, 0 when it runs in the shift configuration (1, SP x TP).
+ * Returns -1 on negative arguments. */
+int32_t shiftattn_use_base_config(int32_t n_tokens, int32_t threshold);
+
+/* ---- Measurement aids for benchmark reports (not part of the attention path) -------------------
+ * Rates the chip attains on the two resources the kernels are priced against, to report beside
+ * the datasheet peaks (Sec. 4.3 names them: attention compute for long prompts, KV-cache reads
+ * for decoding).  Both only enqueue one kernel on `stream`; the caller times it.
+ * ceiling_mfma_bf16: every wavefront of a chip-filling grid issues iters x 16 independent
+ *   32x32x16 bf16 MFMAs on the operand values found in `operands` (device, 2 KiB = 128 lanes x
+ *   8 bf16; random values give the clock real data gives).  *flops (host) receives the flops of
+ *   the launch.  sink: device, 4 bytes, never written in practice.
+ * ceiling_hbm_read: streams `bytes` (rounded down to 16 KiB) of `src` (device) through every
+ *   wavefront with 16-byte non-temporal loads.  *bytes_read (host) receives the bytes requested. */
+int shiftattn_ceiling_mfma_bf16(const void *operands, void *sink, int32_t iters, int64_t *flops, void *stream);
+int shiftattn_ceiling_hbm_read(const void *src, size_t bytes, void *sink, int64_t *bytes_read, void *stream);
 
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char *shiftattn_last_error(void);

@@ -67,6 +67,10 @@ def lib() -> ctypes.CDLL:
         L.shiftattn_kv_head_of_block.restype = i32
         L.shiftattn_padded_tokens.argtypes = [i32, i32]
         L.shiftattn_padded_tokens.restype = i32
+        L.shiftattn_use_base_config.argtypes = [i32, i32]
+        L.shiftattn_use_base_config.restype = i32
+        L.shiftattn_ceiling_mfma_bf16.argtypes = [vp, vp, i32, ctypes.POINTER(ctypes.c_int64), vp]
+        L.shiftattn_ceiling_hbm_read.argtypes = [vp, sz, vp, ctypes.POINTER(ctypes.c_int64), vp]
         L.shiftattn_last_error.restype = ctypes.c_char_p
         _lib = L
     return _lib
@@ -114,6 +118,27 @@ def kv_head_of_block(block: int, P: int, h_kv: int) -> int:
 
 def padded_tokens(n: int, sp: int) -> int:
     return int(lib().shiftattn_padded_tokens(n, sp))
+
+
+def use_base_config(n_tokens: int, threshold: int) -> int:
+    return int(lib().shiftattn_use_base_config(n_tokens, threshold))
+
+
+def ceiling_mfma_bf16(operands: torch.Tensor, sink: torch.Tensor, iters: int) -> int:
+    """Enqueue the MFMA-only probe; returns the flops of the launch."""
+    assert operands.numel() * operands.element_size() >= 2048 and operands.is_contiguous()
+    flops = ctypes.c_int64(0)
+    _check(lib().shiftattn_ceiling_mfma_bf16(_ptr(operands), _ptr(sink), iters, ctypes.byref(flops), _stream()))
+    return flops.value
+
+
+def ceiling_hbm_read(src: torch.Tensor, sink: torch.Tensor) -> int:
+    """Enqueue the streaming-read probe over all of `src`; returns the bytes requested."""
+    assert src.is_contiguous()
+    n = ctypes.c_int64(0)
+    _check(lib().shiftattn_ceiling_hbm_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), ctypes.byref(n),
+                                            _stream()))
+    return n.value
 
 
 def local_kv_heads(P: int, h_kv: int) -> int:

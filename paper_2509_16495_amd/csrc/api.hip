@@ -148,6 +148,26 @@ int32_t shiftattn_padded_tokens(int32_t n, int32_t sp) {
     return padded > 0x7FFFFFFF ? -1 : static_cast<int32_t>(padded);
 }
 
+int32_t shiftattn_use_base_config(int32_t n_tokens, int32_t threshold) {
+    if (n_tokens < 0 || threshold < 0) return -1;
+    return n_tokens > threshold ? 1 : 0;
+}
+
+int shiftattn_ceiling_mfma_bf16(const void* operands, void* sink, int32_t iters, int64_t* flops, void* stream) {
+    if (!operands || !sink || !flops) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(operands)) return fail(SHIFTATTN_EINVAL, "operands must be 16-byte aligned");
+    if (iters < 1 || iters > (1 << 24)) return fail(SHIFTATTN_EINVAL, "iters = %d", iters);
+    hipError_t e = launch_mfma_ceiling(operands, sink, iters, flops, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "ceiling_mfma launch");
+}
+
+int shiftattn_ceiling_hbm_read(const void* src, size_t bytes, void* sink, int64_t* bytes_read, void* stream) {
+    if (!src || !sink || !bytes_read) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(src)) return fail(SHIFTATTN_EINVAL, "src must be 16-byte aligned");
+    hipError_t e = launch_hbm_read_ceiling(src, bytes, sink, bytes_read, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "ceiling_hbm_read launch");
+}
+
 int shiftattn_pack_seq2head(const void* qkv, void* send, int32_t T, int32_t T_pad, const shiftattn_xchg* x,
                             void* stream) {
     XchgShape s;

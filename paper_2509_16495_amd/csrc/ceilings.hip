@@ -1,0 +1,95 @@
+// Measurement aids: what the chip attains on the two resources the attention kernels are priced
+// against, under the conditions those kernels run in.  The datasheet peaks (2.5 PFLOP/s dense bf16
+// MFMA, 8 TB/s HBM) assume the top clock and ideal access streams; these two kernels give the rates
+// a benchmark report can put beside them:
+//   * an MFMA-only loop: every SIMD of the chip issues independent 32x32x16 bf16 MFMAs on operands
+//     taken from memory (with random operand values the shader clock settles well below its
+//     maximum, so this is lower than the same loop on constants), and
+//   * a streaming read: every wavefront reads 16 KiB pieces of a large buffer with 16-byte
+//     non-temporal loads, one KiB per instruction, the request shape of the decode kernel.
+#include "internal.h"
+
+namespace shiftattn {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kProbeWorkgroups = 256;  // one per compute unit
+constexpr int kProbeThreads = 512;     // two wavefronts per SIMD
+constexpr int kProbeUnroll = 16;
+
+__global__ __launch_bounds__(kProbeThreads) void mfma_ceiling_kernel(const u32x4* __restrict__ operands,
+                                                                     float* __restrict__ sink, int iters) {
+    const int lane = threadIdx.x & 63;
+    const bf16x8 a = __builtin_bit_cast(bf16x8, operands[lane]);
+    const bf16x8 b = __builtin_bit_cast(bf16x8, operands[64 + lane]);
+    f32x16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int m = 0; m < kProbeUnroll; ++m)
+            acc[m % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[m % 4], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    if (s == 12345.678f) sink[0] = s;  // keeps the loop alive; practically never true
+}
+
+constexpr int kReadWorkgroups = 512;
+constexpr int kReadThreads = 256;
+constexpr int kReadPiece = 16384;  // bytes a wavefront requests before it consumes any
+
+__global__ __launch_bounds__(kReadThreads, 2) void hbm_read_ceiling_kernel(const unsigned char* __restrict__ src,
+                                                                           size_t n_pieces, uint32_t* __restrict__ sink) {
+    const int lane = threadIdx.x & 63;
+    const size_t worker = static_cast<size_t>(blockIdx.x) * (kReadThreads / 64) + (threadIdx.x >> 6);
+    const size_t n_workers = static_cast<size_t>(gridDim.x) * (kReadThreads / 64);
+    uint32_t acc = 0;
+    u32x4 cur[16], nxt[16];
+    auto issue = [&](size_t piece, u32x4 (&d)[16]) {
+        const u32x4* p = reinterpret_cast<const u32x4*>(src + piece * kReadPiece) + lane;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) d[j] = __builtin_nontemporal_load(p + 64 * j);
+    };
+    size_t piece = worker;
+    if (piece < n_pieces) issue(piece, cur);
+    for (; piece < n_pieces; piece += n_workers) {
+        const bool more = piece + n_workers < n_pieces;
+        if (more) issue(piece + n_workers, nxt);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc ^= cur[j][0] + cur[j][3];
+        if (more) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) cur[j] = nxt[j];
+        }
+    }
+    if (acc == 0x9E3779B9u) sink[0] = acc;
+}
+
+}  // namespace
+
+hipError_t launch_mfma_ceiling(const void* operands, void* sink, int iters, int64_t* flops, hipStream_t st) {
+    mfma_ceiling_kernel<<<kProbeWorkgroups, kProbeThreads, 0, st>>>(static_cast<const u32x4*>(operands),
+                                                                     static_cast<float*>(sink), iters);
+    *flops = static_cast<int64_t>(kProbeWorkgroups) * (kProbeThreads / 64) * iters * kProbeUnroll * (2LL * 32 * 32 * 16);
+    return hipGetLastError();
+}
+
+hipError_t launch_hbm_read_ceiling(const void* src, size_t bytes, void* sink, int64_t* bytes_read, hipStream_t st) {
+    const size_t n_pieces = bytes / kReadPiece;
+    *bytes_read = static_cast<int64_t>(n_pieces) * kReadPiece;
+    if (n_pieces == 0) return hipSuccess;
+    hbm_read_ceiling_kernel<<<kReadWorkgroups, kReadThreads, 0, st>>>(static_cast<const unsigned char*>(src), n_pieces,
+                                                                      static_cast<uint32_t*>(sink));
+    return hipGetLastError();
+}
+
+}  // namespace shiftattn

@@ -64,6 +64,10 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
                                int total_q, int max_q_len, int max_seq_len, void* out, void* workspace,
                                const AttnShape& a, hipStream_t st);
 
+// ceilings.hip : attainable-rate probes for benchmark reports
+hipError_t launch_mfma_ceiling(const void* operands, void* sink, int iters, int64_t* flops, hipStream_t st);
+hipError_t launch_hbm_read_ceiling(const void* src, size_t bytes, void* sink, int64_t* bytes_read, hipStream_t st);
+
 // element offsets inside the cache: kv_cache[block][kv head][2][16*D]
 __host__ __device__ inline size_t cache_part_offset(int64_t block, int g, int part, int hkv_l, int D) {
     return ((static_cast<size_t>(block) * hkv_l + g) * 2 + part) * static_cast<size_t>(kBlockSize) * D;

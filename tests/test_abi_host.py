@@ -55,6 +55,13 @@ def test_head_block_matches_paper_example(B):
     assert B.head_block(3, 2, 6) == -1 and B.head_block(0, 2, 0) == -1 and B.head_block(3, 2, -1) == -1
 
 
+def test_shift_dispatcher_threshold(B):
+    """Algorithm 2: batches larger than the threshold run in the base configuration, the rest in the
+    shift configuration."""
+    assert B.use_base_config(4097, 4096) == 1 and B.use_base_config(4096, 4096) == 0 and B.use_base_config(0, 0) == 0
+    assert B.use_base_config(1, 0) == 1 and B.use_base_config(-1, 5) == -1 and B.use_base_config(5, -1) == -1
+
+
 def test_replication_and_padding_helpers(B):
     assert [B.kv_head_of_block(p, 8, 4) for p in range(8)] == [0, 0, 1, 1, 2, 2, 3, 3]
     assert [B.kv_head_of_block(p, 4, 8) for p in range(4)] == [0, 2, 4, 6]
