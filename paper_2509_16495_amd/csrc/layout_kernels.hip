@@ -113,6 +113,59 @@ __global__ __launch_bounds__(kThreads) void kv_write_kernel(const Elem* __restri
     for (int j = 0; j < kPer; ++j) vdst[j * kBlockSize] = u.e[j];
 }
 
+// bf16, D = 128: one workgroup appends 16 consecutive new tokens of one KV head.  When those tokens
+// fill exactly one cache block in order (the usual case for a prefill chunk) the V rows are
+// transposed through LDS and the block's V part is written as 4 KiB of consecutive bytes; any other
+// slot pattern takes the element-wise scatter of kv_write_kernel.  Same bytes in the cache either way.
+__global__ __launch_bounds__(kThreads) void kv_write_block_kernel(const uint16_t* __restrict__ k_new,
+                                                                  const uint16_t* __restrict__ v_new,
+                                                                  const int64_t* __restrict__ slots, int n_tokens,
+                                                                  uint16_t* __restrict__ cache, int hkv_l,
+                                                                  int64_t kv_stride) {
+    constexpr int D = 128, kPitch = D + 8;  // LDS row pitch in elements: 16-byte aligned, 4-bank skew per row
+    __shared__ __attribute__((aligned(16))) uint16_t tile[kBlockSize * kPitch];
+    const int g = blockIdx.y;
+    const int t_loc = threadIdx.x >> 4, dv = threadIdx.x & 15;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlockSize + t_loc;
+    const bool in_range = i < n_tokens;
+    const int64_t slot = in_range ? slots[i] : -1;
+    const int64_t first = slots[static_cast<int64_t>(blockIdx.x) * kBlockSize];  // blockIdx.x * 16 < n_tokens
+    const bool ordered = in_range && first >= 0 && (first % kBlockSize) == 0 && slot == first + t_loc;
+    const bool whole_block = __syncthreads_and(ordered);
+    u32x4 kvec = {0u, 0u, 0u, 0u}, vvec = {0u, 0u, 0u, 0u};
+    if (in_range && slot >= 0) {
+        const size_t src = static_cast<size_t>(i) * kv_stride + static_cast<size_t>(g) * D + dv * 8;
+        kvec = *reinterpret_cast<const u32x4*>(k_new + src);
+        vvec = *reinterpret_cast<const u32x4*>(v_new + src);
+        const int64_t blk = slot / kBlockSize;
+        const int off = static_cast<int>(slot % kBlockSize);
+        *reinterpret_cast<u32x4*>(cache + cache_part_offset(blk, g, 0, hkv_l, D) + static_cast<size_t>(off) * D + dv * 8) = kvec;
+        if (!whole_block) {
+            union {
+                u32x4 v;
+                uint16_t e[8];
+            } u;
+            u.v = vvec;
+            uint16_t* vdst = cache + cache_part_offset(blk, g, 1, hkv_l, D) + static_cast<size_t>(dv * 8) * kBlockSize + off;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) vdst[j * kBlockSize] = u.e[j];
+        }
+    }
+    if (!whole_block) return;  // uniform
+    *reinterpret_cast<u32x4*>(tile + t_loc * kPitch + dv * 8) = vvec;
+    __syncthreads();
+    // thread -> (head-dim row d, half h): eight consecutive tokens of row d
+    const int d = threadIdx.x >> 1, h = threadIdx.x & 1;
+    union {
+        u32x4 v;
+        uint16_t e[8];
+    } o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o.e[j] = tile[(8 * h + j) * kPitch + d];
+    uint16_t* vblk = cache + cache_part_offset(first / kBlockSize, g, 1, hkv_l, D);
+    *reinterpret_cast<u32x4*>(vblk + static_cast<size_t>(d) * kBlockSize + 8 * h) = o.v;
+}
+
 }  // namespace
 
 hipError_t launch_pack(const void* qkv, void* send, const XchgShape& s, hipStream_t st) {
@@ -141,6 +194,13 @@ hipError_t launch_kv_write(const void* k_new, const void* v_new, const int64_t* 
     const int64_t total = static_cast<int64_t>(n_tokens) * a.hkv_l * (a.D * a.elem / 16);
     if (total == 0) return hipSuccess;
     const unsigned grid = static_cast<unsigned>((total + kThreads - 1) / kThreads);
+    if (a.elem == 2 && a.D == 128 && a.hkv_l <= 65535) {
+        dim3 g2(static_cast<unsigned>((n_tokens + kBlockSize - 1) / kBlockSize), static_cast<unsigned>(a.hkv_l));
+        kv_write_block_kernel<<<g2, kThreads, 0, st>>>(static_cast<const uint16_t*>(k_new),
+                                                       static_cast<const uint16_t*>(v_new), slots, n_tokens,
+                                                       static_cast<uint16_t*>(cache), a.hkv_l, a.kv_stride);
+        return hipGetLastError();
+    }
     if (a.elem == 2)
         kv_write_kernel<uint16_t><<<grid, kThreads, 0, st>>>(static_cast<const uint16_t*>(k_new),
                                                             static_cast<const uint16_t*>(v_new), slots, n_tokens,

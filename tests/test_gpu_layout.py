@@ -66,6 +66,25 @@ def test_kv_write_bit_exact(oracle, G, dtype, hkv_l, D):
     assert B.to_host(cache).tobytes() == want.tobytes()
 
 
+@pytest.mark.parametrize("hkv_l", [1, 2])
+def test_kv_write_whole_blocks_and_ragged_runs(oracle, G, hkv_l):
+    """bf16, D=128: runs of 16 new tokens that fill a cache block in order go through the block-wise
+    writer, every other pattern (misaligned run, padding row inside a run, tail of the batch)
+    through the element-wise one; the cache bytes do not depend on which."""
+    from paper_2509_16495_amd import binding as B
+    case = W.make_attn_case("t", 45, "bf16", [(64, 64), (32, 160), (16, 21), (48, 48), (5, 5)], hkv_l, hkv_l, 128,
+                            pool_factor=1.4)
+    for holes in ((), (3,), (70, 71, 120)):
+        slots = case.slots[case.new_token_index].copy()
+        slots[list(holes)] = -1
+        k, v = case.k_ctx[case.new_token_index], case.v_ctx[case.new_token_index]
+        want = oracle.new_cache(case.num_blocks, hkv_l, 16, 128, "bf16", fill_byte=0x7F)   # untouched slots keep it
+        oracle.kv_write(want, k, v, slots, 16, "bf16")
+        cache = G.new_cache(case.num_blocks, hkv_l, 128, "bf16", fill_byte=0x7F)
+        G.kv_write(cache, k, v, slots, "bf16")
+        assert B.to_host(cache).tobytes() == want.tobytes()
+
+
 @pytest.mark.parametrize("sp,tp,H,H_kv", [(3, 2, 12, 6), (8, 1, 32, 4), (4, 2, 16, 8)])
 def test_sp_cache_equals_tp_cache_on_gpu(oracle, G, sp, tp, H, H_kv):
     """KV-cache invariance through the GPU kernels: pack -> exchange -> fused KV write in SP mode
