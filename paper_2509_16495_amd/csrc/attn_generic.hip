@@ -145,8 +145,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* _
                                                                   const float* __restrict__ ml_part, int n_rows,
                                                                   int hq_l, int D, int n_parts, int mode,
                                                                   const int32_t* __restrict__ seq_lens, int chunk,
-                                                                  Elem* __restrict__ out, int64_t out_stride,
-                                                                  const int2* __restrict__ plan) {
+                                                                  Elem* __restrict__ out, int64_t out_stride) {
     __shared__ float w_s[kCombineMaxParts];
     __shared__ float l_s[kCombineMaxParts];
     __shared__ float red_s[kCombineThreads / 64];
@@ -155,15 +154,8 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* _
     int np = n_parts;
     if (mode == 1) np = (seq_lens[tok] + chunk - 1) / chunk;
     // partial row of part c: row0 + c * part_rows
-    size_t part_rows = static_cast<size_t>(n_rows) * hq_l;
-    size_t row0 = row;
-    if (mode == 2) {
-        const int G = chunk;
-        const int2 e = plan[tok * (hq_l / G) + head / G];
-        np = e.y;
-        part_rows = G;
-        row0 = static_cast<size_t>(e.x) * G + head % G;
-    }
+    const size_t part_rows = static_cast<size_t>(n_rows) * hq_l;
+    const size_t row0 = row;
     np = min(np, kCombineMaxParts);
     const int tid = threadIdx.x;
     // the first parts of this thread's output elements are requested before the weights are known,
@@ -212,7 +204,95 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* _
     }
 }
 
+// Merge for the flat decode kernel (bf16 output, D = 128): one workgroup of one or four thread groups
+// per output row; group pg sums the parts c = pg, pg + groups, ... for its 128 head-dim elements (with
+// four groups sixteen partial rows are in flight per element) and the sums are added in group order.
+// Four groups pay off when rows are few and parts many (small batches), one when it is the reverse.  The parts of a
+// row are the partial rows (plan[pair].x + c) * G + head % G, c < plan[pair].y.
+template <int kFlatCombineGroups>
+__global__ __launch_bounds__(128 * kFlatCombineGroups) void combine_flat_kernel(
+    const float* __restrict__ o_part, const float* __restrict__ ml_part, const int2* __restrict__ plan, int hq_l, int G,
+    uint16_t* __restrict__ out, int64_t out_stride) {
+    constexpr int D = 128, kThreadsF = 128 * kFlatCombineGroups;
+    __shared__ float w_s[kCombineMaxParts];
+    __shared__ float l_s[kCombineMaxParts];
+    __shared__ float red_s[kThreadsF / 64];
+    __shared__ float acc_s[kFlatCombineGroups][D];
+    __shared__ float lsum_s[kFlatCombineGroups];
+    const int row = blockIdx.x;  // sequence * hq_l + head
+    const int tok = row / hq_l, head = row % hq_l;
+    const int2 e = plan[tok * (hq_l / G) + head / G];
+    const int np = min(e.y, kCombineMaxParts);
+    const size_t row0 = static_cast<size_t>(e.x) * G + head % G;
+    const int tid = threadIdx.x, d = tid & (D - 1), pg = tid >> 7;
+    // this thread's first four parts are requested before the weights are known
+    float early[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int c = pg + kFlatCombineGroups * x;
+        early[x] = c < np ? o_part[(row0 + static_cast<size_t>(c) * G) * D + d] : 0.f;
+    }
+    float m_loc = -INFINITY;
+    for (int c = tid; c < np; c += kThreadsF) {
+        const float m_c = ml_part[(row0 + static_cast<size_t>(c) * G) * 2];
+        w_s[c] = m_c;
+        l_s[c] = ml_part[(row0 + static_cast<size_t>(c) * G) * 2 + 1];
+        m_loc = fmaxf(m_loc, m_c);
+    }
+    m_loc = wave_max(m_loc);
+    if ((tid & 63) == 0) red_s[tid >> 6] = m_loc;
+    __syncthreads();
+    float m_star = red_s[0];
+#pragma unroll
+    for (int w = 1; w < kThreadsF / 64; ++w) m_star = fmaxf(m_star, red_s[w]);
+    for (int c = tid; c < np; c += kThreadsF) {
+        const float m_c = w_s[c];
+        w_s[c] = (m_c == -INFINITY) ? 0.f : exp2f(m_c - m_star);
+    }
+    __syncthreads();
+    float acc = 0.f, lsum = 0.f;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int c = pg + kFlatCombineGroups * x;
+        if (c < np) {
+            acc = fmaf(early[x], w_s[c], acc);
+            lsum = fmaf(l_s[c], w_s[c], lsum);
+        }
+    }
+#pragma unroll 4
+    for (int c = pg + 4 * kFlatCombineGroups; c < np; c += kFlatCombineGroups) {
+        acc = fmaf(o_part[(row0 + static_cast<size_t>(c) * G) * D + d], w_s[c], acc);
+        lsum = fmaf(l_s[c], w_s[c], lsum);
+    }
+    acc_s[pg][d] = acc;
+    if (d == 0) lsum_s[pg] = lsum;
+    __syncthreads();
+    if (pg == 0) {
+        float a = acc_s[0][d], l = lsum_s[0];
+#pragma unroll
+        for (int g2 = 1; g2 < kFlatCombineGroups; ++g2) {
+            a += acc_s[g2][d];
+            l += lsum_s[g2];
+        }
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        store_elem(out + static_cast<size_t>(tok) * out_stride + static_cast<size_t>(head) * D + d, a * inv);
+    }
+}
+
 }  // namespace
+
+hipError_t launch_combine_flat(const float* o_part, const float* ml_part, const int2* plan, int num_seqs, int hq_l, int G,
+                               void* out, int64_t out_stride, hipStream_t st) {
+    const int64_t rows = static_cast<int64_t>(num_seqs) * hq_l;
+    if (rows == 0) return hipSuccess;
+    if (rows >= 1024)
+        combine_flat_kernel<1><<<static_cast<unsigned>(rows), 128, 0, st>>>(o_part, ml_part, plan, hq_l, G,
+                                                                            static_cast<uint16_t*>(out), out_stride);
+    else
+        combine_flat_kernel<4><<<static_cast<unsigned>(rows), 512, 0, st>>>(o_part, ml_part, plan, hq_l, G,
+                                                                            static_cast<uint16_t*>(out), out_stride);
+    return hipGetLastError();
+}
 
 hipError_t launch_attn_generic(const void* q, const void* cache, const int32_t* block_table,
                                const int32_t* cu_seqlens_q, const int32_t* seq_lens, int num_seqs, int total_q,
@@ -234,17 +314,16 @@ hipError_t launch_attn_generic(const void* q, const void* cache, const int32_t* 
 
 hipError_t launch_combine(const float* o_part, const float* ml_part, int n_rows, int hq_l, int D, int n_parts,
                           int mode, const int32_t* seq_lens, int chunk, void* out, int64_t out_stride, int elem,
-                          hipStream_t st, const int2* plan) {
+                          hipStream_t st) {
     const int64_t rows = static_cast<int64_t>(n_rows) * hq_l;
     if (rows == 0) return hipSuccess;
     if (elem == 2)
         combine_kernel<uint16_t><<<static_cast<unsigned>(rows), 128, 0, st>>>(
-            o_part, ml_part, n_rows, hq_l, D, n_parts, mode, seq_lens, chunk, static_cast<uint16_t*>(out), out_stride,
-            plan);
+            o_part, ml_part, n_rows, hq_l, D, n_parts, mode, seq_lens, chunk, static_cast<uint16_t*>(out), out_stride);
     else
         combine_kernel<float><<<static_cast<unsigned>(rows), 128, 0, st>>>(o_part, ml_part, n_rows, hq_l, D, n_parts,
                                                                           mode, seq_lens, chunk,
-                                                                          static_cast<float*>(out), out_stride, plan);
+                                                                          static_cast<float*>(out), out_stride);
     return hipGetLastError();
 }
 

@@ -602,8 +602,7 @@ hipError_t launch_decode_mfma(const void* q, const void* cache, const int32_t* b
             seq_lens, o_part, ml_part, plan, num_seqs, a.hq_l, a.hkv_l, c, r_min);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        return launch_combine(o_part, ml_part, num_seqs, a.hq_l, kD, 0, 2, seq_lens, a.hq_l / a.hkv_l, out, a.out_stride,
-                              a.elem, st, plan);
+        return launch_combine_flat(o_part, ml_part, plan, num_seqs, a.hq_l, a.hq_l / a.hkv_l, out, a.out_stride, st);
     }
     const int chunk = chunk_tokens(num_seqs, a.hkv_l, max_seq_len);
     const int max_chunks = max_chunks_of(num_seqs, a.hkv_l, max_seq_len);

@@ -42,12 +42,14 @@ hipError_t launch_attn_generic(const void* q, const void* cache, const int32_t* 
 // Merge of split-context partial results (shared by decode and split prefill).
 // Partials: o[part][row][D] fp32 un-normalised, ml[part][row][2] = (max logit * log2e*scale, sum).
 // mode 0: every row has n_parts parts.  mode 1 (decode): row = (sequence, head), the number of
-// parts of a row is ceil(seq_lens[sequence] / chunk).  mode 2 (flat decode): `chunk` is the number
-// of query heads per KV head G; the parts of (sequence, head) are the partial rows
-// (plan[pair].x + i) * G + head % G for i < plan[pair].y, pair = (sequence, head / G).
+// parts of a row is ceil(seq_lens[sequence] / chunk).
 hipError_t launch_combine(const float* o_part, const float* ml_part, int n_rows, int hq_l, int D,
                           int n_parts, int mode, const int32_t* seq_lens, int chunk, void* out,
-                          int64_t out_stride, int elem, hipStream_t st, const int2* plan = nullptr);
+                          int64_t out_stride, int elem, hipStream_t st);
+
+// Merge for the flat decode kernel (bf16, D = 128): see combine_flat_kernel.
+hipError_t launch_combine_flat(const float* o_part, const float* ml_part, const int2* plan, int num_seqs, int hq_l, int G,
+                               void* out, int64_t out_stride, hipStream_t st);
 
 // decode_mfma.hip : bf16, D = 128, hq_l/hkv_l <= 16
 bool decode_mfma_supported(const AttnShape& a);
