@@ -229,7 +229,7 @@ def main() -> int:
         result["decode_kv_read"] = {"workload": f"configs[3]: 256 decode sequences, contexts U[512,8192], realised sum "
                                                 f"{int(c4.ctx_lens.sum())} tokens, 8q/1kv, D=128, bf16 paged KV",
                                     "kv_bytes": c4.kv_bytes(), "ms": round(ms, 5),
-                                    "roofline": {"kernel": "decode_splitk_kernel + combine_kernel", "bound": "hbm",
+                                    "roofline": {"kernel": "decode_flat_kernel + combine_flat_kernel", "bound": "hbm",
                                                  "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                                                  "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": traffic.get("decode_256seq")}}
         log(f"[bench] decode cfg4: {ms * 1e3:.1f} us, {gbps:.0f} GB/s of KV ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
@@ -275,6 +275,59 @@ def main() -> int:
                                               "traffic": traffic.get("prefill_70b")}}
         log(f"[bench] prefill cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%} of bf16 MFMA peak)")
         del cache3
+        # mixed long-context step (configs[4]): one 2048-token chunk on a 131072-token cached context, then 64 decode
+        # sequences, one shared block pool; both calls also write their new tokens' K/V
+        c5, n_pre = W.config5_attn()
+        pre5, dec5 = W.sub_case(c5, range(n_pre)), W.sub_case(c5, range(n_pre, c5.num_seqs))
+        cache5 = torch.zeros((c5.num_blocks, 1, 2, 16 * D), dtype=bf, device=dev)
+        cached_slots = c5.slots.copy()
+        cached_slots[c5.new_token_index] = -1
+        B.kv_write(B.to_device(c5.k_ctx, "bf16", dev), B.to_device(c5.v_ctx, "bf16", dev), ti(cached_slots, np.int64), cache5)
+
+        def dev_case(c):
+            nw = c.new_token_index
+            return dict(q=B.to_device(c.q, "bf16", dev), k=B.to_device(c.k_ctx[nw], "bf16", dev),
+                        v=B.to_device(c.v_ctx[nw], "bf16", dev), slots=ti(c.slots[nw], np.int64),
+                        table=ti(c.block_table, np.int32), cu=ti(c.cu_seqlens_q, np.int32), sl=ti(c.ctx_lens, np.int32),
+                        max_q=int(c.q_lens.max()), max_ctx=int(c.ctx_lens.max()))
+
+        p5, d5 = dev_case(pre5), dev_case(dec5)
+        p5["out"], d5["out"] = torch.empty_like(p5["q"]), torch.empty_like(d5["q"])
+        ap5 = B.attn_desc(p5["q"], cache5, p5["table"], c5.softmax_scale, p5["k"], p5["out"])
+        ad5 = B.attn_desc(d5["q"], cache5, d5["table"], c5.softmax_scale, d5["k"], d5["out"])
+        wp5 = torch.empty(max(B.prefill_workspace_bytes(pre5.num_seqs, pre5.total_q, p5["max_q"], p5["max_ctx"], ap5), 16),
+                          dtype=torch.uint8, device=dev)
+        wd5 = torch.empty(max(B.decode_workspace_bytes(dec5.num_seqs, d5["max_ctx"], ad5), 16), dtype=torch.uint8, device=dev)
+
+        def chunk5():
+            B.prefill(p5["q"], cache5, p5["table"], p5["cu"], p5["sl"], p5["max_q"], p5["max_ctx"], p5["out"], c5.softmax_scale,
+                      k_new=p5["k"], v_new=p5["v"], slot_mapping=p5["slots"], workspace=wp5)
+
+        def decode5():
+            B.decode(d5["q"], cache5, d5["table"], d5["sl"], d5["max_ctx"], d5["out"], c5.softmax_scale, k_new=d5["k"],
+                     v_new=d5["v"], slot_mapping=d5["slots"], workspace=wd5)
+
+        def both5():
+            chunk5()
+            decode5()
+
+        ms_a, ms_b, ms_ab = time_events(chunk5, reps), time_events(decode5, reps), time_events(both5, reps)
+        tf5 = pre5.flops() / (ms_a * 1e-3) / 1e12
+        gb5 = dec5.kv_bytes() / (ms_b * 1e-3) / 1e9
+        result["mixed_long_context"] = {
+            "workload": "configs[4]: 8q/1kv, D=128, bf16; (a) 2048-token chunk continuing a 131072-token cached context; "
+                        f"(b) 64 decode sequences, contexts U[1024,32768], realised sum {int(dec5.ctx_lens.sum())} tokens; "
+                        "both with the K/V write of their new tokens",
+            "chunked_prefill": {"flops": pre5.flops(), "ms": round(ms_a, 5),
+                                "roofline": {"bound": "mfma", "achieved": round(tf5, 2), "peak": PEAK_BF16_TFLOPS,
+                                             "unit": "TFLOP/s", "frac": round(tf5 / PEAK_BF16_TFLOPS, 4), "traffic": None}},
+            "decode": {"kv_bytes": dec5.kv_bytes(), "ms": round(ms_b, 5),
+                       "roofline": {"bound": "hbm", "achieved": round(gb5, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                    "frac": round(gb5 / PEAK_HBM_GBPS, 4), "traffic": None}},
+            "back_to_back_ms": round(ms_ab, 5)}
+        log(f"[bench] mixed cfg5: chunk {ms_a * 1e3:.1f} us ({tf5:.1f} TFLOP/s, {tf5 / PEAK_BF16_TFLOPS:.1%}), decode "
+            f"{ms_b * 1e3:.1f} us ({gb5:.0f} GB/s, {gb5 / PEAK_HBM_GBPS:.1%}), back to back {ms_ab * 1e3:.1f} us")
+        del cache5, wp5, wd5
 
     # ---- what the chip attains on the two priced resources (context for the roofline fractions) -------------
     if not args.no_extras:
