@@ -160,11 +160,31 @@ int shiftattn_decode(const void *q, const void *k_new, const void *v_new, const 
                      int32_t max_seq_len, void *out, void *workspace, size_t workspace_bytes,
                      const shiftattn_attn *a, void *stream);
 
+/* ---- Algorithm 1, boxed line, on a unified batch: prefill chunks and decode rows in one call ------
+ * A chunked-prefill engine (Sec. 5, related work on chunked prefill) puts both kinds of rows into one
+ * batch.  Sequences 0 .. num_prefill_seqs-1 carry the chunks (any q_len, described by cu_seqlens_q
+ * [num_prefill_seqs + 1]); the num_decode_seqs sequences after them carry one new token each.
+ * Row order of q, out, k_new, v_new, slot_mapping: the total_prefill_q rows of the chunks, then one
+ * row per decode sequence.  block_table and seq_lens cover all sequences in that order.
+ * The K/V of all rows is written once, then each kind of row runs through its kernel; the result is
+ * the same as shiftattn_prefill on the first part followed by shiftattn_decode on the second.
+ * max_prefill_seq_len / max_decode_seq_len bound seq_lens of the two parts.  The workspace is shared
+ * by the two parts: at least shiftattn_mixed_workspace_bytes(...).  Either part may be empty. */
+int shiftattn_mixed(const void *q, const void *k_new, const void *v_new, const int64_t *slot_mapping,
+                    void *kv_cache, const int32_t *block_table, const int32_t *cu_seqlens_q,
+                    const int32_t *seq_lens, int32_t num_prefill_seqs, int32_t total_prefill_q,
+                    int32_t max_q_len, int32_t max_prefill_seq_len, int32_t num_decode_seqs,
+                    int32_t max_decode_seq_len, void *out, void *workspace, size_t workspace_bytes,
+                    const shiftattn_attn *a, void *stream);
+
 /* Workspace sizes (host only, no GPU work).  Return 0 when no workspace is needed; SIZE_MAX on
  * invalid arguments. */
 size_t shiftattn_prefill_workspace_bytes(int32_t num_seqs, int32_t total_q, int32_t max_q_len,
                                          int32_t max_seq_len, const shiftattn_attn *a);
 size_t shiftattn_decode_workspace_bytes(int32_t num_seqs, int32_t max_seq_len, const shiftattn_attn *a);
+size_t shiftattn_mixed_workspace_bytes(int32_t num_prefill_seqs, int32_t total_prefill_q, int32_t max_q_len,
+                                       int32_t max_prefill_seq_len, int32_t num_decode_seqs,
+                                       int32_t max_decode_seq_len, const shiftattn_attn *a);
 
 /* ---- Host-side index helpers (no GPU work) -------------------------------------------------------
  * Head block held by global rank `rank` in base configuration (SP=sp, TP=tp): TP groups are runs

@@ -61,6 +61,9 @@ def lib() -> ctypes.CDLL:
         L.shiftattn_prefill_workspace_bytes.restype = sz
         L.shiftattn_decode_workspace_bytes.argtypes = [i32, i32, ap]
         L.shiftattn_decode_workspace_bytes.restype = sz
+        L.shiftattn_mixed.argtypes = [vp, vp, vp, i64p, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, sz, ap, vp]
+        L.shiftattn_mixed_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, ap]
+        L.shiftattn_mixed_workspace_bytes.restype = sz
         L.shiftattn_head_block.argtypes = [i32, i32, i32]
         L.shiftattn_head_block.restype = i32
         L.shiftattn_kv_head_of_block.argtypes = [i32, i32, i32]
@@ -237,6 +240,36 @@ def decode(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, s
     _check(lib().shiftattn_decode(_ptr(q), _ptr(k_new), _ptr(v_new), _ptr(slot_mapping), _ptr(kv_cache),
                                   _ptr(block_table), _ptr(seq_lens), num_seqs, max_seq_len, _ptr(out),
                                   _ptr(workspace), ws_bytes, ctypes.byref(a), _stream()))
+
+
+def mixed_workspace_bytes(num_prefill_seqs: int, total_prefill_q: int, max_q_len: int, max_prefill_seq_len: int,
+                          num_decode_seqs: int, max_decode_seq_len: int, a: Attn) -> int:
+    return int(lib().shiftattn_mixed_workspace_bytes(num_prefill_seqs, total_prefill_q, max_q_len, max_prefill_seq_len,
+                                                     num_decode_seqs, max_decode_seq_len, ctypes.byref(a)))
+
+
+def mixed(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, cu_seqlens_q: torch.Tensor,
+          seq_lens: torch.Tensor, num_prefill_seqs: int, max_q_len: int, max_prefill_seq_len: int,
+          max_decode_seq_len: int, out: torch.Tensor, softmax_scale: float, k_new: Optional[torch.Tensor] = None,
+          v_new: Optional[torch.Tensor] = None, slot_mapping: Optional[torch.Tensor] = None,
+          workspace: Optional[torch.Tensor] = None) -> None:
+    """Unified batch: the first num_prefill_seqs sequences are chunks (cu_seqlens_q [num_prefill_seqs + 1]), the
+    others carry one row each; q/out hold the chunk rows first, then the decode rows."""
+    num_decode_seqs = seq_lens.shape[0] - num_prefill_seqs
+    total_prefill_q = q.shape[0] - num_decode_seqs
+    assert num_decode_seqs >= 0 and total_prefill_q >= 0 and cu_seqlens_q.shape[0] == num_prefill_seqs + 1
+    assert cu_seqlens_q.dtype == torch.int32 and seq_lens.dtype == torch.int32
+    assert out.shape == q.shape and out.dtype == q.dtype and block_table.shape[0] == seq_lens.shape[0]
+    a = attn_desc(q, kv_cache, block_table, softmax_scale, k_new, out)
+    need = mixed_workspace_bytes(num_prefill_seqs, total_prefill_q, max_q_len, max_prefill_seq_len, num_decode_seqs,
+                                 max_decode_seq_len, a)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().shiftattn_mixed(_ptr(q), _ptr(k_new), _ptr(v_new), _ptr(slot_mapping), _ptr(kv_cache), _ptr(block_table),
+                                 _ptr(cu_seqlens_q), _ptr(seq_lens), num_prefill_seqs, total_prefill_q, max_q_len,
+                                 max_prefill_seq_len, num_decode_seqs, max_decode_seq_len, _ptr(out), _ptr(workspace),
+                                 ws_bytes, ctypes.byref(a), _stream()))
 
 
 # ---- numpy <-> device helpers for tests and benchmarks (storage only) ------------------------------------

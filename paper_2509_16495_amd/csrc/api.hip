@@ -289,4 +289,56 @@ int shiftattn_decode(const void* q, const void* k_new, const void* v_new, const 
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "decode launch");
 }
 
+size_t shiftattn_mixed_workspace_bytes(int32_t num_prefill_seqs, int32_t total_prefill_q, int32_t max_q_len,
+                                       int32_t max_prefill_seq_len, int32_t num_decode_seqs, int32_t max_decode_seq_len,
+                                       const shiftattn_attn* a) {
+    const size_t wp = shiftattn_prefill_workspace_bytes(num_prefill_seqs, total_prefill_q, max_q_len, max_prefill_seq_len, a);
+    const size_t wd = shiftattn_decode_workspace_bytes(num_decode_seqs, max_decode_seq_len, a);
+    if (wp == SIZE_MAX || wd == SIZE_MAX) return SIZE_MAX;
+    return wp > wd ? wp : wd;
+}
+
+int shiftattn_mixed(const void* q, const void* k_new, const void* v_new, const int64_t* slot_mapping, void* kv_cache,
+                    const int32_t* block_table, const int32_t* cu_seqlens_q, const int32_t* seq_lens,
+                    int32_t num_prefill_seqs, int32_t total_prefill_q, int32_t max_q_len, int32_t max_prefill_seq_len,
+                    int32_t num_decode_seqs, int32_t max_decode_seq_len, void* out, void* workspace,
+                    size_t workspace_bytes, const shiftattn_attn* a, void* stream) {
+    AttnShape s;
+    if (int rc = check_attn(a, &s)) return rc;
+    if (num_prefill_seqs < 0 || total_prefill_q < 0 || max_q_len < 0 || max_prefill_seq_len < 0 || num_decode_seqs < 0 ||
+        max_decode_seq_len < 0)
+        return fail(SHIFTATTN_EINVAL, "negative size argument");
+    if (num_prefill_seqs == 0 && total_prefill_q != 0)
+        return fail(SHIFTATTN_EINVAL, "total_prefill_q = %d without prefill sequences", total_prefill_q);
+    bool new_kv;
+    if (int rc = check_new_kv(k_new, v_new, slot_mapping, &new_kv)) return rc;
+    const int64_t rows = static_cast<int64_t>(total_prefill_q) + num_decode_seqs;
+    if (rows > INT32_MAX) return fail(SHIFTATTN_EINVAL, "batch of %lld rows is too large", static_cast<long long>(rows));
+    if (rows == 0) return SHIFTATTN_OK;
+    if (!q || !kv_cache || !block_table || !seq_lens || !out || (num_prefill_seqs > 0 && !cu_seqlens_q))
+        return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    const size_t need = shiftattn_mixed_workspace_bytes(num_prefill_seqs, total_prefill_q, max_q_len, max_prefill_seq_len,
+                                                        num_decode_seqs, max_decode_seq_len, a);
+    if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace)))
+        return fail(SHIFTATTN_EWORKSPACE, "mixed batch needs %zu workspace bytes, got %zu", need,
+                    workspace ? workspace_bytes : static_cast<size_t>(0));
+    if (new_kv) {
+        if (!aligned16(kv_cache)) return fail(SHIFTATTN_EINVAL, "kv_cache must be 16-byte aligned");
+        hipError_t e = launch_kv_write(k_new, v_new, slot_mapping, static_cast<int>(rows), kv_cache, s,
+                                       static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return hip_fail(e, "kv_write launch");
+    }
+    // the two kinds of rows go to the kernel built for each; both read the cache written above
+    if (int rc = shiftattn_prefill(q, nullptr, nullptr, nullptr, kv_cache, block_table, cu_seqlens_q, seq_lens,
+                                   num_prefill_seqs, total_prefill_q, max_q_len, max_prefill_seq_len, out, workspace,
+                                   workspace_bytes, a, stream))
+        return rc;
+    const size_t q_off = static_cast<size_t>(total_prefill_q) * s.q_stride * s.elem;
+    const size_t o_off = static_cast<size_t>(total_prefill_q) * s.out_stride * s.elem;
+    return shiftattn_decode(static_cast<const char*>(q) + q_off, nullptr, nullptr, nullptr, kv_cache,
+                            block_table + static_cast<size_t>(num_prefill_seqs) * s.max_blocks, seq_lens + num_prefill_seqs,
+                            num_decode_seqs, max_decode_seq_len, static_cast<char*>(out) + o_off, workspace, workspace_bytes,
+                            a, stream);
+}
+
 }  // extern "C"

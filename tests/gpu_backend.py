@@ -102,3 +102,25 @@ def decode_case(case, cache: torch.Tensor, fused_new_kv: bool = False) -> np.nda
              int(case.ctx_lens.max()) if case.num_seqs else 0, out, case.softmax_scale, **kw)
     torch.cuda.synchronize()
     return B.to_host(out)
+
+
+def mixed_case(case, n_prefill: int, cache: torch.Tensor, fused_new_kv: bool = True) -> np.ndarray:
+    """shiftattn_mixed on a case whose first n_prefill sequences are chunks and whose others have one new token."""
+    assert np.all(case.q_lens[n_prefill:] == 1)
+    dt = case.dtype
+    out = torch.empty((case.total_q, case.hq_l, case.D), dtype=torch_dtype(dt), device=DEV)
+    kw = {}
+    if fused_new_kv:
+        fused = np.concatenate([case.q, case.k_ctx[case.new_token_index], case.v_ctx[case.new_token_index]], axis=1)
+        ft = t(fused, dt)
+        q = ft[:, :case.hq_l]
+        kw = dict(k_new=ft[:, case.hq_l:case.hq_l + case.hkv_l], v_new=ft[:, case.hq_l + case.hkv_l:],
+                  slot_mapping=ti(case.slots[case.new_token_index], np.int64))
+    else:
+        q = t(case.q, dt)
+    pre_q, pre_ctx, dec_ctx = case.q_lens[:n_prefill], case.ctx_lens[:n_prefill], case.ctx_lens[n_prefill:]
+    B.mixed(q, cache, ti(case.block_table, np.int32), ti(case.cu_seqlens_q[:n_prefill + 1], np.int32),
+            ti(case.ctx_lens, np.int32), n_prefill, int(pre_q.max()) if n_prefill else 0,
+            int(pre_ctx.max()) if n_prefill else 0, int(dec_ctx.max()) if len(dec_ctx) else 0, out, case.softmax_scale, **kw)
+    torch.cuda.synchronize()
+    return B.to_host(out)

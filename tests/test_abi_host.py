@@ -155,6 +155,19 @@ def test_attention_entry_points_reject_bad_arguments(B):
     # empty batches are valid no-ops
     assert prefill(ok, q=None, cache=None, table=None, cu=None, sl=None, out=None, S=0, tq=0, mq=0, ms=0) == B.OK
     assert decode(ok, q=None, cache=None, table=None, sl=None, out=None, S=0, ms=0) == B.OK
+    # unified batch: same checks, plus its own
+    def mixed(a, q=FAKE, k=None, v=None, slots=None, cache=FAKE, table=FAKE, cu=FAKE, sl=FAKE, Sp=1, tq=32, mq=32, msp=64,
+              Sd=4, msd=64, out=FAKE, ws=None, wsb=0):
+        return L.shiftattn_mixed(q, k, v, slots, cache, table, cu, sl, Sp, tq, mq, msp, Sd, msd, out, ws, wsb,
+                                 None if a is None else ctypes.byref(a), None)
+
+    assert mixed(None) == B.EINVAL and mixed(ok, Sd=-1) == B.EINVAL and mixed(ok, Sp=0, tq=32) == B.EINVAL
+    assert mixed(ok, q=None) == B.EINVAL and mixed(ok, cu=None) == B.EINVAL and mixed(ok, k=FAKE) == B.EINVAL
+    assert mixed(ok) == B.EWORKSPACE  # the decode part needs one
+    assert B.mixed_workspace_bytes(1, 32, 32, 64, 4, 64, ok) == B.decode_workspace_bytes(4, 64, ok)
+    assert B.mixed_workspace_bytes(1, 2048, 2048, 133120, 4, 64, long_ctx) == \
+        max(B.prefill_workspace_bytes(1, 2048, 2048, 133120, long_ctx), B.decode_workspace_bytes(4, 64, long_ctx))
+    assert mixed(ok, q=None, cache=None, table=None, cu=None, sl=None, out=None, Sp=0, tq=0, mq=0, msp=0, Sd=0, msd=0) == B.OK
     kvw = L.shiftattn_kv_write
     assert kvw(None, FAKE, FAKE, 4, FAKE, ctypes.byref(ok), None) == B.EINVAL
     assert kvw(FAKE, FAKE, FAKE, -1, FAKE, ctypes.byref(ok), None) == B.EINVAL

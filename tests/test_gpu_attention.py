@@ -201,6 +201,35 @@ def test_config4_batch_decode_full(oracle, G):
     _check(got, want, "bf16")
 
 
+@pytest.mark.parametrize("dtype,D,hq,hkv", [("bf16", 128, 8, 1), ("bf16", 128, 4, 2), ("f32", 64, 4, 1)])
+def test_mixed_batch_one_call(oracle, G, dtype, D, hq, hkv):
+    """Chunks and decode rows in one call: same results and same cache as the oracle's write-then-attend, with either
+    part empty as well."""
+    from paper_2509_16495_amd import binding as B
+    chunks = [(70, 70), (33, 200), (0, 5), (1, 1), (128, 300)]
+    decodes = [(1, 1), (1, 17), (1, 250), (1, 64), (1, 1000), (1, 33)]
+    for seqs, n_pre in ((chunks + decodes, len(chunks)), (chunks, len(chunks)), (decodes, 0)):
+        case = W.make_attn_case("mixed_small", 77, dtype, seqs, hq, hkv, D, pool_factor=1.5)
+        ocache = oracle.cache_for_case(case)
+        cache = G.cache_for_case(case, only_cached=True)
+        got = G.mixed_case(case, n_pre, cache)
+        assert B.to_host(cache).tobytes() == ocache.tobytes()
+        _check(got, oracle.attention_case(case, ocache), dtype)
+
+
+def test_config5_mixed_step_one_call(oracle, G):
+    """The long-context step through the unified entry point."""
+    from paper_2509_16495_amd import binding as B
+    case, n_prefill = W.config5_attn()
+    ocache = oracle.cache_for_case(case)
+    cache = G.cache_for_case(case, only_cached=True)
+    got = G.mixed_case(case, n_prefill, cache)
+    assert B.to_host(cache).tobytes() == ocache.tobytes()
+    n_chunk = int(case.q_lens[:n_prefill].sum())
+    rows = np.concatenate([_sample_rows(W.sub_case(case, range(n_prefill)), 8, 5, edge=8), np.arange(n_chunk, case.total_q)])
+    _check(got[rows], oracle.attention_case(case, ocache, rows), "bf16")
+
+
 def test_config5_mixed_step(oracle, G):
     """One 2048-token chunk on a 131072-token cached context plus 64 decodes in one block pool; the new
     tokens' K/V are written by the calls themselves."""
