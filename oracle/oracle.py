@@ -24,8 +24,8 @@ _SRC = os.path.join(_HERE, "shiftattn_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
-DTYPE_CODE = {"bf16": 0, "f32": 1}
-_NP_STORE = {"bf16": np.uint16, "f32": np.float32}
+DTYPE_CODE = {"bf16": 0, "f32": 1, "fp8_e4m3": 2}
+_NP_STORE = {"bf16": np.uint16, "f32": np.float32, "fp8_e4m3": np.uint8}
 
 
 def build(force: bool = False) -> str:
@@ -49,6 +49,14 @@ def lib() -> ctypes.CDLL:
         L.oracle_unpack_head2seq.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32]
         L.oracle_kv_write.argtypes = [vp, vp, vp, i64, vp, i32, i32, i32, i32]
         L.oracle_attention.argtypes = [vp, vp, i32, vp, i32, vp, vp, i32, i32, i32, i32, i32, dbl, vp, i64, vp]
+        flt, u8 = ctypes.c_float, ctypes.c_uint8
+        L.oracle_kv_write_fp8.argtypes = [vp, vp, vp, i64, vp, i32, i32, i32, i32, flt, flt]
+        L.oracle_attention_kv.argtypes = [vp, i32, vp, i32, dbl, dbl, vp, i32, vp, vp, i32, i32, i32, i32, i32, dbl, vp,
+                                          i64, vp]
+        L.oracle_e4m3_value.argtypes = [u8]
+        L.oracle_e4m3_value.restype = dbl
+        L.oracle_e4m3_from_float.argtypes = [flt]
+        L.oracle_e4m3_from_float.restype = u8
         _lib = L
     return _lib
 
@@ -136,12 +144,37 @@ def kv_write(cache: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, slots: np.
     assert rc == 0
 
 
+def e4m3_value(code: int) -> float:
+    return float(lib().oracle_e4m3_value(int(code) & 0xFF))
+
+
+def e4m3_from_float(x: float) -> int:
+    return int(lib().oracle_e4m3_from_float(float(np.float32(x))))
+
+
+def kv_write_fp8(cache: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, slots: np.ndarray, B: int, src_dtype: str,
+                 k_scale: float, v_scale: float) -> None:
+    """Append into an FP8 E4M3 cache (uint8 [num_blocks, hkv_l, 2, B*D]); k_new/v_new stored in src_dtype."""
+    n, hkv_l, D = k_new.shape
+    k_new = np.ascontiguousarray(k_new, dtype=_NP_STORE[src_dtype])
+    v_new = np.ascontiguousarray(v_new, dtype=_NP_STORE[src_dtype])
+    slots = np.ascontiguousarray(slots, dtype=np.int64)
+    assert cache.dtype == np.uint8 and cache.flags.c_contiguous and cache.shape[1] == hkv_l and cache.shape[3] == B * D
+    rc = lib().oracle_kv_write_fp8(_p(k_new), _p(v_new), _p(slots), n, _p(cache), hkv_l, D, B, DTYPE_CODE[src_dtype],
+                                   float(k_scale), float(v_scale))
+    assert rc == 0
+
+
 # ---------------------------------------------------------------------------
 # attention (Algorithm 1 boxed line; Sec. 2.2)
 # ---------------------------------------------------------------------------
 def attention(q: np.ndarray, cache: np.ndarray, dtype: str, block_table: np.ndarray, cu_seqlens_q: np.ndarray,
               seq_lens: np.ndarray, hq_l: int, hkv_l: int, D: int, B: int, scale: float,
-              rows: Optional[np.ndarray] = None) -> np.ndarray:
+              rows: Optional[np.ndarray] = None, kv_dtype: Optional[str] = None, k_scale: float = 1.0,
+              v_scale: float = 1.0) -> np.ndarray:
+    """kv_dtype: how the cache is stored when it differs from q's type ("fp8_e4m3" with its two scales)."""
+    kv_dtype = kv_dtype or dtype
+    assert cache.dtype == _NP_STORE[kv_dtype]
     q = np.ascontiguousarray(q, dtype=_NP_STORE[dtype])
     block_table = np.ascontiguousarray(block_table, dtype=np.int32)
     cu = np.ascontiguousarray(cu_seqlens_q, dtype=np.int32)
@@ -155,26 +188,34 @@ def attention(q: np.ndarray, cache: np.ndarray, dtype: str, block_table: np.ndar
     out = np.zeros((n_rows, hq_l, D), dtype=np.float64)
     if n_rows == 0:
         return out
-    rc = lib().oracle_attention(_p(q), _p(cache), DTYPE_CODE[dtype], _p(block_table), block_table.shape[1],
-                                _p(cu), _p(sl), S, hq_l, hkv_l, D, B, float(scale), _p(rows), n_rows, _p(out))
+    rc = lib().oracle_attention_kv(_p(q), DTYPE_CODE[dtype], _p(cache), DTYPE_CODE[kv_dtype], float(k_scale),
+                                   float(v_scale), _p(block_table), block_table.shape[1], _p(cu), _p(sl), S, hq_l, hkv_l,
+                                   D, B, float(scale), _p(rows), n_rows, _p(out))
     assert rc == 0, "oracle_attention: inconsistent arguments"
     return out
 
 
-def attention_case(case, cache: np.ndarray, rows: Optional[np.ndarray] = None) -> np.ndarray:
-    """Attention for a workloads.AttnCase over an already written cache."""
+def attention_case(case, cache: np.ndarray, rows: Optional[np.ndarray] = None, k_scale: float = 1.0,
+                   v_scale: float = 1.0) -> np.ndarray:
+    """Attention for a workloads.AttnCase over an already written cache (a uint8 cache is read as FP8 E4M3)."""
+    kv_dtype = "fp8_e4m3" if cache.dtype == np.uint8 else case.dtype
     return attention(case.q, cache, case.dtype, case.block_table, case.cu_seqlens_q, case.ctx_lens,
-                     case.hq_l, case.hkv_l, case.D, case.block_size, case.softmax_scale, rows)
+                     case.hq_l, case.hkv_l, case.D, case.block_size, case.softmax_scale, rows, kv_dtype, k_scale, v_scale)
 
 
-def cache_for_case(case, only_cached: bool = False) -> np.ndarray:
+def cache_for_case(case, only_cached: bool = False, fp8_scales: Optional[Sequence[float]] = None) -> np.ndarray:
     """Sentinel-filled cache with the case's context written through kv_write.
-    only_cached=True leaves out the new tokens (their K/V arrive with the call under test)."""
-    cache = new_cache(case.num_blocks, case.hkv_l, case.block_size, case.D, case.dtype)
+    only_cached=True leaves out the new tokens (their K/V arrive with the call under test).
+    fp8_scales=(k_scale, v_scale): an FP8 E4M3 cache instead of one in the case's own type."""
     slots = case.slots
     if only_cached:
         slots = slots.copy()
         slots[case.new_token_index] = -1
+    if fp8_scales is not None:
+        cache = new_cache(case.num_blocks, case.hkv_l, case.block_size, case.D, "fp8_e4m3")
+        kv_write_fp8(cache, case.k_ctx, case.v_ctx, slots, case.block_size, case.dtype, fp8_scales[0], fp8_scales[1])
+        return cache
+    cache = new_cache(case.num_blocks, case.hkv_l, case.block_size, case.D, case.dtype)
     kv_write(cache, case.k_ctx, case.v_ctx, slots, case.block_size, case.dtype)
     return cache
 

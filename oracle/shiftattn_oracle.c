@@ -30,6 +30,17 @@
  * is K stored token-major  K[off][d]  and part 1 is V stored dimension-major
  * V[d][off]  (off = token offset in the block).
  *
+ * FP8 KV cache (Sec. 4.1 names an FP8 KV cache for the long-trace experiment and
+ * gives no format or scale rule; the convention below is this build's - parity
+ * against the paper's own system is unpinned for it):  cache bytes are OCP
+ * FP8 E4M3 codes (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no
+ * infinities, S.1111.111 = NaN, largest finite 448) in the same K token-major /
+ * V dimension-major arrangement; a stored value stands for code_value * scale
+ * with one float scale for K and one for V; the writer takes x / scale in
+ * float32 (round to nearest) and rounds that to the nearest E4M3 value, ties to
+ * the even code, magnitudes beyond 448 saturating to 448.  Attention over such a
+ * cache is the same definition over the values the codes stand for.
+ *
  * Parity pins live in tests/test_oracle_*.py (brute force, closed forms,
  * library cross-checks, the paper's worked examples).
  */
@@ -41,10 +52,42 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_BF16 = 0, ORACLE_F32 = 1 };
+enum { ORACLE_BF16 = 0, ORACLE_F32 = 1, ORACLE_FP8_E4M3 = 2 };
+
+/* value of an E4M3 code: exponent field 0 is subnormal (m/8 * 2^-6), field 15 with mantissa 7 is NaN */
+double oracle_e4m3_value(uint8_t code)
+{
+    int e = (code >> 3) & 15, m = code & 7;
+    double mag;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0)
+        mag = ldexp((double)m / 8.0, -6);
+    else
+        mag = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return (code & 0x80) ? -mag : mag;
+}
+
+/* nearest E4M3 code of a float: search the 127 finite magnitudes (codes 0x00..0x7e ascend with their
+ * values), take the closer neighbour, the even code on a tie, 0x7e (448) beyond the range */
+uint8_t oracle_e4m3_from_float(float f)
+{
+    uint8_t sign = signbit(f) ? 0x80 : 0x00;
+    double a = fabs((double)f);
+    int lo = 0;
+    if (isnan(f)) return (uint8_t)(sign | 0x7f);
+    if (a >= 448.0) return (uint8_t)(sign | 0x7e);
+    while (lo < 0x7e && oracle_e4m3_value((uint8_t)(lo + 1)) <= a) ++lo; /* value(lo) <= a < value(lo+1) */
+    {
+        double below = a - oracle_e4m3_value((uint8_t)lo), above = oracle_e4m3_value((uint8_t)(lo + 1)) - a;
+        int pick = lo;
+        if (above < below || (above == below && (lo & 1))) pick = lo + 1;
+        return (uint8_t)(sign | pick);
+    }
+}
 
 static double widen(const void *base, size_t idx, int dtype)
 {
+    if (dtype == ORACLE_FP8_E4M3) return oracle_e4m3_value(((const uint8_t *)base)[idx]);
     if (dtype == ORACLE_BF16) {
         uint32_t bits = ((uint32_t)((const uint16_t *)base)[idx]) << 16;
         float f;
@@ -54,7 +97,7 @@ static double widen(const void *base, size_t idx, int dtype)
     return (double)((const float *)base)[idx];
 }
 
-static size_t esize_of(int dtype) { return dtype == ORACLE_BF16 ? 2 : 4; }
+static size_t esize_of(int dtype) { return dtype == ORACLE_BF16 ? 2 : (dtype == ORACLE_FP8_E4M3 ? 1 : 4); }
 
 /* element index of K[token offset `off`][d] of KV head g in cache block `blk` */
 static size_t k_elem(int64_t blk, int g, int off, int d, int hkv_l, int B, int D)
@@ -175,6 +218,30 @@ int oracle_kv_write(const void *k_new, const void *v_new, const int64_t *slot_ma
     return 0;
 }
 
+/* Append into an FP8 E4M3 cache: element x of k_new (stored in `src_dtype`) becomes the code nearest to
+ * x / k_scale, the division taken in float32; v_new likewise with v_scale.  Same slots, same arrangement. */
+int oracle_kv_write_fp8(const void *k_new, const void *v_new, const int64_t *slot_mapping, int64_t n,
+                        void *kv_cache, int hkv_l, int D, int B, int src_dtype, float k_scale, float v_scale)
+{
+    uint8_t *c = (uint8_t *)kv_cache;
+    if (!(k_scale > 0.0f) || !(v_scale > 0.0f)) return -1;
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t slot = slot_mapping[i];
+        if (slot < 0) continue;
+        int64_t blk = slot / B;
+        int off = (int)(slot % B);
+        for (int g = 0; g < hkv_l; ++g)
+            for (int d = 0; d < D; ++d) {
+                size_t s = ((size_t)i * hkv_l + g) * D + d;
+                float kx = (float)widen(k_new, s, src_dtype), vx = (float)widen(v_new, s, src_dtype);
+                volatile float kq = kx / k_scale, vq = vx / v_scale; /* float32 quotients, not kept wider */
+                c[k_elem(blk, g, off, d, hkv_l, B, D)] = oracle_e4m3_from_float(kq);
+                c[v_elem(blk, g, off, d, hkv_l, B, D)] = oracle_e4m3_from_float(vq);
+            }
+    }
+    return 0;
+}
+
 /* ---------------------------------------------------------------------------
  * Attention of the local head shard over the paged cache (Algorithm 1, boxed
  * line; Sec. 2.2).  For sequence s with q_len new tokens out of ctx total,
@@ -190,10 +257,27 @@ int oracle_kv_write(const void *k_new, const void *v_new, const int64_t *slot_ma
  *       out is [n_rows][hq_l][D] doubles in the order of `rows`.
  * Returns 0, or -1 on inconsistent arguments.
  * ------------------------------------------------------------------------- */
+int oracle_attention_kv(const void *q, int dtype, const void *kv_cache, int kv_dtype, double k_scale,
+                        double v_scale, const int32_t *block_table, int max_blocks_per_seq,
+                        const int32_t *cu_seqlens_q, const int32_t *seq_lens, int num_seqs, int hq_l, int hkv_l,
+                        int D, int B, double scale, const int64_t *rows, int64_t n_rows, double *out);
+
+/* cache stored in the same type as q, values as stored */
 int oracle_attention(const void *q, const void *kv_cache, int dtype, const int32_t *block_table,
                      int max_blocks_per_seq, const int32_t *cu_seqlens_q, const int32_t *seq_lens,
                      int num_seqs, int hq_l, int hkv_l, int D, int B, double scale, const int64_t *rows,
                      int64_t n_rows, double *out)
+{
+    return oracle_attention_kv(q, dtype, kv_cache, dtype, 1.0, 1.0, block_table, max_blocks_per_seq, cu_seqlens_q,
+                               seq_lens, num_seqs, hq_l, hkv_l, D, B, scale, rows, n_rows, out);
+}
+
+/* cache stored in `kv_dtype`; a stored K element stands for its value times k_scale, a V element for its
+ * value times v_scale (both 1 for an unquantised cache) */
+int oracle_attention_kv(const void *q, int dtype, const void *kv_cache, int kv_dtype, double k_scale,
+                        double v_scale, const int32_t *block_table, int max_blocks_per_seq,
+                        const int32_t *cu_seqlens_q, const int32_t *seq_lens, int num_seqs, int hq_l, int hkv_l,
+                        int D, int B, double scale, const int64_t *rows, int64_t n_rows, double *out)
 {
     int64_t total_q = num_seqs ? cu_seqlens_q[num_seqs] : 0;
     int group = hq_l / hkv_l;
@@ -225,7 +309,7 @@ int oracle_attention(const void *q, const void *kv_cache, int dtype, const int32
             double dot = 0.0;
             for (int d = 0; d < D; ++d)
                 dot += widen(q, ((size_t)tok * hq_l + j) * D + d, dtype) *
-                       widen(kv_cache, k_elem(blk, g, t % B, d, hkv_l, B, D), dtype);
+                       (k_scale * widen(kv_cache, k_elem(blk, g, t % B, d, hkv_l, B, D), kv_dtype));
             logit[t] = scale * dot;
             if (logit[t] > top) top = logit[t];
         }
@@ -239,7 +323,7 @@ int oracle_attention(const void *q, const void *kv_cache, int dtype, const int32
             int64_t blk = table[t / B];
             double p = logit[t] / denom;
             for (int d = 0; d < D; ++d)
-                o[d] += p * widen(kv_cache, v_elem(blk, g, t % B, d, hkv_l, B, D), dtype);
+                o[d] += p * (v_scale * widen(kv_cache, v_elem(blk, g, t % B, d, hkv_l, B, D), kv_dtype));
         }
         free(logit);
     }
