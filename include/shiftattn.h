@@ -39,6 +39,13 @@
  *   with offset = token position % block_size.  Slot id = block * block_size + offset.
  *   block_size is 16.  block_table[s][i] is the cache block of tokens [16 i, 16 i + 16) of
  *   sequence s; entries past the sequence's last block are never read.
+ *
+ * FP8 KV cache (kv_format = SHIFTATTN_KV_FP8_E4M3; Sec. 4.1 runs its long-trace experiment with
+ * an FP8 KV cache and gives no format or scale rule - the rule here is this library's): the same
+ * arrangement with one byte per element, an OCP FP8 E4M3 code (bias 7, no infinities, largest
+ * finite 448).  A stored element stands for code_value * k_scale (K) or code_value * v_scale (V).
+ * The writer computes x / scale in float32 and rounds to the nearest code, ties to the even code,
+ * magnitudes beyond 448 saturating; NaN gives a NaN code.  q, k_new, v_new and out keep `dtype`.
  */
 #ifndef SHIFTATTN_H
 #define SHIFTATTN_H
@@ -59,6 +66,7 @@ enum {
 };
 
 enum { SHIFTATTN_BF16 = 0, SHIFTATTN_F32 = 1 };
+enum { SHIFTATTN_KV_SAME = 0 /* cache elements have `dtype` */, SHIFTATTN_KV_FP8_E4M3 = 1 };
 
 /* One sequence<->head exchange among P ranks (Algorithm 1: P is the SP degree of the base
  * configuration; h and h_kv are the heads a source rank holds, i.e. model heads / TP). */
@@ -87,6 +95,10 @@ typedef struct shiftattn_attn {
     int64_t q_stride;           /* elements between consecutive tokens of q;   0 = hq_l*D (dense)  */
     int64_t kv_stride;          /* same for k_new and v_new;                   0 = hkv_l*D         */
     int64_t out_stride;         /* same for out;                               0 = hq_l*D          */
+    int32_t kv_format;          /* SHIFTATTN_KV_SAME | SHIFTATTN_KV_FP8_E4M3 (needs head_dim % 16 == 0) */
+    float k_scale;              /* FP8 cache only: value of a K element = code value * k_scale, > 0 */
+    float v_scale;              /* FP8 cache only: same for V                                      */
+    int32_t reserved;           /* must be 0                                                       */
 } shiftattn_attn;
 /* Strides let q, k_new and v_new be views into one fused receive buffer
  * [n_pad][hq_l + 2*hkv_l][D]: q = buf, k_new = buf + hq_l*D, v_new = buf + (hq_l+hkv_l)*D,

@@ -37,7 +37,12 @@ class Attn(ctypes.Structure):
     _fields_ = [("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("block_size", ctypes.c_int32), ("num_blocks", ctypes.c_int32),
                 ("max_blocks_per_seq", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
-                ("q_stride", ctypes.c_int64), ("kv_stride", ctypes.c_int64), ("out_stride", ctypes.c_int64)]
+                ("q_stride", ctypes.c_int64), ("kv_stride", ctypes.c_int64), ("out_stride", ctypes.c_int64),
+                ("kv_format", ctypes.c_int32), ("k_scale", ctypes.c_float), ("v_scale", ctypes.c_float),
+                ("reserved", ctypes.c_int32)]
+
+
+KV_SAME, KV_FP8_E4M3 = 0, 1
 
 
 _lib: Optional[ctypes.CDLL] = None
@@ -170,14 +175,17 @@ def unpack_head2seq(recv: torch.Tensor, out: torch.Tensor) -> None:
 
 # ---- KV cache and attention -------------------------------------------------------------------------
 def attn_desc(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, softmax_scale: float,
-              k_new: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> Attn:
-    """Descriptor from tensor shapes.  kv_cache is [num_blocks, hkv_l, 2, 16*D]."""
+              k_new: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None, k_scale: float = 1.0,
+              v_scale: float = 1.0) -> Attn:
+    """Descriptor from tensor shapes.  kv_cache is [num_blocks, hkv_l, 2, 16*D] in q's type, or uint8 for an
+    FP8 E4M3 cache (then k_scale / v_scale give the value of a code)."""
     hq_l, D = q.shape[1], q.shape[2]
     num_blocks, hkv_l, two, bd = kv_cache.shape
-    assert two == 2 and bd == BLOCK_SIZE * D and kv_cache.is_contiguous() and kv_cache.dtype == q.dtype
+    fp8 = kv_cache.dtype == torch.uint8
+    assert two == 2 and bd == BLOCK_SIZE * D and kv_cache.is_contiguous() and (fp8 or kv_cache.dtype == q.dtype)
     assert block_table.dtype == torch.int32 and block_table.dim() == 2 and block_table.is_contiguous()
     a = Attn(hq_l, hkv_l, D, _dtype_code(q), BLOCK_SIZE, num_blocks, block_table.shape[1], float(softmax_scale),
-             _row_stride(q), 0, 0)
+             _row_stride(q), 0, 0, KV_FP8_E4M3 if fp8 else KV_SAME, float(k_scale), float(v_scale), 0)
     if k_new is not None:
         a.kv_stride = _row_stride(k_new)
     if out is not None:
@@ -185,13 +193,16 @@ def attn_desc(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor
     return a
 
 
-def kv_write(k_new: torch.Tensor, v_new: torch.Tensor, slot_mapping: torch.Tensor, kv_cache: torch.Tensor) -> None:
+def kv_write(k_new: torch.Tensor, v_new: torch.Tensor, slot_mapping: torch.Tensor, kv_cache: torch.Tensor,
+             k_scale: float = 1.0, v_scale: float = 1.0) -> None:
     n, hkv_l, D = k_new.shape
     assert v_new.shape == k_new.shape and slot_mapping.dtype == torch.int64 and slot_mapping.shape[0] == n
     assert _row_stride(v_new) == _row_stride(k_new)
     num_blocks = kv_cache.shape[0]
     assert kv_cache.shape[1:] == (hkv_l, 2, BLOCK_SIZE * D) and kv_cache.is_contiguous()
-    a = Attn(hkv_l, hkv_l, D, _dtype_code(k_new), BLOCK_SIZE, num_blocks, 0, 1.0, 0, _row_stride(k_new), 0)
+    fp8 = kv_cache.dtype == torch.uint8
+    a = Attn(hkv_l, hkv_l, D, _dtype_code(k_new), BLOCK_SIZE, num_blocks, 0, 1.0, 0, _row_stride(k_new), 0,
+             KV_FP8_E4M3 if fp8 else KV_SAME, float(k_scale), float(v_scale), 0)
     _check(lib().shiftattn_kv_write(_ptr(k_new), _ptr(v_new), _ptr(slot_mapping), n, _ptr(kv_cache), ctypes.byref(a),
                                     _stream()))
 
@@ -207,13 +218,14 @@ def decode_workspace_bytes(num_seqs: int, max_seq_len: int, a: Attn) -> int:
 def prefill(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, cu_seqlens_q: torch.Tensor,
             seq_lens: torch.Tensor, max_q_len: int, max_seq_len: int, out: torch.Tensor, softmax_scale: float,
             k_new: Optional[torch.Tensor] = None, v_new: Optional[torch.Tensor] = None,
-            slot_mapping: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> None:
+            slot_mapping: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, k_scale: float = 1.0,
+            v_scale: float = 1.0) -> None:
     """Causal attention of prefill chunks; q/out [total_q, hq_l, D] (row-strided views allowed)."""
     total_q = q.shape[0]
     num_seqs = seq_lens.shape[0]
     assert cu_seqlens_q.dtype == torch.int32 and seq_lens.dtype == torch.int32 and cu_seqlens_q.shape[0] == num_seqs + 1
     assert out.shape == q.shape and out.dtype == q.dtype
-    a = attn_desc(q, kv_cache, block_table, softmax_scale, k_new, out)
+    a = attn_desc(q, kv_cache, block_table, softmax_scale, k_new, out, k_scale, v_scale)
     need = prefill_workspace_bytes(num_seqs, total_q, max_q_len, max_seq_len, a)
     if need and workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
@@ -227,12 +239,12 @@ def prefill(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, 
 def decode(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, seq_lens: torch.Tensor,
            max_seq_len: int, out: torch.Tensor, softmax_scale: float, k_new: Optional[torch.Tensor] = None,
            v_new: Optional[torch.Tensor] = None, slot_mapping: Optional[torch.Tensor] = None,
-           workspace: Optional[torch.Tensor] = None) -> None:
+           workspace: Optional[torch.Tensor] = None, k_scale: float = 1.0, v_scale: float = 1.0) -> None:
     """One new token per sequence; q/out [num_seqs, hq_l, D]."""
     num_seqs = q.shape[0]
     assert seq_lens.dtype == torch.int32 and seq_lens.shape[0] == num_seqs
     assert out.shape == q.shape and out.dtype == q.dtype
-    a = attn_desc(q, kv_cache, block_table, softmax_scale, k_new, out)
+    a = attn_desc(q, kv_cache, block_table, softmax_scale, k_new, out, k_scale, v_scale)
     need = decode_workspace_bytes(num_seqs, max_seq_len, a)
     if need and workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
@@ -252,7 +264,7 @@ def mixed(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, cu
           seq_lens: torch.Tensor, num_prefill_seqs: int, max_q_len: int, max_prefill_seq_len: int,
           max_decode_seq_len: int, out: torch.Tensor, softmax_scale: float, k_new: Optional[torch.Tensor] = None,
           v_new: Optional[torch.Tensor] = None, slot_mapping: Optional[torch.Tensor] = None,
-          workspace: Optional[torch.Tensor] = None) -> None:
+          workspace: Optional[torch.Tensor] = None, k_scale: float = 1.0, v_scale: float = 1.0) -> None:
     """Unified batch: the first num_prefill_seqs sequences are chunks (cu_seqlens_q [num_prefill_seqs + 1]), the
     others carry one row each; q/out hold the chunk rows first, then the decode rows."""
     num_decode_seqs = seq_lens.shape[0] - num_prefill_seqs
@@ -260,7 +272,7 @@ def mixed(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, cu
     assert num_decode_seqs >= 0 and total_prefill_q >= 0 and cu_seqlens_q.shape[0] == num_prefill_seqs + 1
     assert cu_seqlens_q.dtype == torch.int32 and seq_lens.dtype == torch.int32
     assert out.shape == q.shape and out.dtype == q.dtype and block_table.shape[0] == seq_lens.shape[0]
-    a = attn_desc(q, kv_cache, block_table, softmax_scale, k_new, out)
+    a = attn_desc(q, kv_cache, block_table, softmax_scale, k_new, out, k_scale, v_scale)
     need = mixed_workspace_bytes(num_prefill_seqs, total_prefill_q, max_q_len, max_prefill_seq_len, num_decode_seqs,
                                  max_decode_seq_len, a)
     if need and workspace is None:

@@ -109,6 +109,19 @@ int check_attn(const shiftattn_attn* a, AttnShape* s) {
         return fail(SHIFTATTN_EINVAL, "a row stride is smaller than the row it strides over");
     if ((s->q_stride * e) % 16 || (s->kv_stride * e) % 16 || (s->out_stride * e) % 16)
         return fail(SHIFTATTN_EINVAL, "row strides must be multiples of 16 bytes");
+    s->kv_elem = e;
+    s->k_scale = s->v_scale = 1.f;
+    if (a->kv_format == SHIFTATTN_KV_FP8_E4M3) {
+        if (!(a->k_scale > 0.f) || !(a->v_scale > 0.f) || a->k_scale > 3.0e38f || a->v_scale > 3.0e38f)
+            return fail(SHIFTATTN_EINVAL, "k_scale and v_scale of an FP8 cache must be positive and finite");
+        if (a->head_dim % 16) return fail(SHIFTATTN_EUNSUPPORTED, "head_dim = %d: an FP8 cache needs a multiple of 16", a->head_dim);
+        s->kv_elem = 1;
+        s->k_scale = a->k_scale;
+        s->v_scale = a->v_scale;
+    } else if (a->kv_format != SHIFTATTN_KV_SAME) {
+        return fail(SHIFTATTN_EINVAL, "unknown kv_format %d", a->kv_format);
+    }
+    if (a->reserved != 0) return fail(SHIFTATTN_EINVAL, "reserved field must be 0");
     return 0;
 }
 

@@ -13,6 +13,8 @@ namespace {
 
 __device__ inline float to_float(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
 __device__ inline float to_float(float f) { return f; }
+// value of an FP8 E4M3 code (the scale is applied by the caller)
+__device__ inline float to_float(uint8_t c) { return __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c), false)[0]; }
 
 __device__ inline uint16_t bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
@@ -37,12 +39,12 @@ __device__ inline float wave_sum(float v) {
 constexpr int kWaves = 4;
 constexpr int kMaxD = 256;
 
-template <typename Elem>
+template <typename Elem, typename KvElem>
 __global__ __launch_bounds__(kWaves * 64) void attn_rows_kernel(
-    const Elem* __restrict__ q, const Elem* __restrict__ cache, const int32_t* __restrict__ block_table,
+    const Elem* __restrict__ q, const KvElem* __restrict__ cache, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ cu_seqlens_q, const int32_t* __restrict__ seq_lens, int num_seqs, int total_q,
     Elem* __restrict__ out, AttnShape a) {
-    constexpr int kPer = 16 / sizeof(Elem);  // elements per 16-byte vector
+    constexpr int kPer = 16 / sizeof(KvElem);  // cache elements per 16-byte vector
     __shared__ float q_s[kWaves][kMaxD];
     __shared__ float p_s[kWaves][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -81,15 +83,15 @@ __global__ __launch_bounds__(kWaves * 64) void attn_rows_kernel(
         float logit = -INFINITY;
         if (t <= pos) {
             const int64_t blk = table[t / kBlockSize];
-            const Elem* k_row = cache + cache_part_offset(blk, g, 0, a.hkv_l, D) + static_cast<size_t>(t % kBlockSize) * D;
+            const KvElem* k_row = cache + cache_part_offset(blk, g, 0, a.hkv_l, D) + static_cast<size_t>(t % kBlockSize) * D;
             float dot = 0.f;
             for (int dv = 0; dv < D / kPer; ++dv) {
-                union { u32x4 v; Elem e[kPer]; } u;
+                union { u32x4 v; KvElem e[kPer]; } u;
                 u.v = *reinterpret_cast<const u32x4*>(k_row + dv * kPer);
 #pragma unroll
                 for (int x = 0; x < kPer; ++x) dot = fmaf(q_s[wave][dv * kPer + x], to_float(u.e[x]), dot);
             }
-            logit = dot * a.scale;
+            logit = dot * (a.scale * a.k_scale);
         }
         const float m_new = fmaxf(m_run, wave_max(logit));  // finite: key t0 is always visible
         const float p = (t <= pos) ? expf(logit - m_new) : 0.f;
@@ -102,15 +104,15 @@ __global__ __launch_bounds__(kWaves * 64) void attn_rows_kernel(
         for (int x = 0; x < kMaxD / 64; ++x) o[x] *= alpha;
         for (int b = 0; b < 4 && t0 + b * kBlockSize <= pos; ++b) {
             const int64_t blk = table[(t0 + b * kBlockSize) / kBlockSize];
-            const Elem* v_part = cache + cache_part_offset(blk, g, 1, a.hkv_l, D);
+            const KvElem* v_part = cache + cache_part_offset(blk, g, 1, a.hkv_l, D);
 #pragma unroll
             for (int x = 0; x < kMaxD / 64; ++x) {
                 const int d = lane + 64 * x;
                 if (d < D) {
-                    const Elem* v_row = v_part + static_cast<size_t>(d) * kBlockSize;
+                    const KvElem* v_row = v_part + static_cast<size_t>(d) * kBlockSize;
 #pragma unroll
                     for (int vv = 0; vv < kBlockSize / kPer; ++vv) {
-                        union { u32x4 v; Elem e[kPer]; } u;
+                        union { u32x4 v; KvElem e[kPer]; } u;
                         u.v = *reinterpret_cast<const u32x4*>(v_row + vv * kPer);
 #pragma unroll
                         for (int y = 0; y < kPer; ++y) {
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(kWaves * 64) void attn_rows_kernel(
         __builtin_amdgcn_wave_barrier();
     }
     Elem* o_row = out + static_cast<size_t>(tok) * a.out_stride + static_cast<size_t>(j) * D;
-    const float inv = 1.f / l_run;
+    const float inv = a.v_scale / l_run;
 #pragma unroll
     for (int x = 0; x < kMaxD / 64; ++x) {
         const int d = lane + 64 * x;
@@ -300,15 +302,25 @@ hipError_t launch_attn_generic(const void* q, const void* cache, const int32_t* 
     const int64_t rows = static_cast<int64_t>(total_q) * a.hq_l;
     if (rows == 0) return hipSuccess;
     const unsigned grid = static_cast<unsigned>((rows + kWaves - 1) / kWaves);
-    if (a.elem == 2)
-        attn_rows_kernel<uint16_t><<<grid, kWaves * 64, 0, st>>>(
+    if (a.kv_fp8()) {
+        if (a.elem == 2)
+            attn_rows_kernel<uint16_t, uint8_t><<<grid, kWaves * 64, 0, st>>>(
+                static_cast<const uint16_t*>(q), static_cast<const uint8_t*>(cache), block_table, cu_seqlens_q, seq_lens,
+                num_seqs, total_q, static_cast<uint16_t*>(out), a);
+        else
+            attn_rows_kernel<float, uint8_t><<<grid, kWaves * 64, 0, st>>>(
+                static_cast<const float*>(q), static_cast<const uint8_t*>(cache), block_table, cu_seqlens_q, seq_lens,
+                num_seqs, total_q, static_cast<float*>(out), a);
+    } else if (a.elem == 2) {
+        attn_rows_kernel<uint16_t, uint16_t><<<grid, kWaves * 64, 0, st>>>(
             static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(cache), block_table, cu_seqlens_q, seq_lens,
             num_seqs, total_q, static_cast<uint16_t*>(out), a);
-    else
-        attn_rows_kernel<float><<<grid, kWaves * 64, 0, st>>>(static_cast<const float*>(q),
-                                                            static_cast<const float*>(cache), block_table,
-                                                            cu_seqlens_q, seq_lens, num_seqs, total_q,
-                                                            static_cast<float*>(out), a);
+    } else {
+        attn_rows_kernel<float, float><<<grid, kWaves * 64, 0, st>>>(static_cast<const float*>(q),
+                                                                   static_cast<const float*>(cache), block_table,
+                                                                   cu_seqlens_q, seq_lens, num_seqs, total_q,
+                                                                   static_cast<float*>(out), a);
+    }
     return hipGetLastError();
 }
 

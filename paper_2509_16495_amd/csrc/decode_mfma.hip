@@ -560,7 +560,7 @@ inline int max_chunks_of(int num_seqs, int hkv_l, int max_seq_len) {
 }  // namespace
 
 bool decode_mfma_supported(const AttnShape& a) {
-    return a.elem == 2 && a.D == kD && a.hq_l % a.hkv_l == 0 && a.hq_l / a.hkv_l <= 16;
+    return a.elem == 2 && !a.kv_fp8() && a.D == kD && a.hq_l % a.hkv_l == 0 && a.hq_l / a.hkv_l <= 16;
 }
 
 namespace {

@@ -25,6 +25,9 @@ struct AttnShape {
     int num_blocks, max_blocks;
     float scale;
     int64_t q_stride, kv_stride, out_stride;  // in elements
+    int kv_elem;                  // bytes per cache element: elem, or 1 for an FP8 E4M3 cache
+    float k_scale, v_scale;       // FP8 cache: value = code value * scale (1 otherwise)
+    bool kv_fp8() const { return kv_elem == 1; }
 };
 
 // layout_kernels.hip

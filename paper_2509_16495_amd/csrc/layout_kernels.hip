@@ -166,6 +166,59 @@ __global__ __launch_bounds__(kThreads) void kv_write_block_kernel(const uint16_t
     *reinterpret_cast<u32x4*>(vblk + static_cast<size_t>(d) * kBlockSize + 8 * h) = o.v;
 }
 
+// FP8 E4M3 cache: one thread quantises eight consecutive head-dim elements of one (token, KV head) for
+// K and for V.  code = nearest E4M3 value of x / scale (float32 quotient, ties to the even code, clamped
+// to +-448 first so that nothing overflows; a NaN quotient gives a NaN code).  K codes go out as one
+// 8-byte store, V codes as eight byte stores into the dimension-major rows.
+__device__ inline float elem_to_float(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+__device__ inline float elem_to_float(float f) { return f; }
+
+__device__ inline uint32_t e4m3_pair(float a, float b, float scale) {
+    const float qa = a / scale, qb = b / scale;
+    const float ca = fminf(fmaxf(qa, -448.f), 448.f), cb = fminf(fmaxf(qb, -448.f), 448.f);
+    uint32_t w = static_cast<uint32_t>(__builtin_amdgcn_cvt_pk_fp8_f32(ca, cb, 0, false)) & 0xFFFFu;
+    if (qa != qa) w |= 0x7Fu;
+    if (qb != qb) w |= 0x7F00u;
+    return w;
+}
+
+template <typename Elem>
+__global__ __launch_bounds__(kThreads) void kv_write_fp8_kernel(const Elem* __restrict__ k_new,
+                                                                const Elem* __restrict__ v_new,
+                                                                const int64_t* __restrict__ slots, int n_tokens,
+                                                                uint8_t* __restrict__ cache, int hkv_l, int D,
+                                                                int64_t kv_stride, float k_scale, float v_scale) {
+    const int groups = D / 8;
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (id >= static_cast<int64_t>(n_tokens) * hkv_l * groups) return;
+    const int dg = static_cast<int>(id % groups);
+    const int g = static_cast<int>((id / groups) % hkv_l);
+    const int64_t i = id / (static_cast<int64_t>(groups) * hkv_l);
+    const int64_t slot = slots[i];
+    if (slot < 0) return;
+    const int64_t blk = slot / kBlockSize;
+    const int off = static_cast<int>(slot % kBlockSize);
+    const size_t src = static_cast<size_t>(i) * kv_stride + static_cast<size_t>(g) * D + dg * 8;
+    float kx[8], vx[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        kx[j] = elem_to_float(k_new[src + j]);
+        vx[j] = elem_to_float(v_new[src + j]);
+    }
+    uint32_t kc[2], vc[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        kc[h] = e4m3_pair(kx[4 * h], kx[4 * h + 1], k_scale) | (e4m3_pair(kx[4 * h + 2], kx[4 * h + 3], k_scale) << 16);
+        vc[h] = e4m3_pair(vx[4 * h], vx[4 * h + 1], v_scale) | (e4m3_pair(vx[4 * h + 2], vx[4 * h + 3], v_scale) << 16);
+    }
+    uint8_t* kdst = cache + cache_part_offset(blk, g, 0, hkv_l, D) + static_cast<size_t>(off) * D + dg * 8;
+    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+    *reinterpret_cast<u32x2_t*>(kdst) = u32x2_t{kc[0], kc[1]};
+    uint8_t* vdst = cache + cache_part_offset(blk, g, 1, hkv_l, D) + static_cast<size_t>(dg * 8) * kBlockSize + off;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) vdst[j * kBlockSize] = static_cast<uint8_t>(vc[j >> 2] >> (8 * (j & 3)));
+}
+
 }  // namespace
 
 hipError_t launch_pack(const void* qkv, void* send, const XchgShape& s, hipStream_t st) {
@@ -191,6 +244,20 @@ hipError_t launch_unpack(const void* recv, void* out, const XchgShape& s, hipStr
 
 hipError_t launch_kv_write(const void* k_new, const void* v_new, const int64_t* slots, int n_tokens, void* cache,
                            const AttnShape& a, hipStream_t st) {
+    if (a.kv_fp8()) {
+        const int64_t items = static_cast<int64_t>(n_tokens) * a.hkv_l * (a.D / 8);
+        if (items == 0) return hipSuccess;
+        const unsigned grid8 = static_cast<unsigned>((items + kThreads - 1) / kThreads);
+        if (a.elem == 2)
+            kv_write_fp8_kernel<uint16_t><<<grid8, kThreads, 0, st>>>(
+                static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new), slots, n_tokens,
+                static_cast<uint8_t*>(cache), a.hkv_l, a.D, a.kv_stride, a.k_scale, a.v_scale);
+        else
+            kv_write_fp8_kernel<float><<<grid8, kThreads, 0, st>>>(
+                static_cast<const float*>(k_new), static_cast<const float*>(v_new), slots, n_tokens,
+                static_cast<uint8_t*>(cache), a.hkv_l, a.D, a.kv_stride, a.k_scale, a.v_scale);
+        return hipGetLastError();
+    }
     const int64_t total = static_cast<int64_t>(n_tokens) * a.hkv_l * (a.D * a.elem / 16);
     if (total == 0) return hipSuccess;
     const unsigned grid = static_cast<unsigned>((total + kThreads - 1) / kThreads);

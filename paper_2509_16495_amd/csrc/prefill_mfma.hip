@@ -550,7 +550,9 @@ Plan make_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const 
 
 }  // namespace
 
-bool prefill_mfma_supported(const AttnShape& a) { return a.elem == 2 && a.D == kD && a.hq_l % a.hkv_l == 0; }
+bool prefill_mfma_supported(const AttnShape& a) {
+    return a.elem == 2 && !a.kv_fp8() && a.D == kD && a.hq_l % a.hkv_l == 0;
+}
 
 size_t prefill_mfma_workspace(int num_seqs, int total_q, int max_q_len, int max_seq_len, const AttnShape& a) {
     const Plan pl = make_plan(num_seqs, total_q, max_q_len, max_seq_len, a);

@@ -38,7 +38,7 @@ def test_every_declared_symbol_is_exported(B):
 
 def test_struct_layouts_match_header(B):
     assert ctypes.sizeof(B.Xchg) == 20
-    assert ctypes.sizeof(B.Attn) == 56 and B.Attn.q_stride.offset == 32
+    assert ctypes.sizeof(B.Attn) == 72 and B.Attn.q_stride.offset == 32 and B.Attn.kv_format.offset == 56
 
 
 def test_head_block_matches_paper_example(B):
@@ -78,7 +78,8 @@ def _xchg(B, **kw):
 
 def _attn(B, **kw):
     d = dict(num_q_heads=8, num_kv_heads=1, head_dim=128, dtype=B.BF16, block_size=16, num_blocks=64,
-             max_blocks_per_seq=8, softmax_scale=0.1, q_stride=0, kv_stride=0, out_stride=0)
+             max_blocks_per_seq=8, softmax_scale=0.1, q_stride=0, kv_stride=0, out_stride=0, kv_format=0, k_scale=0.0,
+             v_scale=0.0, reserved=0)
     d.update(kw)
     return B.Attn(*[d[f[0]] for f in B.Attn._fields_])
 
@@ -132,7 +133,11 @@ def test_attention_entry_points_reject_bad_arguments(B):
                      (dict(block_size=32), B.EUNSUPPORTED), (dict(softmax_scale=0.0), B.EINVAL),
                      (dict(softmax_scale=-1.0), B.EINVAL), (dict(softmax_scale=float("nan")), B.EINVAL),
                      (dict(q_stride=100), B.EINVAL), (dict(kv_stride=8), B.EINVAL), (dict(out_stride=1028), B.EINVAL),
-                     (dict(max_blocks_per_seq=2), B.EINVAL)]:
+                     (dict(max_blocks_per_seq=2), B.EINVAL), (dict(kv_format=7), B.EINVAL), (dict(reserved=1), B.EINVAL),
+                     (dict(kv_format=B.KV_FP8_E4M3), B.EINVAL),  # scales missing
+                     (dict(kv_format=B.KV_FP8_E4M3, k_scale=1.0, v_scale=-1.0), B.EINVAL),
+                     (dict(kv_format=B.KV_FP8_E4M3, k_scale=float("inf"), v_scale=1.0), B.EINVAL),
+                     (dict(kv_format=B.KV_FP8_E4M3, k_scale=1.0, v_scale=1.0, head_dim=72), B.EUNSUPPORTED)]:
         assert prefill(_attn(B, **kw)) == code, kw
         assert decode(_attn(B, **kw)) == code, kw
     for kw in (dict(q=None), dict(cache=None), dict(table=None), dict(sl=None), dict(out=None)):

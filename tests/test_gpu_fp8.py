@@ -1,0 +1,86 @@
+"""GPU parity of the FP8 E4M3 KV cache against the CPU oracle, through the C ABI.
+
+The cache bytes must be identical to the oracle's (the code of an element is decided by a float32
+quotient and a nearest-even rounding on both sides); attention over such a cache is compared with the
+oracle's attention over the same codes, to the bf16 / fp32 tolerances of the unquantised path - the
+quantisation error itself is common to both sides and not part of the comparison.
+"""
+import numpy as np
+import pytest
+
+from paper_2509_16495_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+BF16_MAX, BF16_MEAN, F32_MAX = 2e-2, 1e-3, 1e-5
+SCALES = (0.0371, 0.0293)   # no powers of two: the quotient rounds
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_backend
+    return gpu_backend
+
+
+def _check(got_bits, want, dtype):
+    got = W.to_f64(got_bits, dtype)
+    assert got.shape == want.shape and np.all(np.isfinite(got))
+    err = np.abs(got - want)
+    if dtype == "f32":
+        assert err.max() <= F32_MAX, err.max()
+    else:
+        assert err.max() <= BF16_MAX and err.mean() <= BF16_MEAN, (err.max(), err.mean())
+
+
+@pytest.mark.parametrize("dtype,D,hkv", [("bf16", 128, 1), ("bf16", 64, 2), ("f32", 64, 1), ("f32", 128, 3)])
+def test_quantising_write_is_bit_exact(oracle, G, dtype, D, hkv):
+    """Codes over five decades of magnitude, values that saturate, ragged and skipped slots."""
+    from paper_2509_16495_amd import binding as B
+    rng = np.random.Generator(np.random.PCG64(31))
+    n, nb = 777, 64
+    mag = 10.0 ** rng.uniform(-4.5, 1.5, size=(n, hkv, D))
+    k = (rng.standard_normal((n, hkv, D)) * mag).astype(np.float32)
+    v = (rng.standard_normal((n, hkv, D)) * mag[::-1]).astype(np.float32)
+    k[5, 0, :8] = [0.0, -0.0, 1e-30, -1e-30, 1e30, -1e30, 448 * SCALES[0], 464 * SCALES[0]]
+    if dtype == "bf16":
+        k, v = W.f32_to_bf16_bits(k), W.f32_to_bf16_bits(v)
+    slots = rng.permutation(nb * 16)[:n].astype(np.int64)
+    slots[rng.integers(0, n, size=40)] = -1
+    want = oracle.new_cache(nb, hkv, 16, D, "fp8_e4m3")
+    oracle.kv_write_fp8(want, k, v, slots, 16, dtype, *SCALES)
+    cache = G.new_cache_fp8(nb, hkv, D)
+    G.kv_write(cache, k, v, slots, dtype, SCALES)
+    got = B.to_host(cache)
+    assert got.dtype == np.uint8 and got.tobytes() == want.tobytes()
+
+
+@pytest.mark.parametrize("dtype,D,hq,hkv", [("bf16", 128, 8, 1), ("bf16", 128, 4, 2), ("bf16", 64, 4, 1), ("f32", 64, 4, 2)])
+def test_prefill_decode_and_mixed_over_fp8_cache(oracle, G, dtype, D, hq, hkv):
+    from paper_2509_16495_amd import binding as B
+    chunks = [(70, 70), (33, 200), (0, 5), (1, 1), (128, 300)]
+    decodes = [(1, 1), (1, 17), (1, 250), (1, 64), (1, 1000), (1, 33)]
+    case = W.make_attn_case("mixed_fp8", 78, dtype, chunks + decodes, hq, hkv, D, pool_factor=1.5)
+    n_pre = len(chunks)
+    ocache = oracle.cache_for_case(case, fp8_scales=SCALES)
+    want = oracle.attention_case(case, ocache, k_scale=SCALES[0], v_scale=SCALES[1])
+    n_chunk = int(case.q_lens[:n_pre].sum())
+    # one unified call that also writes the new tokens
+    cache = G.cache_for_case(case, only_cached=True, fp8_scales=SCALES)
+    got = G.mixed_case(case, n_pre, cache, fp8_scales=SCALES)
+    assert B.to_host(cache).tobytes() == ocache.tobytes()
+    _check(got, want, dtype)
+    # the two kinds of rows through their own entry points over the finished cache
+    pre, dec = W.sub_case(case, range(n_pre)), W.sub_case(case, range(n_pre, case.num_seqs))
+    _check(G.prefill_case(pre, cache, fp8_scales=SCALES), want[:n_chunk], dtype)
+    _check(G.decode_case(dec, cache, fp8_scales=SCALES), want[n_chunk:], dtype)
+
+
+def test_decode_fp8_many_sequences_long_contexts(oracle, G):
+    """Decode batch that spans many wavefront ranges: 96 sequences, contexts 1..6000, 8q/1kv."""
+    rng = np.random.Generator(np.random.PCG64(32))
+    ctx = np.concatenate([[1, 15, 16, 17, 31, 32, 33, 6000], rng.integers(1, 4000, size=88)])
+    case = W.make_attn_case("dec_fp8", 79, "bf16", [(1, int(c)) for c in ctx], 8, 1, 128, pool_factor=1.2)
+    ocache = oracle.cache_for_case(case, fp8_scales=SCALES)
+    cache = G.cache_for_case(case, fp8_scales=SCALES)
+    got = G.decode_case(case, cache, fp8_scales=SCALES)
+    _check(got, oracle.attention_case(case, ocache, k_scale=SCALES[0], v_scale=SCALES[1]), "bf16")
