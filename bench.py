@@ -233,7 +233,23 @@ def main() -> int:
                                                  "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                                                  "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": traffic.get("decode_256seq")}}
         log(f"[bench] decode cfg4: {ms * 1e3:.1f} us, {gbps:.0f} GB/s of KV ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
-        del cache4, w4
+        # the same batch over an FP8 E4M3 cache: half the bytes per token
+        k_scale, v_scale = 0.05, 0.05
+        cache4q = torch.zeros((c4.num_blocks, 1, 2, 16 * D), dtype=torch.uint8, device=dev)
+        B.kv_write(B.to_device(c4.k_ctx, "bf16", dev), B.to_device(c4.v_ctx, "bf16", dev), ti(c4.slots, np.int64), cache4q,
+                   k_scale, v_scale)
+        ms = time_events(lambda: B.decode(q4, cache4q, t4, s4, m4, o4, c4.softmax_scale, workspace=w4, k_scale=k_scale,
+                                          v_scale=v_scale), reps)
+        gbps = c4.kv_bytes() / 2 / (ms * 1e-3) / 1e9
+        result["decode_kv_read_fp8"] = {"workload": "configs[3] batch over an FP8 E4M3 KV cache (1 byte per element, "
+                                                    "per-tensor K and V scales)",
+                                        "kv_bytes": c4.kv_bytes() // 2, "ms": round(ms, 5),
+                                        "roofline": {"kernel": "decode_flat_kernel<fp8> + combine_flat_kernel", "bound": "hbm",
+                                                     "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                                     "frac": round(gbps / PEAK_HBM_GBPS, 4),
+                                                     "traffic": traffic.get("decode_256seq_fp8")}}
+        log(f"[bench] decode cfg4, FP8 cache: {ms * 1e3:.1f} us, {gbps:.0f} GB/s of KV ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
+        del cache4, cache4q, w4
         # exchange of the 70B hidden state (configs[2])
         x3 = W.config3_xchg()
         copies = 3

@@ -136,7 +136,7 @@ int check_new_kv(const void* k_new, const void* v_new, const int64_t* slots, boo
 
 bool use_prefill_mfma(const AttnShape& s) { return !force_generic() && prefill_mfma_supported(s); }
 bool use_decode_mfma(const AttnShape& s, int num_seqs) {
-    return !force_generic() && decode_mfma_supported(s) && num_seqs <= 65535;
+    return !force_generic() && decode_mfma_supported(s, num_seqs) && num_seqs <= 65535;
 }
 
 }  // namespace

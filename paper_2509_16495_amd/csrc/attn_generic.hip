@@ -206,7 +206,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* _
     }
 }
 
-// Merge for the flat decode kernel (bf16 output, D = 128): one workgroup of one or four thread groups
+// Merge for the flat decode kernel (bf16 output, D = 128; out_scale = v_scale of an FP8 cache, else 1): one workgroup of one or four thread groups
 // per output row; group pg sums the parts c = pg, pg + groups, ... for its 128 head-dim elements (with
 // four groups sixteen partial rows are in flight per element) and the sums are added in group order.
 // Four groups pay off when rows are few and parts many (small batches), one when it is the reverse.  The parts of a
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* _
 template <int kFlatCombineGroups>
 __global__ __launch_bounds__(128 * kFlatCombineGroups) void combine_flat_kernel(
     const float* __restrict__ o_part, const float* __restrict__ ml_part, const int2* __restrict__ plan, int hq_l, int G,
-    uint16_t* __restrict__ out, int64_t out_stride) {
+    uint16_t* __restrict__ out, int64_t out_stride, float out_scale) {
     constexpr int D = 128, kThreadsF = 128 * kFlatCombineGroups;
     __shared__ float w_s[kCombineMaxParts];
     __shared__ float l_s[kCombineMaxParts];
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(128 * kFlatCombineGroups) void combine_flat_kernel(
             a += acc_s[g2][d];
             l += lsum_s[g2];
         }
-        const float inv = l > 0.f ? 1.f / l : 0.f;
+        const float inv = l > 0.f ? out_scale / l : 0.f;
         store_elem(out + static_cast<size_t>(tok) * out_stride + static_cast<size_t>(head) * D + d, a * inv);
     }
 }
@@ -284,15 +284,15 @@ __global__ __launch_bounds__(128 * kFlatCombineGroups) void combine_flat_kernel(
 }  // namespace
 
 hipError_t launch_combine_flat(const float* o_part, const float* ml_part, const int2* plan, int num_seqs, int hq_l, int G,
-                               void* out, int64_t out_stride, hipStream_t st) {
+                               void* out, int64_t out_stride, float out_scale, hipStream_t st) {
     const int64_t rows = static_cast<int64_t>(num_seqs) * hq_l;
     if (rows == 0) return hipSuccess;
     if (rows >= 1024)
         combine_flat_kernel<1><<<static_cast<unsigned>(rows), 128, 0, st>>>(o_part, ml_part, plan, hq_l, G,
-                                                                            static_cast<uint16_t*>(out), out_stride);
+                                                                            static_cast<uint16_t*>(out), out_stride, out_scale);
     else
         combine_flat_kernel<4><<<static_cast<unsigned>(rows), 512, 0, st>>>(o_part, ml_part, plan, hq_l, G,
-                                                                            static_cast<uint16_t*>(out), out_stride);
+                                                                            static_cast<uint16_t*>(out), out_stride, out_scale);
     return hipGetLastError();
 }
 

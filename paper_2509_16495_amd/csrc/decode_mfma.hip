@@ -24,6 +24,12 @@
 // these partials are numbered (wavefront index + pair index), so the parts of a pair are
 // consecutive rows.  decode_splitk_kernel (one workgroup per fixed-size chunk of one sequence) remains
 // for batches with more pairs than the flat kernel indexes in LDS.
+//
+// FP8 E4M3 cache (flat kernel only): a cache block is half as many bytes in the same arrangement, so a
+// group takes eight 1-KiB loads instead of sixteen; every loaded 16-byte piece (16 codes) is widened in
+// registers to the two bf16 pieces it stands for (exact: every E4M3 value is a bf16 value) and parked
+// where the bf16 path would have put them, so the LDS layout, the operand reads and all arithmetic are
+// shared.  k_scale rides in the logit scale, v_scale in the merge.
 #include "internal.h"
 
 #include <stdlib.h>
@@ -61,6 +67,19 @@ constexpr int kFlatWorkers = kFlatWorkgroups * kWaves;    // wavefronts, each wi
 
 // The flat kernel: see the file header.  cum[i + 1] holds the padded token count of pairs 0..i in
 // its upper bits and (padded - real) length of pair i in its low five bits.
+// the two bf16 pieces (8 elements each) of one 16-byte piece of E4M3 codes
+__device__ inline void widen_fp8(u32x4 codes, u32x4& lo, u32x4& hi) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+        lo[2 * w] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(static_cast<int>(codes[w]), 1.0f, false));
+        lo[2 * w + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(static_cast<int>(codes[w]), 1.0f, true));
+        hi[2 * w] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(static_cast<int>(codes[2 + w]), 1.0f, false));
+        hi[2 * w + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(static_cast<int>(codes[2 + w]), 1.0f, true));
+    }
+}
+
+template <bool kFp8>
 __global__ __launch_bounds__(kWaves * 64, 2) void decode_flat_kernel(
     const uint16_t* __restrict__ q, int64_t q_stride, const uint16_t* __restrict__ cache,
     const int32_t* __restrict__ block_table, int max_blocks, const int32_t* __restrict__ seq_lens,
@@ -154,6 +173,17 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_flat_kernel(
     }
     const int vw = 8192 + ((lane ^ ((lane >> 4) & 1)) << 4);
     const int vr = 8192 + (grp >> 1) * 4096 + (((2 * col + (grp & 1)) ^ ((col >> 3) & 1)) << 4);
+    // FP8 cache: a 1-KiB load covers eight K rows (lane >> 3) of eight 16-code pieces (lane & 7), or 64 V^T
+    // rows (lane) of one piece.  Piece q (0 / 1) of the widened pair goes to
+    //   K, block b, load j  : (kw8 ^ 64 (2j ^ b) ^ 16 q) + 4096 b + 2048 j     (same swizzle as above, row 8j + lane/8)
+    //   V^T, block b, load j: (vw8 ^ 16 q) + 4096 b + 2048 j
+    int kw8 = 0, vw8 = 0;
+    if constexpr (kFp8) {
+        const int r8 = lane >> 3, pc = lane & 7;
+        kw8 = r8 * 256 + (((2 * pc) ^ (r8 & 3) ^ (4 * (lane >> 5))) << 4);
+        const int l31 = lane & 31;
+        vw8 = 8192 + 1024 * (lane >> 5) + (((2 * l31) ^ ((l31 >> 3) & 1)) << 4);
+    }
 
     // ---- a position on the line: pair index, its padded token range, its real length (all scalar) --
     int pos = start, pair, seg_begin, seg_end, ctx;
@@ -195,14 +225,27 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_flat_kernel(
     GroupFrags f;
     auto load_group = [&](int pr, int blk0, int blk1) {
         const int g = pr % hkv_l;
-        const u32x4* k0 = reinterpret_cast<const u32x4*>(cache + cache_part_offset(blk0, g, 0, hkv_l, kD)) + lane;
-        const u32x4* k1 = reinterpret_cast<const u32x4*>(cache + cache_part_offset(blk1, g, 0, hkv_l, kD)) + lane;
+        if constexpr (kFp8) {  // one byte per element: K 2 KiB then V^T 2 KiB per (block, head)
+            const unsigned char* cb = reinterpret_cast<const unsigned char*>(cache);
+            const u32x4* k0 = reinterpret_cast<const u32x4*>(cb + cache_part_offset(blk0, g, 0, hkv_l, kD)) + lane;
+            const u32x4* k1 = reinterpret_cast<const u32x4*>(cb + cache_part_offset(blk1, g, 0, hkv_l, kD)) + lane;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            f.k[j] = __builtin_nontemporal_load(k0 + 64 * j);
-            f.k[4 + j] = __builtin_nontemporal_load(k1 + 64 * j);
-            f.v[j] = __builtin_nontemporal_load(k0 + 256 + 64 * j);
-            f.v[4 + j] = __builtin_nontemporal_load(k1 + 256 + 64 * j);
+            for (int j = 0; j < 2; ++j) {
+                f.k[j] = __builtin_nontemporal_load(k0 + 64 * j);
+                f.k[2 + j] = __builtin_nontemporal_load(k1 + 64 * j);
+                f.v[j] = __builtin_nontemporal_load(k0 + 128 + 64 * j);
+                f.v[2 + j] = __builtin_nontemporal_load(k1 + 128 + 64 * j);
+            }
+        } else {
+            const u32x4* k0 = reinterpret_cast<const u32x4*>(cache + cache_part_offset(blk0, g, 0, hkv_l, kD)) + lane;
+            const u32x4* k1 = reinterpret_cast<const u32x4*>(cache + cache_part_offset(blk1, g, 0, hkv_l, kD)) + lane;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                f.k[j] = __builtin_nontemporal_load(k0 + 64 * j);
+                f.k[4 + j] = __builtin_nontemporal_load(k1 + 64 * j);
+                f.v[j] = __builtin_nontemporal_load(k0 + 256 + 64 * j);
+                f.v[4 + j] = __builtin_nontemporal_load(k1 + 256 + 64 * j);
+            }
         }
     };
     bf16x8 qf[4];
@@ -257,12 +300,29 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_flat_kernel(
     }
     while (true) {
         // group (pair, pos) has arrived in f: park it in LDS, then reuse f for the next group
+        if constexpr (kFp8) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            *reinterpret_cast<u32x4*>(my + kw[j] + 1024 * j) = f.k[j];
-            *reinterpret_cast<u32x4*>(my + kw[j ^ 1] + 4096 + 1024 * j) = f.k[4 + j];
-            *reinterpret_cast<u32x4*>(my + vw + 1024 * j) = f.v[j];
-            *reinterpret_cast<u32x4*>(my + vw + 4096 + 1024 * j) = f.v[4 + j];
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    u32x4 lo, hi;
+                    widen_fp8(f.k[2 * b + j], lo, hi);
+                    const int ka = (kw8 ^ (64 * ((2 * j) ^ b))) + 4096 * b + 2048 * j;
+                    *reinterpret_cast<u32x4*>(my + ka) = lo;
+                    *reinterpret_cast<u32x4*>(my + (ka ^ 16)) = hi;
+                    widen_fp8(f.v[2 * b + j], lo, hi);
+                    const int va = vw8 + 4096 * b + 2048 * j;
+                    *reinterpret_cast<u32x4*>(my + va) = lo;
+                    *reinterpret_cast<u32x4*>(my + (va ^ 16)) = hi;
+                }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                *reinterpret_cast<u32x4*>(my + kw[j] + 1024 * j) = f.k[j];
+                *reinterpret_cast<u32x4*>(my + kw[j ^ 1] + 4096 + 1024 * j) = f.k[4 + j];
+                *reinterpret_cast<u32x4*>(my + vw + 1024 * j) = f.v[j];
+                *reinterpret_cast<u32x4*>(my + vw + 4096 + 1024 * j) = f.v[4 + j];
+            }
         }
         int nn_pos = n_pos + kGroup, nn_pair = n_pair, nn_begin = n_begin, nn_end = n_end, nn_ctx = n_ctx;
         bool nn_valid = false;
@@ -559,15 +619,22 @@ inline int max_chunks_of(int num_seqs, int hkv_l, int max_seq_len) {
 
 }  // namespace
 
-bool decode_mfma_supported(const AttnShape& a) {
-    return a.elem == 2 && !a.kv_fp8() && a.D == kD && a.hq_l % a.hkv_l == 0 && a.hq_l / a.hkv_l <= 16;
+namespace {
+
+inline bool use_flat(int num_seqs, const AttnShape& a) {
+    return static_cast<int64_t>(num_seqs) * a.hkv_l <= kFlatMaxPairs && (a.kv_fp8() || env_int("SHIFTATTN_DECODE_FLAT", 1) != 0);
+}
+
+}  // namespace
+
+// an FP8 cache is read by the flat kernel only
+bool decode_mfma_supported(const AttnShape& a, int num_seqs) {
+    return a.elem == 2 && a.D == kD && a.hq_l % a.hkv_l == 0 && a.hq_l / a.hkv_l <= 16 &&
+           (!a.kv_fp8() || static_cast<int64_t>(num_seqs) * a.hkv_l <= kFlatMaxPairs);
 }
 
 namespace {
 
-inline bool use_flat(int num_seqs, const AttnShape& a) {
-    return static_cast<int64_t>(num_seqs) * a.hkv_l <= kFlatMaxPairs && env_int("SHIFTATTN_DECODE_FLAT", 1) != 0;
-}
 // partial rows of the flat kernel: one per (wavefront, pair) whose ranges meet, numbered wavefront + pair
 inline size_t flat_rows(int num_seqs, const AttnShape& a) {
     return (static_cast<size_t>(kFlatWorkers) + static_cast<size_t>(num_seqs) * a.hkv_l) * (a.hq_l / a.hkv_l);
@@ -586,7 +653,7 @@ hipError_t launch_decode_mfma(const void* q, const void* cache, const int32_t* b
                               int num_seqs, int max_seq_len, void* out, void* workspace, const AttnShape& a,
                               hipStream_t st) {
     if (num_seqs == 0 || max_seq_len <= 0) return hipSuccess;
-    const float c = a.scale * 1.4426950408889634f;
+    const float c = a.scale * a.k_scale * 1.4426950408889634f;  // logits of an FP8 cache carry k_scale
     if (use_flat(num_seqs, a)) {
         const size_t rows = flat_rows(num_seqs, a);
         float* o_part = static_cast<float*>(workspace);
@@ -597,12 +664,18 @@ hipError_t launch_decode_mfma(const void* q, const void* cache, const int32_t* b
         const int padded_max = (max_seq_len + kGroup - 1) / kGroup * kGroup;
         int r_min = (padded_max / (kMaxParts - 24) + kGroup) / kGroup * kGroup;
         if (r_min < 2 * kGroup) r_min = 2 * kGroup;
-        decode_flat_kernel<<<kFlatWorkgroups, kWaves * 64, 0, st>>>(
-            static_cast<const uint16_t*>(q), a.q_stride, static_cast<const uint16_t*>(cache), block_table, a.max_blocks,
-            seq_lens, o_part, ml_part, plan, num_seqs, a.hq_l, a.hkv_l, c, r_min);
+        if (a.kv_fp8())
+            decode_flat_kernel<true><<<kFlatWorkgroups, kWaves * 64, 0, st>>>(
+                static_cast<const uint16_t*>(q), a.q_stride, static_cast<const uint16_t*>(cache), block_table, a.max_blocks,
+                seq_lens, o_part, ml_part, plan, num_seqs, a.hq_l, a.hkv_l, c, r_min);
+        else
+            decode_flat_kernel<false><<<kFlatWorkgroups, kWaves * 64, 0, st>>>(
+                static_cast<const uint16_t*>(q), a.q_stride, static_cast<const uint16_t*>(cache), block_table, a.max_blocks,
+                seq_lens, o_part, ml_part, plan, num_seqs, a.hq_l, a.hkv_l, c, r_min);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        return launch_combine_flat(o_part, ml_part, plan, num_seqs, a.hq_l, a.hq_l / a.hkv_l, out, a.out_stride, st);
+        return launch_combine_flat(o_part, ml_part, plan, num_seqs, a.hq_l, a.hq_l / a.hkv_l, out, a.out_stride, a.v_scale,
+                                   st);
     }
     const int chunk = chunk_tokens(num_seqs, a.hkv_l, max_seq_len);
     const int max_chunks = max_chunks_of(num_seqs, a.hkv_l, max_seq_len);

@@ -52,10 +52,10 @@ hipError_t launch_combine(const float* o_part, const float* ml_part, int n_rows,
 
 // Merge for the flat decode kernel (bf16, D = 128): see combine_flat_kernel.
 hipError_t launch_combine_flat(const float* o_part, const float* ml_part, const int2* plan, int num_seqs, int hq_l, int G,
-                               void* out, int64_t out_stride, hipStream_t st);
+                               void* out, int64_t out_stride, float out_scale, hipStream_t st);
 
-// decode_mfma.hip : bf16, D = 128, hq_l/hkv_l <= 16
-bool decode_mfma_supported(const AttnShape& a);
+// decode_mfma.hip : bf16 q/out, D = 128, hq_l/hkv_l <= 16; cache bf16 or FP8 E4M3
+bool decode_mfma_supported(const AttnShape& a, int num_seqs);
 size_t decode_mfma_workspace(int num_seqs, int max_seq_len, const AttnShape& a);
 hipError_t launch_decode_mfma(const void* q, const void* cache, const int32_t* block_table,
                               const int32_t* seq_lens, int num_seqs, int max_seq_len, void* out,
