@@ -134,7 +134,9 @@ int check_new_kv(const void* k_new, const void* v_new, const int64_t* slots, boo
     return 0;
 }
 
-bool use_prefill_mfma(const AttnShape& s) { return !force_generic() && prefill_mfma_supported(s); }
+bool use_prefill_mfma(const AttnShape& s, int num_seqs, int max_seq_len) {
+    return !force_generic() && prefill_mfma_supported(s, num_seqs, max_seq_len);
+}
 bool use_decode_mfma(const AttnShape& s, int num_seqs) {
     return !force_generic() && decode_mfma_supported(s, num_seqs) && num_seqs <= 65535;
 }
@@ -220,7 +222,7 @@ size_t shiftattn_prefill_workspace_bytes(int32_t num_seqs, int32_t total_q, int3
                                          const shiftattn_attn* a) {
     AttnShape s;
     if (check_attn(a, &s) || num_seqs < 0 || total_q < 0 || max_q_len < 0 || max_seq_len < 0) return SIZE_MAX;
-    if (!use_prefill_mfma(s) || num_seqs == 0 || total_q == 0) return 0;
+    if (!use_prefill_mfma(s, num_seqs, max_seq_len) || num_seqs == 0 || total_q == 0) return 0;
     return prefill_mfma_workspace(num_seqs, total_q, max_q_len, max_seq_len, s);
 }
 
@@ -251,7 +253,7 @@ int shiftattn_prefill(const void* q, const void* k_new, const void* v_new, const
         return fail(SHIFTATTN_EINVAL, "q / out / kv_cache must be 16-byte aligned");
     if (static_cast<int64_t>(s.max_blocks) * kBlockSize < max_seq_len)
         return fail(SHIFTATTN_EINVAL, "max_blocks_per_seq = %d cannot hold max_seq_len = %d", s.max_blocks, max_seq_len);
-    const bool mfma = use_prefill_mfma(s);
+    const bool mfma = use_prefill_mfma(s, num_seqs, max_seq_len);
     const size_t need = mfma ? prefill_mfma_workspace(num_seqs, total_q, max_q_len, max_seq_len, s) : 0;
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace)))
         return fail(SHIFTATTN_EWORKSPACE, "prefill needs %zu workspace bytes, got %zu", need,

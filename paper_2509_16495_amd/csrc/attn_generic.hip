@@ -147,7 +147,8 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* _
                                                                   const float* __restrict__ ml_part, int n_rows,
                                                                   int hq_l, int D, int n_parts, int mode,
                                                                   const int32_t* __restrict__ seq_lens, int chunk,
-                                                                  Elem* __restrict__ out, int64_t out_stride) {
+                                                                  Elem* __restrict__ out, int64_t out_stride,
+                                                                  float out_scale) {
     __shared__ float w_s[kCombineMaxParts];
     __shared__ float l_s[kCombineMaxParts];
     __shared__ float red_s[kCombineThreads / 64];
@@ -189,7 +190,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* _
     __syncthreads();
     float l_star = 0.f;  // every thread sums in part order: same value everywhere, no atomics
     for (int c = 0; c < np; ++c) l_star = fmaf(l_s[c], w_s[c], l_star);
-    const float inv = l_star > 0.f ? 1.f / l_star : 0.f;
+    const float inv = l_star > 0.f ? out_scale / l_star : 0.f;
     for (int d = tid; d < D; d += kCombineThreads) {
         float acc = 0.f;
         const float* src = o_part + row0 * D + d;
@@ -326,16 +327,17 @@ hipError_t launch_attn_generic(const void* q, const void* cache, const int32_t* 
 
 hipError_t launch_combine(const float* o_part, const float* ml_part, int n_rows, int hq_l, int D, int n_parts,
                           int mode, const int32_t* seq_lens, int chunk, void* out, int64_t out_stride, int elem,
-                          hipStream_t st) {
+                          float out_scale, hipStream_t st) {
     const int64_t rows = static_cast<int64_t>(n_rows) * hq_l;
     if (rows == 0) return hipSuccess;
     if (elem == 2)
         combine_kernel<uint16_t><<<static_cast<unsigned>(rows), 128, 0, st>>>(
-            o_part, ml_part, n_rows, hq_l, D, n_parts, mode, seq_lens, chunk, static_cast<uint16_t*>(out), out_stride);
+            o_part, ml_part, n_rows, hq_l, D, n_parts, mode, seq_lens, chunk, static_cast<uint16_t*>(out), out_stride,
+            out_scale);
     else
         combine_kernel<float><<<static_cast<unsigned>(rows), 128, 0, st>>>(o_part, ml_part, n_rows, hq_l, D, n_parts,
                                                                           mode, seq_lens, chunk,
-                                                                          static_cast<float*>(out), out_stride);
+                                                                          static_cast<float*>(out), out_stride, out_scale);
     return hipGetLastError();
 }
 

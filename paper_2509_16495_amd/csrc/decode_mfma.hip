@@ -689,7 +689,7 @@ hipError_t launch_decode_mfma(const void* q, const void* cache, const int32_t* b
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_combine(o_part, ml_part, num_seqs, a.hq_l, kD, max_chunks, 1, seq_lens, chunk, out,
-                          a.out_stride, a.elem, st);
+                          a.out_stride, a.elem, 1.f, st);
 }
 
 }  // namespace shiftattn

@@ -35,6 +35,11 @@ hipError_t launch_pack(const void* qkv, void* send, const XchgShape& s, hipStrea
 hipError_t launch_unpack(const void* recv, void* out, const XchgShape& s, hipStream_t st);
 hipError_t launch_kv_write(const void* k_new, const void* v_new, const int64_t* slots, int n_tokens,
                            void* cache, const AttnShape& a, hipStream_t st);
+// D = 128: the FP8 E4M3 cache blocks block_table[s][i], i < ceil(seq_lens[s] / 16), widened to bf16 at
+// scratch block s * nb + i (same K | V^T arrangement); table_out[s][i] = s * nb + i for all i < nb.
+hipError_t launch_fp8_blocks_to_bf16(const void* cache_fp8, const int32_t* block_table, int max_blocks,
+                                     const int32_t* seq_lens, int num_seqs, int nb, int hkv_l, void* scratch_bf16,
+                                     int32_t* table_out, hipStream_t st);
 
 // attn_generic.hip : any dtype / head_dim / head ratio, one wavefront per (token, head) row
 hipError_t launch_attn_generic(const void* q, const void* cache, const int32_t* block_table,
@@ -48,7 +53,7 @@ hipError_t launch_attn_generic(const void* q, const void* cache, const int32_t* 
 // parts of a row is ceil(seq_lens[sequence] / chunk).
 hipError_t launch_combine(const float* o_part, const float* ml_part, int n_rows, int hq_l, int D,
                           int n_parts, int mode, const int32_t* seq_lens, int chunk, void* out,
-                          int64_t out_stride, int elem, hipStream_t st);
+                          int64_t out_stride, int elem, float out_scale, hipStream_t st);
 
 // Merge for the flat decode kernel (bf16, D = 128): see combine_flat_kernel.
 hipError_t launch_combine_flat(const float* o_part, const float* ml_part, const int2* plan, int num_seqs, int hq_l, int G,
@@ -61,8 +66,8 @@ hipError_t launch_decode_mfma(const void* q, const void* cache, const int32_t* b
                               const int32_t* seq_lens, int num_seqs, int max_seq_len, void* out,
                               void* workspace, const AttnShape& a, hipStream_t st);
 
-// prefill_mfma.hip : bf16, D = 128
-bool prefill_mfma_supported(const AttnShape& a);
+// prefill_mfma.hip : bf16 q/out, D = 128; cache bf16, or FP8 E4M3 widened into workspace first
+bool prefill_mfma_supported(const AttnShape& a, int num_seqs, int max_seq_len);
 size_t prefill_mfma_workspace(int num_seqs, int total_q, int max_q_len, int max_seq_len, const AttnShape& a);
 hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* block_table,
                                const int32_t* cu_seqlens_q, const int32_t* seq_lens, int num_seqs,

@@ -219,7 +219,48 @@ __global__ __launch_bounds__(kThreads) void kv_write_fp8_kernel(const Elem* __re
     for (int j = 0; j < 8; ++j) vdst[j * kBlockSize] = static_cast<uint8_t>(vc[j >> 2] >> (8 * (j & 3)));
 }
 
+// FP8 E4M3 cache blocks of the contexts of a batch, widened to bf16 (D = 128): one workgroup per
+// (sequence, block index, KV head), one 16-byte piece of codes per thread.  K and V^T keep their
+// arrangement, so element e of the 4 KiB of codes becomes element e of the 8 KiB of bf16.
+__global__ __launch_bounds__(kThreads) void fp8_blocks_to_bf16_kernel(const uint8_t* __restrict__ cache,
+                                                                      const int32_t* __restrict__ block_table,
+                                                                      int max_blocks, const int32_t* __restrict__ seq_lens,
+                                                                      int nb, int hkv_l, uint16_t* __restrict__ scratch,
+                                                                      int32_t* __restrict__ table_out) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const int i = blockIdx.x % nb, s = blockIdx.x / nb, g = blockIdx.y;
+    const int dst_blk = s * nb + i;
+    if (g == 0 && threadIdx.x == 0) table_out[dst_blk] = dst_blk;
+    if (i * kBlockSize >= seq_lens[s]) return;  // uniform: no token of the context in this block
+    const int64_t src_blk = block_table[static_cast<size_t>(s) * max_blocks + i];
+    constexpr int D = 128, kCodes = 2 * kBlockSize * D;  // codes (and bf16 elements) per (block, head)
+    const u32x4 codes = *(reinterpret_cast<const u32x4*>(cache + (static_cast<size_t>(src_blk) * hkv_l + g) * kCodes) + threadIdx.x);
+    u32x4 lo, hi;
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+        lo[2 * w] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(static_cast<int>(codes[w]), 1.0f, false));
+        lo[2 * w + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(static_cast<int>(codes[w]), 1.0f, true));
+        hi[2 * w] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(static_cast<int>(codes[2 + w]), 1.0f, false));
+        hi[2 * w + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(static_cast<int>(codes[2 + w]), 1.0f, true));
+    }
+    u32x4* dst = reinterpret_cast<u32x4*>(scratch + (static_cast<size_t>(dst_blk) * hkv_l + g) * kCodes) + 2 * threadIdx.x;
+    dst[0] = lo;
+    dst[1] = hi;
+}
+
 }  // namespace
+
+hipError_t launch_fp8_blocks_to_bf16(const void* cache_fp8, const int32_t* block_table, int max_blocks,
+                                     const int32_t* seq_lens, int num_seqs, int nb, int hkv_l, void* scratch_bf16,
+                                     int32_t* table_out, hipStream_t st) {
+    const int64_t wgs = static_cast<int64_t>(num_seqs) * nb;
+    if (wgs == 0) return hipSuccess;
+    if (wgs > 0x7FFFFFFF || hkv_l > 65535) return hipErrorInvalidValue;
+    dim3 grid(static_cast<unsigned>(wgs), static_cast<unsigned>(hkv_l));
+    fp8_blocks_to_bf16_kernel<<<grid, kThreads, 0, st>>>(static_cast<const uint8_t*>(cache_fp8), block_table, max_blocks,
+                                                         seq_lens, nb, hkv_l, static_cast<uint16_t*>(scratch_bf16), table_out);
+    return hipGetLastError();
+}
 
 hipError_t launch_pack(const void* qkv, void* send, const XchgShape& s, hipStream_t st) {
     const uint32_t row_vecs = static_cast<uint32_t>(s.hq_l + 2 * s.hkv_l) * s.vec_per_head;

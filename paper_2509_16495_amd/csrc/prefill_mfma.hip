@@ -97,7 +97,8 @@ struct PrefillParams {
     int head_slots;   // hq_l >> gs_log2
     int n_splits;     // key ranges per tile
     int max_blocks;
-    float c;          // softmax_scale * log2(e)
+    float c;          // softmax_scale * log2(e) (times k_scale for a cache widened from FP8)
+    float out_scale;  // multiplies the normalised output: v_scale of an FP8 cache, else 1
 };
 
 __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
@@ -479,7 +480,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
             // ---- output: accumulator register r of row tile mt is head-dim 32*mt + 8*(r/4) + 4*half + r%4 ----
             if (pos_col >= 0) {
                 if (p.n_splits == 1) {
-                    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+                    const float inv = l_tot > 0.f ? p.out_scale / l_tot : 0.f;
                     uint16_t* op = p.out + static_cast<size_t>(row_col) * p.out_stride + head_col * kD + 4 * half;
 #pragma unroll
                     for (int mt = 0; mt < 4; ++mt)
@@ -548,16 +549,42 @@ Plan make_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const 
     return pl;
 }
 
+// FP8 E4M3 cache: the blocks the batch reads are first widened to bf16 (exact) into a scratch cache in
+// the workspace, block i of sequence s at scratch block s * nb + i with nb = blocks of the longest
+// context, together with the block table that says so; the kernel then runs on the scratch cache with
+// k_scale in its logit scale and v_scale on its output.  The pass moves 1.5 bytes per cached element
+// once, against the 4 * D flops per (query, key) pair of the attention itself.
+constexpr size_t kFp8ScratchLimit = static_cast<size_t>(8) << 30;  // larger batches take the general kernel
+
+struct Fp8Scratch {
+    int nb;               // scratch blocks per sequence
+    size_t cache_bytes;   // bf16 scratch cache
+    size_t table_bytes;   // int32 [num_seqs][nb], padded to 256 bytes
+};
+
+Fp8Scratch fp8_scratch(int num_seqs, int max_seq_len, const AttnShape& a) {
+    Fp8Scratch f;
+    f.nb = (max_seq_len + kBlockSize - 1) / kBlockSize;
+    f.cache_bytes = static_cast<size_t>(num_seqs) * f.nb * a.hkv_l * 2 * kBlockBytes;
+    f.table_bytes = (static_cast<size_t>(num_seqs) * f.nb * sizeof(int32_t) + 255) / 256 * 256;
+    return f;
+}
+
 }  // namespace
 
-bool prefill_mfma_supported(const AttnShape& a) {
-    return a.elem == 2 && !a.kv_fp8() && a.D == kD && a.hq_l % a.hkv_l == 0;
+bool prefill_mfma_supported(const AttnShape& a, int num_seqs, int max_seq_len) {
+    if (!(a.elem == 2 && a.D == kD && a.hq_l % a.hkv_l == 0)) return false;
+    return !a.kv_fp8() || fp8_scratch(num_seqs, max_seq_len, a).cache_bytes <= kFp8ScratchLimit;
 }
 
 size_t prefill_mfma_workspace(int num_seqs, int total_q, int max_q_len, int max_seq_len, const AttnShape& a) {
     const Plan pl = make_plan(num_seqs, total_q, max_q_len, max_seq_len, a);
-    if (pl.n_splits == 1) return 0;
-    return static_cast<size_t>(pl.n_splits) * total_q * a.hq_l * (kD + 2) * sizeof(float);
+    size_t bytes = pl.n_splits == 1 ? 0 : static_cast<size_t>(pl.n_splits) * total_q * a.hq_l * (kD + 2) * sizeof(float);
+    if (a.kv_fp8()) {
+        const Fp8Scratch f = fp8_scratch(num_seqs, max_seq_len, a);
+        bytes = (bytes + 255) / 256 * 256 + f.cache_bytes + f.table_bytes;
+    }
+    return bytes;
 }
 
 hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* block_table,
@@ -566,6 +593,20 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
                                hipStream_t st) {
     if (num_seqs == 0 || total_q == 0 || max_q_len <= 0) return hipSuccess;
     const Plan pl = make_plan(num_seqs, total_q, max_q_len, max_seq_len, a);
+    int max_blocks = a.max_blocks;
+    if (a.kv_fp8()) {  // widen into the scratch cache behind the split partials, then attend over that
+        const Fp8Scratch f = fp8_scratch(num_seqs, max_seq_len, a);
+        const size_t split_bytes =
+            pl.n_splits == 1 ? 0 : (static_cast<size_t>(pl.n_splits) * total_q * a.hq_l * (kD + 2) * sizeof(float) + 255) / 256 * 256;
+        unsigned char* scratch = static_cast<unsigned char*>(workspace) + split_bytes;
+        int32_t* table2 = reinterpret_cast<int32_t*>(scratch + f.cache_bytes);
+        hipError_t e0 = launch_fp8_blocks_to_bf16(cache, block_table, a.max_blocks, seq_lens, num_seqs, f.nb, a.hkv_l, scratch,
+                                                 table2, st);
+        if (e0 != hipSuccess) return e0;
+        cache = scratch;
+        block_table = table2;
+        max_blocks = f.nb;
+    }
     PrefillParams p;
     p.q = static_cast<const uint16_t*>(q);
     p.cache = static_cast<const uint16_t*>(cache);
@@ -586,8 +627,9 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
     p.gs_log2 = pl.gs_log2;
     p.head_slots = pl.head_slots;
     p.n_splits = pl.n_splits;
-    p.max_blocks = a.max_blocks;
-    p.c = a.scale * 1.4426950408889634f;
+    p.max_blocks = max_blocks;
+    p.c = a.scale * a.k_scale * 1.4426950408889634f;
+    p.out_scale = a.v_scale;
 
     const unsigned grid = static_cast<unsigned>(pl.pair_ranks) * pl.n_splits * num_seqs * pl.head_slots;
     static bool attr_done = false;
@@ -603,7 +645,7 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
     if (e != hipSuccess) return e;
     if (pl.n_splits > 1)
         return launch_combine(p.o_part, p.ml_part, total_q, a.hq_l, kD, pl.n_splits, 0, nullptr, 0, out, a.out_stride,
-                              a.elem, st);
+                              a.elem, a.v_scale, st);
     return hipSuccess;
 }
 

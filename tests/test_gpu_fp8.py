@@ -84,3 +84,15 @@ def test_decode_fp8_many_sequences_long_contexts(oracle, G):
     cache = G.cache_for_case(case, fp8_scales=SCALES)
     got = G.decode_case(case, cache, fp8_scales=SCALES)
     _check(got, oracle.attention_case(case, ocache, k_scale=SCALES[0], v_scale=SCALES[1]), "bf16")
+
+
+def test_chunked_prefill_fp8_long_context_with_key_splits(oracle, G):
+    """A short chunk on a long cached context (keys split over workgroups, partials merged) next to ordinary
+    prefills, all over an FP8 cache that the call widens into its workspace."""
+    case = W.make_attn_case("chunk_fp8", 80, "bf16", [(96, 9000), (300, 300), (40, 1234)], 8, 1, 128, pool_factor=1.3)
+    ocache = oracle.cache_for_case(case, fp8_scales=SCALES)
+    cache = G.cache_for_case(case, only_cached=True, fp8_scales=SCALES)
+    got = G.prefill_case(case, cache, fused_new_kv=True, fp8_scales=SCALES)
+    from paper_2509_16495_amd import binding as B
+    assert B.to_host(cache).tobytes() == ocache.tobytes()
+    _check(got, oracle.attention_case(case, ocache, k_scale=SCALES[0], v_scale=SCALES[1]), "bf16")
