@@ -68,6 +68,8 @@ PREFILL_SMALL = [
     ([(90, 190)], 6, 2),                                     # three query heads per KV head (not a power of two)
     ([(300, 300)], 16, 1),
     ([(0, 10), (40, 40), (0, 0)], 4, 1),                     # empty chunks in the batch
+    ([(140, 140), (31, 333)], 5, 1),                         # 40q/8kv model on 8 ranks (Table 4, Llama-17B-16E): 5 per KV head
+    ([(129, 200)], 10, 2),                                   # the same model on 4 ranks
 ]
 
 
@@ -113,7 +115,7 @@ def test_generic_kernel_bf16_and_other_head_dims(oracle, G):
 DECODE_LENS = [1, 15, 16, 17, 31, 32, 33, 100, 511, 512, 513, 1023, 1500, 3000]
 
 
-@pytest.mark.parametrize("hq_l,hkv_l", [(8, 1), (4, 1), (4, 4), (16, 1), (6, 2), (16, 2)])
+@pytest.mark.parametrize("hq_l,hkv_l", [(8, 1), (4, 1), (4, 4), (16, 1), (6, 2), (16, 2), (5, 1), (10, 2)])
 def test_decode_bf16_small(oracle, G, hq_l, hkv_l):
     case = W.make_attn_case("t", 55, "bf16", [(1, c) for c in DECODE_LENS], hq_l, hkv_l, 128, pool_factor=1.3)
     want = oracle.attention_case(case, oracle.cache_for_case(case))

@@ -85,7 +85,7 @@ def test_kv_write_whole_blocks_and_ragged_runs(oracle, G, hkv_l):
         assert B.to_host(cache).tobytes() == want.tobytes()
 
 
-@pytest.mark.parametrize("sp,tp,H,H_kv", [(3, 2, 12, 6), (8, 1, 32, 4), (4, 2, 16, 8)])
+@pytest.mark.parametrize("sp,tp,H,H_kv", [(3, 2, 12, 6), (8, 1, 32, 4), (4, 2, 16, 8), (4, 2, 40, 8)])
 def test_sp_cache_equals_tp_cache_on_gpu(oracle, G, sp, tp, H, H_kv):
     """KV-cache invariance through the GPU kernels: pack -> exchange -> fused KV write in SP mode
     leaves exactly the bytes that the direct TP-mode write leaves, and both equal the oracle's cache."""
