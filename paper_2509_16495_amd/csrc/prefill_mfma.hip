@@ -452,46 +452,100 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
         const int other_barriers = n_other > 0 ? n_other + 2 + ((pass_ragged && !own_ragged) ? 1 : 0) : 0;
         for (int b = barriers; b < other_barriers; ++b) __syncthreads();
 
-        // ---- merge the two groups: group 1 parks (m, l, O) in LDS, group 0 folds it in --------------------
+        // ---- merge the two groups -------------------------------------------------------------------------
         float l_tot = l_run + __shfl_xor(l_run, 32);
         __syncthreads();  // every wavefront is done with the tile stages
-        float* x_o = reinterpret_cast<float*>(lds);                   // [64 values][256 lanes of a group]
-        float* x_ml = x_o + 64 * 256;                                  // [2][256]
-        const int t4 = tid & 255;
-        if (grp == 1) {
+        // the thread index is read through an opaque copy: addresses derived from the plain value are loop
+        // invariants that the optimiser computes before the key loop and then spills around it
+        int tid_m = tid;
+        asm volatile("" : "+v"(tid_m));
+        const int t4 = tid_m & 255;
+        if (p.n_splits == 1) {
+            // Each group finishes one half of the head dimension (group 0 rows 0..63, group 1 rows 64..127): it parks
+            // the other half of its accumulators for the other group, folds in what that group parked, normalises,
+            // and puts bf16 rows into an LDS staging tile; then all eight wavefronts write the tile out in whole
+            // 256-byte rows (one 16-byte piece per lane, 1 KiB of consecutive output per instruction per 4 rows).
+            float* park = reinterpret_cast<float*>(lds);                 // [2 groups][32 values][256 lanes]
+            float* x_ml = park + 2 * 32 * 256;                            // [2 groups][2][256]
+            constexpr int kPitch = 272;                                   // staging row pitch in bytes (256 + 16)
+            unsigned char* stage = lds + (2 * 32 * 256 + 2 * 2 * 256) * 4;  // [128 columns][kPitch]
+            // (register arrays are indexed with compile-time constants only: one copy of the code per group)
+            auto park_half = [&](auto g_c) SHIFTATTN_INLINE {
+                constexpr int GRP = decltype(g_c)::value;
+                float* mine = park + GRP * (32 * 256);
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+                for (int k = 0; k < 2; ++k)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) x_o[(mt * 16 + r) * 256 + t4] = oacc[mt][r];
-            x_ml[t4] = m_used;
-            x_ml[256 + t4] = l_tot;
-        }
-        __syncthreads();
-        if (grp == 0) {
-            const float m1 = x_ml[t4], l1 = x_ml[256 + t4];
-            const float m_star = fmaxf(m_used, m1);
-            const float w0 = m_used == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_used - m_star) * p.c);
-            const float w1 = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m1 - m_star) * p.c);
-            l_tot = l_tot * w0 + l1 * w1;
+                    for (int r = 0; r < 16; ++r) mine[(k * 16 + r) * 256 + t4] = oacc[2 * (1 - GRP) + k][r];
+                x_ml[(GRP * 2) * 256 + t4] = m_used;
+                x_ml[(GRP * 2 + 1) * 256 + t4] = l_tot;
+            };
+            if (grp == 0) park_half(IC<0>{});
+            else park_half(IC<1>{});
+            __syncthreads();
+            auto finish_half = [&](auto g_c) SHIFTATTN_INLINE {
+                constexpr int grp = decltype(g_c)::value;  // shadows the runtime value
+                const float* theirs = park + (1 - grp) * (32 * 256);
+                const float m_o = x_ml[((1 - grp) * 2) * 256 + t4], l_o = x_ml[((1 - grp) * 2 + 1) * 256 + t4];
+                const float m_star = fmaxf(m_used, m_o);
+                const float w_me = m_used == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_used - m_star) * p.c);
+                const float w_o = m_o == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_o - m_star) * p.c);
+                const float l_all = l_tot * w_me + l_o * w_o;
+                const float inv = l_all > 0.f ? p.out_scale / l_all : 0.f;
+                const float a_me = w_me * inv, a_o = w_o * inv;
+                const int cw_m = ((tid_m >> 6) & 3) * 32 + (tid_m & 31), half_m = (tid_m >> 5) & 1;
+                unsigned char* srow = stage + cw_m * kPitch + (64 * grp + 4 * half_m) * 2;
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+                for (int k = 0; k < 2; ++k)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[mt][r] = oacc[mt][r] * w0 + x_o[(mt * 16 + r) * 256 + t4] * w1;
-            // ---- output: accumulator register r of row tile mt is head-dim 32*mt + 8*(r/4) + 4*half + r%4 ----
-            if (pos_col >= 0) {
-                if (p.n_splits == 1) {
-                    const float inv = l_tot > 0.f ? p.out_scale / l_tot : 0.f;
-                    uint16_t* op = p.out + static_cast<size_t>(row_col) * p.out_stride + head_col * kD + 4 * half;
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        bf16x4 v;
 #pragma unroll
-                    for (int mt = 0; mt < 4; ++mt)
+                        for (int x = 0; x < 4; ++x)
+                            v[x] = static_cast<__bf16>(oacc[2 * grp + k][r4 * 4 + x] * a_me + theirs[(k * 16 + r4 * 4 + x) * 256 + t4] * a_o);
+                        *reinterpret_cast<u32x2*>(srow + (32 * k + 8 * r4) * 2) = __builtin_bit_cast(u32x2, v);
+                    }
+            };
+            if (grp == 0) finish_half(IC<0>{});
+            else finish_half(IC<1>{});
+            __syncthreads();
 #pragma unroll
-                        for (int r4 = 0; r4 < 4; ++r4) {
-                            bf16x4 v;
+            for (int i = 0; i < 4; ++i) {
+                const int col = (tid_m >> 4) + 32 * i, piece = tid_m & 15;
+                const int tok_c = tok0 + (col >> p.gs_log2);
+                if (tok_c < q_len) {
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + col * kPitch + piece * 16);
+                    uint16_t* op = p.out + static_cast<size_t>(q_begin + tok_c) * p.out_stride +
+                                   ((hs << p.gs_log2) + (col & gs_mask)) * kD + piece * 8;
+                    *reinterpret_cast<u32x4*>(op) = v;
+                }
+            }
+        } else {
+            // key ranges split over workgroups: group 1 parks (m, l, O) in LDS, group 0 folds it in and writes the
+            // un-normalised partial of this range
+            float* x_o = reinterpret_cast<float*>(lds);                   // [64 values][256 lanes of a group]
+            float* x_ml = x_o + 64 * 256;                                  // [2][256]
+            if (grp == 1) {
 #pragma unroll
-                            for (int x = 0; x < 4; ++x) v[x] = static_cast<__bf16>(oacc[mt][r4 * 4 + x] * inv);
-                            *reinterpret_cast<u32x2*>(op + 32 * mt + 8 * r4) = __builtin_bit_cast(u32x2, v);
-                        }
-                } else {
+                for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) x_o[(mt * 16 + r) * 256 + t4] = oacc[mt][r];
+                x_ml[t4] = m_used;
+                x_ml[256 + t4] = l_tot;
+            }
+            __syncthreads();
+            if (grp == 0) {
+                const float m1 = x_ml[t4], l1 = x_ml[256 + t4];
+                const float m_star = fmaxf(m_used, m1);
+                const float w0 = m_used == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_used - m_star) * p.c);
+                const float w1 = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m1 - m_star) * p.c);
+                l_tot = l_tot * w0 + l1 * w1;
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[mt][r] = oacc[mt][r] * w0 + x_o[(mt * 16 + r) * 256 + t4] * w1;
+                if (pos_col >= 0) {
+                    // accumulator register r of row tile mt is head-dim 32*mt + 8*(r/4) + 4*half + r%4
                     const size_t prow = (static_cast<size_t>(split) * p.total_q + row_col) * p.hq_l + head_col;
                     float* op = p.o_part + prow * kD + 4 * half;
 #pragma unroll
