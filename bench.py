@@ -178,6 +178,21 @@ def main() -> int:
     step_flops = case.flops() + dcase.flops()
     value = step_flops / (ms_per_step * 1e-3) / 1e12
     log(f"[bench] step: {ms_per_step:.4f} ms -> {value:.1f} TFLOP/s of attention")
+    # the same step captured once into a HIP graph and replayed (how the paper's engine issues it, Sec. 3.4); reported
+    # beside the eager figure, which stays the headline
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(args.warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / args.steps
+    log(f"[bench] step replayed from a HIP graph: {ms_per_step_graph:.4f} ms -> "
+        f"{step_flops / (ms_per_step_graph * 1e-3) / 1e12:.1f} TFLOP/s")
 
     # ---- per-phase HIP-event timings, same stream ------------------------------------------------------------
     reps = max(args.steps, 10)
@@ -209,6 +224,7 @@ def main() -> int:
                    "flop_convention": "4*D per (query, visible key) pair per query head",
                    "step_flops": step_flops},
         "roofline": roofline,
+        "ms_per_step_graph_replay": round(ms_per_step_graph, 5),
         "phases": phases,
     }
 
