@@ -128,15 +128,19 @@ __global__ __launch_bounds__(kThreads) void kv_write_block_kernel(const uint16_t
     const int t_loc = threadIdx.x >> 4, dv = threadIdx.x & 15;
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlockSize + t_loc;
     const bool in_range = i < n_tokens;
+    // the rows are requested together with the slots (rows of padding tokens exist too, they are just not
+    // written): one round trip to memory instead of two dependent ones
+    u32x4 kvec = {0u, 0u, 0u, 0u}, vvec = {0u, 0u, 0u, 0u};
+    if (in_range) {
+        const size_t src = static_cast<size_t>(i) * kv_stride + static_cast<size_t>(g) * D + dv * 8;
+        kvec = *reinterpret_cast<const u32x4*>(k_new + src);
+        vvec = *reinterpret_cast<const u32x4*>(v_new + src);
+    }
     const int64_t slot = in_range ? slots[i] : -1;
     const int64_t first = slots[static_cast<int64_t>(blockIdx.x) * kBlockSize];  // blockIdx.x * 16 < n_tokens
     const bool ordered = in_range && first >= 0 && (first % kBlockSize) == 0 && slot == first + t_loc;
     const bool whole_block = __syncthreads_and(ordered);
-    u32x4 kvec = {0u, 0u, 0u, 0u}, vvec = {0u, 0u, 0u, 0u};
     if (in_range && slot >= 0) {
-        const size_t src = static_cast<size_t>(i) * kv_stride + static_cast<size_t>(g) * D + dv * 8;
-        kvec = *reinterpret_cast<const u32x4*>(k_new + src);
-        vvec = *reinterpret_cast<const u32x4*>(v_new + src);
         const int64_t blk = slot / kBlockSize;
         const int off = static_cast<int>(slot % kBlockSize);
         *reinterpret_cast<u32x4*>(cache + cache_part_offset(blk, g, 0, hkv_l, D) + static_cast<size_t>(off) * D + dv * 8) = kvec;

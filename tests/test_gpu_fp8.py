@@ -96,3 +96,14 @@ def test_chunked_prefill_fp8_long_context_with_key_splits(oracle, G):
     from paper_2509_16495_amd import binding as B
     assert B.to_host(cache).tobytes() == ocache.tobytes()
     _check(got, oracle.attention_case(case, ocache, k_scale=SCALES[0], v_scale=SCALES[1]), "bf16")
+
+
+def test_decode_fp8_more_pairs_than_the_flat_kernel_indexes(oracle, G):
+    """2100 (sequence, KV head) pairs: beyond the flat kernel's index, the general kernel takes the FP8 cache."""
+    rng = np.random.Generator(np.random.PCG64(33))
+    ctx = rng.integers(1, 120, size=2100)
+    case = W.make_attn_case("dec_fp8_many", 81, "bf16", [(1, int(c)) for c in ctx], 8, 1, 128, pool_factor=1.1)
+    ocache = oracle.cache_for_case(case, fp8_scales=SCALES)
+    cache = G.cache_for_case(case, fp8_scales=SCALES)
+    got = G.decode_case(case, cache, fp8_scales=SCALES)
+    _check(got, oracle.attention_case(case, ocache, k_scale=SCALES[0], v_scale=SCALES[1]), "bf16")
