@@ -166,7 +166,10 @@ int shiftattn_prefill(const void *q, const void *k_new, const void *v_new, const
  * Same definition with q_len_s = 1, pos = seq_lens[s] - 1.  The contexts of the batch are cut into
  * pieces processed in parallel (equal shares of all tokens per wavefront); partial results are
  * merged in a fixed order, so results are bitwise reproducible from run to run.
- * q, out: [num_seqs][hq_l][D]; k_new/v_new/slot_mapping: n_tokens = num_seqs (or all NULL). */
+ * q, out: [num_seqs][hq_l][D]; k_new/v_new/slot_mapping: n_tokens = num_seqs (or all NULL).
+ * slot_mapping[s], when not negative, must be the slot of position seq_lens[s] - 1 of sequence s as
+ * block_table maps it (the append of a decode step): the tuned kernel writes the new token and attends to
+ * it in one launch and does not re-read that slot through the table. */
 int shiftattn_decode(const void *q, const void *k_new, const void *v_new, const int64_t *slot_mapping,
                      void *kv_cache, const int32_t *block_table, const int32_t *seq_lens, int32_t num_seqs,
                      int32_t max_seq_len, void *out, void *workspace, size_t workspace_bytes,

@@ -293,12 +293,16 @@ int shiftattn_decode(const void* q, const void* k_new, const void* v_new, const 
                     workspace ? workspace_bytes : static_cast<size_t>(0));
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (new_kv) {
+    // the tuned kernel appends the new tokens itself where it can; otherwise a write kernel runs in front
+    const bool fused_append = new_kv && mfma && decode_mfma_appends(num_seqs, s);
+    if (new_kv && !fused_append) {
         e = launch_kv_write(k_new, v_new, slot_mapping, num_seqs, kv_cache, s, st);
         if (e != hipSuccess) return hip_fail(e, "kv_write launch");
     }
     if (mfma)
-        e = launch_decode_mfma(q, kv_cache, block_table, seq_lens, num_seqs, max_seq_len, out, workspace, s, st);
+        e = launch_decode_mfma(q, fused_append ? k_new : nullptr, fused_append ? v_new : nullptr,
+                               fused_append ? slot_mapping : nullptr, kv_cache, block_table, seq_lens, num_seqs, max_seq_len,
+                               out, workspace, s, st);
     else
         e = launch_attn_generic(q, kv_cache, block_table, nullptr, seq_lens, num_seqs, num_seqs, out, s, st);
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "decode launch");

@@ -25,6 +25,12 @@
 // consecutive rows.  decode_splitk_kernel (one workgroup per fixed-size chunk of one sequence) remains
 // for batches with more pairs than the flat kernel indexes in LDS.
 //
+// Appending the new token (flat kernel): when the call brings the new tokens' K/V, the wavefront whose
+// range holds the last group of a (sequence, KV head) pair stores that pair's new K row and V column into
+// the cache itself and overwrites them in its parked copy of the group, so the result is the one of
+// "append, then attend" without a separate launch in front.  The slot of a sequence's new token must be
+// the slot of its position seq_lens - 1 (the append a decode step performs).
+//
 // FP8 E4M3 cache (flat kernel only): a cache block is half as many bytes in the same arrangement, so a
 // group takes eight 1-KiB loads instead of sixteen; every loaded 16-byte piece (16 codes) is widened in
 // registers to the two bf16 pieces it stands for (exact: every E4M3 value is a bf16 value) and parked
@@ -79,12 +85,20 @@ __device__ inline void widen_fp8(u32x4 codes, u32x4& lo, u32x4& hi) {
     }
 }
 
-template <bool kFp8>
+struct AppendArgs {
+    const uint16_t* k_new;   // [num_seqs][hkv_l][D] bf16, row stride kv_stride elements
+    const uint16_t* v_new;
+    const int64_t* slots;    // [num_seqs]; negative: nothing to append for that sequence
+    int64_t kv_stride;
+    float k_scale, v_scale;  // FP8 cache only
+};
+
+template <bool kFp8, bool kAppend>
 __global__ __launch_bounds__(kWaves * 64, 2) void decode_flat_kernel(
-    const uint16_t* __restrict__ q, int64_t q_stride, const uint16_t* __restrict__ cache,
+    const uint16_t* __restrict__ q, int64_t q_stride, uint16_t* __restrict__ cache,
     const int32_t* __restrict__ block_table, int max_blocks, const int32_t* __restrict__ seq_lens,
     float* __restrict__ o_part, float* __restrict__ ml_part, int2* __restrict__ plan, int num_seqs, int hq_l, int hkv_l,
-    float c, int r_min) {
+    float c, int r_min, AppendArgs ap) {
     __shared__ __attribute__((aligned(16))) unsigned char smem[kWaves * kStageBytes];
     __shared__ int cum[kFlatMaxPairs + 1];
     __shared__ int wave_sum[kWaves];
@@ -322,6 +336,59 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_flat_kernel(
                 *reinterpret_cast<u32x4*>(my + kw[j ^ 1] + 4096 + 1024 * j) = f.k[4 + j];
                 *reinterpret_cast<u32x4*>(my + vw + 1024 * j) = f.v[j];
                 *reinterpret_cast<u32x4*>(my + vw + 4096 + 1024 * j) = f.v[4 + j];
+            }
+        }
+        if constexpr (kAppend) {
+            const int off_g = pos - seg_begin;
+            if (off_g + kGroup >= ctx) {  // uniform: this group holds the pair's last token, position ctx - 1
+                const int s_a = pair / hkv_l, g_a = pair % hkv_l;
+                const int64_t slot = ap.slots[s_a];
+                if (slot >= 0) {
+                    const int tl = ctx - 1 - off_g, b = tl >> 4, t = tl & 15;  // block of the group, offset in it
+                    const int64_t blk_a = slot / kBlockSize;
+                    const int off_a = static_cast<int>(slot % kBlockSize);
+                    const size_t row = static_cast<size_t>(s_a) * ap.kv_stride + static_cast<size_t>(g_a) * kD;
+                    unsigned char* cache8 = reinterpret_cast<unsigned char*>(cache);
+                    if (lane < 16) {  // K row: sixteen 16-byte pieces
+                        u32x4 kv = *reinterpret_cast<const u32x4*>(ap.k_new + row + 8 * lane);
+                        if constexpr (kFp8) {
+                            float x[8];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                x[2 * e] = __uint_as_float(kv[e] << 16);
+                                x[2 * e + 1] = __uint_as_float(kv[e] & 0xFFFF0000u);
+                            }
+                            typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+                            u32x2_t codes;
+                            codes[0] = e4m3_pair(x[0], x[1], ap.k_scale) | (e4m3_pair(x[2], x[3], ap.k_scale) << 16);
+                            codes[1] = e4m3_pair(x[4], x[5], ap.k_scale) | (e4m3_pair(x[6], x[7], ap.k_scale) << 16);
+                            *reinterpret_cast<u32x2_t*>(cache8 + cache_part_offset(blk_a, g_a, 0, hkv_l, kD) + off_a * kD + 8 * lane) = codes;
+                            u32x4 lo, hi;
+                            widen_fp8(u32x4{codes[0], codes[1], 0u, 0u}, lo, hi);
+                            kv = lo;  // what the codes stand for
+                        } else {
+                            *reinterpret_cast<u32x4*>(cache + cache_part_offset(blk_a, g_a, 0, hkv_l, kD) + off_a * kD + 8 * lane) = kv;
+                        }
+                        *reinterpret_cast<u32x4*>(my + b * 4096 + t * 256 + ((lane ^ (t & 3) ^ (4 * ((t >> 2) ^ b))) << 4)) = kv;
+                    }
+#pragma unroll
+                    for (int x2 = 0; x2 < 2; ++x2) {  // V column: one element per head-dim row
+                        const int d = lane + 64 * x2;
+                        uint16_t vv = ap.v_new[row + d];
+                        if constexpr (kFp8) {
+                            const uint32_t code = e4m3_pair(__uint_as_float(static_cast<uint32_t>(vv) << 16), 0.f, ap.v_scale) & 0xFFu;
+                            cache8[cache_part_offset(blk_a, g_a, 1, hkv_l, kD) + static_cast<size_t>(d) * kBlockSize + off_a] =
+                                static_cast<unsigned char>(code);
+                            typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+                            vv = static_cast<uint16_t>(__builtin_bit_cast(
+                                uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(static_cast<int>(code), 1.0f, false)) & 0xFFFFu);
+                        } else {
+                            cache[cache_part_offset(blk_a, g_a, 1, hkv_l, kD) + static_cast<size_t>(d) * kBlockSize + off_a] = vv;
+                        }
+                        const int pc = 2 * (d & 31) + (t >> 3);
+                        *reinterpret_cast<uint16_t*>(my + 8192 + 4096 * b + 1024 * (d >> 5) + ((pc ^ ((pc >> 4) & 1)) << 4) + 2 * (t & 7)) = vv;
+                    }
+                }
             }
         }
         int nn_pos = n_pos + kGroup, nn_pair = n_pair, nn_begin = n_begin, nn_end = n_end, nn_ctx = n_ctx;
@@ -649,9 +716,11 @@ size_t decode_mfma_workspace(int num_seqs, int max_seq_len, const AttnShape& a) 
     return rows * (kD + 2) * sizeof(float);
 }
 
-hipError_t launch_decode_mfma(const void* q, const void* cache, const int32_t* block_table, const int32_t* seq_lens,
-                              int num_seqs, int max_seq_len, void* out, void* workspace, const AttnShape& a,
-                              hipStream_t st) {
+bool decode_mfma_appends(int num_seqs, const AttnShape& a) { return use_flat(num_seqs, a); }
+
+hipError_t launch_decode_mfma(const void* q, const void* k_new, const void* v_new, const int64_t* slots, void* cache,
+                              const int32_t* block_table, const int32_t* seq_lens, int num_seqs, int max_seq_len,
+                              void* out, void* workspace, const AttnShape& a, hipStream_t st) {
     if (num_seqs == 0 || max_seq_len <= 0) return hipSuccess;
     const float c = a.scale * a.k_scale * 1.4426950408889634f;  // logits of an FP8 cache carry k_scale
     if (use_flat(num_seqs, a)) {
@@ -664,14 +733,21 @@ hipError_t launch_decode_mfma(const void* q, const void* cache, const int32_t* b
         const int padded_max = (max_seq_len + kGroup - 1) / kGroup * kGroup;
         int r_min = (padded_max / (kMaxParts - 24) + kGroup) / kGroup * kGroup;
         if (r_min < 2 * kGroup) r_min = 2 * kGroup;
-        if (a.kv_fp8())
-            decode_flat_kernel<true><<<kFlatWorkgroups, kWaves * 64, 0, st>>>(
-                static_cast<const uint16_t*>(q), a.q_stride, static_cast<const uint16_t*>(cache), block_table, a.max_blocks,
-                seq_lens, o_part, ml_part, plan, num_seqs, a.hq_l, a.hkv_l, c, r_min);
-        else
-            decode_flat_kernel<false><<<kFlatWorkgroups, kWaves * 64, 0, st>>>(
-                static_cast<const uint16_t*>(q), a.q_stride, static_cast<const uint16_t*>(cache), block_table, a.max_blocks,
-                seq_lens, o_part, ml_part, plan, num_seqs, a.hq_l, a.hkv_l, c, r_min);
+        const AppendArgs ap = {static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new), slots, a.kv_stride,
+                               a.k_scale, a.v_scale};
+        const bool append = k_new != nullptr;
+        auto launch = [&](auto kernel) {
+            kernel<<<kFlatWorkgroups, kWaves * 64, 0, st>>>(static_cast<const uint16_t*>(q), a.q_stride,
+                                                            static_cast<uint16_t*>(cache), block_table, a.max_blocks, seq_lens,
+                                                            o_part, ml_part, plan, num_seqs, a.hq_l, a.hkv_l, c, r_min, ap);
+        };
+        if (a.kv_fp8()) {
+            if (append) launch(decode_flat_kernel<true, true>);
+            else launch(decode_flat_kernel<true, false>);
+        } else {
+            if (append) launch(decode_flat_kernel<false, true>);
+            else launch(decode_flat_kernel<false, false>);
+        }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         return launch_combine_flat(o_part, ml_part, plan, num_seqs, a.hq_l, a.hq_l / a.hkv_l, out, a.out_stride, a.v_scale,

@@ -62,9 +62,12 @@ hipError_t launch_combine_flat(const float* o_part, const float* ml_part, const 
 // decode_mfma.hip : bf16 q/out, D = 128, hq_l/hkv_l <= 16; cache bf16 or FP8 E4M3
 bool decode_mfma_supported(const AttnShape& a, int num_seqs);
 size_t decode_mfma_workspace(int num_seqs, int max_seq_len, const AttnShape& a);
-hipError_t launch_decode_mfma(const void* q, const void* cache, const int32_t* block_table,
-                              const int32_t* seq_lens, int num_seqs, int max_seq_len, void* out,
-                              void* workspace, const AttnShape& a, hipStream_t st);
+// k_new / v_new / slots non-null: the kernel also appends the new token of every sequence (only where
+// decode_mfma_appends() says so; the caller then launches no separate K/V write)
+bool decode_mfma_appends(int num_seqs, const AttnShape& a);
+hipError_t launch_decode_mfma(const void* q, const void* k_new, const void* v_new, const int64_t* slots, void* cache,
+                              const int32_t* block_table, const int32_t* seq_lens, int num_seqs, int max_seq_len,
+                              void* out, void* workspace, const AttnShape& a, hipStream_t st);
 
 // prefill_mfma.hip : bf16 q/out, D = 128; cache bf16, or FP8 E4M3 widened into workspace first
 bool prefill_mfma_supported(const AttnShape& a, int num_seqs, int max_seq_len);
@@ -77,6 +80,17 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
 // ceilings.hip : attainable-rate probes for benchmark reports
 hipError_t launch_mfma_ceiling(const void* operands, void* sink, int iters, int64_t* flops, hipStream_t st);
 hipError_t launch_hbm_read_ceiling(const void* src, size_t bytes, void* sink, int64_t* bytes_read, hipStream_t st);
+
+// FP8 E4M3 codes of a / scale and b / scale in bits 0..7 and 8..15: float32 quotient, nearest code with
+// ties to the even code, clamped to +-448 first so that nothing overflows, NaN quotient -> NaN code
+__device__ inline uint32_t e4m3_pair(float a, float b, float scale) {
+    const float qa = a / scale, qb = b / scale;
+    const float ca = fminf(fmaxf(qa, -448.f), 448.f), cb = fminf(fmaxf(qb, -448.f), 448.f);
+    uint32_t w = static_cast<uint32_t>(__builtin_amdgcn_cvt_pk_fp8_f32(ca, cb, 0, false)) & 0xFFFFu;
+    if (qa != qa) w |= 0x7Fu;
+    if (qb != qb) w |= 0x7F00u;
+    return w;
+}
 
 // element offsets inside the cache: kv_cache[block][kv head][2][16*D]
 __host__ __device__ inline size_t cache_part_offset(int64_t block, int g, int part, int hkv_l, int D) {

@@ -177,14 +177,6 @@ __global__ __launch_bounds__(kThreads) void kv_write_block_kernel(const uint16_t
 __device__ inline float elem_to_float(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
 __device__ inline float elem_to_float(float f) { return f; }
 
-__device__ inline uint32_t e4m3_pair(float a, float b, float scale) {
-    const float qa = a / scale, qb = b / scale;
-    const float ca = fminf(fmaxf(qa, -448.f), 448.f), cb = fminf(fmaxf(qb, -448.f), 448.f);
-    uint32_t w = static_cast<uint32_t>(__builtin_amdgcn_cvt_pk_fp8_f32(ca, cb, 0, false)) & 0xFFFFu;
-    if (qa != qa) w |= 0x7Fu;
-    if (qb != qb) w |= 0x7F00u;
-    return w;
-}
 
 template <typename Elem>
 __global__ __launch_bounds__(kThreads) void kv_write_fp8_kernel(const Elem* __restrict__ k_new,

@@ -155,6 +155,20 @@ def test_decode_fused_kv_write_and_fp32(oracle, G):
     _check(G.decode_case(case, G.cache_for_case(case)), want, "f32")
 
 
+@pytest.mark.parametrize("hq,hkv", [(8, 1), (4, 2), (16, 1)])
+def test_decode_appends_the_new_token_itself(oracle, G, hq, hkv):
+    """Decode with the new tokens' K/V handed to the call (one launch writes and attends): contexts that end at
+    every offset of a block and of a 32-token group."""
+    from paper_2509_16495_amd import binding as B
+    ctx = list(range(1, 70)) + [255, 256, 257, 1000, 1024, 4097]
+    case = W.make_attn_case("dec_append", 83, "bf16", [(1, c) for c in ctx], hq, hkv, 128, pool_factor=1.4)
+    ocache = oracle.cache_for_case(case)
+    cache = G.cache_for_case(case, only_cached=True)
+    got = G.decode_case(case, cache, fused_new_kv=True)
+    assert B.to_host(cache).tobytes() == ocache.tobytes()
+    _check(got, oracle.attention_case(case, ocache), "bf16")
+
+
 def test_unwritten_cache_slots_may_hold_nan(oracle, G):
     """Slots past a sequence's context are never written; whatever they hold must not leak."""
     case = W.make_attn_case("t", 58, "bf16", [(1, 5), (1, 41), (1, 530)], 8, 1, 128)

@@ -107,3 +107,17 @@ def test_decode_fp8_more_pairs_than_the_flat_kernel_indexes(oracle, G):
     cache = G.cache_for_case(case, fp8_scales=SCALES)
     got = G.decode_case(case, cache, fp8_scales=SCALES)
     _check(got, oracle.attention_case(case, ocache, k_scale=SCALES[0], v_scale=SCALES[1]), "bf16")
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 1), (4, 2)])
+def test_decode_fp8_appends_the_new_token_itself(oracle, G, hq, hkv):
+    """Decode with the new tokens' K/V handed to the call: the cache ends up with the oracle's codes and the new
+    token is attended to (contexts that end at every offset of a block and of a 32-token group)."""
+    from paper_2509_16495_amd import binding as B
+    ctx = list(range(1, 70)) + [255, 256, 257, 1000, 1024, 4097]
+    case = W.make_attn_case("dec_fp8_append", 82, "bf16", [(1, c) for c in ctx], hq, hkv, 128, pool_factor=1.4)
+    ocache = oracle.cache_for_case(case, fp8_scales=SCALES)
+    cache = G.cache_for_case(case, only_cached=True, fp8_scales=SCALES)
+    got = G.decode_case(case, cache, fused_new_kv=True, fp8_scales=SCALES)
+    assert B.to_host(cache).tobytes() == ocache.tobytes()
+    _check(got, oracle.attention_case(case, ocache, k_scale=SCALES[0], v_scale=SCALES[1]), "bf16")
