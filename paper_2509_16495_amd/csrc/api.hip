@@ -138,7 +138,7 @@ bool use_prefill_mfma(const AttnShape& s, int num_seqs, int max_seq_len) {
     return !force_generic() && prefill_mfma_supported(s, num_seqs, max_seq_len);
 }
 bool use_decode_mfma(const AttnShape& s, int num_seqs) {
-    return !force_generic() && decode_mfma_supported(s, num_seqs) && num_seqs <= 65535;
+    return !force_generic() && decode_mfma_supported(s, num_seqs);
 }
 
 }  // namespace

@@ -2,9 +2,8 @@
 // paper's observation that decoding re-reads the whole KV cache per token and ends up bound by
 // memory bandwidth, Sec. 4.3).  bf16 cache, head_dim 128, up to 16 query heads per KV head.
 //
-// Work decomposition: one workgroup per (sequence, KV head, chunk of the context); its four
-// wavefronts take 32-token groups (two cache blocks) round-robin.  All query heads of the GQA group
-// ride in the 16-wide N dimension of a 16x16x32 bf16 MFMA, so every K and V byte is read from HBM
+// A wavefront works through its tokens in 32-token groups (two cache blocks).  All query heads of the GQA
+// group ride in the 16-wide N dimension of a 16x16x32 bf16 MFMA, so every K and V byte is read from HBM
 // once per (sequence, KV head) and used for all heads:
 //   S^T[token][head]  = K[token][:] . Q^T[:][head]        A = K rows,   B = Q^T (registers)
 //   O^T[d][head]     += V^T[d][token] . P^T[token][head]   A = V^T rows, B = P^T (from S^T regs)
@@ -13,17 +12,16 @@
 // (two 16-token tiles x four rows) are eight consecutive tokens: exactly the k-slice of P^T the
 // second MFMA needs from that lane, and exactly one 16-byte piece of a V^T row.
 //
-// Each workgroup writes one un-normalised partial (max, sum, O) per head; launch_combine merges
-// the chunks of a sequence in chunk order, so results do not depend on scheduling.
+// Partial results are un-normalised (max, sum, O) per head; the merge kernel folds the parts of a row in
+// part order, so results do not depend on scheduling.
 //
-// Two decompositions share that arithmetic.  decode_flat_kernel (the default) lays all (sequence, KV
-// head) pairs end to end, each padded to a multiple of 32 tokens, and gives every wavefront of a
-// fixed-size grid the same number of tokens of that line, whatever the mix of context lengths: all
-// wavefronts start and finish together, none waits at a barrier, and a wavefront pays its start-up
-// latency once.  A wavefront emits one partial per sequence its range touches; sorted by position
-// these partials are numbered (wavefront index + pair index), so the parts of a pair are
-// consecutive rows.  decode_splitk_kernel (one workgroup per fixed-size chunk of one sequence) remains
-// for batches with more pairs than the flat kernel indexes in LDS.
+// Decomposition: decode_flat_kernel lays all (sequence, KV head) pairs end to end, each padded to a
+// multiple of 32 tokens, and gives every wavefront of a fixed-size grid the same number of tokens of
+// that line, whatever the mix of context lengths: all wavefronts start and finish together, none waits
+// at a barrier, and a wavefront pays its start-up latency once.  A wavefront emits one partial per
+// sequence its range touches; sorted by position these partials are numbered (wavefront index + pair
+// index), so the parts of a pair are consecutive rows.  The kernel indexes up to 2048 pairs in LDS; a
+// larger batch is served in runs of that many pairs, one launch (and one merge) per run.
 //
 // Appending the new token (flat kernel): when the call brings the new tokens' K/V, the wavefront whose
 // range holds the last group of a (sequence, KV head) pair stores that pair's new K row and V column into
@@ -168,7 +166,12 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_flat_kernel(
     const int col = lane & 15;
     const int grp = lane >> 4;
     unsigned char* my = smem + wave * kStageBytes;
-    // LDS positions (see decode_splitk_kernel for the layout), folded so that four bases serve the K
+    // LDS layout of a parked group (per wavefront, 16-byte pieces).  K of block b (4 KiB at 4096 b): row t at
+    // 256 t, piece p of the row stored at column p ^ (t & 3) ^ 4 ((t >> 2) ^ b); load j of a block brings rows
+    // 4 j + lane / 16, piece lane % 16.  V^T of block b (4 KiB at 8192 + 4096 b): piece 64 j + lane of load j
+    // (row 32 j + lane / 2, half lane % 2) stored with its low bit flipped in every other run of 16 pieces.
+    // K operand: token row tau (+4 for tile b) of block k_sel, piece grp + 4 kk; V^T operand: piece
+    // 2 (16 mt + col) + grp % 2 of block grp / 2.  The positions are folded so that four bases serve the K
     // writes, four the K reads and one each the V^T writes and reads; the rest are immediate offsets.
     //   K write, block b, load j   : kw[j ^ b] + 4096 b + 1024 j
     //   K read, tile a / b, step kk: kr[kk] / kr[kk ^ 1] + 1024
@@ -467,279 +470,57 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_flat_kernel(
     flush(pair);
 }
 
-template <bool kPrefetch>
-__global__ __launch_bounds__(kWaves * 64, 2) void decode_splitk_kernel(
-    const uint16_t* __restrict__ q, int64_t q_stride, const uint16_t* __restrict__ cache,
-    const int32_t* __restrict__ block_table, int max_blocks, const int32_t* __restrict__ seq_lens,
-    float* __restrict__ o_part, float* __restrict__ ml_part, int num_seqs, int hq_l, int hkv_l, float c,
-    int chunk_tokens) {
-    const int chunk = blockIdx.x, s = blockIdx.y, g = blockIdx.z;
-    const int ctx = seq_lens[s];
-    const int t_begin = chunk * chunk_tokens;
-    if (t_begin >= ctx) return;  // uniform for the workgroup
-    const int t_end = min(ctx, t_begin + chunk_tokens);
-    const int n_groups = (t_end - t_begin + kGroup - 1) / kGroup;
-    const int G = hq_l / hkv_l;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int col = lane & 15;
-    const int grp = lane >> 4;
-
-    __shared__ __attribute__((aligned(16))) unsigned char smem[kWaves * kStageBytes];
-    unsigned char* my = smem + wave * kStageBytes;
-
-    bf16x8 qf[4];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (col < G)
-            v = *reinterpret_cast<const u32x4*>(q + static_cast<size_t>(s) * q_stride +
-                                                static_cast<size_t>(g * G + col) * kD + 8 * (grp + 4 * kk));
-        qf[kk] = as_bf16x8(v);
-    }
-
-    const int32_t* table = block_table + static_cast<size_t>(s) * max_blocks;
-    const int last_block = (ctx - 1) / kBlockSize;
-    const int tau_a = ((col >> 2) << 3) + (col & 3);
-    const int k_sel = tau_a >> 4;
-    const int k_off_a = tau_a & 15;
-
-    // LDS write positions of this lane's pieces (16-byte units).  K block b, load j: row 4j + lane/16,
-    // piece lane%16 stored at column piece ^ row ^ 4b.  V^T block, load j: piece 64j + lane stored with
-    // its low bit flipped in every other run of 16 pieces.
-    int k_wr[2][4], v_wr[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int row = 4 * j + (lane >> 4);
-#pragma unroll
-        for (int b = 0; b < 2; ++b) k_wr[b][j] = b * 4096 + row * 256 + (((lane & 15) ^ row ^ (4 * b)) << 4);
-        const int piece = 64 * j + lane;
-        v_wr[j] = 8192 + ((piece ^ ((piece >> 4) & 1)) << 4);
-    }
-    // LDS read positions.  K: token row k_off (+4 for tile b) of block k_sel, piece grp + 4kk.
-    int k_rd_a[4], k_rd_b[4], v_rd[8];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        const int piece = grp + 4 * kk;
-        k_rd_a[kk] = k_sel * 4096 + k_off_a * 256 + ((piece ^ k_off_a ^ (4 * k_sel)) << 4);
-        k_rd_b[kk] = k_sel * 4096 + (k_off_a + 4) * 256 + ((piece ^ (k_off_a + 4) ^ (4 * k_sel)) << 4);
-    }
-#pragma unroll
-    for (int mt = 0; mt < 8; ++mt) {
-        const int piece = (16 * mt + col) * 2 + (grp & 1);
-        v_rd[mt] = 8192 + (grp >> 1) * 4096 + ((piece ^ ((piece >> 4) & 1)) << 4);
-    }
-
-    auto load_group = [&](int gi, GroupFrags& f) {
-        const int b0 = (t_begin + gi * kGroup) / kBlockSize;
-        const int64_t blk0 = table[b0];
-        const int64_t blk1 = table[min(b0 + 1, last_block)];
-        const u32x4* k0 = reinterpret_cast<const u32x4*>(cache + cache_part_offset(blk0, g, 0, hkv_l, kD)) + lane;
-        const u32x4* k1 = reinterpret_cast<const u32x4*>(cache + cache_part_offset(blk1, g, 0, hkv_l, kD)) + lane;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            f.k[j] = __builtin_nontemporal_load(k0 + 64 * j);
-            f.k[4 + j] = __builtin_nontemporal_load(k1 + 64 * j);
-            f.v[j] = __builtin_nontemporal_load(k0 + 256 + 64 * j);      // V^T follows K inside the block
-            f.v[4 + j] = __builtin_nontemporal_load(k1 + 256 + 64 * j);
-        }
-    };
-
-    f32x4 o[8];
-#pragma unroll
-    for (int mt = 0; mt < 8; ++mt) o[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY;
-    float l_run = 0.f;
-
-    GroupFrags cur, nxt;
-    if (kPrefetch && wave < n_groups) load_group(wave, cur);
-    for (int gi = wave; gi < n_groups; gi += kWaves) {
-        const bool has_next = kPrefetch && gi + kWaves < n_groups;
-        if (!kPrefetch) load_group(gi, cur);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            *reinterpret_cast<u32x4*>(my + k_wr[0][j]) = cur.k[j];
-            *reinterpret_cast<u32x4*>(my + k_wr[1][j]) = cur.k[4 + j];
-            *reinterpret_cast<u32x4*>(my + v_wr[j]) = cur.v[j];
-            *reinterpret_cast<u32x4*>(my + 4096 + v_wr[j]) = cur.v[4 + j];
-        }
-        if (has_next) load_group(gi + kWaves, nxt);
-
-        f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const bf16x8 ka = as_bf16x8(*reinterpret_cast<const u32x4*>(my + k_rd_a[kk]));
-            const bf16x8 kb = as_bf16x8(*reinterpret_cast<const u32x4*>(my + k_rd_b[kk]));
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[kk], sa, 0, 0, 0);
-            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb, qf[kk], sb, 0, 0, 0);
-        }
-        u32x4 vf[8];
-#pragma unroll
-        for (int mt = 0; mt < 8; ++mt) vf[mt] = *reinterpret_cast<const u32x4*>(my + v_rd[mt]);
-
-        const int t0 = t_begin + gi * kGroup + 8 * grp;
-        const int n_valid = t_end - t0;
-        if (t_begin + (gi + 1) * kGroup > t_end) {  // last, partial group of the context: uniform branch
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                if (r >= n_valid) sa[r] = -INFINITY;
-                if (4 + r >= n_valid) sb[r] = -INFINITY;
-            }
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const uint32_t mask = n_valid > 2 * w + 1 ? 0xFFFFFFFFu : (n_valid > 2 * w ? 0x0000FFFFu : 0u);
-#pragma unroll
-                for (int mt = 0; mt < 8; ++mt) vf[mt][w] &= mask;
-            }
-        }
-        float mx = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])), fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-        const float mc = m_new * c;
-        float pa[4], pb[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            pa[r] = __builtin_amdgcn_exp2f(fmaf(sa[r], c, -mc));
-            pb[r] = __builtin_amdgcn_exp2f(fmaf(sb[r], c, -mc));
-        }
-        l_run = l_run * alpha + ((pa[0] + pa[1]) + (pa[2] + pa[3])) + ((pb[0] + pb[1]) + (pb[2] + pb[3]));
-        m_run = m_new;
-        bf16x8 pf;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            pf[r] = static_cast<__bf16>(pa[r]);
-            pf[4 + r] = static_cast<__bf16>(pb[r]);
-        }
-#pragma unroll
-        for (int mt = 0; mt < 8; ++mt) {
-            o[mt] *= alpha;
-            o[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vf[mt]), pf, o[mt], 0, 0, 0);
-        }
-        if (has_next) cur = nxt;
-    }
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-
-    // merge the four wavefronts through LDS (the staging area is free once every wavefront is done)
-    __syncthreads();
-    float* o_s = reinterpret_cast<float*>(smem);                       // [kWaves][16][kOPad]
-    float* m_s = o_s + kWaves * 16 * kOPad;                            // [kWaves][16]
-    float* l_s = m_s + kWaves * 16;                                    // [kWaves][16]
-#pragma unroll
-    for (int mt = 0; mt < 8; ++mt)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) o_s[(wave * 16 + col) * kOPad + 16 * mt + 4 * grp + r] = o[mt][r];
-    if (grp == 0) {
-        m_s[wave * 16 + col] = m_run * c;
-        l_s[wave * 16 + col] = l_run;
-    }
-    __syncthreads();
-    const size_t part_row0 = (static_cast<size_t>(chunk) * num_seqs + s) * hq_l + static_cast<size_t>(g) * G;
-    for (int idx = threadIdx.x; idx < G * kD; idx += kWaves * 64) {
-        const int head = idx / kD, d = idx % kD;
-        float m_star = m_s[head];
-#pragma unroll
-        for (int w = 1; w < kWaves; ++w) m_star = fmaxf(m_star, m_s[w * 16 + head]);
-        float acc = 0.f, l_star = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float wgt = __builtin_amdgcn_exp2f(m_s[w * 16 + head] - m_star);
-            acc += o_s[(w * 16 + head) * kOPad + d] * wgt;
-            l_star += l_s[w * 16 + head] * wgt;
-        }
-        o_part[(part_row0 + head) * kD + d] = acc;
-        if (d == 0) {
-            ml_part[(part_row0 + head) * 2] = m_star;
-            ml_part[(part_row0 + head) * 2 + 1] = l_star;
-        }
-    }
-}
-
-int env_int(const char* name, int dflt) {
-    const char* v = getenv(name);
-    return v ? atoi(v) : dflt;
-}
-
-// Context tokens per workgroup.  Longer chunks amortise the per-workgroup start-up (three dependent
-// loads before the first K byte arrives) and the partial-result traffic; shorter ones balance the
-// load.  Take about two workgroups per resident slot (256 CUs x 2) for a batch whose sequences all
-// had the maximum length, within [512, 2048], and never more parts per row than the merge kernel
-// holds.  Only host-side quantities enter, so the choice is stable under graph capture.
-inline int chunk_tokens(int num_seqs, int hkv_l, int max_seq_len) {
-    int c = env_int("SHIFTATTN_DECODE_CHUNK", 0);
-    if (c <= 0) {
-        const int64_t tokens = static_cast<int64_t>(max_seq_len) * num_seqs * hkv_l;
-        c = static_cast<int>(tokens / 1024);
-        if (c < kDecodeChunk) c = kDecodeChunk;
-        if (c > 4 * kDecodeChunk) c = 4 * kDecodeChunk;
-    }
-    const int floor_c = (max_seq_len + kMaxParts - 1) / kMaxParts;
-    if (c < floor_c) c = floor_c;
-    if (c < kGroup) c = kGroup;
-    return (c + kGroup - 1) / kGroup * kGroup;
-}
-inline int max_chunks_of(int num_seqs, int hkv_l, int max_seq_len) {
-    const int c = chunk_tokens(num_seqs, hkv_l, max_seq_len);
-    return (max_seq_len + c - 1) / c;
-}
-
 }  // namespace
 
 namespace {
 
-inline bool use_flat(int num_seqs, const AttnShape& a) {
-    return static_cast<int64_t>(num_seqs) * a.hkv_l <= kFlatMaxPairs && (a.kv_fp8() || env_int("SHIFTATTN_DECODE_FLAT", 1) != 0);
+// sequences per launch: as many as give the kernel's pair index its fill
+inline int seqs_per_launch(const AttnShape& a) { return kFlatMaxPairs / a.hkv_l; }
+// partial rows of a launch over n sequences: one per (wavefront, pair) whose ranges meet, numbered wavefront + pair
+inline size_t flat_rows(int n, const AttnShape& a) {
+    return (static_cast<size_t>(kFlatWorkers) + static_cast<size_t>(n) * a.hkv_l) * (a.hq_l / a.hkv_l);
 }
 
 }  // namespace
 
-// an FP8 cache is read by the flat kernel only
-bool decode_mfma_supported(const AttnShape& a, int num_seqs) {
-    return a.elem == 2 && a.D == kD && a.hq_l % a.hkv_l == 0 && a.hq_l / a.hkv_l <= 16 &&
-           (!a.kv_fp8() || static_cast<int64_t>(num_seqs) * a.hkv_l <= kFlatMaxPairs);
+bool decode_mfma_supported(const AttnShape& a, int /*num_seqs*/) {
+    return a.elem == 2 && a.D == kD && a.hq_l % a.hkv_l == 0 && a.hq_l / a.hkv_l <= 16 && a.hkv_l <= kFlatMaxPairs;
 }
 
-namespace {
-
-// partial rows of the flat kernel: one per (wavefront, pair) whose ranges meet, numbered wavefront + pair
-inline size_t flat_rows(int num_seqs, const AttnShape& a) {
-    return (static_cast<size_t>(kFlatWorkers) + static_cast<size_t>(num_seqs) * a.hkv_l) * (a.hq_l / a.hkv_l);
+size_t decode_mfma_workspace(int num_seqs, int /*max_seq_len*/, const AttnShape& a) {
+    const int n = num_seqs < seqs_per_launch(a) ? num_seqs : seqs_per_launch(a);
+    return flat_rows(n, a) * (kD + 2) * sizeof(float) + static_cast<size_t>(n) * a.hkv_l * sizeof(int2);
 }
 
-}  // namespace
-
-size_t decode_mfma_workspace(int num_seqs, int max_seq_len, const AttnShape& a) {
-    if (use_flat(num_seqs, a))
-        return flat_rows(num_seqs, a) * (kD + 2) * sizeof(float) + static_cast<size_t>(num_seqs) * a.hkv_l * sizeof(int2);
-    const size_t rows = static_cast<size_t>(max_chunks_of(num_seqs, a.hkv_l, max_seq_len)) * num_seqs * a.hq_l;
-    return rows * (kD + 2) * sizeof(float);
-}
-
-bool decode_mfma_appends(int num_seqs, const AttnShape& a) { return use_flat(num_seqs, a); }
+bool decode_mfma_appends(int /*num_seqs*/, const AttnShape& /*a*/) { return true; }
 
 hipError_t launch_decode_mfma(const void* q, const void* k_new, const void* v_new, const int64_t* slots, void* cache,
                               const int32_t* block_table, const int32_t* seq_lens, int num_seqs, int max_seq_len,
                               void* out, void* workspace, const AttnShape& a, hipStream_t st) {
     if (num_seqs == 0 || max_seq_len <= 0) return hipSuccess;
     const float c = a.scale * a.k_scale * 1.4426950408889634f;  // logits of an FP8 cache carry k_scale
-    if (use_flat(num_seqs, a)) {
-        const size_t rows = flat_rows(num_seqs, a);
+    // tokens per wavefront never fall below this, so that no output row has more parts than the
+    // merge kernel holds (and tiny batches are not shredded into one-group partials)
+    const int padded_max = (max_seq_len + kGroup - 1) / kGroup * kGroup;
+    int r_min = (padded_max / (kMaxParts - 24) + kGroup) / kGroup * kGroup;
+    if (r_min < 2 * kGroup) r_min = 2 * kGroup;
+    const bool append = k_new != nullptr;
+    const int per = seqs_per_launch(a);
+    for (int s0 = 0; s0 < num_seqs; s0 += per) {  // runs share the workspace: same stream, one after the other
+        const int n = num_seqs - s0 < per ? num_seqs - s0 : per;
+        const size_t rows = flat_rows(n, a);
         float* o_part = static_cast<float*>(workspace);
         float* ml_part = o_part + rows * kD;
         int2* plan = reinterpret_cast<int2*>(ml_part + rows * 2);
-        // tokens per wavefront never fall below this, so that no output row has more parts than the
-        // merge kernel holds (and tiny batches are not shredded into one-group partials)
-        const int padded_max = (max_seq_len + kGroup - 1) / kGroup * kGroup;
-        int r_min = (padded_max / (kMaxParts - 24) + kGroup) / kGroup * kGroup;
-        if (r_min < 2 * kGroup) r_min = 2 * kGroup;
-        const AppendArgs ap = {static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new), slots, a.kv_stride,
-                               a.k_scale, a.v_scale};
-        const bool append = k_new != nullptr;
+        const uint16_t* q_run = static_cast<const uint16_t*>(q) + static_cast<size_t>(s0) * a.q_stride;
+        uint16_t* out_run = static_cast<uint16_t*>(out) + static_cast<size_t>(s0) * a.out_stride;
+        const AppendArgs ap = {append ? static_cast<const uint16_t*>(k_new) + static_cast<size_t>(s0) * a.kv_stride : nullptr,
+                               append ? static_cast<const uint16_t*>(v_new) + static_cast<size_t>(s0) * a.kv_stride : nullptr,
+                               append ? slots + s0 : nullptr, a.kv_stride, a.k_scale, a.v_scale};
         auto launch = [&](auto kernel) {
-            kernel<<<kFlatWorkgroups, kWaves * 64, 0, st>>>(static_cast<const uint16_t*>(q), a.q_stride,
-                                                            static_cast<uint16_t*>(cache), block_table, a.max_blocks, seq_lens,
-                                                            o_part, ml_part, plan, num_seqs, a.hq_l, a.hkv_l, c, r_min, ap);
+            kernel<<<kFlatWorkgroups, kWaves * 64, 0, st>>>(q_run, a.q_stride, static_cast<uint16_t*>(cache),
+                                                            block_table + static_cast<size_t>(s0) * a.max_blocks, a.max_blocks,
+                                                            seq_lens + s0, o_part, ml_part, plan, n, a.hq_l, a.hkv_l, c, r_min, ap);
         };
         if (a.kv_fp8()) {
             if (append) launch(decode_flat_kernel<true, true>);
@@ -750,22 +531,10 @@ hipError_t launch_decode_mfma(const void* q, const void* k_new, const void* v_ne
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        return launch_combine_flat(o_part, ml_part, plan, num_seqs, a.hq_l, a.hq_l / a.hkv_l, out, a.out_stride, a.v_scale,
-                                   st);
+        e = launch_combine_flat(o_part, ml_part, plan, n, a.hq_l, a.hq_l / a.hkv_l, out_run, a.out_stride, a.v_scale, st);
+        if (e != hipSuccess) return e;
     }
-    const int chunk = chunk_tokens(num_seqs, a.hkv_l, max_seq_len);
-    const int max_chunks = max_chunks_of(num_seqs, a.hkv_l, max_seq_len);
-    const size_t rows = static_cast<size_t>(max_chunks) * num_seqs * a.hq_l;
-    float* o_part = static_cast<float*>(workspace);
-    float* ml_part = o_part + rows * kD;
-    dim3 grid(max_chunks, num_seqs, a.hkv_l);
-    decode_splitk_kernel<true><<<grid, kWaves * 64, 0, st>>>(
-        static_cast<const uint16_t*>(q), a.q_stride, static_cast<const uint16_t*>(cache), block_table, a.max_blocks,
-        seq_lens, o_part, ml_part, num_seqs, a.hq_l, a.hkv_l, c, chunk);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    return launch_combine(o_part, ml_part, num_seqs, a.hq_l, kD, max_chunks, 1, seq_lens, chunk, out,
-                          a.out_stride, a.elem, 1.f, st);
+    return hipSuccess;
 }
 
 }  // namespace shiftattn

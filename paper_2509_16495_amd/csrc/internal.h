@@ -8,7 +8,6 @@
 namespace shiftattn {
 
 constexpr int kBlockSize = 16;         // tokens per KV-cache block
-constexpr int kDecodeChunk = 512;      // context tokens per decode workgroup
 constexpr int kPrefillKvTile = 64;     // keys per prefill inner-loop step
 constexpr int kMaxParts = 1024;        // most partial results the merge kernel takes per output row
 

@@ -125,7 +125,7 @@ def test_decode_bf16_small(oracle, G, hq_l, hkv_l):
 
 def test_decode_many_sequences_and_long_contexts(oracle, G):
     """The flat decomposition at the edges of its range: as many (sequence, KV head) pairs as it
-    indexes, one more than that (the per-chunk kernel takes over), a context long enough that the
+    indexes, one more than that (a second run of the kernel takes the rest), a context long enough that the
     minimum range per wavefront is set by the merge kernel's part limit, and a batch so small that
     most wavefronts get no tokens."""
     rng = np.random.default_rng(62)

@@ -99,7 +99,7 @@ def test_chunked_prefill_fp8_long_context_with_key_splits(oracle, G):
 
 
 def test_decode_fp8_more_pairs_than_the_flat_kernel_indexes(oracle, G):
-    """2100 (sequence, KV head) pairs: beyond the flat kernel's index, the general kernel takes the FP8 cache."""
+    """2100 (sequence, KV head) pairs: more than one launch of the decode kernel indexes, served in two runs."""
     rng = np.random.Generator(np.random.PCG64(33))
     ctx = rng.integers(1, 120, size=2100)
     case = W.make_attn_case("dec_fp8_many", 81, "bf16", [(1, int(c)) for c in ctx], 8, 1, 128, pool_factor=1.1)
