@@ -15,7 +15,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libshiftattn.so")
+LIB_PATH = os.environ.get("SHIFTATTN_LIB") or os.path.join(_HERE, "libshiftattn.so")  # the variable names another build
 
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 BF16, F32 = 0, 1
