@@ -249,6 +249,19 @@ def main() -> int:
                                                  "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                                                  "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": traffic.get("decode_256seq")}}
         log(f"[bench] decode cfg4: {ms * 1e3:.1f} us, {gbps:.0f} GB/s of KV ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
+        # K/V append of the whole batch's contexts (the cache fill above, timed): read K and V rows, write cache blocks
+        k4d, v4d, sl4 = B.to_device(c4.k_ctx, "bf16", dev), B.to_device(c4.v_ctx, "bf16", dev), ti(c4.slots, np.int64)
+        ms = time_events(lambda: B.kv_write(k4d, v4d, sl4, cache4), 10)
+        kvw_bytes = 2 * c4.kv_bytes()
+        gbps = kvw_bytes / (ms * 1e-3) / 1e9
+        result["kv_write"] = {"workload": f"K/V of all {int(c4.ctx_lens.sum())} context tokens of the configs[3] batch appended in one "
+                                          "call (1 KV head, D=128, bf16; blocks scattered over the pool)",
+                              "bytes": kvw_bytes, "ms": round(ms, 5),
+                              "roofline": {"kernel": "kv_write_block_kernel", "bound": "hbm", "achieved": round(gbps, 1),
+                                           "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(gbps / PEAK_HBM_GBPS, 4),
+                                           "traffic": None}}
+        log(f"[bench] kv_write of the cfg4 contexts: {ms * 1e3:.1f} us, {gbps:.0f} GB/s read + written ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
+        del k4d, v4d, sl4
         # the same batch over an FP8 E4M3 cache: half the bytes per token
         k_scale, v_scale = 0.05, 0.05
         cache4q = torch.zeros((c4.num_blocks, 1, 2, 16 * D), dtype=torch.uint8, device=dev)

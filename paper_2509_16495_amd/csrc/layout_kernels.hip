@@ -116,7 +116,7 @@ __global__ __launch_bounds__(kThreads) void kv_write_kernel(const Elem* __restri
 // bf16, D = 128: one workgroup appends 16 consecutive new tokens of one KV head.  When those tokens
 // fill exactly one cache block in order (the usual case for a prefill chunk) the V rows are
 // transposed through LDS and the block's V part is written as 4 KiB of consecutive bytes; any other
-// slot pattern takes the element-wise scatter of kv_write_kernel.  Same bytes in the cache either way.
+// slot pattern is scattered element by element out of the same LDS tile.  Same bytes in the cache either way.
 __global__ __launch_bounds__(kThreads) void kv_write_block_kernel(const uint16_t* __restrict__ k_new,
                                                                   const uint16_t* __restrict__ v_new,
                                                                   const int64_t* __restrict__ slots, int n_tokens,
@@ -124,6 +124,7 @@ __global__ __launch_bounds__(kThreads) void kv_write_block_kernel(const uint16_t
                                                                   int64_t kv_stride) {
     constexpr int D = 128, kPitch = D + 8;  // LDS row pitch in elements: 16-byte aligned, 4-bank skew per row
     __shared__ __attribute__((aligned(16))) uint16_t tile[kBlockSize * kPitch];
+    __shared__ int64_t slot_s[kBlockSize];
     const int g = blockIdx.y;
     const int t_loc = threadIdx.x >> 4, dv = threadIdx.x & 15;
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlockSize + t_loc;
@@ -144,20 +145,24 @@ __global__ __launch_bounds__(kThreads) void kv_write_block_kernel(const uint16_t
         const int64_t blk = slot / kBlockSize;
         const int off = static_cast<int>(slot % kBlockSize);
         *reinterpret_cast<u32x4*>(cache + cache_part_offset(blk, g, 0, hkv_l, D) + static_cast<size_t>(off) * D + dv * 8) = kvec;
-        if (!whole_block) {
-            union {
-                u32x4 v;
-                uint16_t e[8];
-            } u;
-            u.v = vvec;
-            uint16_t* vdst = cache + cache_part_offset(blk, g, 1, hkv_l, D) + static_cast<size_t>(dv * 8) * kBlockSize + off;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) vdst[j * kBlockSize] = u.e[j];
-        }
     }
-    if (!whole_block) return;  // uniform
     *reinterpret_cast<u32x4*>(tile + t_loc * kPitch + dv * 8) = vvec;
+    if (dv == 0) slot_s[t_loc] = slot;
     __syncthreads();
+    if (!whole_block) {  // uniform
+        // Any other slot pattern (a run that straddles two blocks, padding rows, the tail of the batch): element by
+        // element out of the LDS tile, lanes running over the tokens of a head-dim row first, so that tokens that
+        // are neighbours in a block leave as neighbouring 2-byte stores of one instruction.
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int item = r * kThreads + threadIdx.x, d = item >> 4, t = item & 15;
+            const int64_t sl = slot_s[t];
+            if (sl >= 0)
+                cache[cache_part_offset(sl / kBlockSize, g, 1, hkv_l, D) + static_cast<size_t>(d) * kBlockSize + sl % kBlockSize] =
+                    tile[t * kPitch + d];
+        }
+        return;
+    }
     // thread -> (head-dim row d, half h): eight consecutive tokens of row d
     const int d = threadIdx.x >> 1, h = threadIdx.x & 1;
     union {
