@@ -9,6 +9,7 @@
  *   shiftattn_kv_write          append new K/V rows to the paged KV cache
  *   shiftattn_prefill           causal attention of new-token chunks over the cache (fused KV append)
  *   shiftattn_decode            one-token-per-sequence attention, split over the context (fused KV append)
+ *   shiftattn_mixed             a unified batch of chunks and decode rows in one call
  *   shiftattn_unpack_head2seq   receive side of the head->sequence all-to-all (SP mode only)
  *
  * In TP mode (the shift configuration, SP=1) a rank calls only kv_write/prefill/decode on the
