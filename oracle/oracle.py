@@ -125,6 +125,50 @@ def unpack_head2seq(recv: np.ndarray, T: int, dtype: str) -> np.ndarray:
 
 
 # ---------------------------------------------------------------------------
+# the projections next to the exchange (Algorithm 1: qkv = embed * W_qkv before the first all-to-all,
+# embed = attn_o * W_o after the second).  float64 over the stored values; the layouts are the pack /
+# unpack above restated on float64 arrays.
+# ---------------------------------------------------------------------------
+def _stored_to_f64(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Exact widening of stored values (bf16 as uint16 bit patterns, or float32) to float64."""
+    if dtype == "bf16":
+        return (np.ascontiguousarray(a, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return np.asarray(a, dtype=np.float32).astype(np.float64)
+
+
+def pack_heads_f64(y: np.ndarray, P: int, h: int, h_kv: int, T_pad: int) -> np.ndarray:
+    """y [T, h + 2 h_kv, D] float64 -> send [P, T_pad, hq_l + 2 hkv_l, D]; pad rows zero."""
+    T, w_in, D = y.shape
+    assert w_in == h + 2 * h_kv and h % P == 0
+    hq_l, hkv_l = h // P, local_kv_heads(P, h_kv)
+    send = np.zeros((P, T_pad, hq_l + 2 * hkv_l, D), dtype=np.float64)
+    for p in range(P):
+        send[p, :T, :hq_l] = y[:, p * hq_l:(p + 1) * hq_l]
+        if h_kv:
+            kv0 = kv_head_of_block(p, P, h_kv)
+            send[p, :T, hq_l:hq_l + hkv_l] = y[:, h + kv0:h + kv0 + hkv_l]
+            send[p, :T, hq_l + hkv_l:] = y[:, h + h_kv + kv0:h + h_kv + kv0 + hkv_l]
+    return send
+
+
+def qkv_proj_pack(x: np.ndarray, w_qkv: np.ndarray, P: int, h: int, h_kv: int, D: int, T_pad: int, dtype: str) -> np.ndarray:
+    """x [T, d] and w_qkv [(h + 2 h_kv) D, d] (one row per output feature, as weights are stored) in `dtype`;
+    returns the float64 send buffers of the first all-to-all."""
+    x64, w64 = _stored_to_f64(x, dtype), _stored_to_f64(w_qkv, dtype)
+    y = x64 @ w64.T
+    return pack_heads_f64(y.reshape(x.shape[0], h + 2 * h_kv, D), P, h, h_kv, T_pad)
+
+
+def unpack_o_proj(recv: np.ndarray, w_o: np.ndarray, T: int, dtype: str) -> np.ndarray:
+    """recv [P, T_pad, hq_l, D] (what the second all-to-all delivers) and w_o [d, h D] in `dtype`;
+    returns embed [T, d] float64 = unpack(recv) * W_o^T."""
+    P, T_pad, hq_l, D = recv.shape
+    r64 = _stored_to_f64(recv, dtype)
+    a = np.concatenate([r64[p, :T] for p in range(P)], axis=1).reshape(T, P * hq_l * D)  # out[t, p hq_l + j] = recv[p][t][j]
+    return a @ _stored_to_f64(w_o, dtype).T
+
+
+# ---------------------------------------------------------------------------
 # KV cache
 # ---------------------------------------------------------------------------
 def new_cache(num_blocks: int, hkv_l: int, B: int, D: int, dtype: str, fill_byte: int = 0xA5) -> np.ndarray:
