@@ -129,6 +129,27 @@ int shiftattn_pack_seq2head(const void *qkv, void *send, int32_t T, int32_t T_pa
 int shiftattn_unpack_head2seq(const void *recv, void *out, int32_t T, int32_t T_pad, const shiftattn_xchg *x,
                               void *stream);
 
+/* ---- Algorithm 1, the projections on either side of the exchange (bf16, head_dim 128) -----------
+ * qkv_proj_pack: qkv = x * W_qkv^T (the line in front of the first all-to-all) written straight into
+ *   the send buffers of shiftattn_pack_seq2head - same buffers, same bytes as projecting into
+ *   [T][h + 2 h_kv][D] and packing, without that tensor ever existing.
+ *   x (device, in)    : [T][d_model]
+ *   w_qkv (device, in): [(h + 2 h_kv) * D][d_model], one row per output feature, features in the
+ *                       order q heads, k heads, v heads
+ *   send (device, out): [P][T_pad][hq_l + 2 hkv_l][D]; rows T..T_pad-1 zero
+ *   Needs d_model % 64 == 0 and an even h + 2 h_kv (else EUNSUPPORTED).
+ * unpack_o_proj: embed = unpack(recv) * W_o^T (the line behind the second all-to-all), the attention
+ *   output read in place from the receive buffers of shiftattn_unpack_head2seq.
+ *   recv (device, in) : [P][T_pad][hq_l][D]
+ *   w_o (device, in)  : [d_model][h * D], one row per output feature
+ *   out (device, out) : [T][d_model]
+ *   Needs d_model % 256 == 0 (else EUNSUPPORTED).
+ * fp32 accumulation, results rounded to bf16 (nearest even).  Other checks as for pack / unpack. */
+int shiftattn_qkv_proj_pack(const void *x, const void *w_qkv, void *send, int32_t T, int32_t T_pad,
+                            int32_t d_model, const shiftattn_xchg *xc, void *stream);
+int shiftattn_unpack_o_proj(const void *recv, const void *w_o, void *out, int32_t T, int32_t T_pad,
+                            int32_t d_model, const shiftattn_xchg *xc, void *stream);
+
 /* ---- KV-cache append (Sec. 2.2: prefill initialises the cache, decoding appends to it) --------
  * k_new, v_new (device, in): [n_tokens][hkv_l][D] with row stride a->kv_stride.
  * slot_mapping (device, in): int64 [n_tokens]; token i goes to slot slot_mapping[i];

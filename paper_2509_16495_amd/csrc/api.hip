@@ -205,6 +205,37 @@ int shiftattn_unpack_head2seq(const void* recv, void* out, int32_t T, int32_t T_
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_head2seq launch");
 }
 
+int shiftattn_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int32_t T, int32_t T_pad, int32_t d_model,
+                            const shiftattn_xchg* xc, void* stream) {
+    XchgShape s;
+    if (int rc = check_xchg(xc, T, T_pad, true, &s)) return rc;
+    if (d_model < 1) return fail(SHIFTATTN_EINVAL, "d_model = %d", d_model);
+    if (!qkv_proj_pack_supported(s, d_model, elem_size(xc->dtype)))
+        return fail(SHIFTATTN_EUNSUPPORTED, "projection into the send buffers is built for bf16, head_dim 128, d_model a multiple "
+                                            "of 64 and an even number of heads per row (got d_model = %d, %d heads)",
+                    d_model, s.h + 2 * s.h_kv);
+    if (s.T_pad == 0) return SHIFTATTN_OK;
+    if (!send || (s.T > 0 && (!x || !w_qkv))) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(x) || !aligned16(w_qkv) || !aligned16(send)) return fail(SHIFTATTN_EINVAL, "x / w_qkv / send must be 16-byte aligned");
+    hipError_t e = launch_qkv_proj_pack(x, w_qkv, send, d_model, s, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "qkv_proj_pack launch");
+}
+
+int shiftattn_unpack_o_proj(const void* recv, const void* w_o, void* out, int32_t T, int32_t T_pad, int32_t d_model,
+                            const shiftattn_xchg* xc, void* stream) {
+    XchgShape s;
+    if (int rc = check_xchg(xc, T, T_pad, false, &s)) return rc;
+    if (d_model < 1) return fail(SHIFTATTN_EINVAL, "d_model = %d", d_model);
+    if (!unpack_o_proj_supported(s, d_model, elem_size(xc->dtype)))
+        return fail(SHIFTATTN_EUNSUPPORTED, "projection out of the receive buffers is built for bf16, head_dim 128 and d_model a "
+                                            "multiple of 256 (got d_model = %d)", d_model);
+    if (s.T == 0) return SHIFTATTN_OK;
+    if (!recv || !w_o || !out) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(recv) || !aligned16(w_o) || !aligned16(out)) return fail(SHIFTATTN_EINVAL, "recv / w_o / out must be 16-byte aligned");
+    hipError_t e = launch_unpack_o_proj(recv, w_o, out, d_model, s, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_o_proj launch");
+}
+
 int shiftattn_kv_write(const void* k_new, const void* v_new, const int64_t* slot_mapping, int32_t n_tokens,
                        void* kv_cache, const shiftattn_attn* a, void* stream) {
     AttnShape s;

@@ -76,6 +76,12 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
                                int total_q, int max_q_len, int max_seq_len, void* out, void* workspace,
                                const AttnShape& a, hipStream_t st);
 
+// proj_gemm.hip : the projections in front of the first exchange and behind the second (bf16, head_dim 128)
+bool qkv_proj_pack_supported(const XchgShape& s, int d_model, int elem);
+bool unpack_o_proj_supported(const XchgShape& s, int d_model, int elem);
+hipError_t launch_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int d_model, const XchgShape& s, hipStream_t st);
+hipError_t launch_unpack_o_proj(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s, hipStream_t st);
+
 // ceilings.hip : attainable-rate probes for benchmark reports
 hipError_t launch_mfma_ceiling(const void* operands, void* sink, int iters, int64_t* flops, hipStream_t st);
 hipError_t launch_hbm_read_ceiling(const void* src, size_t bytes, void* sink, int64_t* bytes_read, hipStream_t st);
