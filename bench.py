@@ -304,6 +304,41 @@ def main() -> int:
                                        "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": traffic.get(nm + "_70b")}}
             log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {gbps:.0f} GB/s ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
         del xin, xsend, xout
+        # the projections next to the two exchanges, fused with the pack / unpack (70B: d_model 8192, 64 + 2 x 8 heads)
+        d_model, h3, hkv3 = 8192, 64, 8
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(33)
+        xe = torch.randn((x3.T, d_model), device=dev, generator=gen).to(bf)
+        wq = (torch.randn(((h3 + 2 * hkv3) * D, d_model), device=dev, generator=gen) * 0.02).to(bf)
+        wo = (torch.randn((d_model, h3 * D), device=dev, generator=gen) * 0.02).to(bf)
+        send3 = torch.empty((x3.P, x3.T, h3 // x3.P + 2 * (hkv3 // x3.P), D), dtype=bf, device=dev)
+        recv3 = torch.randn((x3.P, x3.T, h3 // x3.P, D), device=dev, generator=gen).to(bf)
+        eo = torch.empty((x3.T, d_model), dtype=bf, device=dev)
+        qkv_plain = torch.empty((x3.T, (h3 + 2 * hkv3) * D), dtype=bf, device=dev)
+        att_plain = torch.empty((x3.T, h3 * D), dtype=bf, device=dev)
+
+        def lib_qkv():   # the unfused route: the library's GEMM, then the pack kernel
+            torch.matmul(xe, wq.t(), out=qkv_plain)
+            B.pack_seq2head(qkv_plain.view(x3.T, h3 + 2 * hkv3, D), send3, x3.P, h3, hkv3)
+
+        def lib_o():
+            B.unpack_head2seq(recv3, att_plain.view(x3.T, h3, D))
+            torch.matmul(att_plain, wo.t(), out=eo)
+
+        for nm, fn, ref, fl in (("qkv_proj_pack", lambda: B.qkv_proj_pack(xe, wq, send3, x3.P, h3, hkv3), lib_qkv,
+                                 2.0 * x3.T * d_model * (h3 + 2 * hkv3) * D),
+                                ("unpack_o_proj", lambda: B.unpack_o_proj(recv3, wo, eo), lib_o, 2.0 * x3.T * d_model * h3 * D)):
+            ms = time_events(fn, reps)
+            ms_ref = time_events(ref, reps)
+            tf = fl / (ms * 1e-3) / 1e12
+            result[nm] = {"workload": f"configs[2] shard: {x3.T} tokens, d_model {d_model}, {h3} query + 2 x {hkv3} KV heads of 128, "
+                                      f"{x3.P} exchange buffers, bf16, N(0,1) activations, N(0,0.02) weights",
+                          "flops": fl, "ms": round(ms, 5), "library_gemm_and_separate_layout_kernel_ms": round(ms_ref, 5),
+                          "roofline": {"kernel": "proj_gemm_kernel", "bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_BF16_TFLOPS,
+                                       "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": traffic.get(nm + "_70b")}}
+            log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%} of bf16 MFMA peak); "
+                f"library GEMM + separate layout kernel {ms_ref * 1e3:.1f} us")
+        del xe, wq, wo, send3, recv3, eo, qkv_plain, att_plain
         # 70B-shaped prefill (configs[2])
         c3 = W.config3_attn()
         cache3 = torch.zeros((c3.num_blocks, 1, 2, 16 * D), dtype=bf, device=dev)

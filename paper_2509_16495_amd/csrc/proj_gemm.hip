@@ -9,12 +9,15 @@
 //                   receive buffer p - the unpack kernel disappears.
 // Weights are stored one row per output feature (K contiguous), as linear layers keep them.
 //
-// Kernel: 256 x 256 output tile per workgroup, K in steps of 64, eight wavefronts (4 along the features
-// x 2 along the tokens), v_mfma_f32_32x32x16_bf16 with the weight rows as A operand and the token rows
-// as B operand, so a lane ends up with runs of four consecutive features of one token (8-byte stores).
-// Both tiles of a step (2 x 32 KiB) arrive by direct-to-LDS loads, double buffered; a row of 64 k (128
-// bytes) keeps its eight 16-byte pieces at positions piece ^ ((row / 2) % 8), which makes the operand
-// reads (32 consecutive rows, one piece column) conflict-free.
+// Kernel: 256 x 256 output tile per workgroup, K in tiles of 32, four wavefronts (2 along the features
+// x 2 along the tokens, 128 x 128 each: one wavefront per SIMD with its 256 accumulator registers in the
+// AGPR half of the register file), v_mfma_f32_32x32x16_bf16 with the weight rows as A operand and the
+// token rows as B operand, so a lane ends up with runs of four consecutive features of one token (8-byte
+// stores).  The two operand tiles of a k tile (2 x 16 KiB) arrive by direct-to-LDS loads into a ring of
+// four buffers: one is multiplied while up to three are in flight, and the wait in front of the one
+// meeting per k tile counts loads instead of draining them.  A row of 32 k (64 bytes) keeps its four
+// 16-byte pieces at positions piece ^ ((row / 4) % 4), which makes the operand reads (32 consecutive
+// rows, one piece column) conflict-free.
 #include "internal.h"
 
 namespace shiftattn {
@@ -27,12 +30,25 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kTile = 256;                 // rows of either operand per workgroup
-constexpr int kBK = 64;                    // k per step
-constexpr int kRowBytes = kBK * 2;         // 128
-constexpr int kOperandBytes = kTile * kRowBytes;   // 32768
+constexpr int kBK = 32;                    // k per step
+constexpr int kRowBytes = kBK * 2;         // 64
+constexpr int kOperandBytes = kTile * kRowBytes;   // 16384
 constexpr int kStage = 2 * kOperandBytes;  // weights, then tokens
-constexpr int kGemmLds = 2 * kStage;       // 131072
-constexpr int kGemmThreads = 512;
+constexpr int kStages = 4;                 // ring of k tiles in LDS: one being multiplied, the others in flight
+constexpr int kGemmLds = kStages * kStage; // 131072
+constexpr int kWavesN = 2, kWavesM = 2;    // wavefronts along the features / along the tokens
+constexpr int kGemmThreads = 64 * kWavesN * kWavesM;
+constexpr int kNT = kTile / kWavesN / 32;  // 32-feature tiles per wavefront
+constexpr int kMT = kTile / kWavesM / 32;  // 32-token tiles per wavefront
+constexpr int kLoadRows = kTile / (kWavesN * kWavesM);   // rows of either operand that one wavefront loads
+constexpr int kLoadsPerOperand = kLoadRows / 16;          // 16 rows (1 KiB) per instruction
+constexpr int kLoadsPerTile = 2 * kLoadsPerOperand;       // direct-to-LDS instructions per wavefront and k tile
+constexpr int kLoadEvery = kNT * kMT / kLoadsPerOperand;  // MFMAs between two loads
+static_assert(kNT * kMT % kLoadsPerOperand == 0 && kNT + kMT <= 15, "load spreading / lgkmcnt field");
+
+// s_waitcnt immediates: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8
+constexpr int wait_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (lgkm << 8); }
+constexpr int kNoVm = 63, kNoLgkm = 15;
 constexpr int kHeadDim = 128;
 
 __device__ inline bf16x8 frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -48,97 +64,135 @@ struct GemmParams {
     XchgShape s;
 };
 
-__global__ __launch_bounds__(kGemmThreads, 2) void proj_gemm_kernel(GemmParams p) {
+__global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     typedef __attribute__((address_space(3))) void* lds_ptr;
     typedef const __attribute__((address_space(1))) void* glb_ptr;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int l32 = lane & 31, half = lane >> 5;
-    const int wn = wave & 3, wm = wave >> 2;
+    const int wn = wave % kWavesN, wm = wave / kWavesN;
     // feature tiles vary fastest: workgroups that run together share the token rows in L2
     const int n_tiles = p.N / kTile;
     const int n0 = (blockIdx.x % n_tiles) * kTile, m0 = (blockIdx.x / n_tiles) * kTile;
 
-    // ---- direct-to-LDS loads: this wavefront fills rows 32 wave .. 32 wave + 31 of both operand tiles, eight rows
-    // (1 KiB) per instruction; lane -> row 8 j + lane / 8, LDS piece position lane % 8, logical piece = position ^ key
-    const int ld_row = lane >> 3, ld_pos = lane & 7;
-    size_t w_src[4], x_src[4];   // element offsets of this lane's piece at k = 0
+    // ---- direct-to-LDS loads: this wavefront fills rows 32 wave .. 32 wave + 31 of both operand tiles, sixteen rows
+    // (1 KiB) per instruction; lane -> row 16 j + lane / 4, LDS piece position lane % 4, logical piece = position ^ key
+    // The address of a load is a wavefront-uniform base (tile origin + k, kept in scalar registers and advanced by
+    // scalar adds) plus a 32-bit byte offset per lane that never changes, and the LDS destination is uniform too: no
+    // vector ALU instruction is spent on a load.
+    const int ld_row = lane >> 2, ld_pos = lane & 3;
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const size_t x_row = p.mode == 0 ? static_cast<size_t>(p.K) : static_cast<size_t>(p.s.hq_l) * kHeadDim;   // elements
+    uint32_t w_off[kLoadsPerOperand], x_off[kLoadsPerOperand];   // byte offsets of this lane's piece from the tile origin at k = 0
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int row = 32 * wave + 8 * j + ld_row;
-        const int piece = ld_pos ^ ((row >> 1) & 7);
-        w_src[j] = static_cast<size_t>(n0 + row) * p.K + piece * 8;
-        const int m = min(m0 + row, p.M - 1);   // rows past the end re-read the last one; they are not stored
-        x_src[j] = p.mode == 0 ? static_cast<size_t>(m) * p.K + piece * 8
-                               : static_cast<size_t>(m) * p.s.hq_l * kHeadDim + piece * 8;
+    for (int j = 0; j < kLoadsPerOperand; ++j) {
+        const int row = kLoadRows * wave + 16 * j + ld_row;
+        const int piece = ld_pos ^ ((row >> 2) & 3);
+        w_off[j] = static_cast<uint32_t>((static_cast<size_t>(row) * p.K + piece * 8) * 2);
+        const int m = min(m0 + row, p.M - 1) - m0;   // rows past the end re-read the last one; they are not stored
+        x_off[j] = static_cast<uint32_t>((static_cast<size_t>(m) * x_row + piece * 8) * 2);
     }
-    auto x_k_off = [&](int k0) -> size_t {   // where k-tile k0 of a token row starts (wavefront-uniform)
-        if (p.mode == 0) return static_cast<size_t>(k0);
-        const int head = k0 / kHeadDim, pp = head / p.s.hq_l, j = head - pp * p.s.hq_l;
-        return (static_cast<size_t>(pp) * p.s.T_pad * p.s.hq_l + j) * kHeadDim + (k0 % kHeadDim);
+    const char* w_tile = reinterpret_cast<const char*>(p.w + static_cast<size_t>(n0) * p.K);
+    const char* x_tile = reinterpret_cast<const char*>(p.x + static_cast<size_t>(m0) * x_row);
+    // A token row's k runs contiguously through the hq_l heads that one source rank returned, then jumps to the
+    // next rank's buffer (mode 1); in mode 0 it is contiguous throughout.
+    const int seg_tiles = p.mode == 0 ? p.K / kBK : p.s.hq_l * kHeadDim / kBK;
+    const size_t seg_jump = p.mode == 0 ? 0 : static_cast<size_t>(p.s.T_pad - 1) * p.s.hq_l * kHeadDim * 2;   // bytes
+    int ld_kt = 0, ld_left = seg_tiles;   // next tile to load, and how many tiles remain in its segment
+    auto load_one = [&](int j) {          // first the weight rows, then the token rows
+        unsigned char* dst = lds + (ld_kt % kStages) * kStage + (kLoadRows * wave_s) * kRowBytes;
+        if (j < kLoadsPerOperand) __builtin_amdgcn_global_load_lds((glb_ptr)(w_tile + w_off[j]), (lds_ptr)(dst + j * 1024), 16, 0, 0);
+        else __builtin_amdgcn_global_load_lds((glb_ptr)(x_tile + x_off[j - kLoadsPerOperand]), (lds_ptr)(dst + kOperandBytes + (j - kLoadsPerOperand) * 1024), 16, 0, 0);
     };
-    auto load_stage = [&](int k0, int stage) {
-        unsigned char* dst = lds + stage * kStage + (32 * wave) * kRowBytes;
-        const size_t xo = x_k_off(k0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            __builtin_amdgcn_global_load_lds((glb_ptr)(p.w + w_src[j] + k0), (lds_ptr)(dst + j * 1024), 16, 0, 0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            __builtin_amdgcn_global_load_lds((glb_ptr)(p.x + x_src[j] + xo), (lds_ptr)(dst + kOperandBytes + j * 1024), 16, 0, 0);
+    auto load_advance = [&]() {
+        ++ld_kt;
+        w_tile += kBK * 2;
+        x_tile += kBK * 2;
+        if (--ld_left == 0) { ld_left = seg_tiles; x_tile += seg_jump; }
     };
 
     // ---- operand reads: row l32 of a 32-row tile, piece 2 ks + half
-    const int key = (l32 >> 1) & 7;   // 32-row tiles start at multiples of 32: the key depends on l32 only
-    int rd[4];
+    const int key = (l32 >> 2) & 3;   // 32-row tiles start at multiples of 32: the key depends on l32 only
+    int rd[2];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) rd[ks] = l32 * kRowBytes + (((2 * ks + half) ^ key) << 4);
-    const int a_base = (wn * 64) * kRowBytes;                    // weight rows of this wavefront
-    const int b_base = kOperandBytes + (wm * 128) * kRowBytes;   // token rows of this wavefront
+    for (int ks = 0; ks < 2; ++ks) rd[ks] = l32 * kRowBytes + (((2 * ks + half) ^ key) << 4);
+    const int a_base = (wn * kNT * 32) * kRowBytes;                    // weight rows of this wavefront
+    const int b_base = kOperandBytes + (wm * kMT * 32) * kRowBytes;   // token rows of this wavefront
 
-    f32x16 acc[2][4];
+    f32x16 acc[kNT][kMT];
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
+    for (int nt = 0; nt < kNT; ++nt)
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+        for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[nt][mt][r] = 0.f;
 
+    // Operands are read from LDS one 16-wide k slice ahead of the MFMAs that use them (two register sets).  The
+    // workgroup meets once per k tile, before the tile's last slice is multiplied: by then every wavefront holds
+    // that slice in registers, so the tile's buffer is free, and the first slice of the next tile is fetched while
+    // the last one is multiplied.  The loads of the tile kStages - 1 ahead go into the buffer freed one meeting
+    // earlier and are spread between the MFMAs, one behind every fourth.
+    auto read_ops = [&](const unsigned char* base, int ks, u32x4 (&a)[kNT], u32x4 (&b)[kMT]) {
+#pragma unroll
+        for (int nt = 0; nt < kNT; ++nt) a[nt] = *reinterpret_cast<const u32x4*>(base + a_base + nt * 32 * kRowBytes + rd[ks]);
+#pragma unroll
+        for (int mt = 0; mt < kMT; ++mt) b[mt] = *reinterpret_cast<const u32x4*>(base + b_base + mt * 32 * kRowBytes + rd[ks]);
+    };
+    auto multiply = [&]<int kLoad0>(const u32x4 (&a)[kNT], const u32x4 (&b)[kMT]) {   // kLoad0 < 0: no loads in between
+#pragma unroll
+        for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+            for (int mt = 0; mt < kMT; ++mt) {
+                acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[nt]), frag(b[mt]), acc[nt][mt], 0, 0, 0);
+                if (kLoad0 >= 0 && (nt * kMT + mt) % kLoadEvery == 1) {
+                    load_one(kLoad0 + (nt * kMT + mt) / kLoadEvery);
+                    __builtin_amdgcn_sched_barrier(0);   // keep the load between these MFMAs
+                }
+            }
+    };
+
     const int k_steps = p.K / kBK;
-    load_stage(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    __syncthreads();
-    for (int kt = 0; kt < k_steps; ++kt) {
-        const int st = kt & 1;
-        if (kt + 1 < k_steps) load_stage((kt + 1) * kBK, st ^ 1);
-        const unsigned char* base = lds + st * kStage;
+    u32x4 a0[kNT], b0[kMT], a1[kNT], b1[kMT];
+    for (int t = 0; t < kStages - 1 && t < k_steps; ++t) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            u32x4 a[2], b[4];
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) a[nt] = *reinterpret_cast<const u32x4*>(base + a_base + nt * 32 * kRowBytes + rd[ks]);
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) b[mt] = *reinterpret_cast<const u32x4*>(base + b_base + mt * 32 * kRowBytes + rd[ks]);
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-                    acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[nt]), frag(b[mt]), acc[nt][mt], 0, 0, 0);
-        }
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
+        for (int j = 0; j < kLoadsPerTile; ++j) load_one(j);
+        load_advance();
     }
+    if (k_steps >= kStages - 1) __builtin_amdgcn_s_waitcnt(wait_imm(kLoadsPerTile * (kStages - 2), kNoLgkm));   // tile 0 has landed
+    else __builtin_amdgcn_s_waitcnt(wait_imm(0, kNoLgkm));
+    __builtin_amdgcn_s_barrier();
+    read_ops(lds, 0, a0, b0);
+    auto tile = [&]<bool kLoads>(int kt) {
+        read_ops(lds + (kt % kStages) * kStage, 1, a1, b1);
+        __builtin_amdgcn_sched_barrier(0);   // the reads stay ahead of the MFMAs of the slice before ...
+        __builtin_amdgcn_s_waitcnt(wait_imm(kNoVm, kNT + kMT));  // ... which wait for their own operands only
+        multiply.template operator()<kLoads ? 0 : -1>(a0, b0);
+        // tile kt + 1 has landed (behind it: kStages - 3 whole tiles and the weight loads just issued), and this
+        // wavefront's reads of tile kt are done
+        __builtin_amdgcn_sched_barrier(0);
+        if (kLoads) __builtin_amdgcn_s_waitcnt(wait_imm(kLoadsPerTile * (kStages - 3) + kLoadsPerOperand, 0));
+        else __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
+        __builtin_amdgcn_s_barrier();   // bare: a __syncthreads() would wait for every load in flight
+        read_ops(lds + ((kt + 1) % kStages) * kStage, 0, a0, b0);   // behind the last tile: stale data, not used
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(wait_imm(kNoVm, kNT + kMT));
+        multiply.template operator()<kLoads ? kLoadsPerOperand : -1>(a1, b1);
+        if (kLoads) load_advance();
+    };
+    int kt = 0;
+    for (; kt + kStages - 1 < k_steps; ++kt) tile.template operator()<true>(kt);
+    for (; kt < k_steps; ++kt) tile.template operator()<false>(kt);
 
     // ---- result: register r of acc[nt][mt] is feature 32 nt + 8 (r / 4) + 4 half + r % 4 of token 32 mt + l32
-    const int f_wave = n0 + wn * 64;           // first feature of this wavefront; its 64 features lie in one head
+    const int f_wave = n0 + wn * kNT * 32;     // first feature of this wavefront; its features lie in one head
     auto store_rows = [&](uint16_t* dst_row0, size_t row_stride) {   // dst_row0: feature f_wave of token row 0
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            const int m = m0 + wm * 128 + mt * 32 + l32;
+        for (int mt = 0; mt < kMT; ++mt) {
+            const int m = m0 + wm * kMT * 32 + mt * 32 + l32;
             if (m >= p.M_out) continue;
             uint16_t* row = dst_row0 + static_cast<size_t>(m) * row_stride + 4 * half;
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
+            for (int nt = 0; nt < kNT; ++nt)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     bf16x4 v;
@@ -195,7 +249,7 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
 
 // bf16, head_dim 128; the feature dimension of either product must be a multiple of the 256-wide tile
 bool qkv_proj_pack_supported(const XchgShape& s, int d_model, int elem) {
-    return elem == 2 && s.vec_per_head * 8 == kHeadDim && d_model > 0 && d_model % kBK == 0 && (s.h + 2 * s.h_kv) % 2 == 0;
+    return elem == 2 && s.vec_per_head * 8 == kHeadDim && d_model > 0 && d_model % 64 == 0 && (s.h + 2 * s.h_kv) % 2 == 0;
 }
 bool unpack_o_proj_supported(const XchgShape& s, int d_model, int elem) {
     return elem == 2 && s.vec_per_head * 8 == kHeadDim && d_model > 0 && d_model % kTile == 0 && s.h > 0;

@@ -178,3 +178,36 @@ def test_attention_entry_points_reject_bad_arguments(B):
     assert kvw(FAKE, FAKE, FAKE, -1, FAKE, ctypes.byref(ok), None) == B.EINVAL
     assert kvw(None, None, None, 0, None, ctypes.byref(ok), None) == B.OK
     assert B.lib().shiftattn_decode_workspace_bytes(-1, 64, ctypes.byref(ok)) == ctypes.c_size_t(-1).value
+
+
+def test_projection_entry_points_reject_bad_arguments(B):
+    """The fused projections (Algorithm 1, the products next to the two all-to-alls): bf16, head_dim 128 only."""
+    L = B.lib()
+    ok = dict(P=8, num_q_heads=64, num_kv_heads=8, head_dim=128, dtype=B.BF16)
+    x = _xchg(B, **ok)
+    q, o = L.shiftattn_qkv_proj_pack, L.shiftattn_unpack_o_proj
+    # shapes the GEMM is not built for
+    for kw, d_model in [(dict(dtype=B.F32), 8192), (dict(head_dim=64), 8192), (dict(), 8200), (dict(num_q_heads=9, num_kv_heads=1, P=1), 8192)]:
+        bad = _xchg(B, **{**ok, **kw})
+        assert q(FAKE, FAKE, FAKE, 8, 8, d_model, ctypes.byref(bad), None) == B.EUNSUPPORTED, (kw, d_model)
+        assert "projection" in B.last_error()
+    for kw, d_model in [(dict(dtype=B.F32), 8192), (dict(head_dim=64), 8192), (dict(), 8192 + 64)]:
+        bad = _xchg(B, **{**ok, **kw, "num_kv_heads": 0})
+        assert o(FAKE, FAKE, FAKE, 8, 8, d_model, ctypes.byref(bad), None) == B.EUNSUPPORTED, (kw, d_model)
+    xo = _xchg(B, **{**ok, "num_kv_heads": 0})
+    # invalid arguments: sizes, descriptor, pointers, alignment
+    for fn, desc in ((q, x), (o, xo)):
+        assert fn(FAKE, FAKE, FAKE, 9, 8, 8192, ctypes.byref(desc), None) == B.EINVAL      # T > T_pad
+        assert fn(FAKE, FAKE, FAKE, 8, 8, 0, ctypes.byref(desc), None) == B.EINVAL
+        assert fn(FAKE, FAKE, FAKE, 8, 8, -64, ctypes.byref(desc), None) == B.EINVAL
+        assert fn(FAKE, FAKE, FAKE, 8, 8, 8192, None, None) == B.EINVAL
+        assert fn(None, FAKE, FAKE, 8, 8, 8192, ctypes.byref(desc), None) == B.EINVAL
+        assert fn(FAKE, None, FAKE, 8, 8, 8192, ctypes.byref(desc), None) == B.EINVAL
+        assert fn(FAKE, FAKE, None, 8, 8, 8192, ctypes.byref(desc), None) == B.EINVAL
+        assert fn(FAKE, ctypes.c_void_p(0x1004), FAKE, 8, 8, 8192, ctypes.byref(desc), None) == B.EINVAL
+        assert B.last_error()
+    bad_p = _xchg(B, **{**ok, "P": 3})
+    assert q(FAKE, FAKE, FAKE, 6, 6, 8192, ctypes.byref(bad_p), None) == B.EINVAL          # heads not divisible by P
+    # empty problems are valid no-ops and touch nothing
+    assert q(None, None, None, 0, 0, 8192, ctypes.byref(x), None) == B.OK
+    assert o(None, None, None, 0, 8, 8192, ctypes.byref(xo), None) == B.OK
