@@ -90,3 +90,30 @@ def test_projection_then_attention_inputs_equal_separate_pack(oracle, G):
     B.pack_seq2head(flat[0], packed, P, h, h_kv)
     torch.cuda.synchronize()
     assert torch.equal(fused.view(torch.uint8), packed.view(torch.uint8))
+
+
+def test_full_size_70b_projections_on_sampled_tokens(oracle, G):
+    """The shapes the benchmark times (16384 tokens, d_model 8192, 64 + 2 x 8 heads, 8 buffers): every output of a
+    sample of token rows (tile borders, first, last, random) against the oracle run on those rows alone."""
+    import torch
+    from paper_2509_16495_amd import binding as B
+    rng = np.random.Generator(np.random.PCG64(204))
+    P, h, h_kv, D, d_model, T = 8, 64, 8, 128, 8192, 16384
+    tokens = np.unique(np.concatenate([[0, 1, 127, 128, 255, 256, 257, 8191, 8192, 16127, 16128, 16383], rng.integers(0, T, 8)]))
+    x, w = _bf16(rng, (T, d_model)), _bf16(rng, ((h + 2 * h_kv) * D, d_model))
+    send = torch.empty((P, T, h // P + 2 * B.local_kv_heads(P, h_kv), D), dtype=torch.bfloat16, device=G.DEV)
+    send.view(torch.uint8).fill_(0x55)
+    B.qkv_proj_pack(G.t(x, "bf16"), G.t(w, "bf16"), send, P, h, h_kv)
+    torch.cuda.synchronize()
+    got = B.to_host(send[:, torch.from_numpy(tokens).to(G.DEV)].contiguous())
+    want = oracle.qkv_proj_pack(x[tokens], w, P, h, h_kv, D, len(tokens), "bf16")
+    _check(got, want, d_model)
+    del send, x, w
+    recv, w_o = _bf16(rng, (P, T, h // P, D)), _bf16(rng, (d_model, h * D))
+    out = torch.empty((T, d_model), dtype=torch.bfloat16, device=G.DEV)
+    out.view(torch.uint8).fill_(0x55)
+    B.unpack_o_proj(G.t(recv, "bf16"), G.t(w_o, "bf16"), out)
+    torch.cuda.synchronize()
+    got = B.to_host(out[torch.from_numpy(tokens).to(G.DEV)].contiguous())
+    want = oracle.unpack_o_proj(np.ascontiguousarray(recv[:, tokens]), w_o, len(tokens), "bf16")
+    _check(got, want, h * D)
