@@ -6,11 +6,14 @@
 // head vector (D * elem_size bytes).
 #include "internal.h"
 
+#include <type_traits>
+
 namespace shiftattn {
 
 namespace {
 
 constexpr int kThreads = 256;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));  // one 8-byte vector
 constexpr int kUnroll = 2;  // 16-byte vectors per thread: 2 measured best on the 512 MiB exchange (1: -2 %, 4: -3 %, 8: -40 %)
 
 // One workgroup writes kThreads*kUnroll consecutive vectors of send[p].  The destination index is
@@ -113,66 +116,96 @@ __global__ __launch_bounds__(kThreads) void kv_write_kernel(const Elem* __restri
     for (int j = 0; j < kPer; ++j) vdst[j * kBlockSize] = u.e[j];
 }
 
-// bf16, D = 128: one workgroup appends 16 consecutive new tokens of one KV head.  When those tokens
-// fill exactly one cache block in order (the usual case for a prefill chunk) the V rows are
-// transposed through LDS and the block's V part is written as 4 KiB of consecutive bytes; any other
-// slot pattern is scattered element by element out of the same LDS tile.  Same bytes in the cache either way.
+// bf16, D = 128.  A run is a stretch of consecutive new tokens whose slots are consecutive inside one
+// cache block (at most 16 tokens).  Workgroup w looks at tokens 16 w .. 16 w + 15 and writes every run
+// that *starts* there, to its end - up to 15 tokens into the next window, whose workgroup does not
+// touch them.  So however the token index is aligned against the blocks (a batch of prefills of
+// arbitrary lengths, a chunk that starts in the middle of a block), a full run fills its cache block
+// with one pass: K rows as they come, V transposed through LDS and written as 4 KiB of consecutive
+// bytes.  Short runs (first and last block of a sequence, single decode tokens, rows next to padding)
+// write the part of each V row they own.  Every token belongs to exactly one run, so every cache
+// element is written once and every input row read once; padding rows (negative slots) start no run.
+// kFp8: the cache holds FP8 E4M3 codes (one byte per element) of x / scale instead of the bf16 values.
+template <bool kFp8>
 __global__ __launch_bounds__(kThreads) void kv_write_block_kernel(const uint16_t* __restrict__ k_new,
                                                                   const uint16_t* __restrict__ v_new,
                                                                   const int64_t* __restrict__ slots, int n_tokens,
-                                                                  uint16_t* __restrict__ cache, int hkv_l,
-                                                                  int64_t kv_stride) {
-    constexpr int D = 128, kPitch = D + 8;  // LDS row pitch in elements: 16-byte aligned, 4-bank skew per row
-    __shared__ __attribute__((aligned(16))) uint16_t tile[kBlockSize * kPitch];
-    __shared__ int64_t slot_s[kBlockSize];
+                                                                  void* __restrict__ cache_v, int hkv_l,
+                                                                  int64_t kv_stride, float k_scale, float v_scale) {
+    using CE = typename std::conditional<kFp8, uint8_t, uint16_t>::type;    // cache element
+    using Piece = typename std::conditional<kFp8, u32x2, u32x4>::type;       // eight cache elements
+    constexpr int D = 128, kPitch = D + 16 / sizeof(CE);  // LDS row pitch in elements: 16-byte aligned, 4-bank skew per row
+    __shared__ __attribute__((aligned(16))) CE tile[kBlockSize * kPitch];
+    CE* cache = static_cast<CE*>(cache_v);
     const int g = blockIdx.y;
-    const int t_loc = threadIdx.x >> 4, dv = threadIdx.x & 15;
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlockSize + t_loc;
-    const bool in_range = i < n_tokens;
-    // the rows are requested together with the slots (rows of padding tokens exist too, they are just not
-    // written): one round trip to memory instead of two dependent ones
-    u32x4 kvec = {0u, 0u, 0u, 0u}, vvec = {0u, 0u, 0u, 0u};
-    if (in_range) {
-        const size_t src = static_cast<size_t>(i) * kv_stride + static_cast<size_t>(g) * D + dv * 8;
-        kvec = *reinterpret_cast<const u32x4*>(k_new + src);
-        vvec = *reinterpret_cast<const u32x4*>(v_new + src);
+    const int lane16 = threadIdx.x & 15;
+    const int64_t w0 = static_cast<int64_t>(blockIdx.x) * kBlockSize;
+    // which tokens of the window start a run (every wavefront computes the same 16 bits)
+    uint32_t starts;
+    {
+        const int64_t i = w0 + lane16;
+        const int64_t s = i < n_tokens ? slots[i] : -1;
+        const int64_t sp = i > 0 && i <= n_tokens ? slots[i - 1] : -2;
+        const bool st = s >= 0 && ((s % kBlockSize) == 0 || sp != s - 1);
+        starts = static_cast<uint32_t>(__builtin_amdgcn_ballot_w64(st)) & 0xFFFFu;
     }
-    const int64_t slot = in_range ? slots[i] : -1;
-    const int64_t first = slots[static_cast<int64_t>(blockIdx.x) * kBlockSize];  // blockIdx.x * 16 < n_tokens
-    const bool ordered = in_range && first >= 0 && (first % kBlockSize) == 0 && slot == first + t_loc;
-    const bool whole_block = __syncthreads_and(ordered);
-    if (in_range && slot >= 0) {
-        const int64_t blk = slot / kBlockSize;
-        const int off = static_cast<int>(slot % kBlockSize);
-        *reinterpret_cast<u32x4*>(cache + cache_part_offset(blk, g, 0, hkv_l, D) + static_cast<size_t>(off) * D + dv * 8) = kvec;
-    }
-    *reinterpret_cast<u32x4*>(tile + t_loc * kPitch + dv * 8) = vvec;
-    if (dv == 0) slot_s[t_loc] = slot;
-    __syncthreads();
-    if (!whole_block) {  // uniform
-        // Any other slot pattern (a run that straddles two blocks, padding rows, the tail of the batch): element by
-        // element out of the LDS tile, lanes running over the tokens of a head-dim row first, so that tokens that
-        // are neighbours in a block leave as neighbouring 2-byte stores of one instruction.
+    const int t_loc = threadIdx.x >> 4, dv = lane16;    // loader: token of the run, eight elements of its row
+    const int d = threadIdx.x >> 1, h = threadIdx.x & 1;  // writer of V: head-dim row, half of its 16 positions
+    auto encode = [&](u32x4 x, float scale) -> Piece {
+        if constexpr (kFp8) {
+            float f[8];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int item = r * kThreads + threadIdx.x, d = item >> 4, t = item & 15;
-            const int64_t sl = slot_s[t];
-            if (sl >= 0)
-                cache[cache_part_offset(sl / kBlockSize, g, 1, hkv_l, D) + static_cast<size_t>(d) * kBlockSize + sl % kBlockSize] =
-                    tile[t * kPitch + d];
+            for (int j = 0; j < 4; ++j) {
+                f[2 * j] = __uint_as_float(x[j] << 16);
+                f[2 * j + 1] = __uint_as_float(x[j] & 0xFFFF0000u);
+            }
+            Piece r;
+            r[0] = e4m3_pair(f[0], f[1], scale) | (e4m3_pair(f[2], f[3], scale) << 16);
+            r[1] = e4m3_pair(f[4], f[5], scale) | (e4m3_pair(f[6], f[7], scale) << 16);
+            return r;
+        } else {
+            return x;
         }
-        return;
-    }
-    // thread -> (head-dim row d, half h): eight consecutive tokens of row d
-    const int d = threadIdx.x >> 1, h = threadIdx.x & 1;
-    union {
-        u32x4 v;
-        uint16_t e[8];
-    } o;
+    };
+    while (starts) {   // uniform
+        const int t0 = __builtin_ctz(starts);
+        starts &= starts - 1;
+        const int64_t i0 = w0 + t0;
+        const int64_t slot0 = slots[i0];
+        const int off = static_cast<int>(slot0 % kBlockSize);
+        int len;   // tokens of the run
+        {
+            const int64_t i = i0 + lane16;
+            const bool cont = off + lane16 < kBlockSize && i < n_tokens && slots[i] == slot0 + lane16;
+            const uint32_t m = static_cast<uint32_t>(__builtin_amdgcn_ballot_w64(cont)) & 0xFFFFu;
+            len = __builtin_ctz(~m);   // bit 0 is always set: at least the starting token itself
+        }
+        const int64_t blk = slot0 / kBlockSize;
+        if (t_loc < len) {
+            const size_t src = static_cast<size_t>(i0 + t_loc) * kv_stride + static_cast<size_t>(g) * D + dv * 8;
+            const u32x4 kvec = *reinterpret_cast<const u32x4*>(k_new + src);
+            const u32x4 vvec = *reinterpret_cast<const u32x4*>(v_new + src);
+            *reinterpret_cast<Piece*>(cache + cache_part_offset(blk, g, 0, hkv_l, D) + static_cast<size_t>(off + t_loc) * D + dv * 8) =
+                encode(kvec, k_scale);
+            *reinterpret_cast<Piece*>(tile + t_loc * kPitch + dv * 8) = encode(vvec, v_scale);
+        }
+        __syncthreads();
+        // positions 8 h .. 8 h + 7 of V row d; position p holds token p - off of the run
+        CE* vrow = cache + cache_part_offset(blk, g, 1, hkv_l, D) + static_cast<size_t>(d) * kBlockSize + 8 * h;
+        const int lo = max(off - 8 * h, 0), hi = min(off + len - 8 * h, 8);   // valid positions of this piece: [lo, hi)
+        if (lo == 0 && hi == 8) {
+            union {
+                Piece v;
+                CE e[8];
+            } o;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) o.e[j] = tile[(8 * h + j) * kPitch + d];
-    uint16_t* vblk = cache + cache_part_offset(first / kBlockSize, g, 1, hkv_l, D);
-    *reinterpret_cast<u32x4*>(vblk + static_cast<size_t>(d) * kBlockSize + 8 * h) = o.v;
+            for (int j = 0; j < 8; ++j) o.e[j] = tile[(8 * h + j - off) * kPitch + d];
+            *reinterpret_cast<Piece*>(vrow) = o.v;
+        } else {
+            for (int j = lo; j < hi; ++j) vrow[j] = tile[(8 * h + j - off) * kPitch + d];
+        }
+        if (starts) __syncthreads();   // the next run reuses the tile
+    }
 }
 
 // FP8 E4M3 cache: one thread quantises eight consecutive head-dim elements of one (token, KV head) for
@@ -213,8 +246,7 @@ __global__ __launch_bounds__(kThreads) void kv_write_fp8_kernel(const Elem* __re
         vc[h] = e4m3_pair(vx[4 * h], vx[4 * h + 1], v_scale) | (e4m3_pair(vx[4 * h + 2], vx[4 * h + 3], v_scale) << 16);
     }
     uint8_t* kdst = cache + cache_part_offset(blk, g, 0, hkv_l, D) + static_cast<size_t>(off) * D + dg * 8;
-    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
-    *reinterpret_cast<u32x2_t*>(kdst) = u32x2_t{kc[0], kc[1]};
+    *reinterpret_cast<u32x2*>(kdst) = u32x2{kc[0], kc[1]};
     uint8_t* vdst = cache + cache_part_offset(blk, g, 1, hkv_l, D) + static_cast<size_t>(dg * 8) * kBlockSize + off;
 #pragma unroll
     for (int j = 0; j < 8; ++j) vdst[j * kBlockSize] = static_cast<uint8_t>(vc[j >> 2] >> (8 * (j & 3)));
@@ -290,7 +322,12 @@ hipError_t launch_kv_write(const void* k_new, const void* v_new, const int64_t* 
         const int64_t items = static_cast<int64_t>(n_tokens) * a.hkv_l * (a.D / 8);
         if (items == 0) return hipSuccess;
         const unsigned grid8 = static_cast<unsigned>((items + kThreads - 1) / kThreads);
-        if (a.elem == 2)
+        if (a.elem == 2 && a.D == 128 && a.hkv_l <= 65535) {
+            dim3 g2(static_cast<unsigned>((n_tokens + kBlockSize - 1) / kBlockSize), static_cast<unsigned>(a.hkv_l));
+            kv_write_block_kernel<true><<<g2, kThreads, 0, st>>>(static_cast<const uint16_t*>(k_new),
+                                                                 static_cast<const uint16_t*>(v_new), slots, n_tokens, cache,
+                                                                 a.hkv_l, a.kv_stride, a.k_scale, a.v_scale);
+        } else if (a.elem == 2)
             kv_write_fp8_kernel<uint16_t><<<grid8, kThreads, 0, st>>>(
                 static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new), slots, n_tokens,
                 static_cast<uint8_t*>(cache), a.hkv_l, a.D, a.kv_stride, a.k_scale, a.v_scale);
@@ -305,9 +342,9 @@ hipError_t launch_kv_write(const void* k_new, const void* v_new, const int64_t* 
     const unsigned grid = static_cast<unsigned>((total + kThreads - 1) / kThreads);
     if (a.elem == 2 && a.D == 128 && a.hkv_l <= 65535) {
         dim3 g2(static_cast<unsigned>((n_tokens + kBlockSize - 1) / kBlockSize), static_cast<unsigned>(a.hkv_l));
-        kv_write_block_kernel<<<g2, kThreads, 0, st>>>(static_cast<const uint16_t*>(k_new),
-                                                       static_cast<const uint16_t*>(v_new), slots, n_tokens,
-                                                       static_cast<uint16_t*>(cache), a.hkv_l, a.kv_stride);
+        kv_write_block_kernel<false><<<g2, kThreads, 0, st>>>(static_cast<const uint16_t*>(k_new),
+                                                              static_cast<const uint16_t*>(v_new), slots, n_tokens, cache,
+                                                              a.hkv_l, a.kv_stride, 1.f, 1.f);
         return hipGetLastError();
     }
     if (a.elem == 2)

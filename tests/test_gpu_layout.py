@@ -68,9 +68,9 @@ def test_kv_write_bit_exact(oracle, G, dtype, hkv_l, D):
 
 @pytest.mark.parametrize("hkv_l", [1, 2])
 def test_kv_write_whole_blocks_and_ragged_runs(oracle, G, hkv_l):
-    """bf16, D=128: runs of 16 new tokens that fill a cache block in order go through the block-wise
-    writer, every other pattern (misaligned run, padding row inside a run, tail of the batch)
-    through the element-wise one; the cache bytes do not depend on which."""
+    """bf16, D=128: the writer works run by run (consecutive tokens in consecutive slots of one block): whole
+    blocks, runs that start or end inside a block, a padding row inside a run, the tail of the batch; untouched
+    slots keep their bytes."""
     from paper_2509_16495_amd import binding as B
     case = W.make_attn_case("t", 45, "bf16", [(64, 64), (32, 160), (16, 21), (48, 48), (5, 5)], hkv_l, hkv_l, 128,
                             pool_factor=1.4)
@@ -83,6 +83,55 @@ def test_kv_write_whole_blocks_and_ragged_runs(oracle, G, hkv_l):
         cache = G.new_cache(case.num_blocks, hkv_l, 128, "bf16", fill_byte=0x7F)
         G.kv_write(cache, k, v, slots, "bf16")
         assert B.to_host(cache).tobytes() == want.tobytes()
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+@pytest.mark.parametrize("seed", [46, 47, 48])
+def test_kv_write_arbitrary_slot_patterns(oracle, G, seed, fp8):
+    """bf16, D=128, slot patterns a serving engine can produce in one batch, in random order: runs of every length
+    1..16 at every offset inside a block, runs that continue into another block, single tokens, padding rows, slots
+    that descend, a batch size that is no multiple of 16.  Every slot is used at most once; bit-exact cache."""
+    from paper_2509_16495_amd import binding as B
+    rng = np.random.Generator(np.random.PCG64(seed))
+    hkv_l, D, n_blocks = 2, 128, 400
+    free = list(rng.permutation(n_blocks))
+    pieces = []
+    for _ in range(150):
+        kind = rng.integers(0, 5)
+        if kind == 0:                                   # a run inside one block
+            off = int(rng.integers(0, 16)); ln = int(rng.integers(1, 17 - off))
+            pieces.append(free.pop() * 16 + off + np.arange(ln))
+        elif kind == 1:                                 # a sequence stretch over several blocks, starting anywhere
+            off = int(rng.integers(0, 16)); ln = int(rng.integers(1, 70))
+            pos = off + np.arange(ln)
+            blocks = [free.pop() for _ in range(pos[-1] // 16 + 1)]
+            pieces.append(np.array([blocks[q // 16] * 16 + q % 16 for q in pos]))
+        elif kind == 2:                                 # padding rows
+            pieces.append(np.full(int(rng.integers(1, 4)), -1))
+        elif kind == 3:                                 # single decode tokens
+            pieces.append(np.array([free.pop() * 16 + int(rng.integers(0, 16)) for _ in range(int(rng.integers(1, 6)))]))
+        else:                                           # consecutive slots in descending order
+            off = int(rng.integers(0, 12)); ln = int(rng.integers(2, 17 - off))
+            pieces.append(free.pop() * 16 + off + np.arange(ln)[::-1])
+    slots = np.concatenate(pieces).astype(np.int64)
+    n = len(slots)
+    assert n % 16 != 0
+    used = slots[slots >= 0]
+    assert len(np.unique(used)) == len(used)
+    k = W.f32_to_bf16_bits(rng.standard_normal((n, hkv_l, D), dtype=np.float32))
+    v = W.f32_to_bf16_bits(rng.standard_normal((n, hkv_l, D), dtype=np.float32))
+    if fp8:   # the quantising writer: codes of x / scale, a scale that is no power of two
+        ks, vs = 0.037, 0.021
+        want = oracle.new_cache(n_blocks, hkv_l, 16, D, "fp8_e4m3", fill_byte=0x7F)
+        oracle.kv_write_fp8(want, k, v, slots, 16, "bf16", ks, vs)
+        cache = G.new_cache_fp8(n_blocks, hkv_l, D, fill_byte=0x7F)
+        G.kv_write(cache, k, v, slots, "bf16", fp8_scales=(ks, vs))
+    else:
+        want = oracle.new_cache(n_blocks, hkv_l, 16, D, "bf16", fill_byte=0x7F)
+        oracle.kv_write(want, k, v, slots, 16, "bf16")
+        cache = G.new_cache(n_blocks, hkv_l, D, "bf16", fill_byte=0x7F)
+        G.kv_write(cache, k, v, slots, "bf16")
+    assert B.to_host(cache).tobytes() == want.tobytes()
 
 
 @pytest.mark.parametrize("sp,tp,H,H_kv", [(3, 2, 12, 6), (8, 1, 32, 4), (4, 2, 16, 8), (4, 2, 40, 8)])
