@@ -53,6 +53,7 @@ def lib() -> ctypes.CDLL:
         L.oracle_kv_write_fp8.argtypes = [vp, vp, vp, i64, vp, i32, i32, i32, i32, flt, flt]
         L.oracle_attention_kv.argtypes = [vp, i32, vp, i32, dbl, dbl, vp, i32, vp, vp, i32, i32, i32, i32, i32, dbl, vp,
                                           i64, vp]
+        L.oracle_quantize_rows_e4m3.argtypes = [vp, i32, i64, i64, i64, vp, vp]
         L.oracle_e4m3_value.argtypes = [u8]
         L.oracle_e4m3_value.restype = dbl
         L.oracle_e4m3_from_float.argtypes = [flt]
@@ -166,6 +167,43 @@ def unpack_o_proj(recv: np.ndarray, w_o: np.ndarray, T: int, dtype: str) -> np.n
     r64 = _stored_to_f64(recv, dtype)
     a = np.concatenate([r64[p, :T] for p in range(P)], axis=1).reshape(T, P * hq_l * D)  # out[t, p hq_l + j] = recv[p][t][j]
     return a @ _stored_to_f64(w_o, dtype).T
+
+
+# ---- the same projections with FP8 E4M3 operands (Sec. 4.1 serves FP8 models; scale rule: this build's reading) ----
+def quantize_rows_e4m3(x: np.ndarray, dtype: str):
+    """x [rows, cols] stored in `dtype` -> (codes uint8 [rows, cols], scales float32 [rows]): scale = amax / 448 in
+    float32 (1 for a zero row), code = E4M3 code nearest to the float32 quotient x / scale."""
+    x = np.ascontiguousarray(x, dtype=_NP_STORE[dtype])
+    rows, cols = x.shape
+    codes = np.empty((rows, cols), dtype=np.uint8)
+    scales = np.empty(rows, dtype=np.float32)
+    rc = lib().oracle_quantize_rows_e4m3(_p(x), DTYPE_CODE[dtype], rows, cols, cols, _p(codes), _p(scales))
+    assert rc == 0
+    return codes, scales
+
+
+def e4m3_table() -> np.ndarray:
+    return np.array([e4m3_value(c) for c in range(256)], dtype=np.float64)
+
+
+def recv_rows(recv: np.ndarray, T: int) -> np.ndarray:
+    """recv [P, T_pad, hq_l, D] -> [T, P hq_l D]: token t's attention output, heads in global order."""
+    P, T_pad, hq_l, D = recv.shape
+    return np.concatenate([recv[p, :T].reshape(T, hq_l * D) for p in range(P)], axis=1)
+
+
+def qkv_proj_pack_fp8(x_codes, x_scales, w_codes, w_scales, P: int, h: int, h_kv: int, D: int, T_pad: int) -> np.ndarray:
+    """y[t][f] = x_scale[t] w_scale[f] sum_k value(x_codes[t][k]) value(w_codes[f][k]) in float64, packed like qkv_proj_pack."""
+    tab = e4m3_table()
+    y = (tab[x_codes] @ tab[w_codes].T) * x_scales.astype(np.float64)[:, None] * w_scales.astype(np.float64)[None, :]
+    return pack_heads_f64(y.reshape(x_codes.shape[0], h + 2 * h_kv, D), P, h, h_kv, T_pad)
+
+
+def unpack_o_proj_fp8(recv_codes, a_scales, w_codes, w_scales, T: int) -> np.ndarray:
+    """recv_codes [P, T_pad, hq_l, D] uint8 with one scale per token; w_codes [d, h D] with one scale per output feature."""
+    tab = e4m3_table()
+    a = tab[recv_rows(recv_codes, T)]
+    return (a @ tab[w_codes].T) * a_scales.astype(np.float64)[:T, None] * w_scales.astype(np.float64)[None, :]
 
 
 # ---------------------------------------------------------------------------

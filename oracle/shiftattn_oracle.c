@@ -242,6 +242,32 @@ int oracle_kv_write_fp8(const void *k_new, const void *v_new, const int64_t *slo
     return 0;
 }
 
+/* Rows of a matrix as FP8 E4M3 codes with one scale per row (the dynamic per-token scale of FP8
+ * activations, and the per-output-feature scale of FP8 weights; Sec. 4.1 only says that FP8 models were
+ * served, the rule is this build's reading): scale[r] = max_k |x[r][k]| / 448 as a float32 quotient
+ * (1 for a row of zeros), code = the E4M3 code nearest to the float32 quotient x / scale[r].
+ * x: [rows][cols] stored in `dtype`, row r starting at element r * row_stride. */
+int oracle_quantize_rows_e4m3(const void *x, int dtype, int64_t rows, int64_t cols, int64_t row_stride,
+                              uint8_t *codes, float *scales)
+{
+    if (dtype != ORACLE_BF16 && dtype != ORACLE_F32) return -1;
+    for (int64_t r = 0; r < rows; ++r) {
+        float amax = 0.0f;
+        for (int64_t k = 0; k < cols; ++k) {
+            float a = fabsf((float)widen(x, (size_t)(r * row_stride + k), dtype));
+            if (a > amax) amax = a;
+        }
+        volatile float sc = amax / 448.0f;
+        float scale = amax > 0.0f ? sc : 1.0f;
+        scales[r] = scale;
+        for (int64_t k = 0; k < cols; ++k) {
+            volatile float q = (float)widen(x, (size_t)(r * row_stride + k), dtype) / scale;
+            codes[r * cols + k] = oracle_e4m3_from_float(q);
+        }
+    }
+    return 0;
+}
+
 /* ---------------------------------------------------------------------------
  * Attention of the local head shard over the paged cache (Algorithm 1, boxed
  * line; Sec. 2.2).  For sequence s with q_len new tokens out of ctx total,
