@@ -150,6 +150,33 @@ int shiftattn_qkv_proj_pack(const void *x, const void *w_qkv, void *send, int32_
 int shiftattn_unpack_o_proj(const void *recv, const void *w_o, void *out, int32_t T, int32_t T_pad,
                             int32_t d_model, const shiftattn_xchg *xc, void *stream);
 
+/* ---- The same projections with FP8 E4M3 operands (Sec. 4.1: the served models are FP8) ------------
+ * The paper gives no quantisation rule; this library's: a matrix row r is stored as OCP FP8 E4M3 codes
+ * plus one float32 scale, scale[r] = max_k |x[r][k]| / 448 (1 for a row of zeros), code = the E4M3 code
+ * nearest (ties to even) to the float32 quotient x / scale[r]; a row is a token for activations (dynamic
+ * per-token scale) and an output feature for weights.  A product is
+ *   y[t][f] = x_scale[t] * w_scale[f] * sum_k value(x_code[t][k]) * value(w_code[f][k]),
+ * summed in fp32 by the FP8 matrix cores and rounded once to bf16.
+ * quantize_rows_fp8: x [rows][cols] bf16 (device) -> codes [rows][cols] bytes, scales [rows] floats;
+ *   cols % 8 == 0.  Use it for activations and, once, for weights.
+ * quantize_recv_fp8: the same for the attention output as it lies in the receive buffers: row t is the
+ *   concatenation over p of recv[p][t][0..hq_l-1][0..D-1]; codes come out in the same [P][T_pad][hq_l][D]
+ *   arrangement (one byte per element; rows T..T_pad-1 are left untouched), scales [T].
+ *   xc->dtype must be SHIFTATTN_BF16, head_dim % 8 == 0.
+ * qkv_proj_pack_fp8 / unpack_o_proj_fp8: as the bf16 calls above with the operands replaced by codes and
+ *   their scales; send / out stay bf16, xc describes them (dtype SHIFTATTN_BF16, head_dim 128).
+ *   Same shape requirements as the bf16 calls.  All pointers device, 16-byte aligned (scales: 4). */
+int shiftattn_quantize_rows_fp8(const void *x, void *codes, float *scales, int32_t rows, int32_t cols,
+                                void *stream);
+int shiftattn_quantize_recv_fp8(const void *recv, void *codes, float *scales, int32_t T, int32_t T_pad,
+                                const shiftattn_xchg *xc, void *stream);
+int shiftattn_qkv_proj_pack_fp8(const void *x_codes, const float *x_scales, const void *w_codes,
+                                const float *w_scales, void *send, int32_t T, int32_t T_pad, int32_t d_model,
+                                const shiftattn_xchg *xc, void *stream);
+int shiftattn_unpack_o_proj_fp8(const void *recv_codes, const float *a_scales, const void *w_codes,
+                                const float *w_scales, void *out, int32_t T, int32_t T_pad, int32_t d_model,
+                                const shiftattn_xchg *xc, void *stream);
+
 /* ---- KV-cache append (Sec. 2.2: prefill initialises the cache, decoding appends to it) --------
  * k_new, v_new (device, in): [n_tokens][hkv_l][D] with row stride a->kv_stride.
  * slot_mapping (device, in): int64 [n_tokens]; token i goes to slot slot_mapping[i];

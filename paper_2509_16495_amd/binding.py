@@ -61,6 +61,10 @@ def lib() -> ctypes.CDLL:
         L.shiftattn_unpack_head2seq.argtypes = [vp, vp, i32, i32, xp, vp]
         L.shiftattn_qkv_proj_pack.argtypes = [vp, vp, vp, i32, i32, i32, xp, vp]
         L.shiftattn_unpack_o_proj.argtypes = [vp, vp, vp, i32, i32, i32, xp, vp]
+        L.shiftattn_quantize_rows_fp8.argtypes = [vp, vp, vp, i32, i32, vp]
+        L.shiftattn_quantize_recv_fp8.argtypes = [vp, vp, vp, i32, i32, xp, vp]
+        L.shiftattn_qkv_proj_pack_fp8.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, xp, vp]
+        L.shiftattn_unpack_o_proj_fp8.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, xp, vp]
         L.shiftattn_kv_write.argtypes = [vp, vp, i64p, i32, vp, ap, vp]
         L.shiftattn_prefill.argtypes = [vp, vp, vp, i64p, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, ap, vp]
         L.shiftattn_decode.argtypes = [vp, vp, vp, i64p, vp, vp, vp, i32, i32, vp, vp, sz, ap, vp]
@@ -194,6 +198,51 @@ def unpack_o_proj(recv: torch.Tensor, w_o: torch.Tensor, out: torch.Tensor) -> N
     assert recv.dtype == w_o.dtype == out.dtype
     xc = Xchg(P, P * hq_l, 0, D, _dtype_code(recv))
     _check(lib().shiftattn_unpack_o_proj(_ptr(recv), _ptr(w_o), _ptr(out), T, T_pad, d_model, ctypes.byref(xc), _stream()))
+
+
+def quantize_rows_fp8(x: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor) -> None:
+    """x [rows, cols] bf16 -> codes [rows, cols] uint8 (FP8 E4M3), scales [rows] float32 (amax / 448)."""
+    rows, cols = x.shape
+    assert x.dtype == torch.bfloat16 and codes.dtype == torch.uint8 and scales.dtype == torch.float32
+    assert codes.shape == x.shape and scales.shape == (rows,) and x.is_contiguous() and codes.is_contiguous() and scales.is_contiguous()
+    _check(lib().shiftattn_quantize_rows_fp8(_ptr(x), _ptr(codes), _ptr(scales), rows, cols, _stream()))
+
+
+def quantize_recv_fp8(recv: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor) -> None:
+    """recv [P, T_pad, hq_l, D] bf16 -> codes of the same shape (uint8), scales [T]: one scale per token over all buffers."""
+    P, T_pad, hq_l, D = recv.shape
+    T = scales.shape[0]
+    assert recv.dtype == torch.bfloat16 and codes.dtype == torch.uint8 and scales.dtype == torch.float32 and codes.shape == recv.shape
+    assert recv.is_contiguous() and codes.is_contiguous() and scales.is_contiguous()
+    xc = Xchg(P, P * hq_l, 0, D, BF16)
+    _check(lib().shiftattn_quantize_recv_fp8(_ptr(recv), _ptr(codes), _ptr(scales), T, T_pad, ctypes.byref(xc), _stream()))
+
+
+def qkv_proj_pack_fp8(x_codes: torch.Tensor, x_scales: torch.Tensor, w_codes: torch.Tensor, w_scales: torch.Tensor,
+                      send: torch.Tensor, P: int, h: int, h_kv: int) -> None:
+    """FP8 E4M3 codes x [T, d_model] and w [(h + 2 h_kv) D, d_model] with their row scales -> bf16 send buffers."""
+    T, d_model = x_codes.shape
+    T_pad, D = send.shape[1], send.shape[3]
+    assert x_codes.dtype == w_codes.dtype == torch.uint8 and x_scales.dtype == w_scales.dtype == torch.float32 and send.dtype == torch.bfloat16
+    assert w_codes.shape == ((h + 2 * h_kv) * D, d_model) and x_scales.shape == (T,) and w_scales.shape == (w_codes.shape[0],)
+    assert send.shape[0] == P and send.shape[2] == h // P + 2 * local_kv_heads(P, h_kv)
+    assert all(t.is_contiguous() for t in (x_codes, x_scales, w_codes, w_scales, send))
+    xc = Xchg(P, h, h_kv, D, BF16)
+    _check(lib().shiftattn_qkv_proj_pack_fp8(_ptr(x_codes), _ptr(x_scales), _ptr(w_codes), _ptr(w_scales), _ptr(send), T, T_pad,
+                                             d_model, ctypes.byref(xc), _stream()))
+
+
+def unpack_o_proj_fp8(recv_codes: torch.Tensor, a_scales: torch.Tensor, w_codes: torch.Tensor, w_scales: torch.Tensor,
+                      out: torch.Tensor) -> None:
+    """FP8 E4M3 codes recv [P, T_pad, hq_l, D] (one scale per token) and w [d_model, h D] (one per feature) -> out [T, d_model] bf16."""
+    P, T_pad, hq_l, D = recv_codes.shape
+    T, d_model = out.shape
+    assert recv_codes.dtype == w_codes.dtype == torch.uint8 and a_scales.dtype == w_scales.dtype == torch.float32 and out.dtype == torch.bfloat16
+    assert w_codes.shape == (d_model, P * hq_l * D) and a_scales.shape[0] >= T and w_scales.shape == (d_model,)
+    assert all(t.is_contiguous() for t in (recv_codes, a_scales, w_codes, w_scales, out))
+    xc = Xchg(P, P * hq_l, 0, D, BF16)
+    _check(lib().shiftattn_unpack_o_proj_fp8(_ptr(recv_codes), _ptr(a_scales), _ptr(w_codes), _ptr(w_scales), _ptr(out), T, T_pad,
+                                             d_model, ctypes.byref(xc), _stream()))
 
 
 def attn_desc(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, softmax_scale: float,

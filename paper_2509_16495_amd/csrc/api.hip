@@ -217,7 +217,7 @@ int shiftattn_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int32_
     if (s.T_pad == 0) return SHIFTATTN_OK;
     if (!send || (s.T > 0 && (!x || !w_qkv))) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
     if (!aligned16(x) || !aligned16(w_qkv) || !aligned16(send)) return fail(SHIFTATTN_EINVAL, "x / w_qkv / send must be 16-byte aligned");
-    hipError_t e = launch_qkv_proj_pack(x, w_qkv, send, d_model, s, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_qkv_proj_pack(x, w_qkv, send, d_model, s, nullptr, nullptr, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "qkv_proj_pack launch");
 }
 
@@ -232,8 +232,68 @@ int shiftattn_unpack_o_proj(const void* recv, const void* w_o, void* out, int32_
     if (s.T == 0) return SHIFTATTN_OK;
     if (!recv || !w_o || !out) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
     if (!aligned16(recv) || !aligned16(w_o) || !aligned16(out)) return fail(SHIFTATTN_EINVAL, "recv / w_o / out must be 16-byte aligned");
-    hipError_t e = launch_unpack_o_proj(recv, w_o, out, d_model, s, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_unpack_o_proj(recv, w_o, out, d_model, s, nullptr, nullptr, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_o_proj launch");
+}
+
+int shiftattn_quantize_rows_fp8(const void* x, void* codes, float* scales, int32_t rows, int32_t cols, void* stream) {
+    if (rows < 0 || cols < 1) return fail(SHIFTATTN_EINVAL, "rows = %d, cols = %d", rows, cols);
+    if (cols % 8) return fail(SHIFTATTN_EUNSUPPORTED, "cols = %d is not a multiple of 8", cols);
+    if (rows == 0) return SHIFTATTN_OK;
+    if (!x || !codes || !scales) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(x) || (reinterpret_cast<uintptr_t>(codes) & 7) || (reinterpret_cast<uintptr_t>(scales) & 3))
+        return fail(SHIFTATTN_EINVAL, "x must be 16-byte, codes 8-byte, scales 4-byte aligned");
+    hipError_t e = launch_quantize_rows_fp8(x, codes, scales, rows, cols, cols, 0, cols, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "quantize_rows_fp8 launch");
+}
+
+int shiftattn_quantize_recv_fp8(const void* recv, void* codes, float* scales, int32_t T, int32_t T_pad,
+                                const shiftattn_xchg* xc, void* stream) {
+    XchgShape s;
+    if (int rc = check_xchg(xc, T, T_pad, false, &s)) return rc;
+    if (xc->dtype != SHIFTATTN_BF16) return fail(SHIFTATTN_EUNSUPPORTED, "the quantiser reads bf16 rows");
+    if (xc->head_dim % 8) return fail(SHIFTATTN_EUNSUPPORTED, "head_dim = %d is not a multiple of 8", xc->head_dim);
+    if (s.T == 0) return SHIFTATTN_OK;
+    if (!recv || !codes || !scales) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(recv) || (reinterpret_cast<uintptr_t>(codes) & 7) || (reinterpret_cast<uintptr_t>(scales) & 3))
+        return fail(SHIFTATTN_EINVAL, "recv must be 16-byte, codes 8-byte, scales 4-byte aligned");
+    const int seg = s.hq_l * xc->head_dim;
+    hipError_t e = launch_quantize_rows_fp8(recv, codes, scales, s.T, s.P * seg, seg, static_cast<int64_t>(s.T_pad) * seg, seg,
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "quantize_recv_fp8 launch");
+}
+
+int shiftattn_qkv_proj_pack_fp8(const void* x_codes, const float* x_scales, const void* w_codes, const float* w_scales,
+                                void* send, int32_t T, int32_t T_pad, int32_t d_model, const shiftattn_xchg* xc, void* stream) {
+    XchgShape s;
+    if (int rc = check_xchg(xc, T, T_pad, true, &s)) return rc;
+    if (d_model < 1) return fail(SHIFTATTN_EINVAL, "d_model = %d", d_model);
+    if (!qkv_proj_pack_supported(s, d_model, elem_size(xc->dtype)))
+        return fail(SHIFTATTN_EUNSUPPORTED, "projection into the send buffers is built for bf16 results, head_dim 128, d_model a "
+                                            "multiple of 64 and an even number of heads per row (got d_model = %d, %d heads)",
+                    d_model, s.h + 2 * s.h_kv);
+    if (s.T_pad == 0) return SHIFTATTN_OK;
+    if (!send || (s.T > 0 && (!x_codes || !w_codes || !x_scales || !w_scales))) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(x_codes) || !aligned16(w_codes) || !aligned16(send) || !aligned16(w_scales) || (reinterpret_cast<uintptr_t>(x_scales) & 3))
+        return fail(SHIFTATTN_EINVAL, "x_codes / w_codes / w_scales / send must be 16-byte aligned, x_scales 4-byte");
+    hipError_t e = launch_qkv_proj_pack(x_codes, w_codes, send, d_model, s, x_scales, w_scales, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "qkv_proj_pack_fp8 launch");
+}
+
+int shiftattn_unpack_o_proj_fp8(const void* recv_codes, const float* a_scales, const void* w_codes, const float* w_scales,
+                                void* out, int32_t T, int32_t T_pad, int32_t d_model, const shiftattn_xchg* xc, void* stream) {
+    XchgShape s;
+    if (int rc = check_xchg(xc, T, T_pad, false, &s)) return rc;
+    if (d_model < 1) return fail(SHIFTATTN_EINVAL, "d_model = %d", d_model);
+    if (!unpack_o_proj_supported(s, d_model, elem_size(xc->dtype)))
+        return fail(SHIFTATTN_EUNSUPPORTED, "projection out of the receive buffers is built for bf16 results, head_dim 128 and "
+                                            "d_model a multiple of 256 (got d_model = %d)", d_model);
+    if (s.T == 0) return SHIFTATTN_OK;
+    if (!recv_codes || !a_scales || !w_codes || !w_scales || !out) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(recv_codes) || !aligned16(w_codes) || !aligned16(out) || !aligned16(w_scales) || (reinterpret_cast<uintptr_t>(a_scales) & 3))
+        return fail(SHIFTATTN_EINVAL, "recv_codes / w_codes / w_scales / out must be 16-byte aligned, a_scales 4-byte");
+    hipError_t e = launch_unpack_o_proj(recv_codes, w_codes, out, d_model, s, a_scales, w_scales, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_o_proj_fp8 launch");
 }
 
 int shiftattn_kv_write(const void* k_new, const void* v_new, const int64_t* slot_mapping, int32_t n_tokens,

@@ -79,8 +79,17 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
 // proj_gemm.hip : the projections in front of the first exchange and behind the second (bf16, head_dim 128)
 bool qkv_proj_pack_supported(const XchgShape& s, int d_model, int elem);
 bool unpack_o_proj_supported(const XchgShape& s, int d_model, int elem);
-hipError_t launch_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int d_model, const XchgShape& s, hipStream_t st);
-hipError_t launch_unpack_o_proj(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s, hipStream_t st);
+// scales non-null: the operands are FP8 E4M3 codes with one scale per token row and one per output feature
+// (the result stays bf16); the XchgShape then describes the bf16 side (send buffers) or, for the receive buffers,
+// their head geometry
+hipError_t launch_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int d_model, const XchgShape& s,
+                                const float* x_scales, const float* w_scales, hipStream_t st);
+hipError_t launch_unpack_o_proj(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s,
+                                const float* a_scales, const float* w_scales, hipStream_t st);
+// layout_kernels.hip : rows of bf16 values -> FP8 E4M3 codes + one float32 scale per row (amax / 448).  Element k of
+// row t lies at (k / seg_len) * seg_stride + t * row_stride + k % seg_len, in `x` and in `codes` alike.
+hipError_t launch_quantize_rows_fp8(const void* x, void* codes, float* scales, int rows, int cols, int seg_len,
+                                    int64_t seg_stride, int64_t row_stride, hipStream_t st);
 
 // ceilings.hip : attainable-rate probes for benchmark reports
 hipError_t launch_mfma_ceiling(const void* operands, void* sink, int iters, int64_t* flops, hipStream_t st);

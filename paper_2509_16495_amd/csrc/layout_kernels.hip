@@ -316,6 +316,73 @@ hipError_t launch_unpack(const void* recv, void* out, const XchgShape& s, hipStr
     return hipGetLastError();
 }
 
+// Rows of bf16 values as FP8 E4M3 codes with one scale per row: scale = max |x| / 448 (float32 quotient; 1 for a row
+// of zeros), code = e4m3(x / scale).  One workgroup per row; a thread keeps up to kQuantPieces 16-byte pieces of the
+// row in registers between the maximum and the conversion, longer rows are read a second time.
+constexpr int kQuantPieces = 8;
+__global__ __launch_bounds__(kThreads) void quantize_rows_fp8_kernel(const uint16_t* __restrict__ x, uint8_t* __restrict__ codes,
+                                                                     float* __restrict__ scales, int cols, int seg_len,
+                                                                     int64_t seg_stride, int64_t row_stride) {
+    __shared__ float wave_max[kThreads / 64];
+    const int64_t row = blockIdx.x;
+    const int pieces = cols / 8;
+    auto offset = [&](int piece) -> size_t {
+        const int k = piece * 8, seg = k / seg_len;
+        return static_cast<size_t>(seg) * seg_stride + static_cast<size_t>(row) * row_stride + (k - seg * seg_len);
+    };
+    u32x4 held[kQuantPieces];
+    float amax = 0.f;
+#pragma unroll
+    for (int i = 0; i < kQuantPieces; ++i) {
+        const int piece = threadIdx.x + i * kThreads;
+        held[i] = u32x4{0u, 0u, 0u, 0u};
+        if (piece < pieces) held[i] = *reinterpret_cast<const u32x4*>(x + offset(piece));
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            amax = fmaxf(amax, fmaxf(fabsf(__uint_as_float(held[i][j] << 16)), fabsf(__uint_as_float(held[i][j] & 0xFFFF0000u))));
+    }
+    for (int piece = threadIdx.x + kQuantPieces * kThreads; piece < pieces; piece += kThreads) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(x + offset(piece));
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            amax = fmaxf(amax, fmaxf(fabsf(__uint_as_float(v[j] << 16)), fabsf(__uint_as_float(v[j] & 0xFFFF0000u))));
+    }
+    // fmaxf drops NaN operands: a row with NaN elements is scaled by its largest number, the NaNs become NaN codes
+#pragma unroll
+    for (int sh = 32; sh > 0; sh >>= 1) amax = fmaxf(amax, __shfl_xor(amax, sh));
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
+    const float scale = amax > 0.f ? amax / 448.f : 1.f;
+    if (threadIdx.x == 0) scales[row] = scale;
+    auto encode = [&](u32x4 v) -> u32x2 {
+        float f[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            f[2 * j] = __uint_as_float(v[j] << 16);
+            f[2 * j + 1] = __uint_as_float(v[j] & 0xFFFF0000u);
+        }
+        return u32x2{e4m3_pair(f[0], f[1], scale) | (e4m3_pair(f[2], f[3], scale) << 16),
+                     e4m3_pair(f[4], f[5], scale) | (e4m3_pair(f[6], f[7], scale) << 16)};
+    };
+#pragma unroll
+    for (int i = 0; i < kQuantPieces; ++i) {
+        const int piece = threadIdx.x + i * kThreads;
+        if (piece < pieces) *reinterpret_cast<u32x2*>(codes + offset(piece)) = encode(held[i]);
+    }
+    for (int piece = threadIdx.x + kQuantPieces * kThreads; piece < pieces; piece += kThreads)
+        *reinterpret_cast<u32x2*>(codes + offset(piece)) = encode(*reinterpret_cast<const u32x4*>(x + offset(piece)));
+}
+
+hipError_t launch_quantize_rows_fp8(const void* x, void* codes, float* scales, int rows, int cols, int seg_len,
+                                    int64_t seg_stride, int64_t row_stride, hipStream_t st) {
+    if (rows == 0) return hipSuccess;
+    quantize_rows_fp8_kernel<<<static_cast<unsigned>(rows), kThreads, 0, st>>>(static_cast<const uint16_t*>(x),
+                                                                               static_cast<uint8_t*>(codes), scales, cols, seg_len,
+                                                                               seg_stride, row_stride);
+    return hipGetLastError();
+}
+
 hipError_t launch_kv_write(const void* k_new, const void* v_new, const int64_t* slots, int n_tokens, void* cache,
                            const AttnShape& a, hipStream_t st) {
     if (a.kv_fp8()) {

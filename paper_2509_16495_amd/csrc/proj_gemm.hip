@@ -20,6 +20,8 @@
 // rows, one piece column) conflict-free.
 #include "internal.h"
 
+#include <type_traits>
+
 namespace shiftattn {
 
 namespace {
@@ -27,11 +29,12 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kTile = 256;                 // rows of either operand per workgroup
-constexpr int kBK = 32;                    // k per step
-constexpr int kRowBytes = kBK * 2;         // 64
+constexpr int kRowBytes = 64;              // bytes of a row per k tile: 32 bf16 or 64 FP8 elements
 constexpr int kOperandBytes = kTile * kRowBytes;   // 16384
 constexpr int kStage = 2 * kOperandBytes;  // weights, then tokens
 constexpr int kStages = 4;                 // ring of k tiles in LDS: one being multiplied, the others in flight
@@ -54,9 +57,11 @@ constexpr int kHeadDim = 128;
 __device__ inline bf16x8 frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 struct GemmParams {
-    const uint16_t* __restrict__ w;   // [N][K]
-    const uint16_t* __restrict__ x;   // token rows; see mode
-    uint16_t* __restrict__ c;
+    const unsigned char* __restrict__ w;   // [N][K], bf16 or FP8 E4M3 codes
+    const unsigned char* __restrict__ x;   // token rows of the same type; see mode
+    uint16_t* __restrict__ c;              // bf16
+    const float* __restrict__ xs;          // FP8: one scale per token row
+    const float* __restrict__ ws;          // FP8: one scale per output feature
     int M, M_out, N, K;               // M token rows exist, rows M..M_out-1 of the result are written as zeros
     // mode 0 (qkv_proj_pack): x dense [M][K]; result columns scattered to send buffers (XchgShape below)
     // mode 1 (unpack_o_proj): x gathered from recv [P][T_pad][hq_l][128] (k = (p hq_l + j) 128 + e); result dense [M][N]
@@ -64,7 +69,12 @@ struct GemmParams {
     XchgShape s;
 };
 
+// kFp8: both operands are FP8 E4M3 codes (v_mfma_scale_f32_32x32x64_f8f6f4 with unit block scales, fp32
+// accumulation); the result is multiplied by the token's and the feature's scale before it is rounded to bf16.
+template <bool kFp8>
 __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
+    constexpr int kElem = kFp8 ? 1 : 2;          // bytes per operand element
+    constexpr int kBK = kRowBytes / kElem;       // k per tile
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     typedef __attribute__((address_space(3))) void* lds_ptr;
     typedef const __attribute__((address_space(1))) void* glb_ptr;
@@ -82,22 +92,23 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     // vector ALU instruction is spent on a load.
     const int ld_row = lane >> 2, ld_pos = lane & 3;
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-    const size_t x_row = p.mode == 0 ? static_cast<size_t>(p.K) : static_cast<size_t>(p.s.hq_l) * kHeadDim;   // elements
+    const size_t k_bytes = static_cast<size_t>(p.K) * kElem;
+    const size_t seg_bytes = p.mode == 0 ? k_bytes : static_cast<size_t>(p.s.hq_l) * kHeadDim * kElem;   // contiguous k of a token row
     uint32_t w_off[kLoadsPerOperand], x_off[kLoadsPerOperand];   // byte offsets of this lane's piece from the tile origin at k = 0
 #pragma unroll
     for (int j = 0; j < kLoadsPerOperand; ++j) {
         const int row = kLoadRows * wave + 16 * j + ld_row;
         const int piece = ld_pos ^ ((row >> 2) & 3);
-        w_off[j] = static_cast<uint32_t>((static_cast<size_t>(row) * p.K + piece * 8) * 2);
+        w_off[j] = static_cast<uint32_t>(static_cast<size_t>(row) * k_bytes + piece * 16);
         const int m = min(m0 + row, p.M - 1) - m0;   // rows past the end re-read the last one; they are not stored
-        x_off[j] = static_cast<uint32_t>((static_cast<size_t>(m) * x_row + piece * 8) * 2);
+        x_off[j] = static_cast<uint32_t>(static_cast<size_t>(m) * seg_bytes + piece * 16);
     }
-    const char* w_tile = reinterpret_cast<const char*>(p.w + static_cast<size_t>(n0) * p.K);
-    const char* x_tile = reinterpret_cast<const char*>(p.x + static_cast<size_t>(m0) * x_row);
+    const unsigned char* w_tile = p.w + static_cast<size_t>(n0) * k_bytes;
+    const unsigned char* x_tile = p.x + static_cast<size_t>(m0) * seg_bytes;
     // A token row's k runs contiguously through the hq_l heads that one source rank returned, then jumps to the
     // next rank's buffer (mode 1); in mode 0 it is contiguous throughout.
-    const int seg_tiles = p.mode == 0 ? p.K / kBK : p.s.hq_l * kHeadDim / kBK;
-    const size_t seg_jump = p.mode == 0 ? 0 : static_cast<size_t>(p.s.T_pad - 1) * p.s.hq_l * kHeadDim * 2;   // bytes
+    const int seg_tiles = static_cast<int>(seg_bytes / kRowBytes);
+    const size_t seg_jump = p.mode == 0 ? 0 : static_cast<size_t>(p.s.T_pad - 1) * seg_bytes;
     int ld_kt = 0, ld_left = seg_tiles;   // next tile to load, and how many tiles remain in its segment
     auto load_one = [&](int j) {          // first the weight rows, then the token rows
         unsigned char* dst = lds + (ld_kt % kStages) * kStage + (kLoadRows * wave_s) * kRowBytes;
@@ -106,8 +117,8 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     };
     auto load_advance = [&]() {
         ++ld_kt;
-        w_tile += kBK * 2;
-        x_tile += kBK * 2;
+        w_tile += kRowBytes;
+        x_tile += kRowBytes;
         if (--ld_left == 0) { ld_left = seg_tiles; x_tile += seg_jump; }
     };
 
@@ -152,36 +163,96 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     };
 
     const int k_steps = p.K / kBK;
-    u32x4 a0[kNT], b0[kMT], a1[kNT], b1[kMT];
-    for (int t = 0; t < kStages - 1 && t < k_steps; ++t) {
+    auto prologue = [&]() {   // the first kStages - 1 tiles are requested, tile 0 has landed everywhere
+        for (int t = 0; t < kStages - 1 && t < k_steps; ++t) {
 #pragma unroll
-        for (int j = 0; j < kLoadsPerTile; ++j) load_one(j);
-        load_advance();
-    }
-    if (k_steps >= kStages - 1) __builtin_amdgcn_s_waitcnt(wait_imm(kLoadsPerTile * (kStages - 2), kNoLgkm));   // tile 0 has landed
-    else __builtin_amdgcn_s_waitcnt(wait_imm(0, kNoLgkm));
-    __builtin_amdgcn_s_barrier();
-    read_ops(lds, 0, a0, b0);
-    auto tile = [&]<bool kLoads>(int kt) {
-        read_ops(lds + (kt % kStages) * kStage, 1, a1, b1);
-        __builtin_amdgcn_sched_barrier(0);   // the reads stay ahead of the MFMAs of the slice before ...
-        __builtin_amdgcn_s_waitcnt(wait_imm(kNoVm, kNT + kMT));  // ... which wait for their own operands only
-        multiply.template operator()<kLoads ? 0 : -1>(a0, b0);
-        // tile kt + 1 has landed (behind it: kStages - 3 whole tiles and the weight loads just issued), and this
-        // wavefront's reads of tile kt are done
-        __builtin_amdgcn_sched_barrier(0);
-        if (kLoads) __builtin_amdgcn_s_waitcnt(wait_imm(kLoadsPerTile * (kStages - 3) + kLoadsPerOperand, 0));
-        else __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
-        __builtin_amdgcn_s_barrier();   // bare: a __syncthreads() would wait for every load in flight
-        read_ops(lds + ((kt + 1) % kStages) * kStage, 0, a0, b0);   // behind the last tile: stale data, not used
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(wait_imm(kNoVm, kNT + kMT));
-        multiply.template operator()<kLoads ? kLoadsPerOperand : -1>(a1, b1);
-        if (kLoads) load_advance();
+            for (int j = 0; j < kLoadsPerTile; ++j) load_one(j);
+            load_advance();
+        }
+        if (k_steps >= kStages - 1) __builtin_amdgcn_s_waitcnt(wait_imm(kLoadsPerTile * (kStages - 2), kNoLgkm));
+        else __builtin_amdgcn_s_waitcnt(wait_imm(0, kNoLgkm));
+        __builtin_amdgcn_s_barrier();
     };
-    int kt = 0;
-    for (; kt + kStages - 1 < k_steps; ++kt) tile.template operator()<true>(kt);
-    for (; kt < k_steps; ++kt) tile.template operator()<false>(kt);
+    if constexpr (!kFp8) {
+        u32x4 a0[kNT], b0[kMT], a1[kNT], b1[kMT];
+        prologue();
+        read_ops(lds, 0, a0, b0);
+        auto tile = [&]<bool kLoads>(int kt) {
+            read_ops(lds + (kt % kStages) * kStage, 1, a1, b1);
+            __builtin_amdgcn_sched_barrier(0);   // the reads stay ahead of the MFMAs of the slice before ...
+            __builtin_amdgcn_s_waitcnt(wait_imm(kNoVm, kNT + kMT));  // ... which wait for their own operands only
+            multiply.template operator()<kLoads ? 0 : -1>(a0, b0);
+            // tile kt + 1 has landed (behind it: kStages - 3 whole tiles and the weight loads just issued), and this
+            // wavefront's reads of tile kt are done
+            __builtin_amdgcn_sched_barrier(0);
+            if (kLoads) __builtin_amdgcn_s_waitcnt(wait_imm(kLoadsPerTile * (kStages - 3) + kLoadsPerOperand, 0));
+            else __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
+            __builtin_amdgcn_s_barrier();   // bare: a __syncthreads() would wait for every load in flight
+            read_ops(lds + ((kt + 1) % kStages) * kStage, 0, a0, b0);   // behind the last tile: stale data, not used
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(wait_imm(kNoVm, kNT + kMT));
+            multiply.template operator()<kLoads ? kLoadsPerOperand : -1>(a1, b1);
+            if (kLoads) load_advance();
+        };
+        int kt = 0;
+        for (; kt + kStages - 1 < k_steps; ++kt) tile.template operator()<true>(kt);
+        for (; kt < k_steps; ++kt) tile.template operator()<false>(kt);
+    } else {
+        // One MFMA per (feature tile, token tile) and k tile: its 32-byte operands are the two 16-byte pieces the
+        // bf16 path reads for its two k slices (which k a lane holds does not matter as long as both operands agree).
+        // Two register sets: the next tile's operands are fetched while this tile's MFMAs run.
+        i32x8 a[2][kNT], b[2][kMT];   // [set]
+        auto join = [](u32x4 lo, u32x4 hi) -> i32x8 {
+            return i32x8{static_cast<int>(lo[0]), static_cast<int>(lo[1]), static_cast<int>(lo[2]), static_cast<int>(lo[3]),
+                         static_cast<int>(hi[0]), static_cast<int>(hi[1]), static_cast<int>(hi[2]), static_cast<int>(hi[3])};
+        };
+        auto read_tile = [&](const unsigned char* base, auto set_c) {
+            constexpr int S = decltype(set_c)::value;
+#pragma unroll
+            for (int nt = 0; nt < kNT; ++nt) {
+                const unsigned char* r = base + a_base + nt * 32 * kRowBytes;
+                a[S][nt] = join(*reinterpret_cast<const u32x4*>(r + rd[0]), *reinterpret_cast<const u32x4*>(r + rd[1]));
+            }
+#pragma unroll
+            for (int mt = 0; mt < kMT; ++mt) {
+                const unsigned char* r = base + b_base + mt * 32 * kRowBytes;
+                b[S][mt] = join(*reinterpret_cast<const u32x4*>(r + rd[0]), *reinterpret_cast<const u32x4*>(r + rd[1]));
+            }
+        };
+        // kLoadMode 1: the tile kStages - 1 ahead exists and is requested; 2: checked at run time (the last few tiles)
+        auto tile8 = [&]<int kLoadMode, int S>(int kt) {
+            const bool ld = kLoadMode == 1 || kt + kStages - 1 < k_steps;
+            // tile kt + 1 has landed (behind it kStages - 3 whole tiles), and this wavefront's reads of tile kt are done
+            if (ld) __builtin_amdgcn_s_waitcnt(wait_imm(kLoadsPerTile * (kStages - 3), 0));
+            else __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
+            __builtin_amdgcn_s_barrier();
+            read_tile(lds + ((kt + 1) % kStages) * kStage, std::integral_constant<int, 1 - S>{});   // behind the last tile: stale, unused
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < kMT; ++mt) {
+                    acc[nt][mt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[S][nt], b[S][mt], acc[nt][mt], 0, 0, 0, 127, 0, 127);
+                    if ((nt * kMT + mt) % 2 == 0) {
+                        if (ld) load_one((nt * kMT + mt) / 2);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            if (ld) load_advance();
+        };
+        static_assert(kNT * kMT == 2 * kLoadsPerTile, "one load behind every second MFMA");
+        prologue();
+        read_tile(lds, std::integral_constant<int, 0>{});
+        int kt = 0;
+        for (; kt + kStages < k_steps; kt += 2) {
+            tile8.template operator()<1, 0>(kt);
+            tile8.template operator()<1, 1>(kt + 1);
+        }
+        for (; kt < k_steps; kt += 2) {
+            tile8.template operator()<2, 0>(kt);
+            if (kt + 1 < k_steps) tile8.template operator()<2, 1>(kt + 1);
+        }
+    }
 
     // ---- result: register r of acc[nt][mt] is feature 32 nt + 8 (r / 4) + 4 half + r % 4 of token 32 mt + l32
     const int f_wave = n0 + wn * kNT * 32;     // first feature of this wavefront; its features lie in one head
@@ -191,13 +262,21 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
             const int m = m0 + wm * kMT * 32 + mt * 32 + l32;
             if (m >= p.M_out) continue;
             uint16_t* row = dst_row0 + static_cast<size_t>(m) * row_stride + 4 * half;
+            float row_scale = 1.f;
+            if constexpr (kFp8) row_scale = m < p.M ? p.xs[m] : 0.f;
 #pragma unroll
             for (int nt = 0; nt < kNT; ++nt)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
+                    f32x4 col_scale = {1.f, 1.f, 1.f, 1.f};
+                    if constexpr (kFp8) col_scale = *reinterpret_cast<const f32x4*>(p.ws + f_wave + 32 * nt + 8 * r4 + 4 * half);
                     bf16x4 v;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = static_cast<__bf16>(m < p.M ? acc[nt][mt][4 * r4 + e] : 0.f);
+                    for (int e = 0; e < 4; ++e) {
+                        float y = m < p.M ? acc[nt][mt][4 * r4 + e] : 0.f;
+                        if constexpr (kFp8) y = y * row_scale * col_scale[e];
+                        v[e] = static_cast<__bf16>(y);
+                    }
                     *reinterpret_cast<u32x2*>(row + 32 * nt + 8 * r4) = __builtin_bit_cast(u32x2, v);
                 }
         }
@@ -230,10 +309,11 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     }
 }
 
+template <bool kFp8>
 hipError_t launch(const GemmParams& p, hipStream_t st) {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel<kFp8>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
         if (e != hipSuccess) return e;
         attr_done = true;
@@ -241,7 +321,7 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
     const int64_t wgs = static_cast<int64_t>(p.N / kTile) * ((p.M_out + kTile - 1) / kTile);
     if (wgs == 0) return hipSuccess;
     if (wgs > 0x7FFFFFFF) return hipErrorInvalidValue;
-    proj_gemm_kernel<<<static_cast<unsigned>(wgs), kGemmThreads, kGemmLds, st>>>(p);
+    proj_gemm_kernel<kFp8><<<static_cast<unsigned>(wgs), kGemmThreads, kGemmLds, st>>>(p);
     return hipGetLastError();
 }
 
@@ -255,11 +335,14 @@ bool unpack_o_proj_supported(const XchgShape& s, int d_model, int elem) {
     return elem == 2 && s.vec_per_head * 8 == kHeadDim && d_model > 0 && d_model % kTile == 0 && s.h > 0;
 }
 
-hipError_t launch_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int d_model, const XchgShape& s, hipStream_t st) {
+hipError_t launch_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int d_model, const XchgShape& s,
+                                const float* x_scales, const float* w_scales, hipStream_t st) {
     GemmParams p;
-    p.w = static_cast<const uint16_t*>(w_qkv);
-    p.x = static_cast<const uint16_t*>(x);
+    p.w = static_cast<const unsigned char*>(w_qkv);
+    p.x = static_cast<const unsigned char*>(x);
     p.c = static_cast<uint16_t*>(send);
+    p.xs = x_scales;
+    p.ws = w_scales;
     p.M = s.T;
     p.M_out = s.T_pad;
     p.N = (s.h + 2 * s.h_kv) * kHeadDim;
@@ -267,14 +350,17 @@ hipError_t launch_qkv_proj_pack(const void* x, const void* w_qkv, void* send, in
     p.mode = 0;
     p.s = s;
     if (s.T == 0) return launch_pack(nullptr, send, s, st);  // only padding rows: the pack kernel writes the zeros
-    return launch(p, st);
+    return x_scales ? launch<true>(p, st) : launch<false>(p, st);
 }
 
-hipError_t launch_unpack_o_proj(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s, hipStream_t st) {
+hipError_t launch_unpack_o_proj(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s,
+                                const float* a_scales, const float* w_scales, hipStream_t st) {
     GemmParams p;
-    p.w = static_cast<const uint16_t*>(w_o);
-    p.x = static_cast<const uint16_t*>(recv);
+    p.w = static_cast<const unsigned char*>(w_o);
+    p.x = static_cast<const unsigned char*>(recv);
     p.c = static_cast<uint16_t*>(out);
+    p.xs = a_scales;
+    p.ws = w_scales;
     p.M = s.T;
     p.M_out = s.T;
     p.N = d_model;
@@ -282,7 +368,7 @@ hipError_t launch_unpack_o_proj(const void* recv, const void* w_o, void* out, in
     p.mode = 1;
     p.s = s;
     if (s.T == 0) return hipSuccess;
-    return launch(p, st);
+    return a_scales ? launch<true>(p, st) : launch<false>(p, st);
 }
 
 }  // namespace shiftattn

@@ -1,0 +1,167 @@
+"""GPU parity of the FP8 E4M3 projections (Sec. 4.1 serves FP8 models; the scale rule is this library's reading) against
+the CPU oracle, through the C ABI.
+
+Quantisation: floating point decides integer codes, so both sides decide in float32 (maximum, amax / 448, x / scale) and
+codes and scales are compared bit for bit.
+
+Projection: the kernel and the oracle start from the same codes and scales.  The oracle sums the exact products in
+float64.  The FP8 matrix-core instruction does not: it adds the 64 products of one instruction in small groups whose
+members are aligned to the group's largest product with about 13 bits kept below it (probed on the chip: next to a
+cancelling pair of products of 2^8, products of 2^-5 survive and products of 2^-6 vanish - six of them, the rest of an
+8-product group).  A dropped or truncated product costs at most 2^-13 of its group's largest, so at most 8 * 2^-13 of the
+sum of the group's magnitudes; the fp32 additions between instructions and the two scale multiplications are far below
+that, and the final rounding to bf16 costs 2^-9 relative.  Bound used: |err| <= 2^-8 |ref| + 2^-9 * sum_k |term_k|
+(twice the group bound)."""
+import numpy as np
+import pytest
+
+from paper_2509_16495_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_backend
+    return gpu_backend
+
+
+def _bf16(rng, shape, scale=1.0):
+    return W.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32) * np.float32(scale))
+
+
+def _dev_u8(G, a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint8)).to(G.DEV)
+
+
+def _dev_f32(G, a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(G.DEV)
+
+
+def _check(got_bits, want, abs_terms):
+    """abs_terms: sum over k of |term| for every output, in the output's units (bounds the error of the matrix core's sum)."""
+    got = W.to_f64(got_bits, "bf16")
+    assert got.shape == want.shape and np.all(np.isfinite(got))
+    err = np.abs(got - want)
+    bound = 2.0 ** -8 * np.abs(want) + 2.0 ** -9 * abs_terms + 1e-30
+    assert np.all(err <= bound), float((err / bound).max())
+
+
+@pytest.mark.parametrize("rows,cols", [(5, 64), (300, 512), (33, 8192), (2, 20480), (7, 8)])
+def test_row_quantiser_bit_exact(oracle, G, rows, cols):
+    import torch
+    from paper_2509_16495_amd import binding as B
+    rng = np.random.Generator(np.random.PCG64(301))
+    x = _bf16(rng, (rows, cols), 3.0)
+    x[1] = 0                                             # a zero row
+    x[0, ::3] = W.f32_to_bf16_bits(np.float32(1e-4) * np.ones(len(x[0, ::3]), dtype=np.float32))
+    want_codes, want_scales = oracle.quantize_rows_e4m3(x, "bf16")
+    codes = torch.full((rows, cols), 0x55, dtype=torch.uint8, device=G.DEV)
+    scales = torch.zeros(rows, dtype=torch.float32, device=G.DEV)
+    B.quantize_rows_fp8(G.t(x, "bf16"), codes, scales)
+    torch.cuda.synchronize()
+    assert np.array_equal(scales.cpu().numpy().view(np.uint32), want_scales.view(np.uint32))
+    assert np.array_equal(codes.cpu().numpy(), want_codes)
+
+
+@pytest.mark.parametrize("P,hq_l,T,T_pad", [(8, 8, 37, 40), (4, 10, 5, 8), (1, 2, 3, 3)])
+def test_recv_quantiser_bit_exact(oracle, G, P, hq_l, T, T_pad):
+    import torch
+    from paper_2509_16495_amd import binding as B
+    rng = np.random.Generator(np.random.PCG64(302))
+    D = 128
+    recv = _bf16(rng, (P, T_pad, hq_l, D), 0.7)
+    rows = oracle.recv_rows(recv, T)
+    want_codes, want_scales = oracle.quantize_rows_e4m3(rows, "bf16")
+    codes = torch.full((P, T_pad, hq_l, D), 0x55, dtype=torch.uint8, device=G.DEV)
+    scales = torch.zeros(T, dtype=torch.float32, device=G.DEV)
+    B.quantize_recv_fp8(G.t(recv, "bf16"), codes, scales)
+    torch.cuda.synchronize()
+    got = codes.cpu().numpy()
+    assert np.array_equal(scales.cpu().numpy().view(np.uint32), want_scales.view(np.uint32))
+    assert np.array_equal(oracle.recv_rows(got, T), want_codes)
+    assert np.all(got[:, T:] == 0x55)                    # padding rows are left alone
+
+
+QKV_CASES = [
+    # P, h, h_kv, d_model, T, T_pad
+    (8, 32, 8, 512, 300, 304),
+    (8, 32, 4, 256, 70, 72),       # replication into several send buffers
+    (4, 40, 8, 320, 257, 260),     # d_model no multiple of 128: five k tiles
+    (1, 2, 1, 64, 5, 5),           # one k tile
+    (2, 8, 4, 1024, 600, 600),
+    (2, 8, 4, 192, 9, 10),         # three k tiles: fewer than the ring holds
+    (8, 64, 8, 192, 0, 8),         # padding rows only
+]
+
+
+@pytest.mark.parametrize("P,h,h_kv,d_model,T,T_pad", QKV_CASES)
+def test_qkv_projection_fp8(oracle, G, P, h, h_kv, d_model, T, T_pad):
+    import torch
+    from paper_2509_16495_amd import binding as B
+    rng = np.random.Generator(np.random.PCG64(303))
+    D = 128
+    xc, xs = oracle.quantize_rows_e4m3(_bf16(rng, (max(T, 1), d_model)), "bf16")
+    xc, xs = xc[:T], xs[:T]
+    wc, ws = oracle.quantize_rows_e4m3(_bf16(rng, ((h + 2 * h_kv) * D, d_model), 0.05), "bf16")
+    want = oracle.qkv_proj_pack_fp8(xc, xs, wc, ws, P, h, h_kv, D, T_pad)
+    tab = np.abs(oracle.e4m3_table())
+    tab[np.isnan(tab)] = 0.0
+    terms = (tab[xc] @ tab[wc].T) * xs.astype(np.float64)[:, None] * ws.astype(np.float64)[None, :]
+    terms = oracle.pack_heads_f64(terms.reshape(T, h + 2 * h_kv, D), P, h, h_kv, T_pad)
+    send = torch.empty((P, T_pad, h // P + 2 * B.local_kv_heads(P, h_kv), D), dtype=torch.bfloat16, device=G.DEV)
+    send.view(torch.uint8).fill_(0x55)
+    B.qkv_proj_pack_fp8(_dev_u8(G, xc).reshape(T, d_model), _dev_f32(G, xs), _dev_u8(G, wc), _dev_f32(G, ws), send, P, h, h_kv)
+    torch.cuda.synchronize()
+    got = B.to_host(send)
+    _check(got, want, terms)
+    assert not np.any(got[:, T:])
+
+
+@pytest.mark.parametrize("P,hq_l,d_model,T,T_pad", [(8, 4, 512, 300, 304), (4, 10, 256, 257, 260), (1, 2, 256, 5, 5),
+                                                    (2, 4, 768, 600, 600), (8, 8, 256, 0, 4)])
+def test_o_projection_fp8(oracle, G, P, hq_l, d_model, T, T_pad):
+    import torch
+    from paper_2509_16495_amd import binding as B
+    rng = np.random.Generator(np.random.PCG64(304))
+    D = 128
+    K = P * hq_l * D
+    rc, rs = oracle.quantize_rows_e4m3(_bf16(rng, (max(T, 1), K)), "bf16")
+    rc, rs = rc[:T], rs[:T]
+    recv_codes = rng.integers(0, 0x7F, size=(P, T_pad, hq_l, D), dtype=np.uint8)     # padding rows hold arbitrary finite codes
+    for p in range(P):
+        recv_codes[p, :T] = rc[:, p * hq_l * D:(p + 1) * hq_l * D].reshape(T, hq_l, D)
+    wc, ws = oracle.quantize_rows_e4m3(_bf16(rng, (d_model, K), 0.05), "bf16")
+    want = oracle.unpack_o_proj_fp8(recv_codes, rs, wc, ws, T)
+    tab = np.abs(oracle.e4m3_table())
+    tab[np.isnan(tab)] = 0.0
+    terms = (tab[rc] @ tab[wc].T) * rs.astype(np.float64)[:, None] * ws.astype(np.float64)[None, :]
+    out = torch.empty((T, d_model), dtype=torch.bfloat16, device=G.DEV)
+    out.view(torch.uint8).fill_(0x55)
+    B.unpack_o_proj_fp8(_dev_u8(G, recv_codes), _dev_f32(G, rs), _dev_u8(G, wc), _dev_f32(G, ws), out)
+    torch.cuda.synchronize()
+    _check(B.to_host(out), want, terms)
+
+
+def test_quantise_then_project_stays_close_to_the_bf16_projection(oracle, G):
+    """End to end on the GPU: quantiser + FP8 projection against the oracle's unquantised projection of the same bf16
+    inputs; E4M3 keeps 4 significant bits per operand, so a sum of K products is off by about 2^-4.5 of its root-sum-square."""
+    import torch
+    from paper_2509_16495_amd import binding as B
+    rng = np.random.Generator(np.random.PCG64(305))
+    P, h, h_kv, D, d_model, T = 8, 32, 8, 128, 1024, 200
+    x, w = _bf16(rng, (T, d_model)), _bf16(rng, ((h + 2 * h_kv) * D, d_model), 0.03)
+    xd, wd = G.t(x, "bf16"), G.t(w, "bf16")
+    xq, xs = torch.empty((T, d_model), dtype=torch.uint8, device=G.DEV), torch.empty(T, dtype=torch.float32, device=G.DEV)
+    wq, ws = torch.empty(w.shape, dtype=torch.uint8, device=G.DEV), torch.empty(w.shape[0], dtype=torch.float32, device=G.DEV)
+    B.quantize_rows_fp8(xd, xq, xs)
+    B.quantize_rows_fp8(wd, wq, ws)
+    send = torch.empty((P, T, h // P + 2, D), dtype=torch.bfloat16, device=G.DEV)
+    B.qkv_proj_pack_fp8(xq, xs, wq, ws, send, P, h, h_kv)
+    torch.cuda.synchronize()
+    got = W.to_f64(B.to_host(send), "bf16")
+    want = oracle.qkv_proj_pack(x, w, P, h, h_kv, D, T, "bf16")
+    rel = np.sqrt(np.mean((got - want) ** 2)) / np.sqrt(np.mean(want ** 2))
+    assert rel < 0.06, rel
