@@ -338,7 +338,36 @@ def main() -> int:
                                        "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": traffic.get(nm + "_70b")}}
             log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%} of bf16 MFMA peak); "
                 f"library GEMM + separate layout kernel {ms_ref * 1e3:.1f} us")
-        del xe, wq, wo, send3, recv3, eo, qkv_plain, att_plain
+        # the same two products with FP8 E4M3 operands: activations quantised per token on the fly, weights once
+        PEAK_FP8_TFLOPS = 5000.0
+        xq, xsc = torch.empty(xe.shape, dtype=torch.uint8, device=dev), torch.empty(x3.T, dtype=torch.float32, device=dev)
+        wq8, wsc = torch.empty(wq.shape, dtype=torch.uint8, device=dev), torch.empty(wq.shape[0], dtype=torch.float32, device=dev)
+        rq, rsc = torch.empty(recv3.shape, dtype=torch.uint8, device=dev), torch.empty(x3.T, dtype=torch.float32, device=dev)
+        wo8, wosc = torch.empty(wo.shape, dtype=torch.uint8, device=dev), torch.empty(wo.shape[0], dtype=torch.float32, device=dev)
+        B.quantize_rows_fp8(wq, wq8, wsc)
+        B.quantize_rows_fp8(wo, wo8, wosc)
+        B.quantize_rows_fp8(xe, xq, xsc)
+        B.quantize_recv_fp8(recv3, rq, rsc)
+        for nm, fn, qfn, fl in (("qkv_proj_pack_fp8", lambda: B.qkv_proj_pack_fp8(xq, xsc, wq8, wsc, send3, x3.P, h3, hkv3),
+                                 lambda: B.quantize_rows_fp8(xe, xq, xsc), 2.0 * x3.T * d_model * (h3 + 2 * hkv3) * D),
+                                ("unpack_o_proj_fp8", lambda: B.unpack_o_proj_fp8(rq, rsc, wo8, wosc, eo),
+                                 lambda: B.quantize_recv_fp8(recv3, rq, rsc), 2.0 * x3.T * d_model * h3 * D)):
+            ms = time_events(fn, reps)
+            ms_q = time_events(qfn, reps)
+            tf = fl / (ms * 1e-3) / 1e12
+            q_bytes = 3.0 * x3.T * d_model if nm.startswith("qkv") else 3.0 * x3.T * h3 * D    # 2 bytes read, 1 written per element
+            result[nm] = {"workload": result[nm[:-4]]["workload"] + "; operands as FP8 E4M3 codes with per-row scales, bf16 result",
+                          "flops": fl, "ms": round(ms, 5),
+                          "activation_quantiser": {"ms": round(ms_q, 5), "bytes": q_bytes,
+                                                   "roofline": {"kernel": "quantize_rows_fp8_kernel", "bound": "hbm",
+                                                                "achieved": round(q_bytes / (ms_q * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBPS,
+                                                                "unit": "GB/s", "frac": round(q_bytes / (ms_q * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
+                                                                "traffic": None}},
+                          "roofline": {"kernel": "proj_gemm_kernel<fp8>", "bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_FP8_TFLOPS,
+                                       "unit": "TFLOP/s", "frac": round(tf / PEAK_FP8_TFLOPS, 4), "traffic": traffic.get(nm + "_70b")}}
+            log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_FP8_TFLOPS:.1%} of the fp8 MFMA peak); "
+                f"quantising the activations {ms_q * 1e3:.1f} us ({q_bytes / (ms_q * 1e-3) / 1e9:.0f} GB/s)")
+        del xe, wq, wo, send3, recv3, eo, qkv_plain, att_plain, xq, xsc, wq8, wsc, rq, rsc, wo8, wosc
         # 70B-shaped prefill (configs[2])
         c3 = W.config3_attn()
         cache3 = torch.zeros((c3.num_blocks, 1, 2, 16 * D), dtype=bf, device=dev)

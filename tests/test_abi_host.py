@@ -211,3 +211,39 @@ def test_projection_entry_points_reject_bad_arguments(B):
     # empty problems are valid no-ops and touch nothing
     assert q(None, None, None, 0, 0, 8192, ctypes.byref(x), None) == B.OK
     assert o(None, None, None, 0, 8, 8192, ctypes.byref(xo), None) == B.OK
+
+
+def test_fp8_projection_entry_points_reject_bad_arguments(B):
+    """Row quantiser and the projections over FP8 E4M3 codes: every case fails validation before anything is launched."""
+    L = B.lib()
+    ok = dict(P=8, num_q_heads=64, num_kv_heads=8, head_dim=128, dtype=B.BF16)
+    x, xo = _xchg(B, **ok), _xchg(B, **{**ok, "num_kv_heads": 0})
+    qr, qv, q8, o8 = L.shiftattn_quantize_rows_fp8, L.shiftattn_quantize_recv_fp8, L.shiftattn_qkv_proj_pack_fp8, L.shiftattn_unpack_o_proj_fp8
+    assert qr(FAKE, FAKE, FAKE, -1, 64, None) == B.EINVAL and qr(FAKE, FAKE, FAKE, 4, 0, None) == B.EINVAL
+    assert qr(FAKE, FAKE, FAKE, 4, 12, None) == B.EUNSUPPORTED                 # cols no multiple of 8
+    assert qr(None, FAKE, FAKE, 4, 64, None) == B.EINVAL and qr(FAKE, None, FAKE, 4, 64, None) == B.EINVAL
+    assert qr(FAKE, FAKE, None, 4, 64, None) == B.EINVAL
+    assert qr(ctypes.c_void_p(0x1008), FAKE, FAKE, 4, 64, None) == B.EINVAL    # x not 16-byte aligned
+    assert qr(FAKE, FAKE, ctypes.c_void_p(0x1002), 4, 64, None) == B.EINVAL    # scales not 4-byte aligned
+    assert qr(None, None, None, 0, 64, None) == B.OK
+    assert qv(FAKE, FAKE, FAKE, 9, 8, ctypes.byref(xo), None) == B.EINVAL      # T > T_pad
+    assert qv(FAKE, FAKE, FAKE, 8, 8, ctypes.byref(_xchg(B, **{**ok, "dtype": B.F32, "num_kv_heads": 0})), None) == B.EUNSUPPORTED
+    assert qv(FAKE, FAKE, FAKE, 8, 8, None, None) == B.EINVAL and qv(None, FAKE, FAKE, 8, 8, ctypes.byref(xo), None) == B.EINVAL
+    assert qv(None, None, None, 0, 8, ctypes.byref(xo), None) == B.OK
+    for kw, d_model in [(dict(dtype=B.F32), 8192), (dict(head_dim=64), 8192), (dict(), 8200), (dict(num_q_heads=9, num_kv_heads=1, P=1), 8192)]:
+        bad = _xchg(B, **{**ok, **kw})
+        assert q8(FAKE, FAKE, FAKE, FAKE, FAKE, 8, 8, d_model, ctypes.byref(bad), None) == B.EUNSUPPORTED, (kw, d_model)
+    assert o8(FAKE, FAKE, FAKE, FAKE, FAKE, 8, 8, 8192 + 64, ctypes.byref(xo), None) == B.EUNSUPPORTED
+    for fn, desc in ((q8, x), (o8, xo)):
+        assert fn(FAKE, FAKE, FAKE, FAKE, FAKE, 9, 8, 8192, ctypes.byref(desc), None) == B.EINVAL
+        assert fn(FAKE, FAKE, FAKE, FAKE, FAKE, 8, 8, 0, ctypes.byref(desc), None) == B.EINVAL
+        assert fn(FAKE, FAKE, FAKE, FAKE, FAKE, 8, 8, 8192, None, None) == B.EINVAL
+        for hole in range(5):
+            args = [FAKE] * 5
+            args[hole] = None
+            assert fn(*args, 8, 8, 8192, ctypes.byref(desc), None) == B.EINVAL, hole
+        assert fn(FAKE, ctypes.c_void_p(0x1002), FAKE, FAKE, FAKE, 8, 8, 8192, ctypes.byref(desc), None) == B.EINVAL
+        assert fn(ctypes.c_void_p(0x1008), FAKE, FAKE, FAKE, FAKE, 8, 8, 8192, ctypes.byref(desc), None) == B.EINVAL
+        assert B.last_error()
+    assert q8(None, None, None, None, None, 0, 0, 8192, ctypes.byref(x), None) == B.OK
+    assert o8(None, None, None, None, None, 0, 8, 8192, ctypes.byref(xo), None) == B.OK
