@@ -12,6 +12,12 @@
  *   shiftattn_mixed             a unified batch of chunks and decode rows in one call
  *   shiftattn_unpack_head2seq   receive side of the head->sequence all-to-all (SP mode only)
  *
+ * and, next to the exchange, the two projections fused with its layouts (bf16, or FP8 E4M3 operands):
+ *
+ *   shiftattn_qkv_proj_pack[_fp8]   qkv = x * W_qkv^T written straight into the send buffers
+ *   shiftattn_unpack_o_proj[_fp8]   embed = unpack(recv) * W_o^T read in place from the receive buffers
+ *   shiftattn_quantize_rows_fp8 / shiftattn_quantize_recv_fp8   per-row FP8 quantisation for the above
+ *
  * In TP mode (the shift configuration, SP=1) a rank calls only kv_write/prefill/decode on the
  * fused rows its own QKV projection produced; in SP mode it packs, exchanges, attends,
  * exchanges, unpacks.  Both modes drive the same attention kernels over the same cache: that
