@@ -167,19 +167,14 @@ __global__ __launch_bounds__(kThreads) void kv_write_block_kernel(const uint16_t
             return x;
         }
     };
-    while (starts) {   // uniform
-        const int t0 = __builtin_ctz(starts);
-        starts &= starts - 1;
-        const int64_t i0 = w0 + t0;
-        const int64_t slot0 = slots[i0];
+    auto run_length = [&](int64_t i0, int64_t slot0) -> int {   // tokens from i0 on that continue slot0 inside its block
+        const int64_t i = i0 + lane16;
+        const bool cont = static_cast<int>(slot0 % kBlockSize) + lane16 < kBlockSize && i < n_tokens && slots[i] == slot0 + lane16;
+        const uint32_t m = static_cast<uint32_t>(__builtin_amdgcn_ballot_w64(cont)) & 0xFFFFu;
+        return __builtin_ctz(~m);
+    };
+    auto write_run = [&](int64_t i0, int64_t slot0, int len) {   // tokens i0 .. i0 + len - 1 into slots slot0 .. of one block
         const int off = static_cast<int>(slot0 % kBlockSize);
-        int len;   // tokens of the run
-        {
-            const int64_t i = i0 + lane16;
-            const bool cont = off + lane16 < kBlockSize && i < n_tokens && slots[i] == slot0 + lane16;
-            const uint32_t m = static_cast<uint32_t>(__builtin_amdgcn_ballot_w64(cont)) & 0xFFFFu;
-            len = __builtin_ctz(~m);   // bit 0 is always set: at least the starting token itself
-        }
         const int64_t blk = slot0 / kBlockSize;
         if (t_loc < len) {
             const size_t src = static_cast<size_t>(i0 + t_loc) * kv_stride + static_cast<size_t>(g) * D + dv * 8;
@@ -204,7 +199,49 @@ __global__ __launch_bounds__(kThreads) void kv_write_block_kernel(const uint16_t
         } else {
             for (int j = lo; j < hi; ++j) vrow[j] = tile[(8 * h + j - off) * kPitch + d];
         }
-        if (starts) __syncthreads();   // the next run reuses the tile
+    };
+    if (__builtin_popcount(starts) <= 2) {   // the usual windows: inside a sequence, or across the end of one
+        while (starts) {   // uniform
+            const int t0 = __builtin_ctz(starts);
+            starts &= starts - 1;
+            const int64_t i0 = w0 + t0;
+            const int64_t slot0 = slots[i0];
+            write_run(i0, slot0, run_length(i0, slot0));
+            if (starts) __syncthreads();   // the next run reuses the tile
+        }
+        return;
+    }
+    // Many short runs (decode tokens, rows between padding): every token of the window from the first start on belongs
+    // to a run that starts here, so they are all loaded at once and scattered token by token; what the last run has
+    // beyond the window follows as one run.
+    __shared__ int64_t slot_s[kBlockSize];
+    const int t_first = __builtin_ctz(starts), t_last = 31 - __builtin_clz(starts);
+    {
+        const int64_t i = w0 + t_loc;
+        const int64_t slot = t_loc >= t_first && i < n_tokens ? slots[i] : -1;
+        if (slot >= 0) {
+            const size_t src = static_cast<size_t>(i) * kv_stride + static_cast<size_t>(g) * D + dv * 8;
+            const u32x4 kvec = *reinterpret_cast<const u32x4*>(k_new + src);
+            const u32x4 vvec = *reinterpret_cast<const u32x4*>(v_new + src);
+            *reinterpret_cast<Piece*>(cache + cache_part_offset(slot / kBlockSize, g, 0, hkv_l, D) +
+                                      static_cast<size_t>(slot % kBlockSize) * D + dv * 8) = encode(kvec, k_scale);
+            *reinterpret_cast<Piece*>(tile + t_loc * kPitch + dv * 8) = encode(vvec, v_scale);
+        }
+        if (dv == 0) slot_s[t_loc] = slot;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {   // lanes run over the tokens of a head-dim row first
+        const int item = r * kThreads + threadIdx.x, dd = item >> 4, t = item & 15;
+        const int64_t sl = slot_s[t];
+        if (sl >= 0)
+            cache[cache_part_offset(sl / kBlockSize, g, 1, hkv_l, D) + static_cast<size_t>(dd) * kBlockSize + sl % kBlockSize] = tile[t * kPitch + dd];
+    }
+    const int64_t i_last = w0 + t_last, slot_last = slots[i_last];
+    const int beyond = t_last + run_length(i_last, slot_last) - kBlockSize;   // tokens of the last run past the window
+    if (beyond > 0) {
+        __syncthreads();
+        write_run(w0 + kBlockSize, slot_last + (kBlockSize - t_last), beyond);
     }
 }
 
