@@ -165,3 +165,75 @@ def test_quantise_then_project_stays_close_to_the_bf16_projection(oracle, G):
     want = oracle.qkv_proj_pack(x, w, P, h, h_kv, D, T, "bf16")
     rel = np.sqrt(np.mean((got - want) ** 2)) / np.sqrt(np.mean(want ** 2))
     assert rel < 0.06, rel
+
+
+def test_full_size_70b_fp8_projections_on_sampled_rows(oracle, G):
+    """The shapes the benchmark times (16384 tokens, d_model 8192, 64 + 2 x 8 heads, 8 buffers), quantised on the GPU:
+    codes and scales of sampled token rows and weight rows bit-exact against the oracle's quantiser, and the outputs of
+    those tokens for those features against the oracle's FP8 projection of its own codes."""
+    import torch
+    from paper_2509_16495_amd import binding as B
+    rng = np.random.Generator(np.random.PCG64(306))
+    P, h, h_kv, D, d_model, T = 8, 64, 8, 128, 8192, 16384
+    hq_l, hkv_l = h // P, h_kv // P
+    tokens = np.unique(np.concatenate([[0, 1, 127, 128, 255, 256, 257, 8191, 8192, 16127, 16128, 16383], rng.integers(0, T, 8)]))
+    heads = [0, 1, 13, 63, h, h + 7, h + h_kv, h + 2 * h_kv - 1]       # q heads, first / last k head, first / last v head
+    feats = np.concatenate([np.arange(j * D, (j + 1) * D) for j in heads])
+    tok_d, feat_d = torch.from_numpy(tokens).to(G.DEV), torch.from_numpy(feats).to(G.DEV)
+    tab = oracle.e4m3_table()
+    atab = np.abs(tab)
+    atab[np.isnan(atab)] = 0.0
+    x, w = _bf16(rng, (T, d_model)), _bf16(rng, ((h + 2 * h_kv) * D, d_model), 0.02)
+    xd, wd = G.t(x, "bf16"), G.t(w, "bf16")
+    xq, xs = torch.empty(x.shape, dtype=torch.uint8, device=G.DEV), torch.empty(T, dtype=torch.float32, device=G.DEV)
+    wq, ws = torch.empty(w.shape, dtype=torch.uint8, device=G.DEV), torch.empty(w.shape[0], dtype=torch.float32, device=G.DEV)
+    B.quantize_rows_fp8(xd, xq, xs)
+    B.quantize_rows_fp8(wd, wq, ws)
+    send = torch.empty((P, T, hq_l + 2 * hkv_l, D), dtype=torch.bfloat16, device=G.DEV)
+    send.view(torch.uint8).fill_(0x55)
+    B.qkv_proj_pack_fp8(xq, xs, wq, ws, send, P, h, h_kv)
+    torch.cuda.synchronize()
+    xc_want, xs_want = oracle.quantize_rows_e4m3(x[tokens], "bf16")
+    wc_want, ws_want = oracle.quantize_rows_e4m3(w[feats], "bf16")
+    assert np.array_equal(xq[tok_d].cpu().numpy(), xc_want) and np.array_equal(xs[tok_d].cpu().numpy(), xs_want)
+    assert np.array_equal(wq[feat_d].cpu().numpy(), wc_want) and np.array_equal(ws[feat_d].cpu().numpy(), ws_want)
+    # the oracle on the sampled rows as a problem of its own (one buffer, the sampled heads as query heads): plain y[t][head][D]
+    want = oracle.qkv_proj_pack_fp8(xc_want, xs_want, wc_want, ws_want, 1, len(heads), 0, D, len(tokens))[0]
+    terms = ((atab[xc_want] @ atab[wc_want].T) * xs_want.astype(np.float64)[:, None] * ws_want.astype(np.float64)[None, :]).reshape(want.shape)
+    got_all = B.to_host(send[:, tok_d].contiguous())                  # [P, tokens, hq_l + 2 hkv_l, D]
+    got = np.empty((len(tokens), len(heads), D), dtype=got_all.dtype)
+    for i, j in enumerate(heads):                                      # where the exchange layout puts head j (Sec. 3.2.1)
+        if j < h:
+            got[:, i] = got_all[j // hq_l, :, j % hq_l]
+        elif j < h + h_kv:
+            g = j - h
+            got[:, i] = got_all[g // hkv_l, :, hq_l + g % hkv_l]
+        else:
+            g = j - h - h_kv
+            got[:, i] = got_all[g // hkv_l, :, hq_l + hkv_l + g % hkv_l]
+    _check(got, want, terms)
+    del send, xd, wd, xq, wq, x, w
+    # output projection: quantised out of the receive buffers; sampled output features
+    recv, w_o = _bf16(rng, (P, T, hq_l, D)), _bf16(rng, (d_model, h * D), 0.02)
+    cols = np.unique(np.concatenate([[0, 1, 127, 128, 255, 256, 4095, 4096, 8191], rng.integers(0, d_model, 200)]))
+    col_d = torch.from_numpy(cols).to(G.DEV)
+    rd, wod = G.t(recv, "bf16"), G.t(w_o, "bf16")
+    rq, rs = torch.empty(recv.shape, dtype=torch.uint8, device=G.DEV), torch.empty(T, dtype=torch.float32, device=G.DEV)
+    woq, wos = torch.empty(w_o.shape, dtype=torch.uint8, device=G.DEV), torch.empty(d_model, dtype=torch.float32, device=G.DEV)
+    B.quantize_recv_fp8(rd, rq, rs)
+    B.quantize_rows_fp8(wod, woq, wos)
+    out = torch.empty((T, d_model), dtype=torch.bfloat16, device=G.DEV)
+    out.view(torch.uint8).fill_(0x55)
+    B.unpack_o_proj_fp8(rq, rs, woq, wos, out)
+    torch.cuda.synchronize()
+    rows = oracle.recv_rows(np.ascontiguousarray(recv[:, tokens]), len(tokens))
+    rc_want, rs_want = oracle.quantize_rows_e4m3(rows, "bf16")
+    woc_want, wos_want = oracle.quantize_rows_e4m3(w_o[cols], "bf16")
+    assert np.array_equal(oracle.recv_rows(rq[:, tok_d].cpu().numpy(), len(tokens)), rc_want) and np.array_equal(rs[tok_d].cpu().numpy(), rs_want)
+    assert np.array_equal(woq[col_d].cpu().numpy(), woc_want) and np.array_equal(wos[col_d].cpu().numpy(), wos_want)
+    recv_codes = np.zeros((P, len(tokens), hq_l, D), dtype=np.uint8)
+    for p in range(P):
+        recv_codes[p] = rc_want[:, p * hq_l * D:(p + 1) * hq_l * D].reshape(len(tokens), hq_l, D)
+    want_o = oracle.unpack_o_proj_fp8(recv_codes, rs_want, woc_want, wos_want, len(tokens))
+    terms_o = (atab[rc_want] @ atab[woc_want].T) * rs_want.astype(np.float64)[:, None] * wos_want.astype(np.float64)[None, :]
+    _check(B.to_host(out[tok_d][:, col_d].contiguous()), want_o, terms_o)
