@@ -135,6 +135,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
 
     // ---- LDS addressing ---------------------------------------------------------------------------------
     unsigned char* gbase = lds + grp * kGroupBytes;  // this group's two stages
+    // where this wavefront's direct-to-LDS loads land, as a scalar: the destination of such a load goes through M0,
+    // and a per-lane copy of a wavefront-uniform value would cost vector ALU instructions at every load
+    unsigned char* ld_base = lds + __builtin_amdgcn_readfirstlane(grp * kGroupBytes + wg * kBlockBytes);
     // K operand of MFMA row l32 is K row tau (bits 2 and 3 swapped); piece c of row r sits at c ^ (r & 15)
     const int tau = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
     int k_rd[8];
@@ -220,13 +223,13 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
         };
         int id0 = 0, id1 = 0, id2 = 0;  // ids of tiles j, j+1, j+2 at the top of iteration j (uniform)
         auto load_k = [&](const unsigned char* src, int stage) SHIFTATTN_INLINE {
-            unsigned char* dst = gbase + stage * kStageBytes + wg * kBlockBytes;
+            unsigned char* dst = ld_base + stage * kStageBytes;
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 __builtin_amdgcn_global_load_lds((glb_ptr)(src + k_ld[j]), (lds_ptr)(dst + j * 1024), 16, 0, 0);
         };
         auto load_v = [&](const unsigned char* src, int stage) SHIFTATTN_INLINE {
-            unsigned char* dst = gbase + stage * kStageBytes + kKBytes + wg * kBlockBytes;
+            unsigned char* dst = ld_base + stage * kStageBytes + kKBytes;
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 __builtin_amdgcn_global_load_lds((glb_ptr)(src + v_ld + j * 1024), (lds_ptr)(dst + j * 1024), 16, 0, 0);
