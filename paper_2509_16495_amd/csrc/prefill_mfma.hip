@@ -222,17 +222,38 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
             return cache_g + static_cast<int64_t>(id) * blk_bytes;
         };
         int id0 = 0, id1 = 0, id2 = 0;  // ids of tiles j, j+1, j+2 at the top of iteration j (uniform)
-        auto load_k = [&](const unsigned char* src, int stage) SHIFTATTN_INLINE {
+        // 1 KiB from src (wavefront-uniform, in scalar registers) + a 32-bit byte offset per lane + kImm into LDS at dst + kImm
+        // (dst uniform): written as assembly so that the address is formed by the load itself (scalar base + vector offset)
+        // instead of a 64-bit vector addition per load, which would cost MFMA issue time like any vector instruction.
+        // The loads are waited for with explicit vmcnt(0) waits (wait_vm0) only.
+        auto dma_1k = [&](const unsigned char* src, uint32_t lane_off, auto imm_c, unsigned char* dst) SHIFTATTN_INLINE {
+            constexpr int kImm = decltype(imm_c)::value;
+            const uint32_t m0v = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(dst));
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3"
+                         :: "s"(m0v), "v"(lane_off), "s"(src), "n"(kImm) : "memory");
+        };
+        // the base must sit in scalar registers for the assembly above: said explicitly (it is wavefront-uniform, but the
+        // register allocator may keep a uniform pointer in vector registers)
+        auto scalar_ptr = [](const unsigned char* ptr) SHIFTATTN_INLINE -> const unsigned char* {
+            const uint64_t a = reinterpret_cast<uint64_t>(ptr);
+            const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
+            const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
+            return reinterpret_cast<const unsigned char*>((static_cast<uint64_t>(hi) << 32) | lo);
+        };
+        auto load_k = [&](const unsigned char* src_any, int stage) SHIFTATTN_INLINE {
+            const unsigned char* src = scalar_ptr(src_any);
             unsigned char* dst = ld_base + stage * kStageBytes;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                __builtin_amdgcn_global_load_lds((glb_ptr)(src + k_ld[j]), (lds_ptr)(dst + j * 1024), 16, 0, 0);
+            for (int j = 0; j < 4; ++j) dma_1k(src, static_cast<uint32_t>(k_ld[j]), IC<0>{}, dst + j * 1024);
         };
-        auto load_v = [&](const unsigned char* src, int stage) SHIFTATTN_INLINE {
+        auto load_v = [&](const unsigned char* src_any, int stage) SHIFTATTN_INLINE {
+            const unsigned char* src = scalar_ptr(src_any);
             unsigned char* dst = ld_base + stage * kStageBytes + kKBytes;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                __builtin_amdgcn_global_load_lds((glb_ptr)(src + v_ld + j * 1024), (lds_ptr)(dst + j * 1024), 16, 0, 0);
+            // the instruction's immediate offset moves the LDS destination along with the source
+            dma_1k(src, static_cast<uint32_t>(v_ld), IC<0>{}, dst);
+            dma_1k(src, static_cast<uint32_t>(v_ld), IC<1024>{}, dst);
+            dma_1k(src, static_cast<uint32_t>(v_ld), IC<2048>{}, dst);
+            dma_1k(src, static_cast<uint32_t>(v_ld), IC<3072>{}, dst);
         };
         // zero the V^T entries of keys at or past the context in the given stage (tile kt)
         auto clear_ragged_v = [&](int kt, int stage) SHIFTATTN_INLINE {
