@@ -110,10 +110,24 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     const int seg_tiles = static_cast<int>(seg_bytes / kRowBytes);
     const size_t seg_jump = p.mode == 0 ? 0 : static_cast<size_t>(p.s.T_pad - 1) * seg_bytes;
     int ld_kt = 0, ld_left = seg_tiles;   // next tile to load, and how many tiles remain in its segment
+    // 1 KiB from a wavefront-uniform base (scalar registers) + a 32-bit byte offset per lane into LDS at dst (uniform):
+    // written as assembly so that the load forms the address itself instead of a 64-bit vector addition in front of it.
+    // These loads are waited for with the explicit vmcnt waits below only.
+    auto scalar_ptr = [](const unsigned char* ptr) -> const unsigned char* {
+        const uint64_t a = reinterpret_cast<uint64_t>(ptr);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
+        const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
+        return reinterpret_cast<const unsigned char*>((static_cast<uint64_t>(hi) << 32) | lo);
+    };
+    auto dma_1k = [&](const unsigned char* base, uint32_t lane_off, unsigned char* dst) {
+        const uint32_t m0v = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(dst));
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :: "s"(m0v), "v"(lane_off), "s"(scalar_ptr(base)) : "memory");
+    };
     auto load_one = [&](int j) {          // first the weight rows, then the token rows
         unsigned char* dst = lds + (ld_kt % kStages) * kStage + (kLoadRows * wave_s) * kRowBytes;
-        if (j < kLoadsPerOperand) __builtin_amdgcn_global_load_lds((glb_ptr)(w_tile + w_off[j]), (lds_ptr)(dst + j * 1024), 16, 0, 0);
-        else __builtin_amdgcn_global_load_lds((glb_ptr)(x_tile + x_off[j - kLoadsPerOperand]), (lds_ptr)(dst + kOperandBytes + (j - kLoadsPerOperand) * 1024), 16, 0, 0);
+        if (j < kLoadsPerOperand) dma_1k(w_tile, w_off[j], dst + j * 1024);
+        else dma_1k(x_tile, x_off[j - kLoadsPerOperand], dst + kOperandBytes + (j - kLoadsPerOperand) * 1024);
     };
     auto load_advance = [&]() {
         ++ld_kt;
