@@ -138,6 +138,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
     // where this wavefront's direct-to-LDS loads land, as a scalar: the destination of such a load goes through M0,
     // and a per-lane copy of a wavefront-uniform value would cost vector ALU instructions at every load
     unsigned char* ld_base = lds + __builtin_amdgcn_readfirstlane(grp * kGroupBytes + wg * kBlockBytes);
+    const int grp_u = __builtin_amdgcn_readfirstlane(grp), wg_u = __builtin_amdgcn_readfirstlane(wg);
     // K operand of MFMA row l32 is K row tau (bits 2 and 3 swapped); piece c of row r sits at c ^ (r & 15)
     const int tau = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
     int k_rd[8];
@@ -156,7 +157,16 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
     }
     const int v_ld = kBlockBytes + (lane >> 1) * 32 + (((lane & 1) ^ ((lane >> 4) & 1)) << 4);
     const size_t blk_bytes = static_cast<size_t>(p.hkv_l) * 2 * kBlockBytes;
-    const unsigned char* cache_g = reinterpret_cast<const unsigned char*>(p.cache) + static_cast<size_t>(g) * 2 * kBlockBytes;
+    // uniform values that the register allocator would otherwise keep in vector registers are pinned to scalar ones:
+    // arithmetic on them then costs no vector instruction (each of which costs MFMA issue time in the key loop)
+    auto uniform_ptr = [](const unsigned char* ptr) SHIFTATTN_INLINE -> const unsigned char* {
+        const uint64_t a = reinterpret_cast<uint64_t>(ptr);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
+        const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
+        return reinterpret_cast<const unsigned char*>((static_cast<uint64_t>(hi) << 32) | lo);
+    };
+    const unsigned char* cache_g =
+        uniform_ptr(reinterpret_cast<const unsigned char*>(p.cache) + static_cast<size_t>(g) * 2 * kBlockBytes);
 
     typedef __attribute__((address_space(3))) void* lds_ptr;
     typedef const __attribute__((address_space(1))) void* glb_ptr;
@@ -186,7 +196,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
             }
         }
         const int w_tok_first = tok0 + ((wg * 32) >> p.gs_log2);
-        const int w_pos_min = w_tok_first < q_len ? ctx - q_len + w_tok_first : -1;
+        const int w_pos_min = __builtin_amdgcn_readfirstlane(w_tok_first < q_len ? ctx - q_len + w_tok_first : -1);
 
         // ---- key tiles of this (column tile, split), dealt alternately to the two groups ------------------
         const int tile_pos_max = ctx - q_len + min(tok0 + tile_tokens, q_len) - 1;
@@ -211,12 +221,24 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
         uint32_t pw[2][4][4];
         float m_used = -INFINITY, l_run = 0.f, alpha_pending = 1.f;
 
-        auto kt_of = [&](int j) SHIFTATTN_INLINE { return kt_begin + grp + 2 * j; };
+        auto kt_of = [&](int j) SHIFTATTN_INLINE { return kt_begin + grp_u + 2 * j; };
         // Cache block `wg` of the group's tile j.  Ids are fetched three tiles ahead and waited for a
         // whole iteration later: loads return in order, so a wait right behind the direct-to-LDS loads
         // (or right after the barrier) would stall for a full memory round trip every iteration.
+        const int n_u = __builtin_amdgcn_readfirstlane(n);
+        const int32_t* table_u = reinterpret_cast<const int32_t*>(uniform_ptr(reinterpret_cast<const unsigned char*>(table)));
         auto fetch_id = [&](int j) SHIFTATTN_INLINE -> int {
-            return table[min((kt_begin + grp + 2 * min(j, max(n - 1, 0))) * 4 + wg, last_block)];
+            // every term of the address is uniform and in scalar registers: the id is read with a scalar load (written as
+            // assembly: the compiler takes the vector path for a table it cannot prove unwritten) and arrives in a
+            // scalar register without a vector instruction.  It may be used only behind id_arrived().
+            const int idx = min((kt_begin + grp_u + 2 * min(j, max(n_u - 1, 0))) * 4 + wg_u, last_block);
+            int v;
+            const unsigned char* addr = uniform_ptr(reinterpret_cast<const unsigned char*>(table_u + idx));
+            asm volatile("s_load_dword %0, %1, 0x0" : "=s"(v) : "s"(addr) : "memory");
+            return v;
+        };
+        auto id_arrived = [](int& a) SHIFTATTN_INLINE {   // scalar loads return through lgkmcnt
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(a) : : "memory");
         };
         auto block_base = [&](int id) SHIFTATTN_INLINE -> const unsigned char* {
             return cache_g + static_cast<int64_t>(id) * blk_bytes;
@@ -299,7 +321,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
 
             __syncthreads();
             // fill stage PAR for the next iteration: K of tile j+2, V^T of tile j
-            const int id3_v = fetch_id(j + 3);  // consumed at the bottom of this iteration
+            int id3_v = fetch_id(j + 3);  // consumed at the bottom of this iteration
             if (j + 2 < n) load_k(block_base(id2), PAR);
             load_v(block_base(id0), PAR);
             if (HAS_C) apply_pending();
@@ -324,7 +346,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
                     mx = fmaxf(fmaxf(mx, s_cur[sub][r + 2]), s_cur[sub][r + 3]);
                 } else if constexpr (c == 8) {
                     const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-                    mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                    // one v_max_f32: through fmaxf the two swapped halves would each be canonicalised first
+                    asm("v_max_f32 %0, %1, %2" : "=v"(mx) : "v"(__uint_as_float(sw[0])), "v"(__uint_as_float(sw[1])));
                     const bool grow = mx > m_used + thr;
                     const float m_new = grow ? mx : m_used;
                     alpha = grow ? __builtin_amdgcn_exp2f((m_used - m_new) * p.c) : 1.f;
@@ -406,17 +429,21 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
             wait_vm0();  // this wavefront's loads have landed before it reaches the next barrier
             id0 = id1;
             id1 = id2;
-            id2 = __builtin_amdgcn_readfirstlane(id3_v);
+            id_arrived(id3_v);
+            id2 = id3_v;
         };
 
         int barriers = 0;  // barriers this group executes in the pass; both groups must end up equal
         if (n > 0) {
             // prologue: K of the first two tiles, S^T of the first
             {
-                const int a0 = fetch_id(0), a1 = fetch_id(1), a2 = fetch_id(2);
-                id0 = __builtin_amdgcn_readfirstlane(a0);
-                id1 = __builtin_amdgcn_readfirstlane(a1);
-                id2 = __builtin_amdgcn_readfirstlane(a2);
+                int a0 = fetch_id(0), a1 = fetch_id(1), a2 = fetch_id(2);
+                id_arrived(a0);
+                id_arrived(a1);
+                id_arrived(a2);
+                id0 = a0;
+                id1 = a1;
+                id2 = a2;
                 load_k(block_base(id0), 0);
                 if (n > 1) load_k(block_base(id1), 1);
             }
