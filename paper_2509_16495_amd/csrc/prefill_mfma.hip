@@ -319,7 +319,24 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
             const int kt = kt_of(j);
             const int key0 = kt * kKvTile;
 
+            constexpr int NOPS = (HAS_A ? 16 : 0) + (HAS_C ? 16 : 0);
+            auto op_read = [&](auto tc) SHIFTATTN_INLINE -> u32x4 {
+                constexpr int t = decltype(tc)::value;
+                constexpr bool is_a = HAS_A && (!HAS_C || (t % 2 == 0));
+                constexpr int o = (HAS_A && HAS_C) ? t / 2 : t;
+                if constexpr (is_a)
+                    return *reinterpret_cast<const u32x4*>(gbase + RD * kStageBytes + (o / 8) * 8192 + k_rd[o % 8]);
+                else
+                    return *reinterpret_cast<const u32x4*>(gbase + RD * kStageBytes + v_rd + (o / 4) * kBlockBytes + (o % 4) * 1024);
+            };
             __syncthreads();
+            // the operands of the first two MFMAs are requested first: their LDS latency passes while the loads below
+            // are issued, instead of holding up the first MFMA behind the barrier
+            u32x4 first0 = {0u, 0u, 0u, 0u}, first1 = first0;
+            if constexpr (NOPS > 0) {
+                first0 = op_read(IC<0>{});
+                first1 = op_read(IC<1>{});
+            }
             // fill stage PAR for the next iteration: K of tile j+2, V^T of tile j
             int id3_v = fetch_id(j + 3);  // consumed at the bottom of this iteration
             if (j + 2 < n) load_k(block_base(id2), PAR);
@@ -336,7 +353,6 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
             }
 
             // ---- interleaved block ------------------------------------------------------------------
-            constexpr int NOPS = (HAS_A ? 16 : 0) + (HAS_C ? 16 : 0);
             float mx = -INFINITY, mc = 0.f, alpha = 1.f, psum = 0.f;
             auto chunk = [&](auto cc) SHIFTATTN_INLINE {
                 constexpr int c = decltype(cc)::value;
@@ -373,15 +389,6 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
                     asm volatile("" : "+v"(l_run));
                 }
             };
-            auto op_read = [&](auto tc) SHIFTATTN_INLINE -> u32x4 {
-                constexpr int t = decltype(tc)::value;
-                constexpr bool is_a = HAS_A && (!HAS_C || (t % 2 == 0));
-                constexpr int o = (HAS_A && HAS_C) ? t / 2 : t;
-                if constexpr (is_a)
-                    return *reinterpret_cast<const u32x4*>(gbase + RD * kStageBytes + (o / 8) * 8192 + k_rd[o % 8]);
-                else
-                    return *reinterpret_cast<const u32x4*>(gbase + RD * kStageBytes + v_rd + (o / 4) * kBlockBytes + (o % 4) * 1024);
-            };
             auto op_mfma = [&](auto tc, u32x4 a) SHIFTATTN_INLINE {
                 constexpr int t = decltype(tc)::value;
                 constexpr bool is_a = HAS_A && (!HAS_C || (t % 2 == 0));
@@ -408,8 +415,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
                 (std::make_integer_sequence<int, 26>{});
             } else {
                 u32x4 opnd[NOPS];
-                opnd[0] = op_read(IC<0>{});
-                opnd[1] = op_read(IC<1>{});
+                opnd[0] = first0;
+                opnd[1] = first1;
                 [&]<int... T>(std::integer_sequence<int, T...>) SHIFTATTN_INLINE {
                     (([&]() SHIFTATTN_INLINE {
                          if constexpr (T + 2 < NOPS) opnd[T + 2] = op_read(IC<T + 2>{});
