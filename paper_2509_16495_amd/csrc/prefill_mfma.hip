@@ -339,8 +339,20 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
             }
             // fill stage PAR for the next iteration: K of tile j+2, V^T of tile j
             int id3_v = fetch_id(j + 3);  // consumed at the bottom of this iteration
-            if (j + 2 < n) load_k(block_base(id2), PAR);
-            load_v(block_base(id0), PAR);
+            // In the steady state the two groups issue their loads at different times - the first group here, the second
+            // behind its sixteenth MFMA: all eight wavefronts issuing at once queue up 64 KiB in the CU's one load path,
+            // and a wavefront stuck at a load issues no MFMA; staggered, the other wavefront of its SIMD (which belongs to
+            // the other group) keeps the pipe busy meanwhile.  Later than the middle of the step the loads would not
+            // land before its end.
+            constexpr bool kStagger = HAS_A && HAS_C;
+            constexpr int kLateSlot = 16;
+            const bool more_k = j + 2 < n;
+            const unsigned char* k_src = block_base(id2);
+            const unsigned char* v_src = block_base(id0);
+            if (!kStagger || grp_u == 0) {
+                if (more_k) load_k(k_src, PAR);
+                load_v(v_src, PAR);
+            }
             if (HAS_C) apply_pending();
             if (key0 + kKvTile - 1 > w_pos_min) {  // tile crosses the diagonal of this wavefront: uniform
 #pragma unroll
@@ -421,6 +433,12 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
                     (([&]() SHIFTATTN_INLINE {
                          if constexpr (T + 2 < NOPS) opnd[T + 2] = op_read(IC<T + 2>{});
                          op_mfma(IC<T>{}, opnd[T]);
+                         if constexpr (kStagger && T == kLateSlot) {
+                             if (grp_u != 0) {
+                                 if (more_k) load_k(k_src, PAR);
+                                 load_v(v_src, PAR);
+                             }
+                         }
                          if constexpr (NOPS == 32) {
                              if constexpr (T < 26) chunk(IC<T>{});
                          } else {
