@@ -141,6 +141,38 @@ bool use_decode_mfma(const AttnShape& s, int num_seqs) {
     return !force_generic() && decode_mfma_supported(s, num_seqs);
 }
 
+// Argument checks of a prefill / decode call that need no launch (shared with the mixed entry point, which must
+// not have written the cache when one of them fails).
+int check_prefill_args(const void* q, const void* kv_cache, const int32_t* block_table, const int32_t* cu_seqlens_q,
+                       const int32_t* seq_lens, int32_t num_seqs, int32_t total_q, int32_t max_q_len, int32_t max_seq_len,
+                       const void* out, const AttnShape& s) {
+    if (num_seqs < 0 || total_q < 0 || max_q_len < 0 || max_seq_len < 0)
+        return fail(SHIFTATTN_EINVAL, "negative size argument");
+    if (max_q_len > total_q || max_q_len > max_seq_len)
+        return fail(SHIFTATTN_EINVAL, "max_q_len = %d exceeds total_q = %d or max_seq_len = %d", max_q_len, total_q,
+                    max_seq_len);
+    if (num_seqs == 0 || total_q == 0) return 0;
+    if (!q || !kv_cache || !block_table || !cu_seqlens_q || !seq_lens || !out)
+        return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(q) || !aligned16(out) || !aligned16(kv_cache))
+        return fail(SHIFTATTN_EINVAL, "q / out / kv_cache must be 16-byte aligned");
+    if (static_cast<int64_t>(s.max_blocks) * kBlockSize < max_seq_len)
+        return fail(SHIFTATTN_EINVAL, "max_blocks_per_seq = %d cannot hold max_seq_len = %d", s.max_blocks, max_seq_len);
+    return 0;
+}
+
+int check_decode_args(const void* q, const void* kv_cache, const int32_t* block_table, const int32_t* seq_lens,
+                      int32_t num_seqs, int32_t max_seq_len, const void* out, const AttnShape& s) {
+    if (num_seqs < 0 || max_seq_len < 0) return fail(SHIFTATTN_EINVAL, "negative size argument");
+    if (num_seqs == 0) return 0;
+    if (!q || !kv_cache || !block_table || !seq_lens || !out) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(q) || !aligned16(out) || !aligned16(kv_cache))
+        return fail(SHIFTATTN_EINVAL, "q / out / kv_cache must be 16-byte aligned");
+    if (static_cast<int64_t>(s.max_blocks) * kBlockSize < max_seq_len)
+        return fail(SHIFTATTN_EINVAL, "max_blocks_per_seq = %d cannot hold max_seq_len = %d", s.max_blocks, max_seq_len);
+    return 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -330,20 +362,12 @@ int shiftattn_prefill(const void* q, const void* k_new, const void* v_new, const
                       void* workspace, size_t workspace_bytes, const shiftattn_attn* a, void* stream) {
     AttnShape s;
     if (int rc = check_attn(a, &s)) return rc;
-    if (num_seqs < 0 || total_q < 0 || max_q_len < 0 || max_seq_len < 0)
-        return fail(SHIFTATTN_EINVAL, "negative size argument");
-    if (max_q_len > total_q || max_q_len > max_seq_len)
-        return fail(SHIFTATTN_EINVAL, "max_q_len = %d exceeds total_q = %d or max_seq_len = %d", max_q_len, total_q,
-                    max_seq_len);
     bool new_kv;
     if (int rc = check_new_kv(k_new, v_new, slot_mapping, &new_kv)) return rc;
+    if (int rc = check_prefill_args(q, kv_cache, block_table, cu_seqlens_q, seq_lens, num_seqs, total_q, max_q_len,
+                                    max_seq_len, out, s))
+        return rc;
     if (num_seqs == 0 || total_q == 0) return SHIFTATTN_OK;
-    if (!q || !kv_cache || !block_table || !cu_seqlens_q || !seq_lens || !out)
-        return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
-    if (!aligned16(q) || !aligned16(out) || !aligned16(kv_cache))
-        return fail(SHIFTATTN_EINVAL, "q / out / kv_cache must be 16-byte aligned");
-    if (static_cast<int64_t>(s.max_blocks) * kBlockSize < max_seq_len)
-        return fail(SHIFTATTN_EINVAL, "max_blocks_per_seq = %d cannot hold max_seq_len = %d", s.max_blocks, max_seq_len);
     const bool mfma = use_prefill_mfma(s, num_seqs, max_seq_len);
     const size_t need = mfma ? prefill_mfma_workspace(num_seqs, total_q, max_q_len, max_seq_len, s) : 0;
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace)))
@@ -368,15 +392,10 @@ int shiftattn_decode(const void* q, const void* k_new, const void* v_new, const 
                      void* out, void* workspace, size_t workspace_bytes, const shiftattn_attn* a, void* stream) {
     AttnShape s;
     if (int rc = check_attn(a, &s)) return rc;
-    if (num_seqs < 0 || max_seq_len < 0) return fail(SHIFTATTN_EINVAL, "negative size argument");
     bool new_kv;
     if (int rc = check_new_kv(k_new, v_new, slot_mapping, &new_kv)) return rc;
+    if (int rc = check_decode_args(q, kv_cache, block_table, seq_lens, num_seqs, max_seq_len, out, s)) return rc;
     if (num_seqs == 0) return SHIFTATTN_OK;
-    if (!q || !kv_cache || !block_table || !seq_lens || !out) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
-    if (!aligned16(q) || !aligned16(out) || !aligned16(kv_cache))
-        return fail(SHIFTATTN_EINVAL, "q / out / kv_cache must be 16-byte aligned");
-    if (static_cast<int64_t>(s.max_blocks) * kBlockSize < max_seq_len)
-        return fail(SHIFTATTN_EINVAL, "max_blocks_per_seq = %d cannot hold max_seq_len = %d", s.max_blocks, max_seq_len);
     const bool mfma = use_decode_mfma(s, num_seqs);
     const size_t need = mfma ? decode_mfma_workspace(num_seqs, max_seq_len, s) : 0;
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace)))
@@ -432,6 +451,16 @@ int shiftattn_mixed(const void* q, const void* k_new, const void* v_new, const i
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace)))
         return fail(SHIFTATTN_EWORKSPACE, "mixed batch needs %zu workspace bytes, got %zu", need,
                     workspace ? workspace_bytes : static_cast<size_t>(0));
+    // everything the two parts would refuse is refused here, before the cache is touched
+    const size_t q_off = static_cast<size_t>(total_prefill_q) * s.q_stride * s.elem;
+    const size_t o_off = static_cast<size_t>(total_prefill_q) * s.out_stride * s.elem;
+    const int32_t* table_d = block_table + static_cast<size_t>(num_prefill_seqs) * s.max_blocks;
+    if (int rc = check_prefill_args(q, kv_cache, block_table, cu_seqlens_q, seq_lens, num_prefill_seqs, total_prefill_q,
+                                    max_q_len, max_prefill_seq_len, out, s))
+        return rc;
+    if (int rc = check_decode_args(static_cast<const char*>(q) + q_off, kv_cache, table_d, seq_lens + num_prefill_seqs,
+                                   num_decode_seqs, max_decode_seq_len, static_cast<char*>(out) + o_off, s))
+        return rc;
     if (new_kv) {
         if (!aligned16(kv_cache)) return fail(SHIFTATTN_EINVAL, "kv_cache must be 16-byte aligned");
         hipError_t e = launch_kv_write(k_new, v_new, slot_mapping, static_cast<int>(rows), kv_cache, s,
@@ -443,10 +472,8 @@ int shiftattn_mixed(const void* q, const void* k_new, const void* v_new, const i
                                    num_prefill_seqs, total_prefill_q, max_q_len, max_prefill_seq_len, out, workspace,
                                    workspace_bytes, a, stream))
         return rc;
-    const size_t q_off = static_cast<size_t>(total_prefill_q) * s.q_stride * s.elem;
-    const size_t o_off = static_cast<size_t>(total_prefill_q) * s.out_stride * s.elem;
-    return shiftattn_decode(static_cast<const char*>(q) + q_off, nullptr, nullptr, nullptr, kv_cache,
-                            block_table + static_cast<size_t>(num_prefill_seqs) * s.max_blocks, seq_lens + num_prefill_seqs,
+    return shiftattn_decode(static_cast<const char*>(q) + q_off, nullptr, nullptr, nullptr, kv_cache, table_d,
+                            seq_lens + num_prefill_seqs,
                             num_decode_seqs, max_decode_seq_len, static_cast<char*>(out) + o_off, workspace, workspace_bytes,
                             a, stream);
 }

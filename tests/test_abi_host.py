@@ -173,6 +173,12 @@ def test_attention_entry_points_reject_bad_arguments(B):
     assert B.mixed_workspace_bytes(1, 2048, 2048, 133120, 4, 64, long_ctx) == \
         max(B.prefill_workspace_bytes(1, 2048, 2048, 133120, long_ctx), B.decode_workspace_bytes(4, 64, long_ctx))
     assert mixed(ok, q=None, cache=None, table=None, cu=None, sl=None, out=None, Sp=0, tq=0, mq=0, msp=0, Sd=0, msd=0) == B.OK
+    # a call that brings new K/V is refused as a whole, before its write is launched, when a part is bad
+    need = B.mixed_workspace_bytes(1, 32, 32, 64, 4, 64, ok)
+    small = _attn(B, max_blocks_per_seq=2)  # 32 tokens per sequence at most
+    for bad in (dict(a=small, msp=32, msd=64), dict(a=small, msp=64, msd=32), dict(a=ok, mq=64), dict(a=ok, out=ctypes.c_void_p(0x1002))):
+        a = bad.pop("a")
+        assert mixed(a, k=FAKE, v=FAKE, slots=FAKE, ws=FAKE, wsb=need, **bad) == B.EINVAL, bad
     kvw = L.shiftattn_kv_write
     assert kvw(None, FAKE, FAKE, 4, FAKE, ctypes.byref(ok), None) == B.EINVAL
     assert kvw(FAKE, FAKE, FAKE, -1, FAKE, ctypes.byref(ok), None) == B.EINVAL
