@@ -222,6 +222,8 @@ int shiftattn_prefill(const void *q, const void *k_new, const void *v_new, const
  * pieces processed in parallel (equal shares of all tokens per wavefront); partial results are
  * merged in a fixed order, so results are bitwise reproducible from run to run.
  * q, out: [num_seqs][hq_l][D]; k_new/v_new/slot_mapping: n_tokens = num_seqs (or all NULL).
+ * seq_lens[s] <= 0 marks a padding row (an engine that replays captured graphs pads its batches,
+ * Sec. 3.4): its output rows are zero, its table row is not read, and its slot must be negative.
  * slot_mapping[s], when not negative, must be the slot of position seq_lens[s] - 1 of sequence s as
  * block_table maps it (the append of a decode step): the tuned kernel writes the new token and attends to
  * it in one launch and does not re-read that slot through the table. */

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(kWaves * 64) void attn_rows_kernel(
         __builtin_amdgcn_wave_barrier();
     }
     Elem* o_row = out + static_cast<size_t>(tok) * a.out_stride + static_cast<size_t>(j) * D;
-    const float inv = a.v_scale / l_run;
+    const float inv = l_run > 0.f ? a.v_scale / l_run : 0.f;  // a row without visible keys (padding) is zero
 #pragma unroll
     for (int x = 0; x < kMaxD / 64; ++x) {
         const int d = lane + 64 * x;

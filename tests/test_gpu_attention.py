@@ -155,6 +155,47 @@ def test_decode_fused_kv_write_and_fp32(oracle, G):
     _check(G.decode_case(case, G.cache_for_case(case)), want, "f32")
 
 
+@pytest.mark.parametrize("dtype,D,fp8", [("bf16", 128, False), ("bf16", 128, True), ("f32", 64, False), ("bf16", 64, True)])
+def test_decode_padding_rows_are_zero(oracle, G, dtype, D, fp8):
+    """A batch padded to a fixed size (Sec. 3.4: the engine replays graphs captured per batch size): sequences of
+    length 0 among the real ones, with a negative slot and a table row of invalid ids.  Their output rows are zero,
+    every other row is what it is without them, and the cache is left as the real rows' appends make it."""
+    import torch
+    from paper_2509_16495_amd import binding as B
+    case = W.make_attn_case("t", 66, dtype, [(1, c) for c in (40, 1, 333, 17, 64)], 4, 2, D, pool_factor=1.3)
+    scales = (0.0371, 0.0293) if fp8 else None
+    ref_cache = oracle.cache_for_case(case, fp8_scales=scales)
+    want = oracle.attention_case(case, ref_cache, **(dict(k_scale=scales[0], v_scale=scales[1]) if fp8 else {}))
+    pad_at = [0, 3, 7]                        # positions of the padding rows in the padded batch
+    n = case.num_seqs + len(pad_at)
+    real = [i for i in range(n) if i not in pad_at]
+    lens = np.zeros(n, np.int32)
+    lens[real] = case.ctx_lens
+    table = np.full((n, case.block_table.shape[1]), -1, np.int32)
+    table[real] = case.block_table
+    slots = np.full(n, -1, np.int64)
+    slots[real] = case.slots[case.new_token_index]
+    q = np.zeros((n,) + case.q.shape[1:], case.q.dtype)
+    q[real] = case.q
+    k_new = np.zeros((n,) + case.k_ctx.shape[1:], case.k_ctx.dtype)
+    v_new = np.zeros_like(k_new)
+    k_new[real], v_new[real] = case.k_ctx[case.new_token_index], case.v_ctx[case.new_token_index]
+    cache = G.cache_for_case(case, only_cached=True, fp8_scales=scales)
+    out = torch.full((n, case.hq_l, D), 7.0, dtype=G.torch_dtype(dtype), device=G.DEV)
+    kw = dict(k_scale=scales[0], v_scale=scales[1]) if fp8 else {}
+    B.decode(G.t(q, dtype), cache, G.ti(table, np.int32), G.ti(lens, np.int32), int(lens.max()), out, case.softmax_scale,
+             k_new=G.t(k_new, dtype), v_new=G.t(v_new, dtype), slot_mapping=G.ti(slots, np.int64), **kw)
+    torch.cuda.synchronize()
+    got = W.to_f64(B.to_host(out), dtype)
+    assert np.all(got[pad_at] == 0.0)
+    err = np.abs(got[real] - want)
+    if dtype == "f32":
+        assert err.max() <= F32_MAX, err.max()
+    else:
+        assert err.max() <= BF16_MAX and err.mean() <= BF16_MEAN, (err.max(), err.mean())
+    assert B.to_host(cache).tobytes() == ref_cache.tobytes()
+
+
 @pytest.mark.parametrize("hq,hkv", [(8, 1), (4, 2), (16, 1)])
 def test_decode_appends_the_new_token_itself(oracle, G, hq, hkv):
     """Decode with the new tokens' K/V handed to the call (one launch writes and attends): contexts that end at
