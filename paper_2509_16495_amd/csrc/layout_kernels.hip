@@ -178,10 +178,12 @@ __global__ __launch_bounds__(kThreads) void kv_write_block_kernel(const uint16_t
         const int64_t blk = slot0 / kBlockSize;
         if (t_loc < len) {
             const size_t src = static_cast<size_t>(i0 + t_loc) * kv_stride + static_cast<size_t>(g) * D + dv * 8;
-            const u32x4 kvec = *reinterpret_cast<const u32x4*>(k_new + src);
-            const u32x4 vvec = *reinterpret_cast<const u32x4*>(v_new + src);
-            *reinterpret_cast<Piece*>(cache + cache_part_offset(blk, g, 0, hkv_l, D) + static_cast<size_t>(off + t_loc) * D + dv * 8) =
-                encode(kvec, k_scale);
+            // rows and cache lines are touched once by this kernel: streaming loads and stores
+            const u32x4 kvec = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k_new + src));
+            const u32x4 vvec = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(v_new + src));
+            __builtin_nontemporal_store(encode(kvec, k_scale),
+                                        reinterpret_cast<Piece*>(cache + cache_part_offset(blk, g, 0, hkv_l, D) +
+                                                                 static_cast<size_t>(off + t_loc) * D + dv * 8));
             *reinterpret_cast<Piece*>(tile + t_loc * kPitch + dv * 8) = encode(vvec, v_scale);
         }
         __syncthreads();
@@ -195,7 +197,7 @@ __global__ __launch_bounds__(kThreads) void kv_write_block_kernel(const uint16_t
             } o;
 #pragma unroll
             for (int j = 0; j < 8; ++j) o.e[j] = tile[(8 * h + j - off) * kPitch + d];
-            *reinterpret_cast<Piece*>(vrow) = o.v;
+            __builtin_nontemporal_store(o.v, reinterpret_cast<Piece*>(vrow));
         } else {
             for (int j = lo; j < hi; ++j) vrow[j] = tile[(8 * h + j - off) * kPitch + d];
         }
