@@ -194,6 +194,15 @@ def test_decode_padding_rows_are_zero(oracle, G, dtype, D, fp8):
     else:
         assert err.max() <= BF16_MAX and err.mean() <= BF16_MEAN, (err.max(), err.mean())
     assert B.to_host(cache).tobytes() == ref_cache.tobytes()
+    # a batch of nothing but padding (max_seq_len 0): all rows zero, cache untouched
+    out.fill_(7.0)
+    lens[:] = 0
+    slots[:] = -1
+    B.decode(G.t(q, dtype), cache, G.ti(table, np.int32), G.ti(lens, np.int32), 0, out, case.softmax_scale,
+             k_new=G.t(k_new, dtype), v_new=G.t(v_new, dtype), slot_mapping=G.ti(slots, np.int64), **kw)
+    torch.cuda.synchronize()
+    assert np.all(W.to_f64(B.to_host(out), dtype) == 0.0)
+    assert B.to_host(cache).tobytes() == ref_cache.tobytes()
 
 
 @pytest.mark.parametrize("hq,hkv", [(8, 1), (4, 2), (16, 1)])
