@@ -121,3 +121,53 @@ def test_decode_fp8_appends_the_new_token_itself(oracle, G, hq, hkv):
     got = G.decode_case(case, cache, fused_new_kv=True, fp8_scales=SCALES)
     assert B.to_host(cache).tobytes() == ocache.tobytes()
     _check(got, oracle.attention_case(case, ocache, k_scale=SCALES[0], v_scale=SCALES[1]), "bf16")
+
+
+# ------------------------------------------------------------------------------------------------------
+# benchmark-sized configurations over an FP8 cache, in the launch configuration the benchmark times.  The oracle's
+# quantiser is a linear search per element, so it writes the contexts of sampled sequences only (into a cache of
+# the full pool's shape); the GPU runs the whole batch.
+# ------------------------------------------------------------------------------------------------------
+def _blocks_of(case, seq_ids):
+    return np.concatenate([case.block_table[s, :(int(case.ctx_lens[s]) + 15) // 16] for s in seq_ids])
+
+
+def test_config4_batch_decode_fp8_sampled_sequences(oracle, G):
+    """256 decode sequences, contexts U[512, 8192], over an FP8 cache; the new tokens are quantised and appended by
+    the call.  The shortest, the longest and four random sequences: output rows against the oracle, their cache
+    blocks byte for byte."""
+    from paper_2509_16495_amd import binding as B
+    case = W.config4_attn()
+    rng = np.random.default_rng(4)
+    ids = sorted({int(np.argmin(case.ctx_lens)), int(np.argmax(case.ctx_lens)), *map(int, rng.integers(0, case.num_seqs, size=4))})
+    sub = W.sub_case(case, ids)
+    ocache = oracle.cache_for_case(sub, fp8_scales=SCALES)
+    cache = G.cache_for_case(case, only_cached=True, fp8_scales=SCALES)
+    got = G.decode_case(case, cache, fused_new_kv=True, fp8_scales=SCALES)
+    blocks = _blocks_of(case, ids)
+    assert B.to_host(cache)[blocks].tobytes() == ocache[blocks].tobytes()
+    _check(got[ids], oracle.attention_case(sub, ocache, k_scale=SCALES[0], v_scale=SCALES[1]), "bf16")
+
+
+def test_config5_mixed_step_fp8_one_call_sampled(oracle, G):
+    """The long-context step (2048-token chunk on 131072 cached tokens + 64 decodes) over an FP8 cache through the
+    unified entry point.  The chunk's sequence and two decode sequences: their cache blocks byte for byte, sampled
+    chunk rows and the two decode rows against the oracle."""
+    from paper_2509_16495_amd import binding as B
+    case, n_prefill = W.config5_attn()
+    assert n_prefill == 1
+    dec_lens = case.ctx_lens[n_prefill:]
+    ids = [0, n_prefill + int(np.argmin(dec_lens)), n_prefill + int(np.argsort(dec_lens)[len(dec_lens) // 2])]
+    sub = W.sub_case(case, ids)
+    ocache = oracle.cache_for_case(sub, fp8_scales=SCALES)
+    cache = G.cache_for_case(case, only_cached=True, fp8_scales=SCALES)
+    got = G.mixed_case(case, n_prefill, cache, fp8_scales=SCALES)
+    blocks = _blocks_of(case, ids)
+    assert B.to_host(cache)[blocks].tobytes() == ocache[blocks].tobytes()
+    n_chunk = int(case.q_lens[0])
+    rng = np.random.default_rng(5)
+    chunk_rows = np.unique(np.concatenate([np.arange(8), np.arange(n_chunk - 8, n_chunk), rng.integers(0, n_chunk, size=8)]))
+    rows_sub = np.concatenate([chunk_rows, [n_chunk, n_chunk + 1]])                     # rows of the sub-case
+    rows_all = np.concatenate([chunk_rows, [n_chunk + i - n_prefill for i in ids[1:]]])   # the same rows of the batch
+    want = oracle.attention_case(sub, ocache, rows_sub, k_scale=SCALES[0], v_scale=SCALES[1])
+    _check(got[rows_all], want, "bf16")
