@@ -261,10 +261,16 @@ def test_config3_70b_prefill_sampled(oracle, G):
 
 
 def test_config4_batch_decode_full(oracle, G):
+    """Every output row of the 256-sequence batch; the cache (its 1.1 M context tokens written by the K/V write the
+    benchmark times, the new tokens appended by the decode call) byte for byte."""
+    from paper_2509_16495_amd import binding as B
     case = W.config4_attn()
-    want = oracle.attention_case(case, oracle.cache_for_case(case))
-    got = G.decode_case(case, G.cache_for_case(case, only_cached=True), fused_new_kv=True)
+    ocache = oracle.cache_for_case(case)
+    want = oracle.attention_case(case, ocache)
+    cache = G.cache_for_case(case, only_cached=True)
+    got = G.decode_case(case, cache, fused_new_kv=True)
     _check(got, want, "bf16")
+    assert B.to_host(cache).tobytes() == ocache.tobytes()
 
 
 @pytest.mark.parametrize("dtype,D,hq,hkv", [("bf16", 128, 8, 1), ("bf16", 128, 4, 2), ("f32", 64, 4, 1)])
