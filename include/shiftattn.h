@@ -232,6 +232,23 @@ int shiftattn_decode(const void *q, const void *k_new, const void *v_new, const 
                      int32_t max_seq_len, void *out, void *workspace, size_t workspace_bytes,
                      const shiftattn_attn *a, void *stream);
 
+/* ---- shiftattn_decode for callers that cannot allocate -------------------------------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc: the same
+ * operation, arguments and results as shiftattn_decode, but the split partials go into device memory the
+ * library itself holds (a file-scope array of SHIFTATTN_STATIC_SCRATCH_BYTES on every GPU the library
+ * runs on, until the process ends) instead of a caller-provided workspace.  The call allocates and frees
+ * nothing.  A batch whose shiftattn_decode_workspace_bytes() exceeds SHIFTATTN_STATIC_SCRATCH_BYTES is
+ * refused with SHIFTATTN_EWORKSPACE before anything is enqueued (256 sequences of 8 query heads per KV
+ * head need 9.6 MB).  Nothing in the array has to start at zero: every partial row the merge reads was
+ * written by the same call.  All calls on one GPU share the one array: two calls that overlap in time
+ * on the same GPU (different streams, or different host threads without ordering) race; calls on one
+ * stream are ordered and safe.  The first call on a device looks the array's address up (that device must
+ * be current, as for every call). */
+#define SHIFTATTN_STATIC_SCRATCH_BYTES (16u << 20)
+int shiftattn_decode_static(const void *q, const void *k_new, const void *v_new, const int64_t *slot_mapping,
+                            void *kv_cache, const int32_t *block_table, const int32_t *seq_lens, int32_t num_seqs,
+                            int32_t max_seq_len, void *out, const shiftattn_attn *a, void *stream);
+
 /* ---- Algorithm 1, boxed line, on a unified batch: prefill chunks and decode rows in one call ------
  * A chunked-prefill engine (Sec. 5, related work on chunked prefill) puts both kinds of rows into one
  * batch.  Sequences 0 .. num_prefill_seqs-1 carry the chunks (any q_len, described by cu_seqlens_q

@@ -68,6 +68,7 @@ def lib() -> ctypes.CDLL:
         L.shiftattn_kv_write.argtypes = [vp, vp, i64p, i32, vp, ap, vp]
         L.shiftattn_prefill.argtypes = [vp, vp, vp, i64p, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, ap, vp]
         L.shiftattn_decode.argtypes = [vp, vp, vp, i64p, vp, vp, vp, i32, i32, vp, vp, sz, ap, vp]
+        L.shiftattn_decode_static.argtypes = [vp, vp, vp, i64p, vp, vp, vp, i32, i32, vp, ap, vp]
         L.shiftattn_prefill_workspace_bytes.argtypes = [i32, i32, i32, i32, ap]
         L.shiftattn_prefill_workspace_bytes.restype = sz
         L.shiftattn_decode_workspace_bytes.argtypes = [i32, i32, ap]
@@ -323,6 +324,23 @@ def decode(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, s
     _check(lib().shiftattn_decode(_ptr(q), _ptr(k_new), _ptr(v_new), _ptr(slot_mapping), _ptr(kv_cache),
                                   _ptr(block_table), _ptr(seq_lens), num_seqs, max_seq_len, _ptr(out),
                                   _ptr(workspace), ws_bytes, ctypes.byref(a), _stream()))
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def decode_static(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, seq_lens: torch.Tensor,
+                  max_seq_len: int, out: torch.Tensor, softmax_scale: float, k_new: Optional[torch.Tensor] = None,
+                  v_new: Optional[torch.Tensor] = None, slot_mapping: Optional[torch.Tensor] = None, k_scale: float = 1.0,
+                  v_scale: float = 1.0) -> None:
+    """decode() without a workspace: the library's own static device array takes the split partials."""
+    num_seqs = q.shape[0]
+    assert seq_lens.dtype == torch.int32 and seq_lens.shape[0] == num_seqs
+    assert out.shape == q.shape and out.dtype == q.dtype
+    a = attn_desc(q, kv_cache, block_table, softmax_scale, k_new, out, k_scale, v_scale)
+    _check(lib().shiftattn_decode_static(_ptr(q), _ptr(k_new), _ptr(v_new), _ptr(slot_mapping), _ptr(kv_cache),
+                                         _ptr(block_table), _ptr(seq_lens), num_seqs, max_seq_len, _ptr(out),
+                                         ctypes.byref(a), _stream()))
 
 
 def mixed_workspace_bytes(num_prefill_seqs: int, total_prefill_q: int, max_q_len: int, max_prefill_seq_len: int,

@@ -6,6 +6,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "internal.h"
 
 using namespace shiftattn;
@@ -170,6 +172,32 @@ int check_decode_args(const void* q, const void* kv_cache, const int32_t* block_
         return fail(SHIFTATTN_EINVAL, "q / out / kv_cache must be 16-byte aligned");
     if (static_cast<int64_t>(s.max_blocks) * kBlockSize < max_seq_len)
         return fail(SHIFTATTN_EINVAL, "max_blocks_per_seq = %d cannot hold max_seq_len = %d", s.max_blocks, max_seq_len);
+    return 0;
+}
+
+// ---- device memory the library itself holds, for shiftattn_decode_static -------------------------------------
+// One array per GPU the library runs on, held until the process ends.  In host code the array's name is only a
+// handle: its device address is looked up once per device (with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[SHIFTATTN_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];  // per device: address of `scratch` there, null until first looked up
+
+int static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(SHIFTATTN_EUNSUPPORTED, "device index %d: at most %d devices", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!ptr) return fail(SHIFTATTN_EHIP, "hipGetSymbolAddress(scratch) returned a null address");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
     return 0;
 }
 
@@ -416,6 +444,26 @@ int shiftattn_decode(const void* q, const void* k_new, const void* v_new, const 
     else
         e = launch_attn_generic(q, kv_cache, block_table, nullptr, seq_lens, num_seqs, num_seqs, out, s, st);
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "decode launch");
+}
+
+int shiftattn_decode_static(const void* q, const void* k_new, const void* v_new, const int64_t* slot_mapping, void* kv_cache,
+                            const int32_t* block_table, const int32_t* seq_lens, int32_t num_seqs, int32_t max_seq_len,
+                            void* out, const shiftattn_attn* a, void* stream) {
+    const size_t need = shiftattn_decode_workspace_bytes(num_seqs, max_seq_len, a);
+    if (need == SIZE_MAX) {  // let the ordinary entry point name the bad argument (it needs no workspace to do so)
+        return shiftattn_decode(q, k_new, v_new, slot_mapping, kv_cache, block_table, seq_lens, num_seqs, max_seq_len, out,
+                                nullptr, 0, a, stream);
+    }
+    if (need > SHIFTATTN_STATIC_SCRATCH_BYTES)
+        return fail(SHIFTATTN_EWORKSPACE,
+                    "decode_static: this batch needs %zu bytes of split partials, the library's own scratch holds %zu; "
+                    "use shiftattn_decode with a caller-provided workspace",
+                    need, static_cast<size_t>(SHIFTATTN_STATIC_SCRATCH_BYTES));
+    void* ws = nullptr;
+    if (need > 0)
+        if (int rc = static_scratch(&ws)) return rc;
+    return shiftattn_decode(q, k_new, v_new, slot_mapping, kv_cache, block_table, seq_lens, num_seqs, max_seq_len, out, ws,
+                            need > 0 ? static_cast<size_t>(SHIFTATTN_STATIC_SCRATCH_BYTES) : 0, a, stream);
 }
 
 size_t shiftattn_mixed_workspace_bytes(int32_t num_prefill_seqs, int32_t total_prefill_q, int32_t max_q_len,

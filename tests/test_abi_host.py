@@ -151,6 +151,16 @@ def test_attention_entry_points_reject_bad_arguments(B):
     need = B.decode_workspace_bytes(4, 64, ok)
     assert need > 0
     assert decode(ok) == B.EWORKSPACE and decode(ok, ws=FAKE, wsb=need - 1) == B.EWORKSPACE
+    # the variant without a workspace argument: same argument checks; a batch beyond the library's own array is refused
+    def decode_static(a, q=FAKE, cache=FAKE, table=FAKE, sl=FAKE, S=4, ms=64, out=FAKE):
+        return L.shiftattn_decode_static(q, None, None, None, cache, table, sl, S, ms, out, None if a is None else ctypes.byref(a), None)
+
+    assert decode_static(None) == B.EINVAL and decode_static(_attn(B, head_dim=100)) == B.EUNSUPPORTED
+    assert decode_static(ok, S=-1) == B.EINVAL
+    assert decode_static(ok, q=None, cache=None, table=None, sl=None, out=None, S=0, ms=0) == B.OK
+    wide = _attn(B, num_q_heads=16)
+    assert B.decode_workspace_bytes(2048, 64, wide) > B.STATIC_SCRATCH_BYTES
+    assert decode_static(wide, S=2048) == B.EWORKSPACE and "scratch" in B.last_error()
     # split prefill (short chunk on a long context) needs one too
     long_ctx = _attn(B, max_blocks_per_seq=8320)
     need = B.prefill_workspace_bytes(1, 2048, 2048, 133120, long_ctx)
