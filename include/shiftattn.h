@@ -305,6 +305,22 @@ int32_t shiftattn_use_base_config(int32_t n_tokens, int32_t threshold);
 int shiftattn_ceiling_mfma_bf16(const void *operands, void *sink, int32_t iters, int64_t *flops, void *stream);
 int shiftattn_ceiling_hbm_read(const void *src, size_t bytes, void *sink, int64_t *bytes_read, void *stream);
 
+/* ---- Set-up and tuning switches (for callers and benchmarks; not part of the attention path) -----------
+ * shiftattn_init: optional.  Does, for the current device, the one-time set-up that the first call of an
+ *   entry point would otherwise do there (kernel attributes, the address of the library's own scratch
+ *   array): call it once per device before capturing calls into a HIP graph.  Thread-safe.
+ * shiftattn_set_option / shiftattn_get_option: process-wide switches, 0 = the library decides per call
+ *   (the default, and the fastest).  Set them before asking for workspace sizes: the sizes follow them.
+ *   SHIFTATTN_OPT_PREFILL_TILE   128 | 256: which prefill kernel takes bf16 / head_dim 128 launches
+ *   SHIFTATTN_OPT_PREFILL_SPLITS 1 .. 64: key ranges per column tile of those kernels
+ *   SHIFTATTN_OPT_GENERIC_ONLY   1: every attention call runs the general kernel (any type / head_dim)
+ *   set returns EINVAL for an unknown option or value; get returns -1 for an unknown option. */
+enum { SHIFTATTN_OPT_PREFILL_TILE = 0, SHIFTATTN_OPT_PREFILL_SPLITS = 1, SHIFTATTN_OPT_GENERIC_ONLY = 2,
+       SHIFTATTN_OPT_COUNT = 3 };
+int shiftattn_init(void);
+int shiftattn_set_option(int32_t option, int32_t value);
+int32_t shiftattn_get_option(int32_t option);
+
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char *shiftattn_last_error(void);
 

@@ -86,9 +86,27 @@ def lib() -> ctypes.CDLL:
         L.shiftattn_use_base_config.restype = i32
         L.shiftattn_ceiling_mfma_bf16.argtypes = [vp, vp, i32, ctypes.POINTER(ctypes.c_int64), vp]
         L.shiftattn_ceiling_hbm_read.argtypes = [vp, sz, vp, ctypes.POINTER(ctypes.c_int64), vp]
+        L.shiftattn_set_option.argtypes = [i32, i32]
+        L.shiftattn_get_option.argtypes = [i32]
+        L.shiftattn_get_option.restype = i32
         L.shiftattn_last_error.restype = ctypes.c_char_p
         _lib = L
     return _lib
+
+
+OPT_PREFILL_TILE, OPT_PREFILL_SPLITS, OPT_GENERIC_ONLY = 0, 1, 2
+
+
+def init() -> None:
+    _check(lib().shiftattn_init())
+
+
+def set_option(option: int, value: int) -> None:
+    _check(lib().shiftattn_set_option(option, value))
+
+
+def get_option(option: int) -> int:
+    return int(lib().shiftattn_get_option(option))
 
 
 def last_error() -> str:

@@ -6,6 +6,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <atomic>
 #include <mutex>
 
 #include "internal.h"
@@ -32,12 +33,30 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 int elem_size(int dtype) { return dtype == SHIFTATTN_BF16 ? 2 : (dtype == SHIFTATTN_F32 ? 4 : 0); }
 
-bool force_generic() {
-    static const bool v = [] {
-        const char* e = getenv("SHIFTATTN_FORCE_GENERIC");
-        return e && e[0] == '1';
-    }();
-    return v;
+// process-wide tuning switches (shiftattn_set_option)
+std::atomic<int> g_options[SHIFTATTN_OPT_COUNT];
+
+bool force_generic() { return g_options[SHIFTATTN_OPT_GENERIC_ONLY].load(std::memory_order_relaxed) != 0; }
+
+// Per-device set-up: three kernels need more dynamic LDS than a launch gets by default, which is an attribute of the
+// function on each device.  Done once per device, under a lock, by the first call that may launch one of them there (or
+// by shiftattn_init): safe from several host threads, and never inside a later call.
+constexpr int kMaxDevices = 64;
+std::mutex g_device_mu;
+bool g_device_ready[kMaxDevices];
+
+int ensure_device_ready() {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(SHIFTATTN_EUNSUPPORTED, "device index %d: at most %d devices", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_device_mu);
+    if (g_device_ready[dev]) return 0;
+    if ((e = prefill_mfma_init()) != hipSuccess) return hip_fail(e, "set-up of the prefill kernel");
+    if ((e = prefill_mfma64_init()) != hipSuccess) return hip_fail(e, "set-up of the wide prefill kernel");
+    if ((e = proj_gemm_init()) != hipSuccess) return hip_fail(e, "set-up of the projection kernel");
+    g_device_ready[dev] = true;
+    return 0;
 }
 
 // Fills `s` from the public struct; returns 0 or an error code.
@@ -180,7 +199,6 @@ int check_decode_args(const void* q, const void* kv_cache, const int32_t* block_
 // handle: its device address is looked up once per device (with that device current) and kept.
 static __device__ __align__(256) unsigned char scratch[SHIFTATTN_STATIC_SCRATCH_BYTES];
 
-constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mu;
 void* g_scratch_ptr[kMaxDevices];  // per device: address of `scratch` there, null until first looked up
 
@@ -203,9 +221,44 @@ int static_scratch(void** out) {
 
 }  // namespace
 
+namespace shiftattn {
+int option_prefill_tile() { return g_options[SHIFTATTN_OPT_PREFILL_TILE].load(std::memory_order_relaxed); }
+int option_prefill_splits() { return g_options[SHIFTATTN_OPT_PREFILL_SPLITS].load(std::memory_order_relaxed); }
+}  // namespace shiftattn
+
 extern "C" {
 
 const char* shiftattn_last_error(void) { return g_err; }
+
+int shiftattn_init(void) {
+    if (int rc = ensure_device_ready()) return rc;
+    void* ws = nullptr;
+    return static_scratch(&ws);
+}
+
+int shiftattn_set_option(int32_t option, int32_t value) {
+    switch (option) {
+        case SHIFTATTN_OPT_PREFILL_TILE:
+            if (value != 0 && value != 128 && value != 256)
+                return fail(SHIFTATTN_EINVAL, "SHIFTATTN_OPT_PREFILL_TILE takes 0, 128 or 256, not %d", value);
+            break;
+        case SHIFTATTN_OPT_PREFILL_SPLITS:
+            if (value < 0 || value > 64) return fail(SHIFTATTN_EINVAL, "SHIFTATTN_OPT_PREFILL_SPLITS takes 0 .. 64, not %d", value);
+            break;
+        case SHIFTATTN_OPT_GENERIC_ONLY:
+            if (value != 0 && value != 1) return fail(SHIFTATTN_EINVAL, "SHIFTATTN_OPT_GENERIC_ONLY takes 0 or 1, not %d", value);
+            break;
+        default:
+            return fail(SHIFTATTN_EINVAL, "unknown option %d", option);
+    }
+    g_options[option].store(value, std::memory_order_relaxed);
+    return SHIFTATTN_OK;
+}
+
+int32_t shiftattn_get_option(int32_t option) {
+    if (option < 0 || option >= SHIFTATTN_OPT_COUNT) return -1;
+    return g_options[option].load(std::memory_order_relaxed);
+}
 
 int32_t shiftattn_head_block(int32_t sp, int32_t tp, int32_t rank) {
     if (sp < 1 || tp < 1 || rank < 0 || rank >= sp * tp) return -1;
@@ -277,6 +330,7 @@ int shiftattn_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int32_
     if (s.T_pad == 0) return SHIFTATTN_OK;
     if (!send || (s.T > 0 && (!x || !w_qkv))) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
     if (!aligned16(x) || !aligned16(w_qkv) || !aligned16(send)) return fail(SHIFTATTN_EINVAL, "x / w_qkv / send must be 16-byte aligned");
+    if (int rc = ensure_device_ready()) return rc;
     hipError_t e = launch_qkv_proj_pack(x, w_qkv, send, d_model, s, nullptr, nullptr, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "qkv_proj_pack launch");
 }
@@ -292,6 +346,7 @@ int shiftattn_unpack_o_proj(const void* recv, const void* w_o, void* out, int32_
     if (s.T == 0) return SHIFTATTN_OK;
     if (!recv || !w_o || !out) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
     if (!aligned16(recv) || !aligned16(w_o) || !aligned16(out)) return fail(SHIFTATTN_EINVAL, "recv / w_o / out must be 16-byte aligned");
+    if (int rc = ensure_device_ready()) return rc;
     hipError_t e = launch_unpack_o_proj(recv, w_o, out, d_model, s, nullptr, nullptr, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_o_proj launch");
 }
@@ -336,6 +391,7 @@ int shiftattn_qkv_proj_pack_fp8(const void* x_codes, const float* x_scales, cons
     if (!send || (s.T > 0 && (!x_codes || !w_codes || !x_scales || !w_scales))) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
     if (!aligned16(x_codes) || !aligned16(w_codes) || !aligned16(send) || !aligned16(w_scales) || (reinterpret_cast<uintptr_t>(x_scales) & 3))
         return fail(SHIFTATTN_EINVAL, "x_codes / w_codes / w_scales / send must be 16-byte aligned, x_scales 4-byte");
+    if (int rc = ensure_device_ready()) return rc;
     hipError_t e = launch_qkv_proj_pack(x_codes, w_codes, send, d_model, s, x_scales, w_scales, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "qkv_proj_pack_fp8 launch");
 }
@@ -352,6 +408,7 @@ int shiftattn_unpack_o_proj_fp8(const void* recv_codes, const float* a_scales, c
     if (!recv_codes || !a_scales || !w_codes || !w_scales || !out) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
     if (!aligned16(recv_codes) || !aligned16(w_codes) || !aligned16(out) || !aligned16(w_scales) || (reinterpret_cast<uintptr_t>(a_scales) & 3))
         return fail(SHIFTATTN_EINVAL, "recv_codes / w_codes / w_scales / out must be 16-byte aligned, a_scales 4-byte");
+    if (int rc = ensure_device_ready()) return rc;
     hipError_t e = launch_unpack_o_proj(recv_codes, w_codes, out, d_model, s, a_scales, w_scales, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_o_proj_fp8 launch");
 }
@@ -401,6 +458,8 @@ int shiftattn_prefill(const void* q, const void* k_new, const void* v_new, const
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace)))
         return fail(SHIFTATTN_EWORKSPACE, "prefill needs %zu workspace bytes, got %zu", need,
                     workspace ? workspace_bytes : static_cast<size_t>(0));
+    if (mfma)
+        if (int rc = ensure_device_ready()) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
     if (new_kv) {

@@ -76,6 +76,31 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
                                int total_q, int max_q_len, int max_seq_len, void* out, void* workspace,
                                const AttnShape& a, hipStream_t st);
 
+// prefill_mfma64.hip : the same operation on 256-column workgroup tiles, one 64-column wavefront per SIMD; bf16 cache
+struct Prefill64Plan {
+    int tile_tokens, pair_ranks, n_splits;
+    long workgroups;
+};
+bool prefill_mfma64_supported(const AttnShape& a);
+Prefill64Plan prefill_mfma64_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const AttnShape& a,
+                                  int forced_splits);
+size_t prefill_mfma64_workspace(int total_q, const Prefill64Plan& pl, const AttnShape& a);
+// c: softmax scale in exp2 units (times k_scale), out_scale: factor on the normalised output (v_scale, else 1)
+hipError_t launch_prefill_mfma64(const void* q, const void* cache, const int32_t* block_table, int max_blocks,
+                                 const int32_t* cu_seqlens_q, const int32_t* seq_lens, int num_seqs, int total_q,
+                                 const Prefill64Plan& pl, void* out, void* workspace, const AttnShape& a, float c,
+                                 float out_scale, hipStream_t st);
+
+// Per-device set-up of the kernels that need more dynamic LDS than the default limit (each sets the attribute of its
+// kernels on the current device).  api.hip calls them once per device, under a lock, before the first launch there.
+hipError_t prefill_mfma_init();
+hipError_t prefill_mfma64_init();
+hipError_t proj_gemm_init();
+
+// Process-wide tuning switches (api.hip: shiftattn_set_option); 0 = decided per call
+int option_prefill_tile();    // 0, 128 or 256
+int option_prefill_splits();  // 0 or the number of key ranges
+
 // proj_gemm.hip : the projections in front of the first exchange and behind the second (bf16, head_dim 128)
 bool qkv_proj_pack_supported(const XchgShape& s, int d_model, int elem);
 bool unpack_o_proj_supported(const XchgShape& s, int d_model, int elem);

@@ -45,8 +45,6 @@
 // merged by launch_combine.
 #include "internal.h"
 
-#include <stdlib.h>
-
 #include <utility>
 
 namespace shiftattn {
@@ -648,11 +646,6 @@ struct Plan {
     int gs_log2, head_slots, tile_tokens, pair_ranks, n_splits;
 };
 
-int env_int(const char* name, int dflt) {
-    const char* v = getenv(name);
-    return v ? atoi(v) : dflt;
-}
-
 Plan make_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const AttnShape& a) {
     Plan pl;
     const int G = a.hq_l / a.hkv_l;
@@ -666,7 +659,7 @@ Plan make_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const 
     // Split the keys when the tiles alone cannot fill the chip (long cached context, short chunk).
     const long wgs = static_cast<long>((total_q + pl.tile_tokens - 1) / pl.tile_tokens + num_seqs) / 2 * pl.head_slots + 1;
     int splits = 1;
-    const int forced = env_int("SHIFTATTN_PREFILL_SPLITS", 0);
+    const int forced = option_prefill_splits();
     if (forced > 0) splits = forced;
     else if (wgs < 192) {
         const int by_fill = static_cast<int>((512 + wgs - 1) / wgs);
@@ -707,9 +700,44 @@ bool prefill_mfma_supported(const AttnShape& a, int num_seqs, int max_seq_len) {
     return !a.kv_fp8() || fp8_scratch(num_seqs, max_seq_len, a).cache_bytes <= kFp8ScratchLimit;
 }
 
+namespace {
+
+// Which of the two kernels serves a launch.  The 256-column kernel is the faster one per MFMA; it takes the launch when
+// its tiles fill the chip without splitting keys, or when the 128-column kernel would have to split keys as well (a short
+// chunk on a long context).  A batch like 4 x 4096 tokens with 4 query heads per KV head - 128 pairs of 256-column tiles,
+// 256 pairs of 128-column tiles - stays with the 128-column kernel, which covers the chip with equal workgroups and no
+// merge pass.
+struct Choice {
+    bool wide;
+    Plan narrow;
+    Prefill64Plan w;
+};
+
+Choice choose(int num_seqs, int total_q, int max_q_len, int max_seq_len, const AttnShape& a) {
+    Choice c;
+    c.narrow = make_plan(num_seqs, total_q, max_q_len, max_seq_len, a);
+    c.wide = false;
+    // (a cache widened from FP8 is bf16 by the time a kernel runs, so only the other conditions matter)
+    AttnShape b = a;
+    b.kv_elem = b.elem;
+    if (!prefill_mfma64_supported(b)) return c;
+    c.w = prefill_mfma64_plan(num_seqs, total_q, max_q_len, max_seq_len, a, option_prefill_splits());
+    const int forced = option_prefill_tile();
+    if (forced == 128) return c;
+    c.wide = forced == 256 || c.w.n_splits == 1 || c.narrow.n_splits > 1;
+    return c;
+}
+
+size_t split_bytes_of(const Choice& c, int total_q, const AttnShape& a) {
+    if (c.wide) return prefill_mfma64_workspace(total_q, c.w, a);
+    return c.narrow.n_splits == 1 ? 0 : static_cast<size_t>(c.narrow.n_splits) * total_q * a.hq_l * (kD + 2) * sizeof(float);
+}
+
+}  // namespace
+
 size_t prefill_mfma_workspace(int num_seqs, int total_q, int max_q_len, int max_seq_len, const AttnShape& a) {
-    const Plan pl = make_plan(num_seqs, total_q, max_q_len, max_seq_len, a);
-    size_t bytes = pl.n_splits == 1 ? 0 : static_cast<size_t>(pl.n_splits) * total_q * a.hq_l * (kD + 2) * sizeof(float);
+    const Choice c = choose(num_seqs, total_q, max_q_len, max_seq_len, a);
+    size_t bytes = split_bytes_of(c, total_q, a);
     if (a.kv_fp8()) {
         const Fp8Scratch f = fp8_scratch(num_seqs, max_seq_len, a);
         bytes = (bytes + 255) / 256 * 256 + f.cache_bytes + f.table_bytes;
@@ -717,17 +745,21 @@ size_t prefill_mfma_workspace(int num_seqs, int total_q, int max_q_len, int max_
     return bytes;
 }
 
+hipError_t prefill_mfma_init() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               kLdsBytes);
+}
+
 hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* block_table,
                                const int32_t* cu_seqlens_q, const int32_t* seq_lens, int num_seqs, int total_q,
                                int max_q_len, int max_seq_len, void* out, void* workspace, const AttnShape& a,
                                hipStream_t st) {
     if (num_seqs == 0 || total_q == 0 || max_q_len <= 0) return hipSuccess;
-    const Plan pl = make_plan(num_seqs, total_q, max_q_len, max_seq_len, a);
+    const Choice ch = choose(num_seqs, total_q, max_q_len, max_seq_len, a);
     int max_blocks = a.max_blocks;
     if (a.kv_fp8()) {  // widen into the scratch cache behind the split partials, then attend over that
         const Fp8Scratch f = fp8_scratch(num_seqs, max_seq_len, a);
-        const size_t split_bytes =
-            pl.n_splits == 1 ? 0 : (static_cast<size_t>(pl.n_splits) * total_q * a.hq_l * (kD + 2) * sizeof(float) + 255) / 256 * 256;
+        const size_t split_bytes = (split_bytes_of(ch, total_q, a) + 255) / 256 * 256;
         unsigned char* scratch = static_cast<unsigned char*>(workspace) + split_bytes;
         int32_t* table2 = reinterpret_cast<int32_t*>(scratch + f.cache_bytes);
         hipError_t e0 = launch_fp8_blocks_to_bf16(cache, block_table, a.max_blocks, seq_lens, num_seqs, f.nb, a.hkv_l, scratch,
@@ -737,6 +769,11 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
         block_table = table2;
         max_blocks = f.nb;
     }
+    const float c = a.scale * a.k_scale * 1.4426950408889634f;
+    if (ch.wide)
+        return launch_prefill_mfma64(q, cache, block_table, max_blocks, cu_seqlens_q, seq_lens, num_seqs, total_q, ch.w, out,
+                                     workspace, a, c, a.v_scale, st);
+    const Plan& pl = ch.narrow;
     PrefillParams p;
     p.q = static_cast<const uint16_t*>(q);
     p.cache = static_cast<const uint16_t*>(cache);
@@ -758,20 +795,12 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
     p.head_slots = pl.head_slots;
     p.n_splits = pl.n_splits;
     p.max_blocks = max_blocks;
-    p.c = a.scale * a.k_scale * 1.4426950408889634f;
+    p.c = c;
     p.out_scale = a.v_scale;
 
     const unsigned grid = static_cast<unsigned>(pl.pair_ranks) * pl.n_splits * num_seqs * pl.head_slots;
-    static bool attr_done = false;
-    hipError_t e;
-    if (!attr_done) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
     prefill_kernel<<<grid, kThreads, kLdsBytes, st>>>(p);
-    e = hipGetLastError();
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (pl.n_splits > 1)
         return launch_combine(p.o_part, p.ml_part, total_q, a.hq_l, kD, pl.n_splits, 0, nullptr, 0, out, a.out_stride,

@@ -325,13 +325,6 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
 
 template <bool kFp8>
 hipError_t launch(const GemmParams& p, hipStream_t st) {
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel<kFp8>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
     const int64_t wgs = static_cast<int64_t>(p.N / kTile) * ((p.M_out + kTile - 1) / kTile);
     if (wgs == 0) return hipSuccess;
     if (wgs > 0x7FFFFFFF) return hipErrorInvalidValue;
@@ -342,6 +335,14 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
 }  // namespace
 
 // bf16, head_dim 128; the feature dimension of either product must be a multiple of the 256-wide tile
+hipError_t proj_gemm_init() {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel<false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel<true>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+}
+
 bool qkv_proj_pack_supported(const XchgShape& s, int d_model, int elem) {
     return elem == 2 && s.vec_per_head * 8 == kHeadDim && d_model > 0 && d_model % 64 == 0 && (s.h + 2 * s.h_kv) % 2 == 0;
 }
