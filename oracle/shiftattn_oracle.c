@@ -317,7 +317,11 @@ int oracle_attention_kv(const void *q, int dtype, const void *kv_cache, int kv_d
         int j = (int)(item % hq_l);
         int64_t tok = rows ? rows[r] : r;
         int s = 0;
-        if (tok < 0 || tok >= total_q) { bad = 1; continue; }
+        if (tok < 0 || tok >= total_q) {
+#pragma omp atomic write
+            bad = 1;
+            continue;
+        }
         while (!(cu_seqlens_q[s] <= tok && tok < cu_seqlens_q[s + 1])) ++s;
         int q_len = cu_seqlens_q[s + 1] - cu_seqlens_q[s];
         int ctx = seq_lens[s];
@@ -326,7 +330,11 @@ int oracle_attention_kv(const void *q, int dtype, const void *kv_cache, int kv_d
         int g = j / group;
         const int32_t *table = block_table + (size_t)s * max_blocks_per_seq;
         double *o = out + ((size_t)r * hq_l + j) * D;
-        if (pos < 0 || ctx < q_len) { bad = 1; continue; }
+        if (pos < 0 || ctx < q_len) {
+#pragma omp atomic write
+            bad = 1;
+            continue;
+        }
 
         double *logit = (double *)malloc((size_t)(pos + 1) * sizeof(double));
         double top = -INFINITY;
