@@ -292,19 +292,6 @@ int32_t shiftattn_padded_tokens(int32_t n, int32_t sp);
  * Returns -1 on negative arguments. */
 int32_t shiftattn_use_base_config(int32_t n_tokens, int32_t threshold);
 
-/* ---- Measurement aids for benchmark reports (not part of the attention path) -------------------
- * Rates the chip attains on the two resources the kernels are priced against, to report beside
- * the datasheet peaks (Sec. 4.3 names them: attention compute for long prompts, KV-cache reads
- * for decoding).  Both only enqueue one kernel on `stream`; the caller times it.
- * ceiling_mfma_bf16: every wavefront of a chip-filling grid issues iters x 16 independent
- *   32x32x16 bf16 MFMAs on the operand values found in `operands` (device, 2 KiB = 128 lanes x
- *   8 bf16; random values give the clock real data gives).  *flops (host) receives the flops of
- *   the launch.  sink: device, 4 bytes, never written in practice.
- * ceiling_hbm_read: streams `bytes` (rounded down to 16 KiB) of `src` (device) through every
- *   wavefront with 16-byte non-temporal loads.  *bytes_read (host) receives the bytes requested. */
-int shiftattn_ceiling_mfma_bf16(const void *operands, void *sink, int32_t iters, int64_t *flops, void *stream);
-int shiftattn_ceiling_hbm_read(const void *src, size_t bytes, void *sink, int64_t *bytes_read, void *stream);
-
 /* ---- Set-up and tuning switches (for callers and benchmarks; not part of the attention path) -----------
  * shiftattn_init: optional.  Does, for the current device, the one-time set-up that the first call of an
  *   entry point would otherwise do there (kernel attributes, the address of the library's own scratch

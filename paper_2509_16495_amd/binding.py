@@ -86,6 +86,7 @@ def lib() -> ctypes.CDLL:
         L.shiftattn_use_base_config.restype = i32
         L.shiftattn_ceiling_mfma_bf16.argtypes = [vp, vp, i32, ctypes.POINTER(ctypes.c_int64), vp]
         L.shiftattn_ceiling_hbm_read.argtypes = [vp, sz, vp, ctypes.POINTER(ctypes.c_int64), vp]
+        L.shiftattn_ceiling_hbm_copy.argtypes = [vp, vp, sz, ctypes.POINTER(ctypes.c_int64), vp]
         L.shiftattn_set_option.argtypes = [i32, i32]
         L.shiftattn_get_option.argtypes = [i32]
         L.shiftattn_get_option.restype = i32
@@ -163,6 +164,14 @@ def ceiling_mfma_bf16(operands: torch.Tensor, sink: torch.Tensor, iters: int) ->
     flops = ctypes.c_int64(0)
     _check(lib().shiftattn_ceiling_mfma_bf16(_ptr(operands), _ptr(sink), iters, ctypes.byref(flops), _stream()))
     return flops.value
+
+
+def copy_probe(src: torch.Tensor, dst: torch.Tensor) -> int:
+    """Enqueue the read + write streaming probe over all of `src`; returns the bytes copied."""
+    assert src.is_contiguous() and dst.is_contiguous() and dst.numel() * dst.element_size() >= src.numel() * src.element_size()
+    n = ctypes.c_int64(0)
+    _check(lib().shiftattn_ceiling_hbm_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), ctypes.byref(n), _stream()))
+    return n.value
 
 
 def ceiling_hbm_read(src: torch.Tensor, sink: torch.Tensor) -> int:

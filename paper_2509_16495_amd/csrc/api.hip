@@ -1,6 +1,7 @@
 // C-ABI front end: argument validation on the host, then kernel launches on the caller's stream.
 // Nothing here allocates, frees, synchronises or reads device memory.
 #include "../../include/shiftattn.h"
+#include "../../include/shiftattn_probe.h"
 
 #include <stdarg.h>
 #include <stdio.h>
@@ -158,8 +159,8 @@ int check_new_kv(const void* k_new, const void* v_new, const int64_t* slots, boo
 bool use_prefill_mfma(const AttnShape& s, int num_seqs, int max_seq_len) {
     return !force_generic() && prefill_mfma_supported(s, num_seqs, max_seq_len);
 }
-bool use_decode_mfma(const AttnShape& s, int num_seqs) {
-    return !force_generic() && decode_mfma_supported(s, num_seqs);
+bool use_decode_mfma(const AttnShape& s, int num_seqs, int max_seq_len) {
+    return !force_generic() && decode_mfma_supported(s, num_seqs, max_seq_len);
 }
 
 // Argument checks of a prefill / decode call that need no launch (shared with the mixed entry point, which must
@@ -294,6 +295,13 @@ int shiftattn_ceiling_hbm_read(const void* src, size_t bytes, void* sink, int64_
     if (!aligned16(src)) return fail(SHIFTATTN_EINVAL, "src must be 16-byte aligned");
     hipError_t e = launch_hbm_read_ceiling(src, bytes, sink, bytes_read, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "ceiling_hbm_read launch");
+}
+
+int shiftattn_ceiling_hbm_copy(const void* src, void* dst, size_t bytes, int64_t* bytes_copied, void* stream) {
+    if (!src || !dst || !bytes_copied) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(src) || !aligned16(dst)) return fail(SHIFTATTN_EINVAL, "src / dst must be 16-byte aligned");
+    hipError_t e = launch_hbm_copy_ceiling(src, dst, bytes, bytes_copied, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "ceiling_hbm_copy launch");
 }
 
 int shiftattn_pack_seq2head(const void* qkv, void* send, int32_t T, int32_t T_pad, const shiftattn_xchg* x,
@@ -437,7 +445,7 @@ size_t shiftattn_prefill_workspace_bytes(int32_t num_seqs, int32_t total_q, int3
 size_t shiftattn_decode_workspace_bytes(int32_t num_seqs, int32_t max_seq_len, const shiftattn_attn* a) {
     AttnShape s;
     if (check_attn(a, &s) || num_seqs < 0 || max_seq_len < 0) return SIZE_MAX;
-    if (!use_decode_mfma(s, num_seqs) || num_seqs == 0) return 0;
+    if (!use_decode_mfma(s, num_seqs, max_seq_len) || num_seqs == 0) return 0;
     return decode_mfma_workspace(num_seqs, max_seq_len, s);
 }
 
@@ -483,7 +491,7 @@ int shiftattn_decode(const void* q, const void* k_new, const void* v_new, const 
     if (int rc = check_new_kv(k_new, v_new, slot_mapping, &new_kv)) return rc;
     if (int rc = check_decode_args(q, kv_cache, block_table, seq_lens, num_seqs, max_seq_len, out, s)) return rc;
     if (num_seqs == 0) return SHIFTATTN_OK;
-    const bool mfma = use_decode_mfma(s, num_seqs);
+    const bool mfma = use_decode_mfma(s, num_seqs, max_seq_len);
     const size_t need = mfma ? decode_mfma_workspace(num_seqs, max_seq_len, s) : 0;
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace)))
         return fail(SHIFTATTN_EWORKSPACE, "decode needs %zu workspace bytes, got %zu", need,

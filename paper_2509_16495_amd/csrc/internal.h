@@ -59,7 +59,7 @@ hipError_t launch_combine_flat(const float* o_part, const float* ml_part, const 
                                void* out, int64_t out_stride, float out_scale, hipStream_t st);
 
 // decode_mfma.hip : bf16 q/out, D = 128, hq_l/hkv_l <= 16; cache bf16 or FP8 E4M3
-bool decode_mfma_supported(const AttnShape& a, int num_seqs);
+bool decode_mfma_supported(const AttnShape& a, int num_seqs, int max_seq_len);
 size_t decode_mfma_workspace(int num_seqs, int max_seq_len, const AttnShape& a);
 // k_new / v_new / slots non-null: the kernel also appends the new token of every sequence (only where
 // decode_mfma_appends() says so; the caller then launches no separate K/V write)
@@ -80,7 +80,17 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
 struct Prefill64Plan {
     int tile_tokens, pair_ranks, n_splits;
     long workgroups;
+    double model_seconds;  // launch_model_seconds of this plan
 };
+// Rough duration of a prefill launch, used only to choose between plans: `wgs` workgroups (one per compute unit at a
+// time) of `cols` columns each walk max_seq_len keys cut into `splits` ranges; ranges beyond one cost a merge pass.
+inline double launch_model_seconds(long wgs, int splits, int cols, int total_q, int max_seq_len, int hq_l) {
+    const double unit = 4.0 * 128 * cols * static_cast<double>(max_seq_len) / 3.9e12;  // one workgroup, all keys, at 1 PFLOP/s per chip
+    const double merge = 2.0 * total_q * hq_l * 130 * 4 / 4.0e12;                     // partials written and read back, per range
+    const double load = static_cast<double>(wgs) * splits / 256.0;
+    const double rounds = load <= 1.0 ? 1.0 : load + 0.25;                            // dynamic dispatch: a quarter round of tail
+    return rounds / splits * unit + (splits > 1 ? splits * merge + 5.0e-6 : 0.0);
+}
 bool prefill_mfma64_supported(const AttnShape& a);
 Prefill64Plan prefill_mfma64_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const AttnShape& a,
                                   int forced_splits);
@@ -119,6 +129,7 @@ hipError_t launch_quantize_rows_fp8(const void* x, void* codes, float* scales, i
 // ceilings.hip : attainable-rate probes for benchmark reports
 hipError_t launch_mfma_ceiling(const void* operands, void* sink, int iters, int64_t* flops, hipStream_t st);
 hipError_t launch_hbm_read_ceiling(const void* src, size_t bytes, void* sink, int64_t* bytes_read, hipStream_t st);
+hipError_t launch_hbm_copy_ceiling(const void* src, void* dst, size_t bytes, int64_t* bytes_copied, hipStream_t st);
 
 // FP8 E4M3 codes of a / scale and b / scale in bits 0..7 and 8..15: float32 quotient, nearest code with
 // ties to the even code, clamped to +-448 first so that nothing overflows, NaN quotient -> NaN code

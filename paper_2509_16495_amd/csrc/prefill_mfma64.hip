@@ -707,15 +707,25 @@ Prefill64Plan prefill_mfma64_plan(int num_seqs, int total_q, int max_q_len, int 
     pl.tile_tokens = kCols / G;
     const int tiles = (max_q_len + pl.tile_tokens - 1) / pl.tile_tokens;
     pl.pair_ranks = (tiles + 1) / 2;
-    // Split the keys when the tiles alone cannot fill the chip (long cached context, short chunk).
-    const long wgs = static_cast<long>((total_q + pl.tile_tokens - 1) / pl.tile_tokens + num_seqs) / 2 * a.hkv_l + 1;
+    // Key ranges per column tile: the count that minimises a simple model of the launch (launch_model_seconds) - a
+    // workgroup's time falls with the number of ranges, workgroups beyond one per compute unit queue up, and every range
+    // adds a partial result per (token, head) that the merge kernel writes and reads back.  A long prefill that fills the
+    // chip takes 1; a short chunk on a long context takes as many as fill it.
+    const long wgs = static_cast<long>(pl.pair_ranks) * num_seqs * a.hkv_l;
     int splits = 1;
     if (forced_splits > 0) {
         splits = forced_splits;
-    } else if (wgs < 192) {
-        const int by_fill = static_cast<int>((256 + wgs - 1) / wgs);
+        pl.model_seconds = launch_model_seconds(wgs, splits, kCols, total_q, max_seq_len, a.hq_l);
+    } else {
         const int by_len = max_seq_len / (32 * kKv);  // at least 32 key tiles per range
-        splits = by_fill < by_len ? by_fill : by_len;
+        pl.model_seconds = launch_model_seconds(wgs, 1, kCols, total_q, max_seq_len, a.hq_l);
+        for (int cand = 2; cand <= 16 && cand <= by_len; ++cand) {
+            const double t = launch_model_seconds(wgs, cand, kCols, total_q, max_seq_len, a.hq_l);
+            if (t < pl.model_seconds * 0.97) {  // a further range must pay for itself
+                pl.model_seconds = t;
+                splits = cand;
+            }
+        }
     }
     if (splits < 1) splits = 1;
     if (splits > 64) splits = 64;

@@ -23,9 +23,13 @@ def B():
 
 
 def _declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(shiftattn_[a-z0-9_]+)\s*\(", text)))
+    """Every function declared in any header under include/."""
+    import glob
+    names = set()
+    for header in glob.glob(os.path.join(ROOT, "include", "*.h")):
+        text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+        names |= set(re.findall(r"\b(shiftattn_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(B):
@@ -34,6 +38,29 @@ def test_every_declared_symbol_is_exported(B):
             "shiftattn_kv_write", "shiftattn_last_error"} <= set(names)
     for n in names:
         assert hasattr(B.lib(), n), n
+
+
+def test_options_and_their_bounds(B):
+    """The tuning switches: defaults are 0, values are range-checked, unknown options refused."""
+    L = B.lib()
+    for opt in (B.OPT_PREFILL_TILE, B.OPT_PREFILL_SPLITS, B.OPT_GENERIC_ONLY):
+        assert B.get_option(opt) == 0
+    assert L.shiftattn_set_option(B.OPT_PREFILL_TILE, 64) == B.EINVAL
+    assert L.shiftattn_set_option(B.OPT_PREFILL_SPLITS, 65) == B.EINVAL and L.shiftattn_set_option(B.OPT_PREFILL_SPLITS, -1) == B.EINVAL
+    assert L.shiftattn_set_option(B.OPT_GENERIC_ONLY, 2) == B.EINVAL
+    assert L.shiftattn_set_option(17, 0) == B.EINVAL and B.get_option(17) == -1
+    a = _attn(B, max_blocks_per_seq=8320)
+    auto = B.prefill_workspace_bytes(1, 2048, 2048, 133120, a)
+    try:
+        B.set_option(B.OPT_PREFILL_SPLITS, 4)
+        assert B.get_option(B.OPT_PREFILL_SPLITS) == 4
+        assert B.prefill_workspace_bytes(1, 2048, 2048, 133120, a) == 4 * 2048 * 8 * (128 + 2) * 4   # sizes follow the switch
+        B.set_option(B.OPT_GENERIC_ONLY, 1)
+        assert B.prefill_workspace_bytes(1, 2048, 2048, 133120, a) == 0 and B.decode_workspace_bytes(4, 64, a) == 0
+    finally:
+        for opt in (B.OPT_PREFILL_TILE, B.OPT_PREFILL_SPLITS, B.OPT_GENERIC_ONLY):
+            B.set_option(opt, 0)
+    assert B.prefill_workspace_bytes(1, 2048, 2048, 133120, a) == auto
 
 
 def test_struct_layouts_match_header(B):
