@@ -474,8 +474,14 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_flat_kernel(
 
 namespace {
 
-// sequences per launch: as many as give the kernel's pair index its fill
-inline int seqs_per_launch(const AttnShape& a) { return kFlatMaxPairs / a.hkv_l; }
+inline int padded_len(int max_seq_len) { return max_seq_len / kGroup * kGroup + kGroup; }  // >= the padded longest context
+// sequences per launch: as many as give the kernel's pair index its fill, and few enough that the padded token line of a
+// launch (pairs x padded longest context) stays below 2^31, the range of the kernel's 32-bit prefix sums
+inline int seqs_per_launch(int max_seq_len, const AttnShape& a) {
+    const int64_t by_line = (static_cast<int64_t>(0x7FFFFFFF) - kGroup) / padded_len(max_seq_len > 0 ? max_seq_len : 1) / a.hkv_l;
+    const int64_t by_index = kFlatMaxPairs / a.hkv_l;
+    return static_cast<int>(by_line < by_index ? by_line : by_index);
+}
 // partial rows of a launch over n sequences: one per (wavefront, pair) whose ranges meet, numbered wavefront + pair
 inline size_t flat_rows(int n, const AttnShape& a) {
     return (static_cast<size_t>(kFlatWorkers) + static_cast<size_t>(n) * a.hkv_l) * (a.hq_l / a.hkv_l);
@@ -483,12 +489,14 @@ inline size_t flat_rows(int n, const AttnShape& a) {
 
 }  // namespace
 
-bool decode_mfma_supported(const AttnShape& a, int /*num_seqs*/) {
-    return a.elem == 2 && a.D == kD && a.hq_l % a.hkv_l == 0 && a.hq_l / a.hkv_l <= 16 && a.hkv_l <= kFlatMaxPairs;
+bool decode_mfma_supported(const AttnShape& a, int /*num_seqs*/, int max_seq_len) {
+    return a.elem == 2 && a.D == kD && a.hq_l % a.hkv_l == 0 && a.hq_l / a.hkv_l <= 16 && a.hkv_l <= kFlatMaxPairs &&
+           max_seq_len <= 0x7FFFFFFF - 2 * kGroup && seqs_per_launch(max_seq_len, a) >= 1;
 }
 
-size_t decode_mfma_workspace(int num_seqs, int /*max_seq_len*/, const AttnShape& a) {
-    const int n = num_seqs < seqs_per_launch(a) ? num_seqs : seqs_per_launch(a);
+size_t decode_mfma_workspace(int num_seqs, int max_seq_len, const AttnShape& a) {
+    const int per = seqs_per_launch(max_seq_len, a);
+    const int n = num_seqs < per ? num_seqs : per;
     return flat_rows(n, a) * (kD + 2) * sizeof(float) + static_cast<size_t>(n) * a.hkv_l * sizeof(int2);
 }
 
@@ -505,7 +513,7 @@ hipError_t launch_decode_mfma(const void* q, const void* k_new, const void* v_ne
     int r_min = (padded_max / (kMaxParts - 24) + kGroup) / kGroup * kGroup;
     if (r_min < 2 * kGroup) r_min = 2 * kGroup;
     const bool append = k_new != nullptr;
-    const int per = seqs_per_launch(a);
+    const int per = seqs_per_launch(max_seq_len, a);
     for (int s0 = 0; s0 < num_seqs; s0 += per) {  // runs share the workspace: same stream, one after the other
         const int n = num_seqs - s0 < per ? num_seqs - s0 : per;
         const size_t rows = flat_rows(n, a);

@@ -225,19 +225,16 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
         // (or right after the barrier) would stall for a full memory round trip every iteration.
         const int n_u = __builtin_amdgcn_readfirstlane(n);
         const int32_t* table_u = reinterpret_cast<const int32_t*>(uniform_ptr(reinterpret_cast<const unsigned char*>(table)));
+        typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+        const const_i32_ptr table_c = (const_i32_ptr)table_u;
         auto fetch_id = [&](int j) SHIFTATTN_INLINE -> int {
-            // every term of the address is uniform and in scalar registers: the id is read with a scalar load (written as
-            // assembly: the compiler takes the vector path for a table it cannot prove unwritten) and arrives in a
-            // scalar register without a vector instruction.  It may be used only behind id_arrived().
+            // every term of the address is uniform, and the table is read through the constant address space: the
+            // compiler issues a scalar load, the id arrives in a scalar register without a vector instruction, and the
+            // compiler itself places the wait in front of the first use (the bottom of the iteration, see below)
             const int idx = min((kt_begin + grp_u + 2 * min(j, max(n_u - 1, 0))) * 4 + wg_u, last_block);
-            int v;
-            const unsigned char* addr = uniform_ptr(reinterpret_cast<const unsigned char*>(table_u + idx));
-            asm volatile("s_load_dword %0, %1, 0x0" : "=s"(v) : "s"(addr) : "memory");
-            return v;
+            return table_c[idx];
         };
-        auto id_arrived = [](int& a) SHIFTATTN_INLINE {   // scalar loads return through lgkmcnt
-            asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(a) : : "memory");
-        };
+        auto id_arrived = [](int&) SHIFTATTN_INLINE {};   // the use itself waits
         auto block_base = [&](int id) SHIFTATTN_INLINE -> const unsigned char* {
             return cache_g + static_cast<int64_t>(id) * blk_bytes;
         };
@@ -702,11 +699,10 @@ bool prefill_mfma_supported(const AttnShape& a, int num_seqs, int max_seq_len) {
 
 namespace {
 
-// Which of the two kernels serves a launch.  The 256-column kernel is the faster one per MFMA; it takes the launch when
-// its tiles fill the chip without splitting keys, or when the 128-column kernel would have to split keys as well (a short
-// chunk on a long context).  A batch like 4 x 4096 tokens with 4 query heads per KV head - 128 pairs of 256-column tiles,
-// 256 pairs of 128-column tiles - stays with the 128-column kernel, which covers the chip with equal workgroups and no
-// merge pass.
+// Which of the two kernels serves a launch.  The 256-column kernel is the faster one per MFMA (about 12 %), but its tiles
+// are twice as large: a batch like 4 x 4096 tokens with 4 query heads per KV head makes 128 pairs of 256-column tiles and
+// 256 pairs of 128-column tiles, and only the latter cover the chip with equal workgroups and no merge pass.  The choice
+// compares the two plans under the same rough model of a launch.
 struct Choice {
     bool wide;
     Plan narrow;
@@ -724,7 +720,9 @@ Choice choose(int num_seqs, int total_q, int max_q_len, int max_seq_len, const A
     c.w = prefill_mfma64_plan(num_seqs, total_q, max_q_len, max_seq_len, a, option_prefill_splits());
     const int forced = option_prefill_tile();
     if (forced == 128) return c;
-    c.wide = forced == 256 || c.w.n_splits == 1 || c.narrow.n_splits > 1;
+    const long wgs_n = static_cast<long>(c.narrow.pair_ranks) * num_seqs * c.narrow.head_slots;
+    const double t_narrow = 1.12 * launch_model_seconds(wgs_n, c.narrow.n_splits, 128, total_q, max_seq_len, a.hq_l);
+    c.wide = forced == 256 || c.w.model_seconds < 0.97 * t_narrow;
     return c;
 }
 
