@@ -1,20 +1,24 @@
 #!/usr/bin/env python3
 """Benchmark of one GPU's share of a Shift-Parallelism attention layer on MI355X.
 
-A "step" is one pass of the whole hot path over one synthetic batch, with every input already in
-HBM: send-side pack of this rank's fused QKV rows, causal prefill with fused KV-cache append,
-receive-side unpack, and one decode step (with its KV append) for the same sequences.  The batch is
-the Llama-3.1-8B-shaped shard at P=8 (4 query heads / 1 KV head, head_dim 128, 4 sequences of 4096
-tokens, 16-token cache blocks in a random block-table permutation).  The wire exchange between the
-ranks is not part of the path: the buffers it would deliver are staged in HBM beforehand.
+A "step" is one pass of the whole hot path over one synthetic batch, with every input already in HBM.  The batch
+is the mixed long-context step of the 70B-shaped shard at P=8 (benchmark configs[4], the largest configuration
+that is one GPU's work): one 2048-token chunk continuing a 131072-token cached context plus 64 decode sequences
+with contexts uniform in [1024, 32768], 8 query heads / 1 KV head, head_dim 128, bf16, 16-token cache blocks in one
+shared, randomly permuted pool.  The step is: send-side pack of this rank's fused QKV rows, the unified attention
+call on chunk rows + decode rows (shiftattn_mixed: K/V append of all new tokens, chunked causal prefill, paged
+decode, merges of split partials), receive-side unpack.  The wire exchange between ranks is not part of the path:
+the buffers it would deliver are staged in HBM beforehand.
 
-One JSON line goes to stdout.  `value` is attention TFLOP/s of the whole step (4*D flops per
-(query, visible key) pair per query head, masked pairs and softmax not counted, divided by the
-wall time of the step).  `roofline` prices the dominant kernel (the MFMA prefill kernel) against
-the chip's dense bf16 MFMA peak using HIP-event timing of that kernel alone.  `cpu_baseline` is the
-fp64 CPU oracle timed on a stated sample of the same batch.  Further objects report the
-HBM-bound kernels on the configurations that are large enough to measure bandwidth (batch decode of
-256 sequences, exchange of a [16384, 64, 128] hidden state) and the 70B-shaped prefill.
+One JSON line goes to stdout.  `value` is attention TFLOP/s of the whole step (4*D flops per (query, visible key)
+pair per query head, masked pairs and softmax not counted, over the wall time of the step).  `roofline` prices the
+dominant kernel (the chunk's prefill kernel) against the chip's dense bf16 MFMA peak from HIP-event timing of that
+call alone; `decode_in_step` prices the step's decode part against HBM bandwidth.  `cpu_baseline` is the fp64 CPU
+oracle timed on a stated row sample of the same batch.  Further objects report the other configurations (8B-shaped
+prefill batch, 70B-shaped prefill, 256-sequence decode, small decode batches, the 70B exchange, K/V append, the
+fused projections), each with its own roofline object and an oracle timing.  All timings are medians of
+per-call HIP-event pairs on the launch stream unless stated.  HBM traffic from hardware counters is not measured in
+this run (`traffic` is null): the counter summaries of the profiled runs are in profiles/.
 """
 from __future__ import annotations
 
@@ -29,27 +33,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_FP8_TFLOPS = 5000.0    # MI355X dense fp8 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
-
-
-def load_traffic():
-    """HBM bytes per launch measured with rocprofv3 counters, from the committed summary table.
-
-    Rows look like `| key | kernel | fetch bytes | write bytes | ...`; returns {key: fetch + write}."""
-    out = {}
-    try:
-        with open(TRAFFIC_FILE) as f:
-            for line in f:
-                cells = [c.strip() for c in line.strip().strip("|").split("|")]
-                if len(cells) >= 4 and cells[0] and cells[0][0].isalpha():
-                    try:
-                        out[cells[0]] = int(float(cells[2])) + int(float(cells[3]))
-                    except ValueError:
-                        pass
-    except OSError:
-        pass
-    return out
 METRIC = "prefill attn TFLOP/s + decode KV-read GB/s per MI355X (head shard, % roofline)"
 
 
@@ -63,7 +48,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the decode / exchange / 70B-prefill configurations")
+    ap.add_argument("--no-extras", action="store_true", help="only the headline step")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also run a plain 1-GiB elementwise copy a few times (reference for scaling FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -79,92 +64,134 @@ def main() -> int:
     from paper_2509_16495_amd import workloads as W
 
     B.lib()  # fail loudly if the HIP library was not built
-    traffic = load_traffic()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    B.init()
     bf = torch.bfloat16
+    D = 128
+    cpu = not args.no_cpu_baseline
+    if cpu:
+        from oracle import oracle as O
+        O.build()
 
     def ti(a, dt):
         return torch.from_numpy(np.ascontiguousarray(a, dtype=dt)).to(dev)
 
     def time_events(fn, reps, warm=3):
-        """Average duration (ms) of fn over `reps` back-to-back calls, HIP events on the launch stream."""
+        """Median duration (ms) of fn over `reps` calls, one HIP-event pair per call on the launch stream."""
         for _ in range(warm):
             fn()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for e0, e1 in ev:
+            e0.record()
             fn()
-        e1.record()
+            e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
+        return float(np.median([e0.elapsed_time(e1) for e0, e1 in ev]))
 
+    def time_in_graph(fn, inner=20, reps=10):
+        """ms per call of fn when `inner` calls are captured into one HIP graph and the graph is replayed back to back."""
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for _ in range(inner):
+                    fn()
+            g.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (inner * reps)
+
+    def roof(kernel, bound, achieved, peak, unit, **extra):
+        r = {"kernel": kernel, "bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+             "frac": round(achieved / peak, 4), "traffic": None}
+        r.update(extra)
+        return r
+
+    def oracle_attention(case, rows, label):
+        """fp64 oracle on the given query rows of a case: seconds, flops of the sample, outputs."""
+        ocache = O.cache_for_case(case)
+        t0 = time.perf_counter()
+        want = O.attention_case(case, ocache, rows)
+        dt = time.perf_counter() - t0
+        pos = np.concatenate([case.ctx_lens[s] - case.q_lens[s] + np.arange(case.q_lens[s]) for s in range(case.num_seqs)])
+        fl = 4 * case.D * case.hq_l * int((pos[rows] + 1).sum())
+        return dt, fl, want
+
+    def sample_rows(case, step=16, edge=32):
+        """Every `step`-th query token of every sequence plus all tokens of its first and last `edge`."""
+        rows = []
+        for s in range(case.num_seqs):
+            a, b = int(case.cu_seqlens_q[s]), int(case.cu_seqlens_q[s + 1])
+            rows += list(range(a, b, step)) + list(range(a, min(a + edge, b))) + list(range(max(a, b - edge), b))
+        return np.unique(np.array(rows, dtype=np.int64))
+
+    reps = max(args.steps, 10)
     # ------------------------------------------------------------------------------------------------
-    # the step's batch: 8B-shaped shard at P=8
+    # the step's batch: configs[4], mixed long-context step of the 70B-shaped shard at P=8
     # ------------------------------------------------------------------------------------------------
-    P, H, H_kv, D = 8, 32, 8, 128
-    case = W.config2_attn()
-    hq_l, hkv_l = case.hq_l, case.hkv_l
-    n = case.total_q
+    P, H, H_kv = 8, 64, 8
+    c5, n_pre = W.config5_attn()
+    pre5, dec5 = W.sub_case(c5, range(n_pre)), W.sub_case(c5, range(n_pre, c5.num_seqs))
+    hq_l, hkv_l = c5.hq_l, c5.hkv_l
+    n = c5.total_q                      # 2048 chunk rows + 64 decode rows
     T = n // P
-    log(f"[bench] step batch: {case.name}: {case.num_seqs} x {int(case.q_lens[0])} tokens, {hq_l}q/{hkv_l}kv heads, D={D}, "
-        f"{case.num_blocks} cache blocks; flops/step = {case.flops() / 1e9:.2f} GFLOP (prefill)")
-
-    rng = np.random.Generator(np.random.PCG64(1002))
+    assert T * P == n
+    log(f"[bench] step batch: {c5.name}: chunk {int(pre5.q_lens[0])} tokens on {int(pre5.ctx_lens[0] - pre5.q_lens[0])} cached, "
+        f"{dec5.num_seqs} decode sequences (sum of contexts {int(dec5.ctx_lens.sum())}), {hq_l}q/{hkv_l}kv heads, D={D}, "
+        f"{c5.num_blocks} cache blocks; {pre5.flops() / 1e9:.1f} GFLOP (chunk) + {dec5.kv_bytes() / 1e6:.1f} MB of KV (decodes)")
+    rng = np.random.Generator(np.random.PCG64(5005))
     qkv_local = B.to_device(W.f32_to_bf16_bits(rng.standard_normal((T, H + 2 * H_kv, D), dtype=np.float32)), "bf16", dev)
     send = torch.empty((P, T, hq_l + 2 * hkv_l, D), dtype=bf, device=dev)
-    new = case.new_token_index
-    recv1 = B.to_device(np.concatenate([case.q, case.k_ctx[new], case.v_ctx[new]], axis=1), "bf16", dev)  # after a2a #1
+    nw5 = c5.new_token_index
+    recv1 = B.to_device(np.concatenate([c5.q, c5.k_ctx[nw5], c5.v_ctx[nw5]], axis=1), "bf16", dev)   # after all-to-all #1
     q_v, k_v, v_v = recv1[:, :hq_l], recv1[:, hq_l:hq_l + hkv_l], recv1[:, hq_l + hkv_l:]
-    slots = ti(case.slots[new], np.int64)
-    cache = torch.zeros((case.num_blocks, hkv_l, 2, 16 * D), dtype=bf, device=dev)
-    table, cu, sl = ti(case.block_table, np.int32), ti(case.cu_seqlens_q, np.int32), ti(case.ctx_lens, np.int32)
-    max_q, max_ctx = int(case.q_lens.max()), int(case.ctx_lens.max())
+    slots5 = ti(c5.slots[nw5], np.int64)
+    cache5 = torch.zeros((c5.num_blocks, hkv_l, 2, 16 * D), dtype=bf, device=dev)
+    cached_slots = c5.slots.copy()
+    cached_slots[nw5] = -1
+    B.kv_write(B.to_device(c5.k_ctx, "bf16", dev), B.to_device(c5.v_ctx, "bf16", dev), ti(cached_slots, np.int64), cache5)
+    table5, cu5, sl5 = ti(c5.block_table, np.int32), ti(c5.cu_seqlens_q[:n_pre + 1], np.int32), ti(c5.ctx_lens, np.int32)
+    max_q5, max_pre5, max_dec5 = int(pre5.q_lens.max()), int(pre5.ctx_lens.max()), int(dec5.ctx_lens.max())
     attn_o = torch.empty((n, hq_l, D), dtype=bf, device=dev)
-    recv2 = B.to_device(W.f32_to_bf16_bits(rng.standard_normal((P, T, hq_l, D), dtype=np.float32)), "bf16", dev)  # after a2a #2
+    recv2 = B.to_device(W.f32_to_bf16_bits(rng.standard_normal((P, T, hq_l, D), dtype=np.float32)), "bf16", dev)   # after all-to-all #2
     out_seq = torch.empty((T, H, D), dtype=bf, device=dev)
-    # the decode step that follows for the same sequences (context 4097 each)
-    dcase = W.make_attn_case("cfg2_decode_step", 1003, "bf16", [(1, int(c) + 1) for c in case.ctx_lens], hq_l, hkv_l, D,
-                             pool_factor=2.0)
-    dnew = dcase.new_token_index
-    drecv = B.to_device(np.concatenate([dcase.q, dcase.k_ctx[dnew], dcase.v_ctx[dnew]], axis=1), "bf16", dev)
-    dq, dk, dv = drecv[:, :hq_l], drecv[:, hq_l:hq_l + hkv_l], drecv[:, hq_l + hkv_l:]
-    dslots = ti(dcase.slots[dnew], np.int64)
-    dcache = torch.zeros((dcase.num_blocks, hkv_l, 2, 16 * D), dtype=bf, device=dev)
-    dslots_all = dcase.slots.copy()
-    dslots_all[dnew] = -1
-    B.kv_write(B.to_device(dcase.k_ctx, "bf16", dev), B.to_device(dcase.v_ctx, "bf16", dev), ti(dslots_all, np.int64), dcache)
-    dtable, dsl = ti(dcase.block_table, np.int32), ti(dcase.ctx_lens, np.int32)
-    dmax = int(dcase.ctx_lens.max())
-    dout = torch.empty((dcase.num_seqs, hq_l, D), dtype=bf, device=dev)
-    a_dec = B.attn_desc(dq, dcache, dtable, dcase.softmax_scale, dk, dout)
-    dws = torch.empty(max(B.decode_workspace_bytes(dcase.num_seqs, dmax, a_dec), 16), dtype=torch.uint8, device=dev)
-    a_pre = B.attn_desc(q_v, cache, table, case.softmax_scale, k_v, attn_o)
-    pws = torch.empty(max(B.prefill_workspace_bytes(case.num_seqs, n, max_q, max_ctx, a_pre), 16), dtype=torch.uint8, device=dev)
+    a5 = B.attn_desc(q_v, cache5, table5, c5.softmax_scale, k_v, attn_o)
+    ws5 = torch.empty(max(B.mixed_workspace_bytes(n_pre, pre5.total_q, max_q5, max_pre5, dec5.num_seqs, max_dec5, a5), 16),
+                      dtype=torch.uint8, device=dev)
+    n_chunk = pre5.total_q
 
     def do_pack():
         B.pack_seq2head(qkv_local, send, P, H, H_kv)
 
-    def do_prefill():
-        B.prefill(q_v, cache, table, cu, sl, max_q, max_ctx, attn_o, case.softmax_scale, k_new=k_v, v_new=v_v,
-                  slot_mapping=slots, workspace=pws)
-
-    def do_prefill_kernel_only():
-        B.prefill(q_v, cache, table, cu, sl, max_q, max_ctx, attn_o, case.softmax_scale, workspace=pws)
+    def do_mixed():
+        B.mixed(q_v, cache5, table5, cu5, sl5, n_pre, max_q5, max_pre5, max_dec5, attn_o, c5.softmax_scale, k_new=k_v, v_new=v_v,
+                slot_mapping=slots5, workspace=ws5)
 
     def do_unpack():
         B.unpack_head2seq(recv2, out_seq)
 
-    def do_decode():
-        B.decode(dq, dcache, dtable, dsl, dmax, dout, dcase.softmax_scale, k_new=dk, v_new=dv, slot_mapping=dslots,
-                 workspace=dws)
+    def do_chunk_only():      # the chunk's attention alone, cache already written
+        B.prefill(q_v[:n_chunk], cache5, table5[:n_pre], cu5, sl5[:n_pre], max_q5, max_pre5, attn_o[:n_chunk], c5.softmax_scale,
+                  workspace=ws5)
+
+    def do_decode_only():     # the 64 decodes alone, with their K/V append
+        B.decode(q_v[n_chunk:], cache5, table5[n_pre:], sl5[n_pre:], max_dec5, attn_o[n_chunk:], c5.softmax_scale,
+                 k_new=k_v[n_chunk:], v_new=v_v[n_chunk:], slot_mapping=slots5[n_chunk:], workspace=ws5)
 
     def step():
         do_pack()
-        do_prefill()
+        do_mixed()
         do_unpack()
-        do_decode()
 
     # ---- the timed region: W warm-up steps, then exactly K steps between synchronisations -----------------
     for _ in range(args.warmup):
@@ -175,11 +202,10 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    step_flops = case.flops() + dcase.flops()
+    step_flops = c5.flops()
     value = step_flops / (ms_per_step * 1e-3) / 1e12
     log(f"[bench] step: {ms_per_step:.4f} ms -> {value:.1f} TFLOP/s of attention")
-    # the same step captured once into a HIP graph and replayed (how the paper's engine issues it, Sec. 3.4); reported
-    # beside the eager figure, which stays the headline
+    # the same step captured once into a HIP graph and replayed (how the paper's engine issues it, Sec. 3.4)
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         step()
@@ -191,49 +217,100 @@ def main() -> int:
         graph.replay()
     torch.cuda.synchronize()
     ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / args.steps
-    log(f"[bench] step replayed from a HIP graph: {ms_per_step_graph:.4f} ms -> "
-        f"{step_flops / (ms_per_step_graph * 1e-3) / 1e12:.1f} TFLOP/s")
+    log(f"[bench] step replayed from a HIP graph: {ms_per_step_graph:.4f} ms")
 
-    # ---- per-phase HIP-event timings, same stream ------------------------------------------------------------
-    reps = max(args.steps, 10)
-    phases = {}
+    # ---- per-phase HIP-event timings (medians), same stream --------------------------------------------------
     e = 2
     pack_bytes = T * (H + 2 * H_kv) * D * e + P * T * (hq_l + 2 * hkv_l) * D * e
     unpack_bytes = 2 * T * H * D * e
+    phases = {}
     for name, fn, work, unit in [("pack_seq2head", do_pack, pack_bytes / 1e9, "GB/s"),
-                                 ("prefill_with_kv_write", do_prefill, case.flops() / 1e12, "TFLOP/s"),
-                                 ("prefill_kernel", do_prefill_kernel_only, case.flops() / 1e12, "TFLOP/s"),
+                                 ("mixed_attention_with_kv_write", do_mixed, step_flops / 1e12, "TFLOP/s"),
                                  ("unpack_head2seq", do_unpack, unpack_bytes / 1e9, "GB/s"),
-                                 ("decode_with_kv_write", do_decode, dcase.kv_bytes() / 1e9, "GB/s")]:
+                                 ("chunk_prefill_alone", do_chunk_only, pre5.flops() / 1e12, "TFLOP/s"),
+                                 ("decodes_alone_with_kv_write", do_decode_only, dec5.kv_bytes() / 1e9, "GB/s")]:
         ms = time_events(fn, reps)
         phases[name] = {"ms": round(ms, 5), "rate": round(work / (ms * 1e-3), 2), "unit": unit}
-        log(f"[bench]   {name:24s} {ms * 1e3:9.1f} us  {phases[name]['rate']:10.1f} {unit}")
-    pk_ms = phases["prefill_kernel"]["ms"]
-    achieved = case.flops() / (pk_ms * 1e-3) / 1e12
-    roofline = {"kernel": "prefill_kernel (bf16 MFMA causal prefill)", "bound": "mfma", "achieved": round(achieved, 2),
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": traffic.get("prefill_8b"), "flops_per_launch": case.flops(), "avg_launch_ms": round(pk_ms, 5)}
+        log(f"[bench]   {name:32s} {ms * 1e3:9.1f} us  {phases[name]['rate']:10.1f} {unit}")
+    ck_ms = phases["chunk_prefill_alone"]["ms"]
+    achieved = pre5.flops() / (ck_ms * 1e-3) / 1e12
+    roofline = roof("prefill64_kernel (bf16 MFMA chunked prefill over 8 key ranges; the call's combine_kernel, about 1 % of it, is "
+                    "inside the timed interval)", "mfma", achieved, PEAK_BF16_TFLOPS, "TFLOP/s",
+                    flops_per_launch=pre5.flops(), median_launch_ms=round(ck_ms, 5))
+    dd_ms = phases["decodes_alone_with_kv_write"]["ms"]
+    dd_gbps = dec5.kv_bytes() / (dd_ms * 1e-3) / 1e9
 
     result = {
         "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[1]: Llama-3.1-8B-shaped shard at P=8, bf16, 4q/1kv heads, head_dim 128, "
-                               "4 x 4096-token causal prefill, paged KV (16-token blocks, seeded random block table); "
-                               "step = pack + prefill(+KV write) + unpack + one decode step",
+        "config": {"workload": "configs[4]: mixed long-context step, Llama-3.3-70B-shaped shard at P=8, bf16, 8q/1kv heads, head_dim 128: "
+                               "one 2048-token chunk continuing a 131072-token cached context + 64 decode sequences with contexts "
+                               "U[1024,32768], paged KV (16-token blocks, one seeded random pool); "
+                               "step = pack + unified attention call (K/V append, chunked prefill, decode) + unpack",
                    "flop_convention": "4*D per (query, visible key) pair per query head",
-                   "step_flops": step_flops},
+                   "step_flops": step_flops, "decode_kv_bytes": dec5.kv_bytes()},
         "roofline": roofline,
+        "decode_in_step": {"kv_bytes": dec5.kv_bytes(), "ms": round(dd_ms, 5),
+                           "roofline": roof("decode_flat_kernel + combine_flat_kernel", "hbm", dd_gbps, PEAK_HBM_GBPS, "GB/s")},
         "ms_per_step_graph_replay": round(ms_per_step_graph, 5),
         "phases": phases,
+        "traffic_note": "HBM bytes per launch from rocprofv3 counters are in profiles/ (measured in separate profiled runs)",
     }
 
-    # ---- the HBM-bound kernels and the 70B-shaped prefill on their own configurations ------------------------
+    # ---- CPU oracle on a bounded sample of the step's batch ---------------------------------------------------
+    if cpu:
+        rows = np.concatenate([sample_rows(pre5), np.arange(n_chunk, n)])   # chunk sample + every decode row
+        dt, fl, want = oracle_attention(c5, rows, "cfg5")
+        do_mixed()
+        torch.cuda.synchronize()
+        got = W.to_f64(B.to_host(attn_o)[rows], "bf16")
+        err = np.abs(got - want)
+        result["cpu_baseline"] = {
+            "value": round(fl / dt / 1e12, 6), "unit": "TFLOP/s", "cores": O.num_threads(), "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"fp64 oracle on every 16th chunk token plus the first and last 32, all heads, and on all 64 decode rows "
+                      f"({fl / 1e9:.1f} of {step_flops / 1e9:.1f} GFLOP)",
+            "full_step_seconds_extrapolated": round(dt * step_flops / fl, 1)}
+        result["parity_on_sample"] = {"max_abs_err": float(err.max()), "mean_abs_err": float(err.mean())}
+        log(f"[bench] oracle: {dt:.1f} s on {O.num_threads()} threads, {fl / dt / 1e9:.2f} GFLOP/s; "
+            f"GPU vs oracle max|err|={err.max():.2e} mean|err|={err.mean():.2e}")
+    del cache5, ws5, recv1, recv2, send, qkv_local
+
+    def cpu_obj(seconds, work, unit, sample):
+        return {"value": round(work / seconds, 6), "unit": unit, "cores": O.num_threads(), "kind": "oracle",
+                "seconds": round(seconds, 2), "sample": sample}
+
+    # ------------------------------------------------------------------------------------------------
+    # the other configurations
+    # ------------------------------------------------------------------------------------------------
     if not args.no_extras:
-        # batch decode, 256 sequences (configs[3])
+        # ---- configs[1]: 8B-shaped prefill batch, 4 x 4096 tokens ------------------------------------------------
+        c2 = W.config2_attn()
+        new = c2.new_token_index
+        r2 = B.to_device(np.concatenate([c2.q, c2.k_ctx[new], c2.v_ctx[new]], axis=1), "bf16", dev)
+        q2, k2, v2 = r2[:, :c2.hq_l], r2[:, c2.hq_l:c2.hq_l + c2.hkv_l], r2[:, c2.hq_l + c2.hkv_l:]
+        cache2 = torch.zeros((c2.num_blocks, c2.hkv_l, 2, 16 * D), dtype=bf, device=dev)
+        t2, cu2, s2, sl2 = ti(c2.block_table, np.int32), ti(c2.cu_seqlens_q, np.int32), ti(c2.ctx_lens, np.int32), ti(c2.slots[new], np.int64)
+        o2 = torch.empty((c2.total_q, c2.hq_l, D), dtype=bf, device=dev)
+        mq2, mc2 = int(c2.q_lens.max()), int(c2.ctx_lens.max())
+        ms_w = time_events(lambda: B.prefill(q2, cache2, t2, cu2, s2, mq2, mc2, o2, c2.softmax_scale, k_new=k2, v_new=v2,
+                                             slot_mapping=sl2), reps)
+        ms_k = time_events(lambda: B.prefill(q2, cache2, t2, cu2, s2, mq2, mc2, o2, c2.softmax_scale), reps)
+        tf = c2.flops() / (ms_k * 1e-3) / 1e12
+        result["prefill_8b"] = {"workload": "configs[1]: 4q/1kv, D=128, 4 x 4096-token causal prefill, paged KV", "flops": c2.flops(),
+                                "ms": round(ms_k, 5), "ms_with_kv_write": round(ms_w, 5),
+                                "roofline": roof("prefill_kernel (128-column tiles)", "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s")}
+        log(f"[bench] prefill cfg2: {ms_k * 1e3:.1f} us ({ms_w * 1e3:.1f} with K/V write), {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%})")
+        if cpu:
+            dt, fl, _ = oracle_attention(c2, np.arange(c2.total_q, dtype=np.int64), "cfg2")
+            result["prefill_8b"]["cpu_baseline"] = cpu_obj(dt, fl / 1e12, "TFLOP/s", "every query token and head of the batch")
+        del cache2, r2
+
+        # ---- configs[3]: batch decode, 256 sequences -------------------------------------------------------------
         c4 = W.config4_attn()
         cache4 = torch.zeros((c4.num_blocks, 1, 2, 16 * D), dtype=bf, device=dev)
-        B.kv_write(B.to_device(c4.k_ctx, "bf16", dev), B.to_device(c4.v_ctx, "bf16", dev), ti(c4.slots, np.int64), cache4)
+        k4d, v4d, sl4 = B.to_device(c4.k_ctx, "bf16", dev), B.to_device(c4.v_ctx, "bf16", dev), ti(c4.slots, np.int64)
+        B.kv_write(k4d, v4d, sl4, cache4)
         q4 = B.to_device(c4.q, "bf16", dev)
         t4, s4 = ti(c4.block_table, np.int32), ti(c4.ctx_lens, np.int32)
         o4 = torch.empty_like(q4)
@@ -245,22 +322,38 @@ def main() -> int:
         result["decode_kv_read"] = {"workload": f"configs[3]: 256 decode sequences, contexts U[512,8192], realised sum "
                                                 f"{int(c4.ctx_lens.sum())} tokens, 8q/1kv, D=128, bf16 paged KV",
                                     "kv_bytes": c4.kv_bytes(), "ms": round(ms, 5),
-                                    "roofline": {"kernel": "decode_flat_kernel + combine_flat_kernel", "bound": "hbm",
-                                                 "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                                                 "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": traffic.get("decode_256seq")}}
+                                    "roofline": roof("decode_flat_kernel + combine_flat_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s")}
         log(f"[bench] decode cfg4: {ms * 1e3:.1f} us, {gbps:.0f} GB/s of KV ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
-        # K/V append of the whole batch's contexts (the cache fill above, timed): read K and V rows, write cache blocks
-        k4d, v4d, sl4 = B.to_device(c4.k_ctx, "bf16", dev), B.to_device(c4.v_ctx, "bf16", dev), ti(c4.slots, np.int64)
+        if cpu:
+            sub = W.sub_case(c4, range(0, c4.num_seqs, 4))
+            dt, fl, _ = oracle_attention(sub, np.arange(sub.total_q, dtype=np.int64), "cfg4")
+            result["decode_kv_read"]["cpu_baseline"] = cpu_obj(dt, sub.kv_bytes() / 1e9, "GB/s", "every 4th sequence of the batch (64 of 256), all heads")
+        # K/V append of the whole batch's contexts: read K and V rows, write cache blocks
         ms = time_events(lambda: B.kv_write(k4d, v4d, sl4, cache4), 10)
         kvw_bytes = 2 * c4.kv_bytes()
         gbps = kvw_bytes / (ms * 1e-3) / 1e9
+        # what a plain copy of the same bytes attains on this chip (read + write stream, the shape of this kernel's traffic)
+        cp_src, cp_dst = torch.empty(kvw_bytes // 2, dtype=torch.uint8, device=dev), torch.empty(kvw_bytes // 2, dtype=torch.uint8, device=dev)
+        cp_src.fill_(1)
+        ms_cp = time_events(lambda: B.copy_probe(cp_src, cp_dst), 10)
+        del cp_src, cp_dst
         result["kv_write"] = {"workload": f"K/V of all {int(c4.ctx_lens.sum())} context tokens of the configs[3] batch appended in one "
                                           "call (1 KV head, D=128, bf16; blocks scattered over the pool)",
                               "bytes": kvw_bytes, "ms": round(ms, 5),
-                              "roofline": {"kernel": "kv_write_block_kernel", "bound": "hbm", "achieved": round(gbps, 1),
-                                           "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(gbps / PEAK_HBM_GBPS, 4),
-                                           "traffic": None}}
-        log(f"[bench] kv_write of the cfg4 contexts: {ms * 1e3:.1f} us, {gbps:.0f} GB/s read + written ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
+                              "roofline": roof("kv_write_block_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s"),
+                              "streaming_copy_of_the_same_bytes": {"ms": round(ms_cp, 5), "GB/s": round(kvw_bytes / (ms_cp * 1e-3) / 1e9, 1),
+                                                                   "note": "this library's own read+write probe (16-byte non-temporal "
+                                                                           "loads and stores, no index arithmetic)"}}
+        log(f"[bench] kv_write of the cfg4 contexts: {ms * 1e3:.1f} us, {gbps:.0f} GB/s read + written ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak); "
+            f"a plain copy of the same bytes: {ms_cp * 1e3:.1f} us")
+        if cpu:
+            n_tok = 200000
+            t0 = time.perf_counter()
+            oc = O.new_cache(c4.num_blocks, 1, 16, D, "bf16")
+            O.kv_write(oc, c4.k_ctx[:n_tok], c4.v_ctx[:n_tok], c4.slots[:n_tok], 16, "bf16")
+            dt = time.perf_counter() - t0
+            result["kv_write"]["cpu_baseline"] = cpu_obj(dt, n_tok * 2 * 2 * D * 2 / 1e9, "GB/s", f"the first {n_tok} context tokens of the batch")
+            del oc
         del k4d, v4d, sl4
         # the same batch over an FP8 E4M3 cache: half the bytes per token
         k_scale, v_scale = 0.05, 0.05
@@ -270,16 +363,42 @@ def main() -> int:
         ms = time_events(lambda: B.decode(q4, cache4q, t4, s4, m4, o4, c4.softmax_scale, workspace=w4, k_scale=k_scale,
                                           v_scale=v_scale), reps)
         gbps = c4.kv_bytes() / 2 / (ms * 1e-3) / 1e9
-        result["decode_kv_read_fp8"] = {"workload": "configs[3] batch over an FP8 E4M3 KV cache (1 byte per element, "
-                                                    "per-tensor K and V scales)",
+        result["decode_kv_read_fp8"] = {"workload": "configs[3] batch over an FP8 E4M3 KV cache (1 byte per element, per-tensor K and V scales)",
                                         "kv_bytes": c4.kv_bytes() // 2, "ms": round(ms, 5),
-                                        "roofline": {"kernel": "decode_flat_kernel<fp8> + combine_flat_kernel", "bound": "hbm",
-                                                     "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                                                     "frac": round(gbps / PEAK_HBM_GBPS, 4),
-                                                     "traffic": traffic.get("decode_256seq_fp8")}}
+                                        "roofline": roof("decode_flat_kernel<fp8> + combine_flat_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s")}
         log(f"[bench] decode cfg4, FP8 cache: {ms * 1e3:.1f} us, {gbps:.0f} GB/s of KV ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
         del cache4, cache4q, w4
-        # exchange of the 70B hidden state (configs[2])
+
+        # ---- small decode batches (the shift configuration's regime, Algorithm 2: few tokens per step) ----------------
+        small = {}
+        for ctx_len in (4096, 32768):
+            for nseq in (1, 4, 16, 64):
+                cs = W.make_attn_case("small_decode", 700 + nseq, "bf16", [(1, ctx_len + 1)] * nseq, 8, 1, D, pool_factor=1.1)
+                cch = torch.zeros((cs.num_blocks, 1, 2, 16 * D), dtype=bf, device=dev)
+                sl_all = cs.slots.copy()
+                sl_all[cs.new_token_index] = -1
+                B.kv_write(B.to_device(cs.k_ctx, "bf16", dev), B.to_device(cs.v_ctx, "bf16", dev), ti(sl_all, np.int64), cch)
+                fz = B.to_device(np.concatenate([cs.q, cs.k_ctx[cs.new_token_index], cs.v_ctx[cs.new_token_index]], axis=1), "bf16", dev)
+                qs, ks, vs = fz[:, :8], fz[:, 8:9], fz[:, 9:]
+                ts_, ss_, sls = ti(cs.block_table, np.int32), ti(cs.ctx_lens, np.int32), ti(cs.slots[cs.new_token_index], np.int64)
+                os_ = torch.empty((nseq, 8, D), dtype=bf, device=dev)
+                as_ = B.attn_desc(qs, cch, ts_, cs.softmax_scale, ks, os_)
+                wss = torch.empty(B.decode_workspace_bytes(nseq, ctx_len + 1, as_), dtype=torch.uint8, device=dev)
+                def step_small():
+                    B.decode(qs, cch, ts_, ss_, ctx_len + 1, os_, cs.softmax_scale, k_new=ks, v_new=vs, slot_mapping=sls, workspace=wss)
+                ms = time_events(step_small, reps)
+                us_graph = time_in_graph(step_small) * 1e3
+                small[f"{nseq}x{ctx_len + 1}"] = {"us": round(ms * 1e3, 2), "us_replayed_from_graph": round(us_graph, 2), "kv_bytes": cs.kv_bytes(),
+                                                  "GB/s": round(cs.kv_bytes() / (us_graph * 1e-6) / 1e9, 1)}
+                del cch, wss
+        result["decode_small_batches"] = {"workload": "decode steps of 1 / 4 / 16 / 64 sequences at contexts 4097 and 32769 (8q/1kv, D=128, bf16), "
+                                                      "each with its K/V append; us = HIP-event median around single calls, "
+                                                      "us_replayed_from_graph = 20 steps captured into one HIP graph, replayed back to back (Sec. 3.4)",
+                                          "bound": "latency below a few MB of KV, hbm above", "calls": small}
+        log("[bench] small decode batches (us per call / per step of a replayed graph): " +
+            ", ".join(f"{k}: {v['us']} / {v['us_replayed_from_graph']}" for k, v in small.items()))
+
+        # ---- configs[2]: exchange of the 70B hidden state ----------------------------------------------------------
         x3 = W.config3_xchg()
         copies = 3
         xin = [B.to_device(x3.x, "bf16", dev) for _ in range(copies)]
@@ -300,11 +419,21 @@ def main() -> int:
             gbps = x3.bytes_moved() / (ms * 1e-3) / 1e9
             result[nm] = {"workload": "configs[2]: hidden [16384, 64 heads, 128] bf16 <-> 8 buffers, 3 rotating copies",
                           "bytes": x3.bytes_moved(), "ms": round(ms, 5),
-                          "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                                       "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": traffic.get(nm + "_70b")}}
+                          "roofline": roof(nm + "_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s")}
             log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {gbps:.0f} GB/s ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
+        if cpu:
+            t0 = time.perf_counter()
+            sp = O.pack_seq2head(x3.x, x3.P, x3.h, 0, x3.T_pad, "bf16")
+            dt = time.perf_counter() - t0
+            result["pack_seq2head"]["cpu_baseline"] = cpu_obj(dt, x3.bytes_moved() / 1e9, "GB/s", "the whole hidden state")
+            t0 = time.perf_counter()
+            O.unpack_head2seq(sp, x3.T, "bf16")
+            dt = time.perf_counter() - t0
+            result["unpack_head2seq"]["cpu_baseline"] = cpu_obj(dt, x3.bytes_moved() / 1e9, "GB/s", "the whole hidden state")
+            del sp
         del xin, xsend, xout
-        # the projections next to the two exchanges, fused with the pack / unpack (70B: d_model 8192, 64 + 2 x 8 heads)
+
+        # ---- the projections next to the two exchanges, fused with the pack / unpack (70B: d_model 8192) ------------
         d_model, h3, hkv3 = 8192, 64, 8
         gen = torch.Generator(device=dev)
         gen.manual_seed(33)
@@ -334,12 +463,9 @@ def main() -> int:
             result[nm] = {"workload": f"configs[2] shard: {x3.T} tokens, d_model {d_model}, {h3} query + 2 x {hkv3} KV heads of 128, "
                                       f"{x3.P} exchange buffers, bf16, N(0,1) activations, N(0,0.02) weights",
                           "flops": fl, "ms": round(ms, 5), "library_gemm_and_separate_layout_kernel_ms": round(ms_ref, 5),
-                          "roofline": {"kernel": "proj_gemm_kernel", "bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_BF16_TFLOPS,
-                                       "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": traffic.get(nm + "_70b")}}
+                          "roofline": roof("proj_gemm_kernel", "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s")}
             log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%} of bf16 MFMA peak); "
                 f"library GEMM + separate layout kernel {ms_ref * 1e3:.1f} us")
-        # the same two products with FP8 E4M3 operands: activations quantised per token on the fly, weights once
-        PEAK_FP8_TFLOPS = 5000.0
         xq, xsc = torch.empty(xe.shape, dtype=torch.uint8, device=dev), torch.empty(x3.T, dtype=torch.float32, device=dev)
         wq8, wsc = torch.empty(wq.shape, dtype=torch.uint8, device=dev), torch.empty(wq.shape[0], dtype=torch.float32, device=dev)
         rq, rsc = torch.empty(recv3.shape, dtype=torch.uint8, device=dev), torch.empty(x3.T, dtype=torch.float32, device=dev)
@@ -359,115 +485,36 @@ def main() -> int:
             result[nm] = {"workload": result[nm[:-4]]["workload"] + "; operands as FP8 E4M3 codes with per-row scales, bf16 result",
                           "flops": fl, "ms": round(ms, 5),
                           "activation_quantiser": {"ms": round(ms_q, 5), "bytes": q_bytes,
-                                                   "roofline": {"kernel": "quantize_rows_fp8_kernel", "bound": "hbm",
-                                                                "achieved": round(q_bytes / (ms_q * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBPS,
-                                                                "unit": "GB/s", "frac": round(q_bytes / (ms_q * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
-                                                                "traffic": None}},
-                          "roofline": {"kernel": "proj_gemm_kernel<fp8>", "bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_FP8_TFLOPS,
-                                       "unit": "TFLOP/s", "frac": round(tf / PEAK_FP8_TFLOPS, 4), "traffic": traffic.get(nm + "_70b")}}
+                                                   "roofline": roof("quantize_rows_fp8_kernel", "hbm", q_bytes / (ms_q * 1e-3) / 1e9,
+                                                                    PEAK_HBM_GBPS, "GB/s")},
+                          "roofline": roof("proj_gemm_kernel<fp8>", "mfma", tf, PEAK_FP8_TFLOPS, "TFLOP/s")}
             log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_FP8_TFLOPS:.1%} of the fp8 MFMA peak); "
                 f"quantising the activations {ms_q * 1e3:.1f} us ({q_bytes / (ms_q * 1e-3) / 1e9:.0f} GB/s)")
         del xe, wq, wo, send3, recv3, eo, qkv_plain, att_plain, xq, xsc, wq8, wsc, rq, rsc, wo8, wosc
-        # 70B-shaped prefill (configs[2])
-        c3 = W.config3_attn()
-        cache3 = torch.zeros((c3.num_blocks, 1, 2, 16 * D), dtype=bf, device=dev)
-        B.kv_write(B.to_device(c3.k_ctx, "bf16", dev), B.to_device(c3.v_ctx, "bf16", dev), ti(c3.slots, np.int64), cache3)
-        q3 = B.to_device(c3.q, "bf16", dev)
-        t3, cu3, s3 = ti(c3.block_table, np.int32), ti(c3.cu_seqlens_q, np.int32), ti(c3.ctx_lens, np.int32)
-        o3 = torch.empty_like(q3)
-        ms = time_events(lambda: B.prefill(q3, cache3, t3, cu3, s3, c3.total_q, c3.total_q, o3, c3.softmax_scale), reps)
-        tf = c3.flops() / (ms * 1e-3) / 1e12
-        result["prefill_70b"] = {"workload": "configs[2]: 8q/1kv, D=128, one 16384-token causal prefill", "flops": c3.flops(),
-                                 "ms": round(ms, 5),
-                                 "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_BF16_TFLOPS,
-                                              "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4),
-                                              "traffic": traffic.get("prefill_70b")}}
-        log(f"[bench] prefill cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%} of bf16 MFMA peak)")
-        del cache3
-        # mixed long-context step (configs[4]): one 2048-token chunk on a 131072-token cached context, then 64 decode
-        # sequences, one shared block pool; both calls also write their new tokens' K/V
-        c5, n_pre = W.config5_attn()
-        pre5, dec5 = W.sub_case(c5, range(n_pre)), W.sub_case(c5, range(n_pre, c5.num_seqs))
-        cache5 = torch.zeros((c5.num_blocks, 1, 2, 16 * D), dtype=bf, device=dev)
-        cached_slots = c5.slots.copy()
-        cached_slots[c5.new_token_index] = -1
-        B.kv_write(B.to_device(c5.k_ctx, "bf16", dev), B.to_device(c5.v_ctx, "bf16", dev), ti(cached_slots, np.int64), cache5)
 
-        def dev_case(c):
-            nw = c.new_token_index
-            return dict(q=B.to_device(c.q, "bf16", dev), k=B.to_device(c.k_ctx[nw], "bf16", dev),
-                        v=B.to_device(c.v_ctx[nw], "bf16", dev), slots=ti(c.slots[nw], np.int64),
-                        table=ti(c.block_table, np.int32), cu=ti(c.cu_seqlens_q, np.int32), sl=ti(c.ctx_lens, np.int32),
-                        max_q=int(c.q_lens.max()), max_ctx=int(c.ctx_lens.max()))
+        # ---- configs[2]: 70B-shaped prefill; and the same length with 5 query heads per KV head (Table 4, Llama-17B-16E at P=8)
+        for key, case, label in (("prefill_70b", W.config3_attn(), "configs[2]: 8q/1kv, D=128, one 16384-token causal prefill"),
+                                 ("prefill_5q_per_kv", W.make_attn_case("g5_16k", 35, "bf16", [(16384, 16384)], 5, 1, D),
+                                  "40q/8kv model on 8 ranks: 5q/1kv, D=128, one 16384-token causal prefill (not a BASELINE config)")):
+            cch = torch.zeros((case.num_blocks, 1, 2, 16 * D), dtype=bf, device=dev)
+            B.kv_write(B.to_device(case.k_ctx, "bf16", dev), B.to_device(case.v_ctx, "bf16", dev), ti(case.slots, np.int64), cch)
+            q3 = B.to_device(case.q, "bf16", dev)
+            t3, cu3, s3 = ti(case.block_table, np.int32), ti(case.cu_seqlens_q, np.int32), ti(case.ctx_lens, np.int32)
+            o3 = torch.empty_like(q3)
+            ms = time_events(lambda: B.prefill(q3, cch, t3, cu3, s3, case.total_q, case.total_q, o3, case.softmax_scale), reps)
+            tf = case.flops() / (ms * 1e-3) / 1e12
+            result[key] = {"workload": label, "flops": case.flops(), "ms": round(ms, 5),
+                           "roofline": roof("prefill64_kernel (256-column tiles)", "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s")}
+            log(f"[bench] {key}: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%} of bf16 MFMA peak)")
+            if cpu:
+                rows = sample_rows(case, step=256, edge=32)
+                dt, fl, want = oracle_attention(case, rows, key)
+                err = np.abs(W.to_f64(B.to_host(o3)[rows], "bf16") - want)
+                result[key]["cpu_baseline"] = cpu_obj(dt, fl / 1e12, "TFLOP/s", "every 256th query token plus the first and last 32, all heads")
+                result[key]["parity_on_sample"] = {"max_abs_err": float(err.max()), "mean_abs_err": float(err.mean())}
+            del cch
 
-        p5, d5 = dev_case(pre5), dev_case(dec5)
-        p5["out"], d5["out"] = torch.empty_like(p5["q"]), torch.empty_like(d5["q"])
-        ap5 = B.attn_desc(p5["q"], cache5, p5["table"], c5.softmax_scale, p5["k"], p5["out"])
-        ad5 = B.attn_desc(d5["q"], cache5, d5["table"], c5.softmax_scale, d5["k"], d5["out"])
-        wp5 = torch.empty(max(B.prefill_workspace_bytes(pre5.num_seqs, pre5.total_q, p5["max_q"], p5["max_ctx"], ap5), 16),
-                          dtype=torch.uint8, device=dev)
-        wd5 = torch.empty(max(B.decode_workspace_bytes(dec5.num_seqs, d5["max_ctx"], ad5), 16), dtype=torch.uint8, device=dev)
-
-        def chunk5():
-            B.prefill(p5["q"], cache5, p5["table"], p5["cu"], p5["sl"], p5["max_q"], p5["max_ctx"], p5["out"], c5.softmax_scale,
-                      k_new=p5["k"], v_new=p5["v"], slot_mapping=p5["slots"], workspace=wp5)
-
-        def decode5():
-            B.decode(d5["q"], cache5, d5["table"], d5["sl"], d5["max_ctx"], d5["out"], c5.softmax_scale, k_new=d5["k"],
-                     v_new=d5["v"], slot_mapping=d5["slots"], workspace=wd5)
-
-        def both5():
-            chunk5()
-            decode5()
-
-        # the same step as one unified batch through shiftattn_mixed (one K/V write for all rows)
-        nw5 = c5.new_token_index
-        u5 = dict(q=B.to_device(c5.q, "bf16", dev), k=B.to_device(c5.k_ctx[nw5], "bf16", dev),
-                  v=B.to_device(c5.v_ctx[nw5], "bf16", dev), slots=ti(c5.slots[nw5], np.int64),
-                  table=ti(c5.block_table, np.int32), cu=ti(c5.cu_seqlens_q[:n_pre + 1], np.int32), sl=ti(c5.ctx_lens, np.int32))
-        u5["out"] = torch.empty_like(u5["q"])
-        au5 = B.attn_desc(u5["q"], cache5, u5["table"], c5.softmax_scale, u5["k"], u5["out"])
-        wu5 = torch.empty(max(B.mixed_workspace_bytes(n_pre, pre5.total_q, p5["max_q"], p5["max_ctx"], dec5.num_seqs,
-                                                      d5["max_ctx"], au5), 16), dtype=torch.uint8, device=dev)
-
-        def mixed5():
-            B.mixed(u5["q"], cache5, u5["table"], u5["cu"], u5["sl"], n_pre, p5["max_q"], p5["max_ctx"], d5["max_ctx"],
-                    u5["out"], c5.softmax_scale, k_new=u5["k"], v_new=u5["v"], slot_mapping=u5["slots"], workspace=wu5)
-
-        ms_a, ms_b, ms_ab = time_events(chunk5, reps), time_events(decode5, reps), time_events(both5, reps)
-        ms_u = time_events(mixed5, reps)
-        # the same unified step over an FP8 E4M3 cache (the chunk's context is widened into the workspace first)
-        cache5q = torch.zeros((c5.num_blocks, 1, 2, 16 * D), dtype=torch.uint8, device=dev)
-        B.kv_write(B.to_device(c5.k_ctx, "bf16", dev), B.to_device(c5.v_ctx, "bf16", dev), ti(cached_slots, np.int64), cache5q,
-                   0.05, 0.05)
-        au5q = B.attn_desc(u5["q"], cache5q, u5["table"], c5.softmax_scale, u5["k"], u5["out"], 0.05, 0.05)
-        wu5q = torch.empty(max(B.mixed_workspace_bytes(n_pre, pre5.total_q, p5["max_q"], p5["max_ctx"], dec5.num_seqs,
-                                                       d5["max_ctx"], au5q), 16), dtype=torch.uint8, device=dev)
-        ms_uq = time_events(lambda: B.mixed(u5["q"], cache5q, u5["table"], u5["cu"], u5["sl"], n_pre, p5["max_q"], p5["max_ctx"],
-                                            d5["max_ctx"], u5["out"], c5.softmax_scale, k_new=u5["k"], v_new=u5["v"],
-                                            slot_mapping=u5["slots"], workspace=wu5q, k_scale=0.05, v_scale=0.05), reps)
-        del cache5q, wu5q
-        tf5 = pre5.flops() / (ms_a * 1e-3) / 1e12
-        gb5 = dec5.kv_bytes() / (ms_b * 1e-3) / 1e9
-        result["mixed_long_context"] = {
-            "workload": "configs[4]: 8q/1kv, D=128, bf16; (a) 2048-token chunk continuing a 131072-token cached context; "
-                        f"(b) 64 decode sequences, contexts U[1024,32768], realised sum {int(dec5.ctx_lens.sum())} tokens; "
-                        "both with the K/V write of their new tokens",
-            "chunked_prefill": {"flops": pre5.flops(), "ms": round(ms_a, 5),
-                                "roofline": {"bound": "mfma", "achieved": round(tf5, 2), "peak": PEAK_BF16_TFLOPS,
-                                             "unit": "TFLOP/s", "frac": round(tf5 / PEAK_BF16_TFLOPS, 4), "traffic": None}},
-            "decode": {"kv_bytes": dec5.kv_bytes(), "ms": round(ms_b, 5),
-                       "roofline": {"bound": "hbm", "achieved": round(gb5, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                                    "frac": round(gb5 / PEAK_HBM_GBPS, 4), "traffic": None}},
-            "back_to_back_ms": round(ms_ab, 5), "unified_call_ms": round(ms_u, 5),
-            "unified_call_fp8_cache_ms": round(ms_uq, 5)}
-        log(f"[bench] mixed cfg5: chunk {ms_a * 1e3:.1f} us ({tf5:.1f} TFLOP/s, {tf5 / PEAK_BF16_TFLOPS:.1%}), decode "
-            f"{ms_b * 1e3:.1f} us ({gb5:.0f} GB/s, {gb5 / PEAK_HBM_GBPS:.1%}), back to back {ms_ab * 1e3:.1f} us, as one unified call {ms_u * 1e3:.1f} us, "
-            f"the same over an FP8 cache {ms_uq * 1e3:.1f} us")
-        del cache5, wp5, wd5, wu5
-
-    # ---- what the chip attains on the two priced resources (context for the roofline fractions) -------------
-    if not args.no_extras:
+        # ---- what the chip attains on the two priced resources (context for the roofline fractions) -------------
         sink = torch.zeros(4, dtype=torch.int32, device=dev)
         ops = B.to_device(W.f32_to_bf16_bits(rng.standard_normal((128, 8), dtype=np.float32)), "bf16", dev)
         flops = [0]
@@ -503,28 +550,6 @@ def main() -> int:
         torch.cuda.synchronize()
         log(f"[bench] calibration copy: {src.numel() * 2} bytes read and written per launch of torch's elementwise kernel")
         del src, dst
-
-    # ---- CPU oracle on a bounded sample of the step's batch --------------------------------------------------
-    if not args.no_cpu_baseline:
-        from oracle import oracle as O
-        rows = np.arange(0, n, dtype=np.int64)                         # the whole prefill batch of the step
-        ocache = O.cache_for_case(case)
-        t0 = time.perf_counter()
-        want = O.attention_case(case, ocache, rows)
-        dt = time.perf_counter() - t0
-        pos = np.concatenate([case.ctx_lens[s] - case.q_lens[s] + np.arange(case.q_lens[s]) for s in range(case.num_seqs)])
-        sample_flops = 4 * D * hq_l * int((pos[rows] + 1).sum())
-        do_prefill()
-        torch.cuda.synchronize()
-        got = W.to_f64(B.to_host(attn_o)[rows], "bf16")
-        err = np.abs(got - want)
-        result["cpu_baseline"] = {"value": round(sample_flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": O.num_threads(),
-                                  "kind": "oracle", "seconds": round(dt, 2),
-                                  "sample": f"fp64 oracle on every query token and head of the step's prefill batch "
-                                            f"({sample_flops / 1e9:.1f} of {case.flops() / 1e9:.1f} GFLOP)"}
-        result["parity_on_sample"] = {"max_abs_err": float(err.max()), "mean_abs_err": float(err.mean())}
-        log(f"[bench] oracle: {dt:.1f} s on {O.num_threads()} threads, {sample_flops / dt / 1e9:.2f} GFLOP/s; "
-            f"GPU vs oracle max|err|={err.max():.2e} mean|err|={err.mean():.2e}")
 
     print(json.dumps(result), flush=True)
     return 0
