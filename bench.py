@@ -490,6 +490,62 @@ def main() -> int:
                           "roofline": roof("proj_gemm_kernel<fp8>", "mfma", tf, PEAK_FP8_TFLOPS, "TFLOP/s")}
             log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_FP8_TFLOPS:.1%} of the fp8 MFMA peak); "
                 f"quantising the activations {ms_q * 1e3:.1f} us ({q_bytes / (ms_q * 1e-3) / 1e9:.0f} GB/s)")
+
+        # ---- the same projections at the token counts of a decode step (Algorithm 2: below the threshold) ---------
+        # three copies of each weight matrix in rotation (504 / 403 MB), so that no pass is served from the 256 MB cache in
+        # front of HBM; every figure is the time per call of 12 calls captured in one HIP graph and replayed
+        wq_rot = [wq] + [(torch.randn(wq.shape, device=dev, generator=gen) * 0.02).to(bf) for _ in range(2)]
+        wo_rot = [wo] + [(torch.randn(wo.shape, device=dev, generator=gen) * 0.02).to(bf) for _ in range(2)]
+        small_proj = {}
+        for Ts in (1, 8, 16, 32, 64, 256):
+            xs_ = torch.randn((Ts, d_model), device=dev, generator=gen).to(bf)
+            snd = torch.empty((x3.P, Ts, h3 // x3.P + 2 * (hkv3 // x3.P), D), dtype=bf, device=dev)
+            rcv = torch.randn((x3.P, Ts, h3 // x3.P, D), device=dev, generator=gen).to(bf)
+            eo_s = torch.empty((Ts, d_model), dtype=bf, device=dev)
+            plain_q = torch.empty((Ts, (h3 + 2 * hkv3) * D), dtype=bf, device=dev)
+            plain_a = torch.empty((Ts, h3 * D), dtype=bf, device=dev)
+            ws_q = torch.empty(max(B.proj_workspace_bytes(Ts, wq.shape[0], d_model), 16), dtype=torch.uint8, device=dev)
+            ws_o = torch.empty(max(B.proj_workspace_bytes(Ts, d_model, h3 * D), 16), dtype=torch.uint8, device=dev)
+            turn = [0]
+
+            def nxt(lst):
+                turn[0] = (turn[0] + 1) % 3
+                return lst[turn[0]]
+
+            def lib_q_small():
+                torch.matmul(xs_, nxt(wq_rot).t(), out=plain_q)
+                B.pack_seq2head(plain_q.view(Ts, h3 + 2 * hkv3, D), snd, x3.P, h3, hkv3)
+
+            def lib_o_small():
+                B.unpack_head2seq(rcv, plain_a.view(Ts, h3, D))
+                torch.matmul(plain_a, nxt(wo_rot).t(), out=eo_s)
+
+            row = {}
+            for nm, fn, ref, wbytes in (("qkv_proj_pack", lambda: B.qkv_proj_pack(xs_, nxt(wq_rot), snd, x3.P, h3, hkv3, workspace=ws_q),
+                                         lib_q_small, wq.numel() * 2),
+                                        ("unpack_o_proj", lambda: B.unpack_o_proj(rcv, nxt(wo_rot), eo_s, workspace=ws_o),
+                                         lib_o_small, wo.numel() * 2)):
+                us, us_ref = time_in_graph(fn, inner=12) * 1e3, time_in_graph(ref, inner=12) * 1e3
+                gbps = wbytes / (us * 1e-6) / 1e9
+                row[nm] = {"us": round(us, 2), "library_gemm_and_separate_layout_kernel_us": round(us_ref, 2),
+                           "weight_bytes": wbytes, "us_to_stream_the_weights_at_peak": round(wbytes / PEAK_HBM_GBPS / 1e3, 2),
+                           "roofline": roof("proj_stream_kernel" if Ts <= 64 else "proj_gemm_kernel<bf16>", "hbm", gbps, PEAK_HBM_GBPS, "GB/s")}
+            small_proj[f"T={Ts}"] = row
+            if cpu and Ts == 16:
+                t0 = time.perf_counter()
+                O.qkv_proj_pack(B.to_host(xs_), B.to_host(wq), x3.P, h3, hkv3, D, Ts, "bf16")
+                dt = time.perf_counter() - t0
+                small_proj["cpu_baseline"] = cpu_obj(dt, 2.0 * Ts * d_model * wq.shape[0] / 1e9, "GFLOP/s", "qkv_proj_pack of the 16-token call, whole")
+            del xs_, snd, rcv, eo_s, plain_q, plain_a, ws_q, ws_o
+        result["decode_sized_projections"] = {
+            "workload": f"the configs[2] shard's projections (d_model {d_model}, {h3} query + 2 x {hkv3} KV heads of 128, {x3.P} exchange buffers, bf16) "
+                        "at 1 .. 256 token rows; one pass over the weights bounds them",
+            "calls": small_proj}
+        log("[bench] projections at decode-sized token counts, us (ours / library GEMM + layout kernel): " +
+            ", ".join(f"{k}: qkv {v['qkv_proj_pack']['us']}/{v['qkv_proj_pack']['library_gemm_and_separate_layout_kernel_us']} "
+                      f"o {v['unpack_o_proj']['us']}/{v['unpack_o_proj']['library_gemm_and_separate_layout_kernel_us']}"
+                      for k, v in small_proj.items() if k.startswith("T=")))
+        del wq_rot, wo_rot
         del xe, wq, wo, send3, recv3, eo, qkv_plain, att_plain, xq, xsc, wq8, wsc, rq, rsc, wo8, wosc
 
         # ---- configs[2]: 70B-shaped prefill; and the same length with 5 query heads per KV head (Table 4, Llama-17B-16E at P=8)

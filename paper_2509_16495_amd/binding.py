@@ -61,6 +61,10 @@ def lib() -> ctypes.CDLL:
         L.shiftattn_unpack_head2seq.argtypes = [vp, vp, i32, i32, xp, vp]
         L.shiftattn_qkv_proj_pack.argtypes = [vp, vp, vp, i32, i32, i32, xp, vp]
         L.shiftattn_unpack_o_proj.argtypes = [vp, vp, vp, i32, i32, i32, xp, vp]
+        L.shiftattn_qkv_proj_pack_ws.argtypes = [vp, vp, vp, i32, i32, i32, xp, vp, ctypes.c_size_t, vp]
+        L.shiftattn_unpack_o_proj_ws.argtypes = [vp, vp, vp, i32, i32, i32, xp, vp, ctypes.c_size_t, vp]
+        L.shiftattn_proj_workspace_bytes.argtypes = [i32, i32, i32]
+        L.shiftattn_proj_workspace_bytes.restype = ctypes.c_size_t
         L.shiftattn_quantize_rows_fp8.argtypes = [vp, vp, vp, i32, i32, vp]
         L.shiftattn_quantize_recv_fp8.argtypes = [vp, vp, vp, i32, i32, xp, vp]
         L.shiftattn_qkv_proj_pack_fp8.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, xp, vp]
@@ -208,24 +212,38 @@ def unpack_head2seq(recv: torch.Tensor, out: torch.Tensor) -> None:
 
 
 # ---- KV cache and attention -------------------------------------------------------------------------
-def qkv_proj_pack(x: torch.Tensor, w_qkv: torch.Tensor, send: torch.Tensor, P: int, h: int, h_kv: int) -> None:
+def proj_workspace_bytes(rows: int, n_features: int, k: int) -> int:
+    """Bytes of workspace that make a projection of `rows` token rows with an [n_features, k] matrix one pass over the weights."""
+    return int(lib().shiftattn_proj_workspace_bytes(rows, n_features, k))
+
+
+def qkv_proj_pack(x: torch.Tensor, w_qkv: torch.Tensor, send: torch.Tensor, P: int, h: int, h_kv: int,
+                  workspace: Optional[torch.Tensor] = None) -> None:
     """x [T, d_model], w_qkv [(h + 2 h_kv) D, d_model] -> send [P, T_pad, hq_l + 2 hkv_l, D] (projection + pack)."""
     T, d_model = x.shape
     T_pad, D = send.shape[1], send.shape[3]
     assert w_qkv.shape == ((h + 2 * h_kv) * D, d_model) and x.is_contiguous() and w_qkv.is_contiguous() and send.is_contiguous()
     assert send.shape[0] == P and send.shape[2] == h // P + 2 * local_kv_heads(P, h_kv) and x.dtype == w_qkv.dtype == send.dtype
     xc = Xchg(P, h, h_kv, D, _dtype_code(x))
-    _check(lib().shiftattn_qkv_proj_pack(_ptr(x), _ptr(w_qkv), _ptr(send), T, T_pad, d_model, ctypes.byref(xc), _stream()))
+    if workspace is None:
+        _check(lib().shiftattn_qkv_proj_pack(_ptr(x), _ptr(w_qkv), _ptr(send), T, T_pad, d_model, ctypes.byref(xc), _stream()))
+    else:
+        _check(lib().shiftattn_qkv_proj_pack_ws(_ptr(x), _ptr(w_qkv), _ptr(send), T, T_pad, d_model, ctypes.byref(xc), _ptr(workspace),
+                                                workspace.numel() * workspace.element_size(), _stream()))
 
 
-def unpack_o_proj(recv: torch.Tensor, w_o: torch.Tensor, out: torch.Tensor) -> None:
+def unpack_o_proj(recv: torch.Tensor, w_o: torch.Tensor, out: torch.Tensor, workspace: Optional[torch.Tensor] = None) -> None:
     """recv [P, T_pad, hq_l, D], w_o [d_model, h D] -> out [T, d_model] (unpack + projection)."""
     P, T_pad, hq_l, D = recv.shape
     T, d_model = out.shape
     assert w_o.shape == (d_model, P * hq_l * D) and recv.is_contiguous() and w_o.is_contiguous() and out.is_contiguous()
     assert recv.dtype == w_o.dtype == out.dtype
     xc = Xchg(P, P * hq_l, 0, D, _dtype_code(recv))
-    _check(lib().shiftattn_unpack_o_proj(_ptr(recv), _ptr(w_o), _ptr(out), T, T_pad, d_model, ctypes.byref(xc), _stream()))
+    if workspace is None:
+        _check(lib().shiftattn_unpack_o_proj(_ptr(recv), _ptr(w_o), _ptr(out), T, T_pad, d_model, ctypes.byref(xc), _stream()))
+    else:
+        _check(lib().shiftattn_unpack_o_proj_ws(_ptr(recv), _ptr(w_o), _ptr(out), T, T_pad, d_model, ctypes.byref(xc), _ptr(workspace),
+                                                workspace.numel() * workspace.element_size(), _stream()))
 
 
 def quantize_rows_fp8(x: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor) -> None:

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libshiftattn.so")
-SOURCES = ["api.hip", "layout_kernels.hip", "attn_generic.hip", "decode_mfma.hip", "prefill_mfma.hip", "prefill_mfma64.hip", "ceilings.hip", "proj_gemm.hip"]
+SOURCES = ["api.hip", "layout_kernels.hip", "attn_generic.hip", "decode_mfma.hip", "prefill_mfma.hip", "prefill_mfma64.hip", "ceilings.hip", "proj_gemm.hip", "proj_stream.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared", "-fno-gpu-rdc",
     # packed fp32 VALU forms are kept out of the generated code

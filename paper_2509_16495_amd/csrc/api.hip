@@ -56,6 +56,7 @@ int ensure_device_ready() {
     if ((e = prefill_mfma_init()) != hipSuccess) return hip_fail(e, "set-up of the prefill kernel");
     if ((e = prefill_mfma64_init()) != hipSuccess) return hip_fail(e, "set-up of the wide prefill kernel");
     if ((e = proj_gemm_init()) != hipSuccess) return hip_fail(e, "set-up of the projection kernel");
+    if ((e = proj_stream_init()) != hipSuccess) return hip_fail(e, "set-up of the small-batch projection kernel");
     g_device_ready[dev] = true;
     return 0;
 }
@@ -326,8 +327,8 @@ int shiftattn_unpack_head2seq(const void* recv, void* out, int32_t T, int32_t T_
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_head2seq launch");
 }
 
-int shiftattn_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int32_t T, int32_t T_pad, int32_t d_model,
-                            const shiftattn_xchg* xc, void* stream) {
+int shiftattn_qkv_proj_pack_ws(const void* x, const void* w_qkv, void* send, int32_t T, int32_t T_pad, int32_t d_model,
+                               const shiftattn_xchg* xc, void* workspace, size_t workspace_bytes, void* stream) {
     XchgShape s;
     if (int rc = check_xchg(xc, T, T_pad, true, &s)) return rc;
     if (d_model < 1) return fail(SHIFTATTN_EINVAL, "d_model = %d", d_model);
@@ -338,13 +339,25 @@ int shiftattn_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int32_
     if (s.T_pad == 0) return SHIFTATTN_OK;
     if (!send || (s.T > 0 && (!x || !w_qkv))) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
     if (!aligned16(x) || !aligned16(w_qkv) || !aligned16(send)) return fail(SHIFTATTN_EINVAL, "x / w_qkv / send must be 16-byte aligned");
+    if (workspace_bytes > 0 && (!workspace || !aligned16(workspace)))
+        return fail(SHIFTATTN_EINVAL, "workspace is NULL or not 16-byte aligned");
     if (int rc = ensure_device_ready()) return rc;
-    hipError_t e = launch_qkv_proj_pack(x, w_qkv, send, d_model, s, nullptr, nullptr, static_cast<hipStream_t>(stream));
+    const int n_feat = (s.h + 2 * s.h_kv) * 128;
+    hipError_t e;
+    if (s.T > 0 && !force_generic() && proj_stream_takes(s.T_pad, n_feat, d_model, workspace_bytes))
+        e = launch_qkv_proj_stream(x, w_qkv, send, d_model, s, workspace, static_cast<hipStream_t>(stream));
+    else
+        e = launch_qkv_proj_pack(x, w_qkv, send, d_model, s, nullptr, nullptr, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "qkv_proj_pack launch");
 }
 
-int shiftattn_unpack_o_proj(const void* recv, const void* w_o, void* out, int32_t T, int32_t T_pad, int32_t d_model,
+int shiftattn_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int32_t T, int32_t T_pad, int32_t d_model,
                             const shiftattn_xchg* xc, void* stream) {
+    return shiftattn_qkv_proj_pack_ws(x, w_qkv, send, T, T_pad, d_model, xc, nullptr, 0, stream);
+}
+
+int shiftattn_unpack_o_proj_ws(const void* recv, const void* w_o, void* out, int32_t T, int32_t T_pad, int32_t d_model,
+                               const shiftattn_xchg* xc, void* workspace, size_t workspace_bytes, void* stream) {
     XchgShape s;
     if (int rc = check_xchg(xc, T, T_pad, false, &s)) return rc;
     if (d_model < 1) return fail(SHIFTATTN_EINVAL, "d_model = %d", d_model);
@@ -354,9 +367,25 @@ int shiftattn_unpack_o_proj(const void* recv, const void* w_o, void* out, int32_
     if (s.T == 0) return SHIFTATTN_OK;
     if (!recv || !w_o || !out) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
     if (!aligned16(recv) || !aligned16(w_o) || !aligned16(out)) return fail(SHIFTATTN_EINVAL, "recv / w_o / out must be 16-byte aligned");
+    if (workspace_bytes > 0 && (!workspace || !aligned16(workspace)))
+        return fail(SHIFTATTN_EINVAL, "workspace is NULL or not 16-byte aligned");
     if (int rc = ensure_device_ready()) return rc;
-    hipError_t e = launch_unpack_o_proj(recv, w_o, out, d_model, s, nullptr, nullptr, static_cast<hipStream_t>(stream));
+    hipError_t e;
+    if (!force_generic() && proj_stream_takes(s.T, d_model, s.h * 128, workspace_bytes))
+        e = launch_o_proj_stream(recv, w_o, out, d_model, s, workspace, static_cast<hipStream_t>(stream));
+    else
+        e = launch_unpack_o_proj(recv, w_o, out, d_model, s, nullptr, nullptr, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_o_proj launch");
+}
+
+int shiftattn_unpack_o_proj(const void* recv, const void* w_o, void* out, int32_t T, int32_t T_pad, int32_t d_model,
+                            const shiftattn_xchg* xc, void* stream) {
+    return shiftattn_unpack_o_proj_ws(recv, w_o, out, T, T_pad, d_model, xc, nullptr, 0, stream);
+}
+
+size_t shiftattn_proj_workspace_bytes(int32_t rows, int32_t n_features, int32_t k) {
+    if (rows < 1 || n_features < 1 || k < 1 || force_generic()) return 0;
+    return proj_stream_workspace(rows, n_features, k);
 }
 
 int shiftattn_quantize_rows_fp8(const void* x, void* codes, float* scales, int32_t rows, int32_t cols, void* stream) {

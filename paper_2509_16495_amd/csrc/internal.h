@@ -106,6 +106,7 @@ hipError_t launch_prefill_mfma64(const void* q, const void* cache, const int32_t
 hipError_t prefill_mfma_init();
 hipError_t prefill_mfma64_init();
 hipError_t proj_gemm_init();
+hipError_t proj_stream_init();
 
 // Process-wide tuning switches (api.hip: shiftattn_set_option); 0 = decided per call
 int option_prefill_tile();    // 0, 128 or 256
@@ -121,6 +122,13 @@ hipError_t launch_qkv_proj_pack(const void* x, const void* w_qkv, void* send, in
                                 const float* x_scales, const float* w_scales, hipStream_t st);
 hipError_t launch_unpack_o_proj(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s,
                                 const float* a_scales, const float* w_scales, hipStream_t st);
+// proj_stream.hip : the same two products for up to 64 token rows, organised around one pass over the weights
+size_t proj_stream_workspace(int M_out, int N, int K);
+bool proj_stream_takes(int M_out, int N, int K, size_t workspace_bytes);
+hipError_t launch_qkv_proj_stream(const void* x, const void* w_qkv, void* send, int d_model, const XchgShape& s,
+                                  void* workspace, hipStream_t st);
+hipError_t launch_o_proj_stream(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s,
+                                void* workspace, hipStream_t st);
 // layout_kernels.hip : rows of bf16 values -> FP8 E4M3 codes + one float32 scale per row (amax / 448).  Element k of
 // row t lies at (k / seg_len) * seg_stride + t * row_stride + k % seg_len, in `x` and in `codes` alike.
 hipError_t launch_quantize_rows_fp8(const void* x, void* codes, float* scales, int rows, int cols, int seg_len,
