@@ -18,11 +18,14 @@ oracle timed on a stated row sample of the same batch.  Further objects report t
 prefill batch, 70B-shaped prefill, 256-sequence decode, small decode batches, the 70B exchange, K/V append, the
 fused projections), each with its own roofline object and an oracle timing.  All timings are medians of
 per-call HIP-event pairs on the launch stream unless stated.  HBM traffic from hardware counters is not measured in
-this run (`traffic` is null): the counter summaries of the profiled runs are in profiles/.
+this run: `traffic` repeats the figure of the profiled runs summarised in profiles/hbm_traffic.md when that table was
+measured on exactly the kernel sources of this tree (it carries their hash), and is null otherwise.
 """
 from __future__ import annotations
 
 import argparse
+import glob
+import hashlib
 import json
 import os
 import sys
@@ -40,6 +43,35 @@ METRIC = "prefill attn TFLOP/s + decode KV-read GB/s per MI355X (head shard, % r
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def source_stamp() -> str:
+    """Hash of the kernel sources the library is built from (names and bytes of csrc/*)."""
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2509_16495_amd", "csrc", "*"))):
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def counter_traffic() -> dict:
+    """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs, scaled by a copy of known size) by
+    workload key, from profiles/hbm_traffic.md - used only if that table was measured on exactly these kernel sources
+    (it carries their stamp); otherwise every `traffic` stays null."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+    out = {}
+    try:
+        text = open(path).read()
+    except OSError:
+        return out
+    if f"source stamp: `{source_stamp()}`" not in text:
+        return out
+    for line in text.splitlines():
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 4 and cells[2].isdigit() and cells[3].isdigit():
+            out[cells[0]] = int(cells[2]) + int(cells[3])
+    return out
 
 
 def main() -> int:
@@ -111,9 +143,11 @@ def main() -> int:
             torch.cuda.synchronize()
         return e0.elapsed_time(e1) / (inner * reps)
 
-    def roof(kernel, bound, achieved, peak, unit, **extra):
+    traffic_by_key = counter_traffic()
+
+    def roof(kernel, bound, achieved, peak, unit, traffic_key=None, **extra):
         r = {"kernel": kernel, "bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
-             "frac": round(achieved / peak, 4), "traffic": None}
+             "frac": round(achieved / peak, 4), "traffic": traffic_by_key.get(traffic_key)}
         r.update(extra)
         return r
 
@@ -184,10 +218,6 @@ def main() -> int:
         B.prefill(q_v[:n_chunk], cache5, table5[:n_pre], cu5, sl5[:n_pre], max_q5, max_pre5, attn_o[:n_chunk], c5.softmax_scale,
                   workspace=ws5)
 
-    def do_decode_only():     # the 64 decodes alone, with their K/V append
-        B.decode(q_v[n_chunk:], cache5, table5[n_pre:], sl5[n_pre:], max_dec5, attn_o[n_chunk:], c5.softmax_scale,
-                 k_new=k_v[n_chunk:], v_new=v_v[n_chunk:], slot_mapping=slots5[n_chunk:], workspace=ws5)
-
     def step():
         do_pack()
         do_mixed()
@@ -219,25 +249,52 @@ def main() -> int:
     ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / args.steps
     log(f"[bench] step replayed from a HIP graph: {ms_per_step_graph:.4f} ms")
 
-    # ---- per-phase HIP-event timings (medians), same stream --------------------------------------------------
+    # ---- the same step as separate calls in the same order, one HIP-event pair around every part (medians) -----------
+    # pack | K/V append of all 2112 new rows | chunk attention (prefill64_kernel + the merge of its key ranges) |
+    # the 64 decodes (decode kernel + merge) | unpack: the kernels of the unified call, each between two events on the
+    # launch stream, every part in the cache state the step leaves it in (the chunk's 68 MB of K/V do not survive the
+    # decodes' 538 MB in the 256 MB cache in front of HBM; timed alone in a loop they would)
     e = 2
     pack_bytes = T * (H + 2 * H_kv) * D * e + P * T * (hq_l + 2 * hkv_l) * D * e
     unpack_bytes = 2 * T * H * D * e
+
+    def do_append():
+        B.kv_write(k_v, v_v, slots5, cache5)
+
+    def do_decode_part():
+        B.decode(q_v[n_chunk:], cache5, table5[n_pre:], sl5[n_pre:], max_dec5, attn_o[n_chunk:], c5.softmax_scale, workspace=ws5)
+
+    parts = [("pack_seq2head", do_pack, pack_bytes / 1e9, "GB/s"),
+             ("kv_write_of_the_new_rows", do_append, 2.0 * n * hkv_l * D * e * 2 / 1e9, "GB/s"),
+             ("chunk_prefill", do_chunk_only, pre5.flops() / 1e12, "TFLOP/s"),
+             ("decodes", do_decode_part, dec5.kv_bytes() / 1e9, "GB/s"),
+             ("unpack_head2seq", do_unpack, unpack_bytes / 1e9, "GB/s")]
+    for _ in range(3):
+        for _, fn, _, _ in parts:
+            fn()
+    torch.cuda.synchronize()
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(len(parts) + 1)] for _ in range(reps)]
+    for ev in marks:
+        ev[0].record()
+        for i, (_, fn, _, _) in enumerate(parts):
+            fn()
+            ev[i + 1].record()
+    torch.cuda.synchronize()
     phases = {}
-    for name, fn, work, unit in [("pack_seq2head", do_pack, pack_bytes / 1e9, "GB/s"),
-                                 ("mixed_attention_with_kv_write", do_mixed, step_flops / 1e12, "TFLOP/s"),
-                                 ("unpack_head2seq", do_unpack, unpack_bytes / 1e9, "GB/s"),
-                                 ("chunk_prefill_alone", do_chunk_only, pre5.flops() / 1e12, "TFLOP/s"),
-                                 ("decodes_alone_with_kv_write", do_decode_only, dec5.kv_bytes() / 1e9, "GB/s")]:
-        ms = time_events(fn, reps)
+    for i, (name, _, work, unit) in enumerate(parts):
+        ms = float(np.median([ev[i].elapsed_time(ev[i + 1]) for ev in marks]))
         phases[name] = {"ms": round(ms, 5), "rate": round(work / (ms * 1e-3), 2), "unit": unit}
         log(f"[bench]   {name:32s} {ms * 1e3:9.1f} us  {phases[name]['rate']:10.1f} {unit}")
-    ck_ms = phases["chunk_prefill_alone"]["ms"]
+    ms = float(np.median([ev[0].elapsed_time(ev[-1]) for ev in marks]))
+    phases["all_parts_as_separate_calls"] = {"ms": round(ms, 5), "rate": round(step_flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s"}
+    ms = time_events(do_mixed, reps)
+    phases["unified_call_alone"] = {"ms": round(ms, 5), "rate": round(step_flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s"}
+    ck_ms = phases["chunk_prefill"]["ms"]
     achieved = pre5.flops() / (ck_ms * 1e-3) / 1e12
-    roofline = roof("prefill64_kernel (bf16 MFMA chunked prefill over 8 key ranges; the call's combine_kernel, about 1 % of it, is "
+    roofline = roof("prefill64_kernel (bf16 MFMA chunked prefill over 8 key ranges; the call's combine_kernel, about 1.5 % of it, is "
                     "inside the timed interval)", "mfma", achieved, PEAK_BF16_TFLOPS, "TFLOP/s",
-                    flops_per_launch=pre5.flops(), median_launch_ms=round(ck_ms, 5))
-    dd_ms = phases["decodes_alone_with_kv_write"]["ms"]
+                    traffic_key="chunk_prefill_long_context", flops_per_launch=pre5.flops(), median_launch_ms=round(ck_ms, 5))
+    dd_ms = phases["decodes"]["ms"]
     dd_gbps = dec5.kv_bytes() / (dd_ms * 1e-3) / 1e9
 
     result = {
@@ -252,10 +309,11 @@ def main() -> int:
                    "step_flops": step_flops, "decode_kv_bytes": dec5.kv_bytes()},
         "roofline": roofline,
         "decode_in_step": {"kv_bytes": dec5.kv_bytes(), "ms": round(dd_ms, 5),
-                           "roofline": roof("decode_flat_kernel + combine_flat_kernel", "hbm", dd_gbps, PEAK_HBM_GBPS, "GB/s")},
+                           "roofline": roof("decode_flat_kernel + combine_flat_kernel", "hbm", dd_gbps, PEAK_HBM_GBPS, "GB/s", traffic_key="decode_64_long_contexts")},
         "ms_per_step_graph_replay": round(ms_per_step_graph, 5),
         "phases": phases,
-        "traffic_note": "HBM bytes per launch from rocprofv3 counters are in profiles/ (measured in separate profiled runs)",
+        "traffic_note": "HBM bytes per launch (FETCH_SIZE + WRITE_SIZE) from the profiled runs in profiles/hbm_traffic.md; null when "
+                        "that table was not measured on this tree's kernel sources",
     }
 
     # ---- CPU oracle on a bounded sample of the step's batch ---------------------------------------------------
@@ -299,7 +357,7 @@ def main() -> int:
         tf = c2.flops() / (ms_k * 1e-3) / 1e12
         result["prefill_8b"] = {"workload": "configs[1]: 4q/1kv, D=128, 4 x 4096-token causal prefill, paged KV", "flops": c2.flops(),
                                 "ms": round(ms_k, 5), "ms_with_kv_write": round(ms_w, 5),
-                                "roofline": roof("prefill_kernel (128-column tiles)", "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s")}
+                                "roofline": roof("prefill_kernel (128-column tiles)", "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s", traffic_key="prefill_8b")}
         log(f"[bench] prefill cfg2: {ms_k * 1e3:.1f} us ({ms_w * 1e3:.1f} with K/V write), {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%})")
         if cpu:
             dt, fl, _ = oracle_attention(c2, np.arange(c2.total_q, dtype=np.int64), "cfg2")
@@ -322,7 +380,7 @@ def main() -> int:
         result["decode_kv_read"] = {"workload": f"configs[3]: 256 decode sequences, contexts U[512,8192], realised sum "
                                                 f"{int(c4.ctx_lens.sum())} tokens, 8q/1kv, D=128, bf16 paged KV",
                                     "kv_bytes": c4.kv_bytes(), "ms": round(ms, 5),
-                                    "roofline": roof("decode_flat_kernel + combine_flat_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s")}
+                                    "roofline": roof("decode_flat_kernel + combine_flat_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s", traffic_key="decode_256seq")}
         log(f"[bench] decode cfg4: {ms * 1e3:.1f} us, {gbps:.0f} GB/s of KV ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
         if cpu:
             sub = W.sub_case(c4, range(0, c4.num_seqs, 4))
@@ -340,7 +398,7 @@ def main() -> int:
         result["kv_write"] = {"workload": f"K/V of all {int(c4.ctx_lens.sum())} context tokens of the configs[3] batch appended in one "
                                           "call (1 KV head, D=128, bf16; blocks scattered over the pool)",
                               "bytes": kvw_bytes, "ms": round(ms, 5),
-                              "roofline": roof("kv_write_block_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s"),
+                              "roofline": roof("kv_write_block_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s", traffic_key="kv_write_256seq"),
                               "streaming_copy_of_the_same_bytes": {"ms": round(ms_cp, 5), "GB/s": round(kvw_bytes / (ms_cp * 1e-3) / 1e9, 1),
                                                                    "note": "this library's own read+write probe (16-byte non-temporal "
                                                                            "loads and stores, no index arithmetic)"}}
@@ -365,7 +423,7 @@ def main() -> int:
         gbps = c4.kv_bytes() / 2 / (ms * 1e-3) / 1e9
         result["decode_kv_read_fp8"] = {"workload": "configs[3] batch over an FP8 E4M3 KV cache (1 byte per element, per-tensor K and V scales)",
                                         "kv_bytes": c4.kv_bytes() // 2, "ms": round(ms, 5),
-                                        "roofline": roof("decode_flat_kernel<fp8> + combine_flat_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s")}
+                                        "roofline": roof("decode_flat_kernel<fp8> + combine_flat_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s", traffic_key="decode_256seq_fp8")}
         log(f"[bench] decode cfg4, FP8 cache: {ms * 1e3:.1f} us, {gbps:.0f} GB/s of KV ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
         del cache4, cache4q, w4
 
@@ -419,7 +477,7 @@ def main() -> int:
             gbps = x3.bytes_moved() / (ms * 1e-3) / 1e9
             result[nm] = {"workload": "configs[2]: hidden [16384, 64 heads, 128] bf16 <-> 8 buffers, 3 rotating copies",
                           "bytes": x3.bytes_moved(), "ms": round(ms, 5),
-                          "roofline": roof(nm + "_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s")}
+                          "roofline": roof(nm + "_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s", traffic_key=nm + "_70b")}
             log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {gbps:.0f} GB/s ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak)")
         if cpu:
             t0 = time.perf_counter()
@@ -463,7 +521,7 @@ def main() -> int:
             result[nm] = {"workload": f"configs[2] shard: {x3.T} tokens, d_model {d_model}, {h3} query + 2 x {hkv3} KV heads of 128, "
                                       f"{x3.P} exchange buffers, bf16, N(0,1) activations, N(0,0.02) weights",
                           "flops": fl, "ms": round(ms, 5), "library_gemm_and_separate_layout_kernel_ms": round(ms_ref, 5),
-                          "roofline": roof("proj_gemm_kernel", "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s")}
+                          "roofline": roof("proj_gemm_kernel", "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s", traffic_key=nm + "_70b")}
             log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%} of bf16 MFMA peak); "
                 f"library GEMM + separate layout kernel {ms_ref * 1e3:.1f} us")
         xq, xsc = torch.empty(xe.shape, dtype=torch.uint8, device=dev), torch.empty(x3.T, dtype=torch.float32, device=dev)
@@ -487,7 +545,7 @@ def main() -> int:
                           "activation_quantiser": {"ms": round(ms_q, 5), "bytes": q_bytes,
                                                    "roofline": roof("quantize_rows_fp8_kernel", "hbm", q_bytes / (ms_q * 1e-3) / 1e9,
                                                                     PEAK_HBM_GBPS, "GB/s")},
-                          "roofline": roof("proj_gemm_kernel<fp8>", "mfma", tf, PEAK_FP8_TFLOPS, "TFLOP/s")}
+                          "roofline": roof("proj_gemm_kernel<fp8>", "mfma", tf, PEAK_FP8_TFLOPS, "TFLOP/s", traffic_key=nm + "_70b")}
             log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_FP8_TFLOPS:.1%} of the fp8 MFMA peak); "
                 f"quantising the activations {ms_q * 1e3:.1f} us ({q_bytes / (ms_q * 1e-3) / 1e9:.0f} GB/s)")
 
@@ -529,7 +587,7 @@ def main() -> int:
                 gbps = wbytes / (us * 1e-6) / 1e9
                 row[nm] = {"us": round(us, 2), "library_gemm_and_separate_layout_kernel_us": round(us_ref, 2),
                            "weight_bytes": wbytes, "us_to_stream_the_weights_at_peak": round(wbytes / PEAK_HBM_GBPS / 1e3, 2),
-                           "roofline": roof("proj_stream_kernel" if Ts <= 64 else "proj_gemm_kernel<bf16>", "hbm", gbps, PEAK_HBM_GBPS, "GB/s")}
+                           "roofline": roof("proj_stream_kernel" if Ts <= 64 else "proj_gemm_kernel<bf16>", "hbm", gbps, PEAK_HBM_GBPS, "GB/s", traffic_key=f"{nm}_T{Ts}")}
             small_proj[f"T={Ts}"] = row
             if cpu and Ts == 16:
                 t0 = time.perf_counter()
@@ -560,7 +618,7 @@ def main() -> int:
             ms = time_events(lambda: B.prefill(q3, cch, t3, cu3, s3, case.total_q, case.total_q, o3, case.softmax_scale), reps)
             tf = case.flops() / (ms * 1e-3) / 1e12
             result[key] = {"workload": label, "flops": case.flops(), "ms": round(ms, 5),
-                           "roofline": roof("prefill64_kernel (256-column tiles)", "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s")}
+                           "roofline": roof("prefill64_kernel (256-column tiles)" if key == "prefill_70b" else "prefill_kernel (128-column tiles)", "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s", traffic_key=key)}
             log(f"[bench] {key}: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%} of bf16 MFMA peak)")
             if cpu:
                 rows = sample_rows(case, step=256, edge=32)
