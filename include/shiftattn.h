@@ -158,14 +158,15 @@ int shiftattn_unpack_o_proj(const void *recv, const void *w_o, void *out, int32_
 
 /* ---- The same two projections with a workspace (Algorithm 2: the few-token steps below the threshold) ----
  * With up to 64 token rows (T_pad for qkv_proj_pack, T for unpack_o_proj) the product is one pass over the
- * weight matrix; from 17 rows on (at d_model = 8192) that pass is split over k between workgroups, whose
- * fp32 partial results need device memory:
+ * weight matrix; from 17 rows on (at d_model = 8192) that pass is split over k between workgroups.  With a few
+ * hundred rows the large-batch kernel has too few output tiles to fill the chip and splits k as well.  Either
+ * way the fp32 partial results need device memory:
  *   shiftattn_proj_workspace_bytes(rows, n_features, k): bytes for a product of `rows` token rows with a
  *     [n_features][k] weight matrix (qkv: n_features = (h + 2 h_kv) * D, k = d_model; o: n_features =
  *     d_model, k = h * D); 0 when none is needed.
  * workspace (device, scratch): at least that many bytes, 16-byte aligned; NULL / 0 is always accepted and
- *   means "use a kernel that needs none" (the calls above do exactly that) - for 17 .. 64 rows that is the
- *   large-batch kernel, several times slower there.  Calls that share a workspace must not overlap.
+ *   means "use a kernel that needs none" (the calls above do exactly that) - between 17 rows and a few
+ *   hundred that is up to several times slower.  Calls that share a workspace must not overlap.
  * Results are bitwise reproducible with and without a workspace, not bitwise equal between the two. */
 size_t shiftattn_proj_workspace_bytes(int32_t rows, int32_t n_features, int32_t k);
 int shiftattn_qkv_proj_pack_ws(const void *x, const void *w_qkv, void *send, int32_t T, int32_t T_pad,

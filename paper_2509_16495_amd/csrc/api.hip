@@ -347,7 +347,7 @@ int shiftattn_qkv_proj_pack_ws(const void* x, const void* w_qkv, void* send, int
     if (s.T > 0 && !force_generic() && proj_stream_takes(s.T_pad, n_feat, d_model, workspace_bytes))
         e = launch_qkv_proj_stream(x, w_qkv, send, d_model, s, workspace, static_cast<hipStream_t>(stream));
     else
-        e = launch_qkv_proj_pack(x, w_qkv, send, d_model, s, nullptr, nullptr, static_cast<hipStream_t>(stream));
+        e = launch_qkv_proj_pack(x, w_qkv, send, d_model, s, nullptr, nullptr, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "qkv_proj_pack launch");
 }
 
@@ -374,7 +374,7 @@ int shiftattn_unpack_o_proj_ws(const void* recv, const void* w_o, void* out, int
     if (!force_generic() && proj_stream_takes(s.T, d_model, s.h * 128, workspace_bytes))
         e = launch_o_proj_stream(recv, w_o, out, d_model, s, workspace, static_cast<hipStream_t>(stream));
     else
-        e = launch_unpack_o_proj(recv, w_o, out, d_model, s, nullptr, nullptr, static_cast<hipStream_t>(stream));
+        e = launch_unpack_o_proj(recv, w_o, out, d_model, s, nullptr, nullptr, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_o_proj launch");
 }
 
@@ -385,7 +385,8 @@ int shiftattn_unpack_o_proj(const void* recv, const void* w_o, void* out, int32_
 
 size_t shiftattn_proj_workspace_bytes(int32_t rows, int32_t n_features, int32_t k) {
     if (rows < 1 || n_features < 1 || k < 1 || force_generic()) return 0;
-    return proj_stream_workspace(rows, n_features, k);
+    if (proj_stream_takes(rows, n_features, k, static_cast<size_t>(-1))) return proj_stream_workspace(rows, n_features, k);
+    return proj_gemm_workspace(rows, n_features, k);
 }
 
 int shiftattn_quantize_rows_fp8(const void* x, void* codes, float* scales, int32_t rows, int32_t cols, void* stream) {
@@ -429,7 +430,7 @@ int shiftattn_qkv_proj_pack_fp8(const void* x_codes, const float* x_scales, cons
     if (!aligned16(x_codes) || !aligned16(w_codes) || !aligned16(send) || !aligned16(w_scales) || (reinterpret_cast<uintptr_t>(x_scales) & 3))
         return fail(SHIFTATTN_EINVAL, "x_codes / w_codes / w_scales / send must be 16-byte aligned, x_scales 4-byte");
     if (int rc = ensure_device_ready()) return rc;
-    hipError_t e = launch_qkv_proj_pack(x_codes, w_codes, send, d_model, s, x_scales, w_scales, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_qkv_proj_pack(x_codes, w_codes, send, d_model, s, x_scales, w_scales, nullptr, 0, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "qkv_proj_pack_fp8 launch");
 }
 
@@ -446,7 +447,7 @@ int shiftattn_unpack_o_proj_fp8(const void* recv_codes, const float* a_scales, c
     if (!aligned16(recv_codes) || !aligned16(w_codes) || !aligned16(out) || !aligned16(w_scales) || (reinterpret_cast<uintptr_t>(a_scales) & 3))
         return fail(SHIFTATTN_EINVAL, "recv_codes / w_codes / w_scales / out must be 16-byte aligned, a_scales 4-byte");
     if (int rc = ensure_device_ready()) return rc;
-    hipError_t e = launch_unpack_o_proj(recv_codes, w_codes, out, d_model, s, a_scales, w_scales, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_unpack_o_proj(recv_codes, w_codes, out, d_model, s, a_scales, w_scales, nullptr, 0, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_o_proj_fp8 launch");
 }
 

@@ -66,6 +66,8 @@ struct GemmParams {
     // mode 0 (qkv_proj_pack): x dense [M][K]; result columns scattered to send buffers (XchgShape below)
     // mode 1 (unpack_o_proj): x gathered from recv [P][T_pad][hq_l][128] (k = (p hq_l + j) 128 + e); result dense [M][N]
     int mode;
+    int k_splits;                     // workgroups that share an output tile, each with a range of k tiles (bf16 only)
+    float* __restrict__ partial;      // k_splits > 1: fp32 partial results [k_splits][M_out][N] instead of c
     XchgShape s;
 };
 
@@ -83,7 +85,12 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     const int wn = wave % kWavesN, wm = wave / kWavesN;
     // feature tiles vary fastest: workgroups that run together share the token rows in L2
     const int n_tiles = p.N / kTile;
-    const int n0 = (blockIdx.x % n_tiles) * kTile, m0 = (blockIdx.x / n_tiles) * kTile;
+    const int tile_id = blockIdx.x / p.k_splits, split = blockIdx.x - tile_id * p.k_splits;
+    const int n0 = (tile_id % n_tiles) * kTile, m0 = (tile_id / n_tiles) * kTile;
+    // this workgroup's k tiles: [kt0, kt0 + k_steps) of the K / kBK in all
+    const int kt_all = p.K / kBK;
+    const int kt0 = static_cast<int>(static_cast<int64_t>(kt_all) * split / p.k_splits);
+    const int k_steps = static_cast<int>(static_cast<int64_t>(kt_all) * (split + 1) / p.k_splits) - kt0;
 
     // ---- direct-to-LDS loads: this wavefront fills rows 32 wave .. 32 wave + 31 of both operand tiles, sixteen rows
     // (1 KiB) per instruction; lane -> row 16 j + lane / 4, LDS piece position lane % 4, logical piece = position ^ key
@@ -109,7 +116,9 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     // next rank's buffer (mode 1); in mode 0 it is contiguous throughout.
     const int seg_tiles = static_cast<int>(seg_bytes / kRowBytes);
     const size_t seg_jump = p.mode == 0 ? 0 : static_cast<size_t>(p.s.T_pad - 1) * seg_bytes;
-    int ld_kt = 0, ld_left = seg_tiles;   // next tile to load, and how many tiles remain in its segment
+    int ld_kt = 0, ld_left = seg_tiles - kt0 % seg_tiles;   // next tile to load (counted from kt0), and how many tiles remain in its segment
+    w_tile += static_cast<size_t>(kt0) * kRowBytes;
+    x_tile += static_cast<size_t>(kt0) * kRowBytes + static_cast<size_t>(kt0 / seg_tiles) * seg_jump;
     // 1 KiB from a wavefront-uniform base (scalar registers) + a 32-bit byte offset per lane into LDS at dst (uniform):
     // written as assembly so that the load forms the address itself instead of a 64-bit vector addition in front of it.
     // These loads are waited for with the explicit vmcnt waits below only.
@@ -176,7 +185,6 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
             }
     };
 
-    const int k_steps = p.K / kBK;
     auto prologue = [&]() {   // the first kStages - 1 tiles are requested, tile 0 has landed everywhere
         for (int t = 0; t < kStages - 1 && t < k_steps; ++t) {
 #pragma unroll
@@ -295,6 +303,22 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
                 }
         }
     };
+    if (p.k_splits > 1) {   // this k range's fp32 sums, [split][token][feature]; proj_finish adds the ranges and does the layout
+        float* base = p.partial + static_cast<size_t>(split) * p.M_out * p.N + f_wave + 4 * half;
+#pragma unroll
+        for (int mt = 0; mt < kMT; ++mt) {
+            const int m = m0 + wm * kMT * 32 + mt * 32 + l32;
+            if (m >= p.M) continue;   // rows past the last token are zeros in the result and are not read
+            float* row = base + static_cast<size_t>(m) * p.N;
+#pragma unroll
+            for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4)
+                    *reinterpret_cast<f32x4*>(row + 32 * nt + 8 * r4) =
+                        f32x4{acc[nt][mt][4 * r4], acc[nt][mt][4 * r4 + 1], acc[nt][mt][4 * r4 + 2], acc[nt][mt][4 * r4 + 3]};
+        }
+        return;
+    }
     if (p.mode == 1) {
         store_rows(p.c + f_wave, static_cast<size_t>(p.N));
         return;
@@ -325,11 +349,22 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
 
 template <bool kFp8>
 hipError_t launch(const GemmParams& p, hipStream_t st) {
-    const int64_t wgs = static_cast<int64_t>(p.N / kTile) * ((p.M_out + kTile - 1) / kTile);
+    const int64_t wgs = static_cast<int64_t>(p.N / kTile) * ((p.M_out + kTile - 1) / kTile) * p.k_splits;
     if (wgs == 0) return hipSuccess;
     if (wgs > 0x7FFFFFFF) return hipErrorInvalidValue;
     proj_gemm_kernel<kFp8><<<static_cast<unsigned>(wgs), kGemmThreads, kGemmLds, st>>>(p);
     return hipGetLastError();
+}
+
+// Few output tiles (a few hundred token rows): k is split over workgroups until the tiles fill the chip, each range at
+// least 16 k tiles long.  1: no split (enough tiles, a short k, or FP8 operands).
+int k_splits_for(int M_out, int N, int K) {
+    const int64_t tiles = static_cast<int64_t>(N / kTile) * ((M_out + kTile - 1) / kTile);
+    if (tiles == 0 || tiles >= 128) return 1;
+    const int by_fill = static_cast<int>((256 + tiles / 2) / tiles);
+    const int by_length = K / 32 / 16;
+    const int sp = by_fill < by_length ? by_fill : by_length;
+    return sp < 2 ? 1 : sp;
 }
 
 }  // namespace
@@ -350,8 +385,28 @@ bool unpack_o_proj_supported(const XchgShape& s, int d_model, int elem) {
     return elem == 2 && s.vec_per_head * 8 == kHeadDim && d_model > 0 && d_model % kTile == 0 && s.h > 0;
 }
 
+size_t proj_gemm_workspace(int M_out, int N, int K) {
+    const int sp = k_splits_for(M_out, N, K);
+    return sp == 1 ? 0 : static_cast<size_t>(sp) * M_out * N * sizeof(float);
+}
+
+// runs the product with its k split when that pays and the workspace holds the partial results
+static hipError_t run_gemm(GemmParams& p, void* workspace, size_t workspace_bytes, hipStream_t st) {
+    p.k_splits = 1;
+    p.partial = nullptr;
+    if (p.xs) return launch<true>(p, st);
+    const size_t need = proj_gemm_workspace(p.M_out, p.N, p.K);
+    if (need == 0 || need > workspace_bytes || !workspace) return launch<false>(p, st);
+    p.k_splits = k_splits_for(p.M_out, p.N, p.K);
+    p.partial = static_cast<float*>(workspace);
+    const hipError_t e = launch<false>(p, st);
+    if (e != hipSuccess) return e;
+    return launch_proj_finish(p.partial, p.k_splits, p.M_out, p.c, p.M, p.M_out, p.N, p.mode, p.s, st);
+}
+
 hipError_t launch_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int d_model, const XchgShape& s,
-                                const float* x_scales, const float* w_scales, hipStream_t st) {
+                                const float* x_scales, const float* w_scales, void* workspace, size_t workspace_bytes,
+                                hipStream_t st) {
     GemmParams p;
     p.w = static_cast<const unsigned char*>(w_qkv);
     p.x = static_cast<const unsigned char*>(x);
@@ -365,11 +420,12 @@ hipError_t launch_qkv_proj_pack(const void* x, const void* w_qkv, void* send, in
     p.mode = 0;
     p.s = s;
     if (s.T == 0) return launch_pack(nullptr, send, s, st);  // only padding rows: the pack kernel writes the zeros
-    return x_scales ? launch<true>(p, st) : launch<false>(p, st);
+    return run_gemm(p, workspace, workspace_bytes, st);
 }
 
 hipError_t launch_unpack_o_proj(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s,
-                                const float* a_scales, const float* w_scales, hipStream_t st) {
+                                const float* a_scales, const float* w_scales, void* workspace, size_t workspace_bytes,
+                                hipStream_t st) {
     GemmParams p;
     p.w = static_cast<const unsigned char*>(w_o);
     p.x = static_cast<const unsigned char*>(recv);
@@ -383,7 +439,7 @@ hipError_t launch_unpack_o_proj(const void* recv, const void* w_o, void* out, in
     p.mode = 1;
     p.s = s;
     if (s.T == 0) return hipSuccess;
-    return a_scales ? launch<true>(p, st) : launch<false>(p, st);
+    return run_gemm(p, workspace, workspace_bytes, st);
 }
 
 }  // namespace shiftattn

@@ -337,13 +337,28 @@ hipError_t run_stream(StreamParams p, const StreamPlan& pl, void* workspace, hip
 #define SHIFTATTN_STREAM_LAUNCH(tb_, kwb_) if (pl.tb == tb_ && pl.kwb == kwb_) e = launch_stream<tb_, kwb_>(p, st);
     SHIFTATTN_STREAM_SHAPES(SHIFTATTN_STREAM_LAUNCH)
 #undef SHIFTATTN_STREAM_LAUNCH
-    if (e != hipSuccess || pl.kg == 1) return e;
-    const int64_t items = static_cast<int64_t>(p.M_out) * (p.N / 4);
-    proj_stream_finish_kernel<<<static_cast<unsigned>((items + 255) / 256), 256, 0, st>>>(p, 16 * pl.tb);
-    return hipGetLastError();
+    return e;
 }
 
 }  // namespace
+
+// result = sum over kg partial results [kg][t_rows][N] (fp32) in group order, rounded once, stored with the layout of `mode`
+hipError_t launch_proj_finish(const float* partial, int kg, int t_rows, void* c, int M, int M_out, int N, int mode,
+                              const XchgShape& s, hipStream_t st) {
+    StreamParams p = {};
+    p.partial = const_cast<float*>(partial);
+    p.c = static_cast<uint16_t*>(c);
+    p.M = M;
+    p.M_out = M_out;
+    p.N = N;
+    p.mode = mode;
+    p.kg = kg;
+    p.s = s;
+    const int64_t items = static_cast<int64_t>(M_out) * (N / 4);
+    if (items == 0) return hipSuccess;
+    proj_stream_finish_kernel<<<static_cast<unsigned>((items + 255) / 256), 256, 0, st>>>(p, t_rows);
+    return hipGetLastError();
+}
 
 hipError_t proj_stream_init() {
     hipError_t e = hipSuccess;
@@ -377,7 +392,10 @@ hipError_t launch_qkv_proj_stream(const void* x, const void* w_qkv, void* send, 
     p.K = d_model;
     p.mode = 0;
     p.s = s;
-    return run_stream(p, plan_stream(p.M_out, p.K), workspace, st);
+    const StreamPlan pl = plan_stream(p.M_out, p.K);
+    const hipError_t e = run_stream(p, pl, workspace, st);
+    if (e != hipSuccess || pl.kg == 1) return e;
+    return launch_proj_finish(static_cast<const float*>(workspace), pl.kg, 16 * pl.tb, send, p.M, p.M_out, p.N, 0, s, st);
 }
 
 hipError_t launch_o_proj_stream(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s,
@@ -392,7 +410,10 @@ hipError_t launch_o_proj_stream(const void* recv, const void* w_o, void* out, in
     p.K = s.h * kHeadDim;
     p.mode = 1;
     p.s = s;
-    return run_stream(p, plan_stream(p.M_out, p.K), workspace, st);
+    const StreamPlan pl = plan_stream(p.M_out, p.K);
+    const hipError_t e = run_stream(p, pl, workspace, st);
+    if (e != hipSuccess || pl.kg == 1) return e;
+    return launch_proj_finish(static_cast<const float*>(workspace), pl.kg, 16 * pl.tb, out, p.M, p.M_out, p.N, 1, s, st);
 }
 
 }  // namespace shiftattn

@@ -1,7 +1,7 @@
 """The projections for the few token rows of a decode step (Algorithm 2: the side of the threshold where batches are
 small; Algorithm 1: the QKV and O products) against the CPU float64 oracle, through the C ABI: 1 to 64 rows take the
-weight-streaming kernel (from 17 rows on with a workspace for its k groups), 256 rows and calls without a workspace
-take the large-batch kernel.  Tolerance as for all bf16 projections: |err| <= 2^-8 |ref| + 1e-3 sqrt(K); padding rows
+weight-streaming kernel (from 17 rows on with a workspace for its k groups), a few hundred rows the large-batch kernel
+with k split over workgroups, and calls without a workspace the large-batch kernel as it is.  Tolerance as for all bf16 projections: |err| <= 2^-8 |ref| + 1e-3 sqrt(K); padding rows
 are exact zeros, every byte of the outputs is written, and a call repeated gives the same bits."""
 import numpy as np
 import pytest
@@ -49,6 +49,10 @@ QKV_SMALL = [
     (4, 40, 8, 1024, 5, 8),        # five query heads per KV head; 28 features per workgroup
     (1, 2, 1, 1024, 3, 3),         # fewer features than workgroups x 4
     (8, 64, 8, 5120, 8, 8),        # k not served by the streaming kernel: the large-batch kernel takes it
+    (8, 64, 8, 8192, 100, 104),    # above 64 rows: the large-batch kernel, k split over six workgroups per tile
+    (8, 64, 8, 8192, 256, 256),
+    (8, 32, 8, 4096, 300, 304),    # two token tiles, five k ranges
+    (2, 8, 4, 1024, 600, 600),     # short k: two ranges
 ]
 
 
@@ -85,6 +89,9 @@ O_SMALL = [
     (4, 10, 1024, 7, 8),           # k = 5120: not served by the streaming kernel
     (2, 4, 768, 20, 20),
     (1, 8, 256, 3, 4),
+    (8, 8, 8192, 256, 256),        # the large-batch kernel with k split over eight workgroups per tile
+    (8, 4, 4096, 130, 136),
+    (2, 4, 768, 300, 300),         # a k range that starts inside the second receive buffer
 ]
 
 
@@ -119,9 +126,11 @@ def test_projection_workspace_sizes_and_a_short_workspace():
     assert B.proj_workspace_bytes(16, 10240, 8192) == 0
     assert B.proj_workspace_bytes(17, 10240, 8192) == 2 * 32 * 10240 * 4
     assert B.proj_workspace_bytes(64, 10240, 8192) == 4 * 64 * 10240 * 4
-    assert B.proj_workspace_bytes(65, 10240, 8192) == 0
+    assert B.proj_workspace_bytes(65, 10240, 8192) == 6 * 65 * 10240 * 4       # 40 output tiles: six k ranges each
+    assert B.proj_workspace_bytes(256, 8192, 8192) == 8 * 256 * 8192 * 4
+    assert B.proj_workspace_bytes(16384, 10240, 8192) == 0                     # enough tiles without a split
     assert B.proj_workspace_bytes(64, 6144, 4096) == 2 * 64 * 6144 * 4
-    assert B.proj_workspace_bytes(8, 10240, 5120) == 0
+    assert B.proj_workspace_bytes(8, 10240, 5120) == 6 * 8 * 10240 * 4          # not served by the streaming kernel: split large-batch kernel
     dev = torch.device("cuda:0")
     P, h, h_kv, D, d_model, T = 8, 64, 8, 128, 8192, 20
     g = torch.Generator(device=dev)
