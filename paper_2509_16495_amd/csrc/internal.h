@@ -88,7 +88,10 @@ inline double launch_model_seconds(long wgs, int splits, int cols, int total_q, 
     const double unit = 4.0 * 128 * cols * static_cast<double>(max_seq_len) / 3.9e12;  // one workgroup, all keys, at 1 PFLOP/s per chip
     const double merge = 2.0 * total_q * hq_l * 130 * 4 / 4.0e12;                     // partials written and read back, per range
     const double load = static_cast<double>(wgs) * splits / 256.0;
-    const double rounds = load <= 1.0 ? 1.0 : load + 0.25;                            // dynamic dispatch: a quarter round of tail
+    // equal workgroups are dispatched as compute units fall free: whole rounds while they are few, half a round of tail
+    // once their durations have drifted apart
+    const double whole = static_cast<double>(static_cast<long>(load + 0.999999));
+    const double rounds = load <= 1.0 ? 1.0 : (whole < load + 0.5 ? whole : load + 0.5);
     return rounds / splits * unit + (splits > 1 ? splits * merge + 5.0e-6 : 0.0);
 }
 bool prefill_mfma64_supported(const AttnShape& a);

@@ -653,15 +653,24 @@ Plan make_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const 
     pl.tile_tokens = 128 >> pl.gs_log2;
     const int tiles = (max_q_len + pl.tile_tokens - 1) / pl.tile_tokens;
     pl.pair_ranks = (tiles + 1) / 2;
-    // Split the keys when the tiles alone cannot fill the chip (long cached context, short chunk).
-    const long wgs = static_cast<long>((total_q + pl.tile_tokens - 1) / pl.tile_tokens + num_seqs) / 2 * pl.head_slots + 1;
+    // Key ranges per column tile: the count that minimises the model of a launch that also decides between the two
+    // kernels - more ranges when the tiles alone cannot fill the chip (long cached context, short chunk) or fill it
+    // with a ragged last round (320 equal workgroups on 256 compute units), as long as the merge does not eat the gain.
+    const long wgs = static_cast<long>(pl.pair_ranks) * num_seqs * pl.head_slots;
     int splits = 1;
     const int forced = option_prefill_splits();
-    if (forced > 0) splits = forced;
-    else if (wgs < 192) {
-        const int by_fill = static_cast<int>((512 + wgs - 1) / wgs);
+    if (forced > 0) {
+        splits = forced;
+    } else {
         const int by_len = max_seq_len / (16 * kKvTile);  // at least 16 key tiles per range
-        splits = by_fill < by_len ? by_fill : by_len;
+        double best = launch_model_seconds(wgs, 1, 128, total_q, max_seq_len, a.hq_l);
+        for (int cand = 2; cand <= 16 && cand <= by_len; ++cand) {
+            const double t = launch_model_seconds(wgs, cand, 128, total_q, max_seq_len, a.hq_l);
+            if (t < best * 0.97) {  // a further range must pay for itself
+                best = t;
+                splits = cand;
+            }
+        }
     }
     if (splits < 1) splits = 1;
     if (splits > 64) splits = 64;
