@@ -130,6 +130,8 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     };
     auto dma_1k = [&](const unsigned char* base, uint32_t lane_off, unsigned char* dst) {
         const uint32_t m0v = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(dst));
+        // (M0 is reserved by the compiler - it sets it right before each use of its own and keeps no value in it, and
+        // rejects it on a clobber list - so writing it here needs no clobber.)
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :: "s"(m0v), "v"(lane_off), "s"(scalar_ptr(base)) : "memory");
     };

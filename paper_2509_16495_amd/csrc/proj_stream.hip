@@ -126,6 +126,8 @@ __global__ __launch_bounds__(kSThreads) void proj_stream_kernel(StreamParams p) 
     };
     // 1 KiB from a wavefront-uniform base + a 32-bit byte offset per lane into LDS at dst (uniform); waited for by count
     auto dma_1k = [&](const unsigned char* base, uint32_t lane_off, uint32_t dst) {
+        // (M0 is reserved by the compiler - it sets it right before each use of its own and keeps no value in it, and
+        // rejects it on a clobber list - so writing it here needs no clobber.)
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" SHIFTATTN_STREAM_HINT
                      :: "s"(dst), "v"(lane_off), "s"(scalar_ptr(base)) : "memory");
     };
