@@ -358,15 +358,32 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
     return hipGetLastError();
 }
 
-// Few output tiles (a few hundred token rows): k is split over workgroups until the tiles fill the chip, each range at
-// least 16 k tiles long.  1: no split (enough tiles, a short k, or FP8 operands).
+// Few output tiles (up to about a thousand token rows): k is split over workgroups when a rough model of the launch
+// says so - a workgroup walks its k range at about 6.5 TFLOP/s, workgroups beyond one per compute unit queue up in
+// rounds, and every range adds fp32 partial results that are written and read back.  Ranges are at least 16 k tiles
+// long.  1: no split (enough tiles, a short k, or FP8 operands).
 int k_splits_for(int M_out, int N, int K) {
     const int64_t tiles = static_cast<int64_t>(N / kTile) * ((M_out + kTile - 1) / kTile);
-    if (tiles == 0 || tiles >= 128) return 1;
-    const int by_fill = static_cast<int>((256 + tiles / 2) / tiles);
+    if (tiles == 0 || tiles >= 512) return 1;
+    const double walk = 2.0 * kTile * kTile * static_cast<double>(K) / 6.5e12;   // one workgroup over all of k
+    const double partial = 2.0 * M_out * static_cast<double>(N) * sizeof(float) / 4.0e12;
+    auto model = [&](int sp) {
+        const double load = static_cast<double>(tiles) * sp / 256.0;
+        const double whole = static_cast<double>(static_cast<long>(load + 0.999999));
+        const double rounds = load <= 1.0 ? 1.0 : (whole < load + 0.5 ? whole : load + 0.5);
+        return rounds / sp * walk + (sp > 1 ? sp * partial + 5.0e-6 : 0.0);
+    };
     const int by_length = K / 32 / 16;
-    const int sp = by_fill < by_length ? by_fill : by_length;
-    return sp < 2 ? 1 : sp;
+    int best = 1;
+    double t_best = model(1);
+    for (int sp = 2; sp <= 16 && sp <= by_length; ++sp) {
+        const double t = model(sp);
+        if (t < 0.97 * t_best) {
+            t_best = t;
+            best = sp;
+        }
+    }
+    return best;
 }
 
 }  // namespace

@@ -89,7 +89,7 @@ O_SMALL = [
     (4, 10, 1024, 7, 8),           # k = 5120: not served by the streaming kernel
     (2, 4, 768, 20, 20),
     (1, 8, 256, 3, 4),
-    (8, 8, 8192, 256, 256),        # the large-batch kernel with k split over eight workgroups per tile
+    (8, 8, 8192, 256, 256),        # the large-batch kernel with k split over five workgroups per tile
     (8, 4, 4096, 130, 136),
     (2, 4, 768, 300, 300),         # a k range that starts inside the second receive buffer
 ]
@@ -127,7 +127,7 @@ def test_projection_workspace_sizes_and_a_short_workspace():
     assert B.proj_workspace_bytes(17, 10240, 8192) == 2 * 32 * 10240 * 4
     assert B.proj_workspace_bytes(64, 10240, 8192) == 4 * 64 * 10240 * 4
     assert B.proj_workspace_bytes(65, 10240, 8192) == 6 * 65 * 10240 * 4       # 40 output tiles: six k ranges each
-    assert B.proj_workspace_bytes(256, 8192, 8192) == 8 * 256 * 8192 * 4
+    assert B.proj_workspace_bytes(256, 8192, 8192) == 5 * 256 * 8192 * 4
     assert B.proj_workspace_bytes(16384, 10240, 8192) == 0                     # enough tiles without a split
     assert B.proj_workspace_bytes(64, 6144, 4096) == 2 * 64 * 6144 * 4
     assert B.proj_workspace_bytes(8, 10240, 5120) == 6 * 8 * 10240 * 4          # not served by the streaming kernel: split large-batch kernel
