@@ -207,6 +207,56 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float* _
     }
 }
 
+// Merge of a split prefill (bf16 output, D = 128, every row has the same few parts): many rows, few parts, so a row
+// takes 32 threads (four head-dim elements each, 16-byte loads of a part's row, one 8-byte store) and a workgroup eight
+// rows; the parts are added in part order with the arithmetic of combine_kernel, so both give the same bits.
+constexpr int kSplitRowsPerWg = 8;
+__global__ __launch_bounds__(32 * kSplitRowsPerWg) void combine_splits_kernel(const float* __restrict__ o_part,
+                                                                              const float* __restrict__ ml_part,
+                                                                              int64_t rows, int hq_l, int n_parts,
+                                                                              uint16_t* __restrict__ out, int64_t out_stride,
+                                                                              float out_scale) {
+    constexpr int D = 128;
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * kSplitRowsPerWg + (threadIdx.x >> 5);
+    if (row >= rows) return;
+    const int q4 = threadIdx.x & 31;
+    const float* o_row = o_part + row * D + 4 * q4;
+    const size_t part_stride = static_cast<size_t>(rows) * D;
+    // the first parts' rows are requested before the weights are known
+    constexpr int kEarly = 4;
+    f32x4 early[kEarly];
+#pragma unroll
+    for (int c = 0; c < kEarly; ++c) early[c] = c < n_parts ? *reinterpret_cast<const f32x4*>(o_row + c * part_stride) : f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_star = -INFINITY;
+    for (int c = 0; c < n_parts; ++c) m_star = fmaxf(m_star, ml_part[(c * rows + row) * 2]);
+    float l_star = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    auto add_part = [&](int c, f32x4 v) {
+        const f32x2 ml = *reinterpret_cast<const f32x2*>(ml_part + (c * rows + row) * 2);
+        const float w = (ml[0] == -INFINITY) ? 0.f : exp2f(ml[0] - m_star);
+        l_star = fmaf(ml[1], w, l_star);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] = fmaf(v[e], w, acc[e]);
+    };
+#pragma unroll
+    for (int c = 0; c < kEarly; ++c)
+        if (c < n_parts) add_part(c, early[c]);
+#pragma unroll 4
+    for (int c = kEarly; c < n_parts; ++c) add_part(c, *reinterpret_cast<const f32x4*>(o_row + c * part_stride));
+    const float inv = l_star > 0.f ? out_scale / l_star : 0.f;
+    const int64_t tok = row / hq_l;
+    const int head = static_cast<int>(row - tok * hq_l);
+    uint16_t* dst = out + tok * out_stride + static_cast<int64_t>(head) * D + 4 * q4;
+    uint16_t h[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) store_elem(&h[e], acc[e] * inv);
+    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+    *reinterpret_cast<u32x2_t*>(dst) = u32x2_t{static_cast<uint32_t>(h[0]) | (static_cast<uint32_t>(h[1]) << 16),
+                                               static_cast<uint32_t>(h[2]) | (static_cast<uint32_t>(h[3]) << 16)};
+}
+
 // Merge for the flat decode kernel (bf16 output, D = 128; out_scale = v_scale of an FP8 cache, else 1): one workgroup of one or four thread groups
 // per output row; group pg sums the parts c = pg, pg + groups, ... for its 128 head-dim elements (with
 // four groups sixteen partial rows are in flight per element) and the sums are added in group order.
@@ -330,6 +380,11 @@ hipError_t launch_combine(const float* o_part, const float* ml_part, int n_rows,
                           float out_scale, hipStream_t st) {
     const int64_t rows = static_cast<int64_t>(n_rows) * hq_l;
     if (rows == 0) return hipSuccess;
+    if (elem == 2 && D == 128 && mode == 0 && n_parts <= kCombineMaxParts && (out_stride % 4) == 0) {
+        combine_splits_kernel<<<static_cast<unsigned>((rows + kSplitRowsPerWg - 1) / kSplitRowsPerWg), 32 * kSplitRowsPerWg, 0, st>>>(
+            o_part, ml_part, rows, hq_l, n_parts, static_cast<uint16_t*>(out), out_stride, out_scale);
+        return hipGetLastError();
+    }
     if (elem == 2)
         combine_kernel<uint16_t><<<static_cast<unsigned>(rows), 128, 0, st>>>(
             o_part, ml_part, n_rows, hq_l, D, n_parts, mode, seq_lens, chunk, static_cast<uint16_t*>(out), out_stride,
