@@ -73,7 +73,8 @@ struct GemmParams {
 
 // kFp8: both operands are FP8 E4M3 codes (v_mfma_scale_f32_32x32x64_f8f6f4 with unit block scales, fp32
 // accumulation); the result is multiplied by the token's and the feature's scale before it is rounded to bf16.
-template <bool kFp8>
+// kSplit: the workgroup covers one of p.k_splits ranges of k and leaves fp32 sums in p.partial (bf16 operands only)
+template <bool kFp8, bool kSplit>
 __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     constexpr int kElem = kFp8 ? 1 : 2;          // bytes per operand element
     constexpr int kBK = kRowBytes / kElem;       // k per tile
@@ -85,12 +86,13 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     const int wn = wave % kWavesN, wm = wave / kWavesN;
     // feature tiles vary fastest: workgroups that run together share the token rows in L2
     const int n_tiles = p.N / kTile;
-    const int tile_id = blockIdx.x / p.k_splits, split = blockIdx.x - tile_id * p.k_splits;
+    const int n_splits = kSplit ? p.k_splits : 1;
+    const int tile_id = blockIdx.x / n_splits, split = blockIdx.x - tile_id * n_splits;
     const int n0 = (tile_id % n_tiles) * kTile, m0 = (tile_id / n_tiles) * kTile;
     // this workgroup's k tiles: [kt0, kt0 + k_steps) of the K / kBK in all
     const int kt_all = p.K / kBK;
-    const int kt0 = static_cast<int>(static_cast<int64_t>(kt_all) * split / p.k_splits);
-    const int k_steps = static_cast<int>(static_cast<int64_t>(kt_all) * (split + 1) / p.k_splits) - kt0;
+    const int kt0 = kSplit ? static_cast<int>(static_cast<int64_t>(kt_all) * split / n_splits) : 0;
+    const int k_steps = kSplit ? static_cast<int>(static_cast<int64_t>(kt_all) * (split + 1) / n_splits) - kt0 : kt_all;
 
     // ---- direct-to-LDS loads: this wavefront fills rows 32 wave .. 32 wave + 31 of both operand tiles, sixteen rows
     // (1 KiB) per instruction; lane -> row 16 j + lane / 4, LDS piece position lane % 4, logical piece = position ^ key
@@ -305,7 +307,7 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
                 }
         }
     };
-    if (p.k_splits > 1) {   // this k range's fp32 sums, [split][token][feature]; proj_finish adds the ranges and does the layout
+    if constexpr (kSplit) {   // this k range's fp32 sums, [split][token][feature]; proj_finish adds the ranges and does the layout
         float* base = p.partial + static_cast<size_t>(split) * p.M_out * p.N + f_wave + 4 * half;
 #pragma unroll
         for (int mt = 0; mt < kMT; ++mt) {
@@ -354,7 +356,13 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
     const int64_t wgs = static_cast<int64_t>(p.N / kTile) * ((p.M_out + kTile - 1) / kTile) * p.k_splits;
     if (wgs == 0) return hipSuccess;
     if (wgs > 0x7FFFFFFF) return hipErrorInvalidValue;
-    proj_gemm_kernel<kFp8><<<static_cast<unsigned>(wgs), kGemmThreads, kGemmLds, st>>>(p);
+    if constexpr (!kFp8) {
+        if (p.k_splits > 1) {
+            proj_gemm_kernel<false, true><<<static_cast<unsigned>(wgs), kGemmThreads, kGemmLds, st>>>(p);
+            return hipGetLastError();
+        }
+    }
+    proj_gemm_kernel<kFp8, false><<<static_cast<unsigned>(wgs), kGemmThreads, kGemmLds, st>>>(p);
     return hipGetLastError();
 }
 
@@ -390,10 +398,13 @@ int k_splits_for(int M_out, int N, int K) {
 
 // bf16, head_dim 128; the feature dimension of either product must be a multiple of the 256-wide tile
 hipError_t proj_gemm_init() {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel<false>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel<false, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel<true>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel<false, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel<true, false>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
 }
 
