@@ -63,6 +63,37 @@ def test_options_and_their_bounds(B):
     assert B.prefill_workspace_bytes(1, 2048, 2048, 133120, a) == auto
 
 
+def test_launch_plans_follow_the_shape_of_the_batch(B):
+    """Host logic behind the workspace queries (no GPU work): how many key ranges a prefill launch takes, seen through
+    the size of its partial results, `ranges x rows x heads x (128 + 2) x 4` bytes; and the k ranges / k groups of the
+    projections.  Shapes: the benchmark's batches (Table 4 head geometries on 8 ranks)."""
+    def ranges(num_seqs, total_q, max_q, max_ctx, hq):
+        a = _attn(B, num_q_heads=hq, max_blocks_per_seq=(max_ctx + 15) // 16)
+        ws = B.prefill_workspace_bytes(num_seqs, total_q, max_q, max_ctx, a)
+        assert ws % (total_q * hq * 130 * 4) == 0
+        return ws // (total_q * hq * 130 * 4)
+
+    assert ranges(4, 16384, 4096, 4096, 4) == 0         # 256 equal workgroups of 128-column tiles: one round, no split
+    assert ranges(1, 16384, 16384, 16384, 8) == 0       # 256 pairs of 256-column tiles
+    assert ranges(1, 2048, 2048, 133120, 8) == 8        # 32 pairs: eight ranges fill the chip
+    assert ranges(1, 16384, 16384, 16384, 5) == 3       # 161 pairs: three ranges make two full rounds
+    assert ranges(4, 16384, 4096, 4096, 5) == 0         # short contexts: the merge would cost more than the ragged round
+    try:
+        B.set_option(B.OPT_PREFILL_TILE, 128)
+        assert ranges(1, 2048, 2048, 133120, 8) == 4    # 64 pairs of 128-column tiles
+        B.set_option(B.OPT_PREFILL_TILE, 256)
+        assert ranges(4, 16384, 4096, 4096, 4) == 2     # 128 pairs of 256-column tiles
+    finally:
+        B.set_option(B.OPT_PREFILL_TILE, 0)
+    # projections: k groups of the streaming kernel (token slice of a wavefront <= 128 registers), k ranges of the
+    # large-batch kernel while its tiles are few, nothing once they fill the chip
+    n, k = 10240, 8192
+    assert [B.proj_workspace_bytes(t, n, k) // (n * 4) for t in (1, 16, 17, 32, 33, 64)] == [0, 0, 2 * 32, 2 * 32, 4 * 64, 4 * 64]
+    assert B.proj_workspace_bytes(65, n, k) == 6 * 65 * n * 4 and B.proj_workspace_bytes(512, n, k) == 3 * 512 * n * 4
+    assert B.proj_workspace_bytes(1024, n, k) == 0 and B.proj_workspace_bytes(16384, n, k) == 0
+    assert B.proj_workspace_bytes(8, 6144, 4096) == 0 and B.proj_workspace_bytes(0, n, k) == 0
+
+
 def test_struct_layouts_match_header(B):
     assert ctypes.sizeof(B.Xchg) == 20
     assert ctypes.sizeof(B.Attn) == 72 and B.Attn.q_stride.offset == 32 and B.Attn.kv_format.offset == 56
