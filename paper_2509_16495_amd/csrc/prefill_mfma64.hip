@@ -186,6 +186,13 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
     if (rank > hi_tile) return;  // uniform
     const int n_pass = (hi_tile == rank) ? 1 : 2;
     const_i32_ptr table = (const_i32_ptr)(p.block_table + static_cast<size_t>(s) * p.max_blocks);
+    // Inside the key loop the block id of the coming iteration is fetched by a *vector* load: a scalar load shares its
+    // counter with the LDS operand reads and returns out of order with them, so while one is outstanding every wait for
+    // an operand becomes a wait for everything (measured: 5 % of the kernel).  The address is made to look per-lane
+    // (a zero the compiler cannot see through); the id is back in a scalar register by the time the loads need it.
+    const int32_t* table_v = p.block_table + static_cast<size_t>(s) * p.max_blocks;
+    int lane_zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
     const int last_block = (ctx - 1) / kBlockSize;
 
     // in the key loop wavefronts 0 and 1 bring K (cache block 0 / 1 of a tile), wavefronts 2 and 3 V^T
@@ -305,7 +312,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         auto load_block_index = [&](int j) SHIFTATTN_INLINE -> int {
             return min(2 * (kt_begin + j + (is_k ? 3 : 1)) + ld_blk, last_block);
         };
-        const unsigned char* ld_src = nullptr;  // source of the loads of the coming iteration (uniform)
+        int id_vec = 0;  // block id of the coming iteration's loads, in a vector register until they are issued
         const int ld_limit = __builtin_amdgcn_readfirstlane(is_k ? n - 3 : n);  // iterations in which this wavefront loads
 
         // zero the V^T entries of keys at or past the context in the given stage (tile kt)
@@ -432,15 +439,16 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             };
             // what runs once per iteration besides the slots: the barrier (with the wait for this wavefront's loads of
             // the iteration before), then the loads into the stages nobody reads any more, then the next block id
-            int id_next = 0;
             auto fill = [&]() SHIFTATTN_INLINE {
                 // a bare barrier: __syncthreads() would first drain every outstanding LDS read.  What has to be complete
-                // is this wavefront's loads of the iteration before (waited for here) and its reads of the stages about
-                // to be overwritten (their data went into MFMAs one iteration ago).
+                // is this wavefront's loads of the iteration before (waited for here, and with them the block id
+                // requested then) and its reads of the stages about to be overwritten (their data went into MFMAs one
+                // iteration ago).
                 wait_vm0();
                 asm volatile("s_barrier" ::: "memory");
-                if (j < ld_limit) dma_4k(ld_src, ld_off, lds + (is_k ? st0 : st1) + ld_dst);
-                id_next = table[load_block_index(j + 1)];  // consumed at the bottom of this iteration
+                if (j < ld_limit)
+                    dma_4k(uniform_ptr(block_base(__builtin_amdgcn_readfirstlane(id_vec))), ld_off, lds + (is_k ? st0 : st1) + ld_dst);
+                id_vec = table_v[load_block_index(j + 1) + lane_zero];  // for the loads of the next iteration
             };
 
             if constexpr (NOPS == 0) {
@@ -518,13 +526,6 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
                 }
                 if (__builtin_amdgcn_ballot_w64(bad)) redo = true;
             }
-            {   // source of the next iteration's loads: forces the wait for the block id here, not at the top
-                const unsigned char* nxt = block_base(id_next);
-                uint32_t lo = static_cast<uint32_t>(reinterpret_cast<uint64_t>(nxt));
-                uint32_t hi = static_cast<uint32_t>(reinterpret_cast<uint64_t>(nxt) >> 32);
-                asm volatile("" : "+s"(lo), "+s"(hi));
-                ld_src = reinterpret_cast<const unsigned char*>((static_cast<uint64_t>(hi) << 32) | lo);
-            }
             const int st_new = st0;  // (j + 3) % 3
             st0 = st1;
             st1 = st2;
@@ -553,7 +554,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
                 // the loads "iteration -1" would have issued: K of tile 2 into stage 2, V^T of tile 0 into stage 0
                 const int id_q = table[load_block_index(-1)];
                 dma_4k(uniform_ptr(block_base(id_q)), ld_off, lds + (is_k ? 2 * kStageBytes : 0) + ld_dst);
-                ld_src = uniform_ptr(block_base(table[load_block_index(0)]));
+                id_vec = table_v[load_block_index(0) + lane_zero];
             }
             st0 = 0, st1 = kStageBytes, st2 = 2 * kStageBytes;
 #pragma unroll
