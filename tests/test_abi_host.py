@@ -282,6 +282,15 @@ def test_projection_entry_points_reject_bad_arguments(B):
         assert B.last_error()
     bad_p = _xchg(B, **{**ok, "P": 3})
     assert q(FAKE, FAKE, FAKE, 6, 6, 8192, ctypes.byref(bad_p), None) == B.EINVAL          # heads not divisible by P
+    # the forms with a workspace: the same checks, and a workspace must exist and be aligned if a size is given
+    qw, ow = L.shiftattn_qkv_proj_pack_ws, L.shiftattn_unpack_o_proj_ws
+    for fn, desc in ((qw, x), (ow, xo)):
+        assert fn(FAKE, FAKE, FAKE, 9, 8, 8192, ctypes.byref(desc), None, 0, None) == B.EINVAL
+        assert fn(None, FAKE, FAKE, 8, 8, 8192, ctypes.byref(desc), None, 0, None) == B.EINVAL
+        assert fn(FAKE, FAKE, FAKE, 32, 32, 8192, ctypes.byref(desc), None, 4096, None) == B.EINVAL and "workspace" in B.last_error()
+        assert fn(FAKE, FAKE, FAKE, 32, 32, 8192, ctypes.byref(desc), ctypes.c_void_p(0x1004), 4096, None) == B.EINVAL
+        assert fn(None, None, None, 0, 0, 8192, ctypes.byref(desc), None, 0, None) == B.OK
+    assert L.shiftattn_proj_workspace_bytes(-1, 10240, 8192) == 0 and L.shiftattn_proj_workspace_bytes(8, 0, 8192) == 0
     # empty problems are valid no-ops and touch nothing
     assert q(None, None, None, 0, 0, 8192, ctypes.byref(x), None) == B.OK
     assert o(None, None, None, 0, 8, 8192, ctypes.byref(xo), None) == B.OK
