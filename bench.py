@@ -595,6 +595,38 @@ def main() -> int:
                 dt = time.perf_counter() - t0
                 small_proj["cpu_baseline"] = cpu_obj(dt, 2.0 * Ts * d_model * wq.shape[0] / 1e9, "GFLOP/s", "qkv_proj_pack of the 16-token call, whole")
             del xs_, snd, rcv, eo_s, plain_q, plain_a, ws_q, ws_o
+        # the same over FP8 operands (four weight copies in rotation: 336 / 268 MB)
+        wq8_rot = [wq8] + [wq8.clone() for _ in range(3)]
+        wo8_rot = [wo8] + [wo8.clone() for _ in range(3)]
+        small_fp8 = {}
+        for Ts in (8, 64, 256):
+            xq_s, xsc_s = xq[:Ts].contiguous(), xsc[:Ts].contiguous()
+            rq_s, rsc_s = rq[:, :Ts].contiguous(), rsc[:Ts].contiguous()
+            snd = torch.empty((x3.P, Ts, h3 // x3.P + 2 * (hkv3 // x3.P), D), dtype=bf, device=dev)
+            eo_s = torch.empty((Ts, d_model), dtype=bf, device=dev)
+            ws_q = torch.empty(max(B.proj_workspace_bytes(Ts, wq.shape[0], d_model, fp8=True), 16), dtype=torch.uint8, device=dev)
+            ws_o = torch.empty(max(B.proj_workspace_bytes(Ts, d_model, h3 * D, fp8=True), 16), dtype=torch.uint8, device=dev)
+            turn = [0]
+
+            def nxt4(lst):
+                turn[0] = (turn[0] + 1) % 4
+                return lst[turn[0]]
+
+            row = {}
+            for nm, fn, wbytes in (("qkv_proj_pack_fp8", lambda: B.qkv_proj_pack_fp8(xq_s, xsc_s, nxt4(wq8_rot), wsc, snd, x3.P, h3, hkv3, workspace=ws_q),
+                                    wq8.numel()),
+                                   ("unpack_o_proj_fp8", lambda: B.unpack_o_proj_fp8(rq_s, rsc_s, nxt4(wo8_rot), wosc, eo_s, workspace=ws_o),
+                                    wo8.numel())):
+                us = time_in_graph(fn, inner=12) * 1e3
+                row[nm] = {"us": round(us, 2), "weight_bytes": wbytes, "us_to_stream_the_weights_at_peak": round(wbytes / PEAK_HBM_GBPS / 1e3, 2),
+                           "roofline": roof("proj_gemm_kernel<fp8> (k split over workgroups) + proj_stream_finish_kernel", "hbm",
+                                            wbytes / (us * 1e-6) / 1e9, PEAK_HBM_GBPS, "GB/s")}
+            small_fp8[f"T={Ts}"] = row
+            del snd, eo_s, ws_q, ws_o
+        small_proj["fp8_operands"] = small_fp8
+        log("[bench] the same over FP8 operands, us: " +
+            ", ".join(f"{k}: qkv {v['qkv_proj_pack_fp8']['us']} o {v['unpack_o_proj_fp8']['us']}" for k, v in small_fp8.items()))
+        del wq8_rot, wo8_rot
         result["decode_sized_projections"] = {
             "workload": f"the configs[2] shard's projections (d_model {d_model}, {h3} query + 2 x {hkv3} KV heads of 128, {x3.P} exchange buffers, bf16) "
                         "at 1 .. 256 token rows; one pass over the weights bounds them",

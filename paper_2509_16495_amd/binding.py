@@ -65,6 +65,10 @@ def lib() -> ctypes.CDLL:
         L.shiftattn_unpack_o_proj_ws.argtypes = [vp, vp, vp, i32, i32, i32, xp, vp, ctypes.c_size_t, vp]
         L.shiftattn_proj_workspace_bytes.argtypes = [i32, i32, i32]
         L.shiftattn_proj_workspace_bytes.restype = ctypes.c_size_t
+        L.shiftattn_proj_workspace_bytes_fp8.argtypes = [i32, i32, i32]
+        L.shiftattn_proj_workspace_bytes_fp8.restype = ctypes.c_size_t
+        L.shiftattn_qkv_proj_pack_fp8_ws.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, xp, vp, ctypes.c_size_t, vp]
+        L.shiftattn_unpack_o_proj_fp8_ws.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, xp, vp, ctypes.c_size_t, vp]
         L.shiftattn_quantize_rows_fp8.argtypes = [vp, vp, vp, i32, i32, vp]
         L.shiftattn_quantize_recv_fp8.argtypes = [vp, vp, vp, i32, i32, xp, vp]
         L.shiftattn_qkv_proj_pack_fp8.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, xp, vp]
@@ -212,8 +216,10 @@ def unpack_head2seq(recv: torch.Tensor, out: torch.Tensor) -> None:
 
 
 # ---- KV cache and attention -------------------------------------------------------------------------
-def proj_workspace_bytes(rows: int, n_features: int, k: int) -> int:
+def proj_workspace_bytes(rows: int, n_features: int, k: int, fp8: bool = False) -> int:
     """Bytes of workspace that make a projection of `rows` token rows with an [n_features, k] matrix one pass over the weights."""
+    if fp8:
+        return int(lib().shiftattn_proj_workspace_bytes_fp8(rows, n_features, k))
     return int(lib().shiftattn_proj_workspace_bytes(rows, n_features, k))
 
 
@@ -265,7 +271,7 @@ def quantize_recv_fp8(recv: torch.Tensor, codes: torch.Tensor, scales: torch.Ten
 
 
 def qkv_proj_pack_fp8(x_codes: torch.Tensor, x_scales: torch.Tensor, w_codes: torch.Tensor, w_scales: torch.Tensor,
-                      send: torch.Tensor, P: int, h: int, h_kv: int) -> None:
+                      send: torch.Tensor, P: int, h: int, h_kv: int, workspace: Optional[torch.Tensor] = None) -> None:
     """FP8 E4M3 codes x [T, d_model] and w [(h + 2 h_kv) D, d_model] with their row scales -> bf16 send buffers."""
     T, d_model = x_codes.shape
     T_pad, D = send.shape[1], send.shape[3]
@@ -274,12 +280,13 @@ def qkv_proj_pack_fp8(x_codes: torch.Tensor, x_scales: torch.Tensor, w_codes: to
     assert send.shape[0] == P and send.shape[2] == h // P + 2 * local_kv_heads(P, h_kv)
     assert all(t.is_contiguous() for t in (x_codes, x_scales, w_codes, w_scales, send))
     xc = Xchg(P, h, h_kv, D, BF16)
-    _check(lib().shiftattn_qkv_proj_pack_fp8(_ptr(x_codes), _ptr(x_scales), _ptr(w_codes), _ptr(w_scales), _ptr(send), T, T_pad,
-                                             d_model, ctypes.byref(xc), _stream()))
+    _check(lib().shiftattn_qkv_proj_pack_fp8_ws(_ptr(x_codes), _ptr(x_scales), _ptr(w_codes), _ptr(w_scales), _ptr(send), T, T_pad,
+                                                d_model, ctypes.byref(xc), _ptr(workspace) if workspace is not None else None,
+                                                workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()))
 
 
 def unpack_o_proj_fp8(recv_codes: torch.Tensor, a_scales: torch.Tensor, w_codes: torch.Tensor, w_scales: torch.Tensor,
-                      out: torch.Tensor) -> None:
+                      out: torch.Tensor, workspace: Optional[torch.Tensor] = None) -> None:
     """FP8 E4M3 codes recv [P, T_pad, hq_l, D] (one scale per token) and w [d_model, h D] (one per feature) -> out [T, d_model] bf16."""
     P, T_pad, hq_l, D = recv_codes.shape
     T, d_model = out.shape
@@ -287,8 +294,9 @@ def unpack_o_proj_fp8(recv_codes: torch.Tensor, a_scales: torch.Tensor, w_codes:
     assert w_codes.shape == (d_model, P * hq_l * D) and a_scales.shape[0] >= T and w_scales.shape == (d_model,)
     assert all(t.is_contiguous() for t in (recv_codes, a_scales, w_codes, w_scales, out))
     xc = Xchg(P, P * hq_l, 0, D, BF16)
-    _check(lib().shiftattn_unpack_o_proj_fp8(_ptr(recv_codes), _ptr(a_scales), _ptr(w_codes), _ptr(w_scales), _ptr(out), T, T_pad,
-                                             d_model, ctypes.byref(xc), _stream()))
+    _check(lib().shiftattn_unpack_o_proj_fp8_ws(_ptr(recv_codes), _ptr(a_scales), _ptr(w_codes), _ptr(w_scales), _ptr(out), T, T_pad,
+                                                d_model, ctypes.byref(xc), _ptr(workspace) if workspace is not None else None,
+                                                workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()))
 
 
 def attn_desc(q: torch.Tensor, kv_cache: torch.Tensor, block_table: torch.Tensor, softmax_scale: float,

@@ -386,7 +386,12 @@ int shiftattn_unpack_o_proj(const void* recv, const void* w_o, void* out, int32_
 size_t shiftattn_proj_workspace_bytes(int32_t rows, int32_t n_features, int32_t k) {
     if (rows < 1 || n_features < 1 || k < 1 || force_generic()) return 0;
     if (proj_stream_takes(rows, n_features, k, static_cast<size_t>(-1))) return proj_stream_workspace(rows, n_features, k);
-    return proj_gemm_workspace(rows, n_features, k);
+    return proj_gemm_workspace(rows, n_features, k, false);
+}
+
+size_t shiftattn_proj_workspace_bytes_fp8(int32_t rows, int32_t n_features, int32_t k) {
+    if (rows < 1 || n_features < 1 || k < 1 || force_generic()) return 0;
+    return proj_gemm_workspace(rows, n_features, k, true);
 }
 
 int shiftattn_quantize_rows_fp8(const void* x, void* codes, float* scales, int32_t rows, int32_t cols, void* stream) {
@@ -416,8 +421,9 @@ int shiftattn_quantize_recv_fp8(const void* recv, void* codes, float* scales, in
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "quantize_recv_fp8 launch");
 }
 
-int shiftattn_qkv_proj_pack_fp8(const void* x_codes, const float* x_scales, const void* w_codes, const float* w_scales,
-                                void* send, int32_t T, int32_t T_pad, int32_t d_model, const shiftattn_xchg* xc, void* stream) {
+int shiftattn_qkv_proj_pack_fp8_ws(const void* x_codes, const float* x_scales, const void* w_codes, const float* w_scales,
+                                   void* send, int32_t T, int32_t T_pad, int32_t d_model, const shiftattn_xchg* xc,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
     XchgShape s;
     if (int rc = check_xchg(xc, T, T_pad, true, &s)) return rc;
     if (d_model < 1) return fail(SHIFTATTN_EINVAL, "d_model = %d", d_model);
@@ -429,13 +435,22 @@ int shiftattn_qkv_proj_pack_fp8(const void* x_codes, const float* x_scales, cons
     if (!send || (s.T > 0 && (!x_codes || !w_codes || !x_scales || !w_scales))) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
     if (!aligned16(x_codes) || !aligned16(w_codes) || !aligned16(send) || !aligned16(w_scales) || (reinterpret_cast<uintptr_t>(x_scales) & 3))
         return fail(SHIFTATTN_EINVAL, "x_codes / w_codes / w_scales / send must be 16-byte aligned, x_scales 4-byte");
+    if (workspace_bytes > 0 && (!workspace || !aligned16(workspace)))
+        return fail(SHIFTATTN_EINVAL, "workspace is NULL or not 16-byte aligned");
     if (int rc = ensure_device_ready()) return rc;
-    hipError_t e = launch_qkv_proj_pack(x_codes, w_codes, send, d_model, s, x_scales, w_scales, nullptr, 0, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_qkv_proj_pack(x_codes, w_codes, send, d_model, s, x_scales, w_scales, force_generic() ? nullptr : workspace,
+                                        workspace_bytes, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "qkv_proj_pack_fp8 launch");
 }
 
-int shiftattn_unpack_o_proj_fp8(const void* recv_codes, const float* a_scales, const void* w_codes, const float* w_scales,
-                                void* out, int32_t T, int32_t T_pad, int32_t d_model, const shiftattn_xchg* xc, void* stream) {
+int shiftattn_qkv_proj_pack_fp8(const void* x_codes, const float* x_scales, const void* w_codes, const float* w_scales,
+                                void* send, int32_t T, int32_t T_pad, int32_t d_model, const shiftattn_xchg* xc, void* stream) {
+    return shiftattn_qkv_proj_pack_fp8_ws(x_codes, x_scales, w_codes, w_scales, send, T, T_pad, d_model, xc, nullptr, 0, stream);
+}
+
+int shiftattn_unpack_o_proj_fp8_ws(const void* recv_codes, const float* a_scales, const void* w_codes, const float* w_scales,
+                                   void* out, int32_t T, int32_t T_pad, int32_t d_model, const shiftattn_xchg* xc,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
     XchgShape s;
     if (int rc = check_xchg(xc, T, T_pad, false, &s)) return rc;
     if (d_model < 1) return fail(SHIFTATTN_EINVAL, "d_model = %d", d_model);
@@ -446,9 +461,17 @@ int shiftattn_unpack_o_proj_fp8(const void* recv_codes, const float* a_scales, c
     if (!recv_codes || !a_scales || !w_codes || !w_scales || !out) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
     if (!aligned16(recv_codes) || !aligned16(w_codes) || !aligned16(out) || !aligned16(w_scales) || (reinterpret_cast<uintptr_t>(a_scales) & 3))
         return fail(SHIFTATTN_EINVAL, "recv_codes / w_codes / w_scales / out must be 16-byte aligned, a_scales 4-byte");
+    if (workspace_bytes > 0 && (!workspace || !aligned16(workspace)))
+        return fail(SHIFTATTN_EINVAL, "workspace is NULL or not 16-byte aligned");
     if (int rc = ensure_device_ready()) return rc;
-    hipError_t e = launch_unpack_o_proj(recv_codes, w_codes, out, d_model, s, a_scales, w_scales, nullptr, 0, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_unpack_o_proj(recv_codes, w_codes, out, d_model, s, a_scales, w_scales, force_generic() ? nullptr : workspace,
+                                        workspace_bytes, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_o_proj_fp8 launch");
+}
+
+int shiftattn_unpack_o_proj_fp8(const void* recv_codes, const float* a_scales, const void* w_codes, const float* w_scales,
+                                void* out, int32_t T, int32_t T_pad, int32_t d_model, const shiftattn_xchg* xc, void* stream) {
+    return shiftattn_unpack_o_proj_fp8_ws(recv_codes, a_scales, w_codes, w_scales, out, T, T_pad, d_model, xc, nullptr, 0, stream);
 }
 
 int shiftattn_kv_write(const void* k_new, const void* v_new, const int64_t* slot_mapping, int32_t n_tokens,

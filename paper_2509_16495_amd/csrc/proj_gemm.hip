@@ -73,7 +73,8 @@ struct GemmParams {
 
 // kFp8: both operands are FP8 E4M3 codes (v_mfma_scale_f32_32x32x64_f8f6f4 with unit block scales, fp32
 // accumulation); the result is multiplied by the token's and the feature's scale before it is rounded to bf16.
-// kSplit: the workgroup covers one of p.k_splits ranges of k and leaves fp32 sums in p.partial (bf16 operands only)
+// kSplit: the workgroup covers one of p.k_splits ranges of k and leaves fp32 sums in p.partial (for FP8 operands: before
+// the scales, which the finishing kernel applies)
 template <bool kFp8, bool kSplit>
 __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     constexpr int kElem = kFp8 ? 1 : 2;          // bytes per operand element
@@ -356,24 +357,22 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
     const int64_t wgs = static_cast<int64_t>(p.N / kTile) * ((p.M_out + kTile - 1) / kTile) * p.k_splits;
     if (wgs == 0) return hipSuccess;
     if (wgs > 0x7FFFFFFF) return hipErrorInvalidValue;
-    if constexpr (!kFp8) {
-        if (p.k_splits > 1) {
-            proj_gemm_kernel<false, true><<<static_cast<unsigned>(wgs), kGemmThreads, kGemmLds, st>>>(p);
-            return hipGetLastError();
-        }
+    if (p.k_splits > 1) {
+        proj_gemm_kernel<kFp8, true><<<static_cast<unsigned>(wgs), kGemmThreads, kGemmLds, st>>>(p);
+        return hipGetLastError();
     }
     proj_gemm_kernel<kFp8, false><<<static_cast<unsigned>(wgs), kGemmThreads, kGemmLds, st>>>(p);
     return hipGetLastError();
 }
 
 // Few output tiles (up to about a thousand token rows): k is split over workgroups when a rough model of the launch
-// says so - a workgroup walks its k range at about 6.5 TFLOP/s, workgroups beyond one per compute unit queue up in
+// says so - a workgroup walks its k range at about 6.5 TFLOP/s (12.5 over FP8 operands), workgroups beyond one per compute unit queue up in
 // rounds, and every range adds fp32 partial results that are written and read back.  Ranges are at least 16 k tiles
-// long.  1: no split (enough tiles, a short k, or FP8 operands).
-int k_splits_for(int M_out, int N, int K) {
+// long.  1: no split (enough tiles or a short k).
+int k_splits_for(int M_out, int N, int K, bool fp8) {
     const int64_t tiles = static_cast<int64_t>(N / kTile) * ((M_out + kTile - 1) / kTile);
     if (tiles == 0 || tiles >= 512) return 1;
-    const double walk = 2.0 * kTile * kTile * static_cast<double>(K) / 6.5e12;   // one workgroup over all of k
+    const double walk = 2.0 * kTile * kTile * static_cast<double>(K) / (fp8 ? 12.5e12 : 6.5e12);   // one workgroup over all of k
     const double partial = 2.0 * M_out * static_cast<double>(N) * sizeof(float) / 4.0e12;
     auto model = [&](int sp) {
         const double load = static_cast<double>(tiles) * sp / 256.0;
@@ -381,7 +380,7 @@ int k_splits_for(int M_out, int N, int K) {
         const double rounds = load <= 1.0 ? 1.0 : (whole < load + 0.5 ? whole : load + 0.5);
         return rounds / sp * walk + (sp > 1 ? sp * partial + 5.0e-6 : 0.0);
     };
-    const int by_length = K / 32 / 16;
+    const int by_length = K / (fp8 ? 64 : 32) / 16;
     int best = 1;
     double t_best = model(1);
     for (int sp = 2; sp <= 16 && sp <= by_length; ++sp) {
@@ -404,7 +403,10 @@ hipError_t proj_gemm_init() {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel<false, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel<true, false>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel<true, false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_gemm_kernel<true, true>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
 }
 
@@ -415,8 +417,8 @@ bool unpack_o_proj_supported(const XchgShape& s, int d_model, int elem) {
     return elem == 2 && s.vec_per_head * 8 == kHeadDim && d_model > 0 && d_model % kTile == 0 && s.h > 0;
 }
 
-size_t proj_gemm_workspace(int M_out, int N, int K) {
-    const int sp = k_splits_for(M_out, N, K);
+size_t proj_gemm_workspace(int M_out, int N, int K, bool fp8) {
+    const int sp = k_splits_for(M_out, N, K, fp8);
     return sp == 1 ? 0 : static_cast<size_t>(sp) * M_out * N * sizeof(float);
 }
 
@@ -424,14 +426,14 @@ size_t proj_gemm_workspace(int M_out, int N, int K) {
 static hipError_t run_gemm(GemmParams& p, void* workspace, size_t workspace_bytes, hipStream_t st) {
     p.k_splits = 1;
     p.partial = nullptr;
-    if (p.xs) return launch<true>(p, st);
-    const size_t need = proj_gemm_workspace(p.M_out, p.N, p.K);
-    if (need == 0 || need > workspace_bytes || !workspace) return launch<false>(p, st);
-    p.k_splits = k_splits_for(p.M_out, p.N, p.K);
+    const bool fp8 = p.xs != nullptr;
+    const size_t need = proj_gemm_workspace(p.M_out, p.N, p.K, fp8);
+    if (need == 0 || need > workspace_bytes || !workspace) return fp8 ? launch<true>(p, st) : launch<false>(p, st);
+    p.k_splits = k_splits_for(p.M_out, p.N, p.K, fp8);
     p.partial = static_cast<float*>(workspace);
-    const hipError_t e = launch<false>(p, st);
+    const hipError_t e = fp8 ? launch<true>(p, st) : launch<false>(p, st);
     if (e != hipSuccess) return e;
-    return launch_proj_finish(p.partial, p.k_splits, p.M_out, p.c, p.M, p.M_out, p.N, p.mode, p.s, st);
+    return launch_proj_finish(p.partial, p.k_splits, p.M_out, p.c, p.M, p.M_out, p.N, p.mode, p.s, p.xs, p.ws, st);
 }
 
 hipError_t launch_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int d_model, const XchgShape& s,

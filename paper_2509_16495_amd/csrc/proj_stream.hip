@@ -47,6 +47,8 @@ struct StreamParams {
     const unsigned char* __restrict__ x;   // token rows, see mode
     uint16_t* __restrict__ c;              // bf16 result (kg == 1)
     float* __restrict__ partial;           // [kg][16 TB][N] fp32 (kg > 1)
+    const float* __restrict__ xs;          // finish only, FP8 products: one scale per token row ...
+    const float* __restrict__ ws;          // ... and one per output feature (nullptr: none)
     int M, M_out, N, K;                    // M token rows exist, rows M .. M_out - 1 of the result are zeros
     int mode;                              // 0: x dense [M][K], result into the send buffers; 1: x gathered from the
                                            // receive buffers (k = (p hq_l + j) 128 + e), result dense [M][N]
@@ -284,6 +286,12 @@ __global__ __launch_bounds__(256) void proj_stream_finish_kernel(StreamParams p,
 #pragma unroll
             for (int e = 0; e < 4; ++e) sum[e] += v[e];
         }
+        if (p.xs) {   // the scales of FP8 operands, applied as the unsplit kernel applies them
+            const float row_scale = p.xs[t];
+            const f32x4 col_scale = *reinterpret_cast<const f32x4*>(p.ws + f);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sum[e] = sum[e] * row_scale * col_scale[e];
+        }
     }
     store4(p, t, f, round4(sum));
 }
@@ -346,8 +354,10 @@ hipError_t run_stream(StreamParams p, const StreamPlan& pl, void* workspace, hip
 
 // result = sum over kg partial results [kg][t_rows][N] (fp32) in group order, rounded once, stored with the layout of `mode`
 hipError_t launch_proj_finish(const float* partial, int kg, int t_rows, void* c, int M, int M_out, int N, int mode,
-                              const XchgShape& s, hipStream_t st) {
+                              const XchgShape& s, const float* x_scales, const float* w_scales, hipStream_t st) {
     StreamParams p = {};
+    p.xs = x_scales;
+    p.ws = w_scales;
     p.partial = const_cast<float*>(partial);
     p.c = static_cast<uint16_t*>(c);
     p.M = M;
@@ -397,7 +407,7 @@ hipError_t launch_qkv_proj_stream(const void* x, const void* w_qkv, void* send, 
     const StreamPlan pl = plan_stream(p.M_out, p.K);
     const hipError_t e = run_stream(p, pl, workspace, st);
     if (e != hipSuccess || pl.kg == 1) return e;
-    return launch_proj_finish(static_cast<const float*>(workspace), pl.kg, 16 * pl.tb, send, p.M, p.M_out, p.N, 0, s, st);
+    return launch_proj_finish(static_cast<const float*>(workspace), pl.kg, 16 * pl.tb, send, p.M, p.M_out, p.N, 0, s, nullptr, nullptr, st);
 }
 
 hipError_t launch_o_proj_stream(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s,
@@ -415,7 +425,7 @@ hipError_t launch_o_proj_stream(const void* recv, const void* w_o, void* out, in
     const StreamPlan pl = plan_stream(p.M_out, p.K);
     const hipError_t e = run_stream(p, pl, workspace, st);
     if (e != hipSuccess || pl.kg == 1) return e;
-    return launch_proj_finish(static_cast<const float*>(workspace), pl.kg, 16 * pl.tb, out, p.M, p.M_out, p.N, 1, s, st);
+    return launch_proj_finish(static_cast<const float*>(workspace), pl.kg, 16 * pl.tb, out, p.M, p.M_out, p.N, 1, s, nullptr, nullptr, st);
 }
 
 }  // namespace shiftattn

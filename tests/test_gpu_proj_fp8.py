@@ -94,11 +94,14 @@ QKV_CASES = [
     (2, 8, 4, 1024, 600, 600),
     (2, 8, 4, 192, 9, 10),         # three k tiles: fewer than the ring holds
     (8, 64, 8, 192, 0, 8),         # padding rows only
+    (8, 64, 8, 4096, 20, 24),      # few output tiles, long k: with a workspace, k split over workgroups
+    (8, 32, 8, 2048, 130, 136),
 ]
 
 
+@pytest.mark.parametrize("give_workspace", [False, True])
 @pytest.mark.parametrize("P,h,h_kv,d_model,T,T_pad", QKV_CASES)
-def test_qkv_projection_fp8(oracle, G, P, h, h_kv, d_model, T, T_pad):
+def test_qkv_projection_fp8(oracle, G, P, h, h_kv, d_model, T, T_pad, give_workspace):
     import torch
     from paper_2509_16495_amd import binding as B
     rng = np.random.Generator(np.random.PCG64(303))
@@ -113,16 +116,22 @@ def test_qkv_projection_fp8(oracle, G, P, h, h_kv, d_model, T, T_pad):
     terms = oracle.pack_heads_f64(terms.reshape(T, h + 2 * h_kv, D), P, h, h_kv, T_pad)
     send = torch.empty((P, T_pad, h // P + 2 * B.local_kv_heads(P, h_kv), D), dtype=torch.bfloat16, device=G.DEV)
     send.view(torch.uint8).fill_(0x55)
-    B.qkv_proj_pack_fp8(_dev_u8(G, xc).reshape(T, d_model), _dev_f32(G, xs), _dev_u8(G, wc), _dev_f32(G, ws), send, P, h, h_kv)
+    ws_dev = None
+    if give_workspace:
+        ws_dev = torch.empty(max(B.proj_workspace_bytes(T_pad, (h + 2 * h_kv) * D, d_model, fp8=True), 16), dtype=torch.uint8, device=G.DEV)
+    B.qkv_proj_pack_fp8(_dev_u8(G, xc).reshape(T, d_model), _dev_f32(G, xs), _dev_u8(G, wc), _dev_f32(G, ws), send, P, h, h_kv,
+                        workspace=ws_dev)
     torch.cuda.synchronize()
     got = B.to_host(send)
     _check(got, want, terms)
     assert not np.any(got[:, T:])
 
 
+@pytest.mark.parametrize("give_workspace", [False, True])
 @pytest.mark.parametrize("P,hq_l,d_model,T,T_pad", [(8, 4, 512, 300, 304), (4, 10, 256, 257, 260), (1, 2, 256, 5, 5),
-                                                    (2, 4, 768, 600, 600), (8, 8, 256, 0, 4)])
-def test_o_projection_fp8(oracle, G, P, hq_l, d_model, T, T_pad):
+                                                    (2, 4, 768, 600, 600), (8, 8, 256, 0, 4), (8, 4, 4096, 40, 40),
+                                                    (4, 8, 1024, 9, 12)])
+def test_o_projection_fp8(oracle, G, P, hq_l, d_model, T, T_pad, give_workspace):
     import torch
     from paper_2509_16495_amd import binding as B
     rng = np.random.Generator(np.random.PCG64(304))
@@ -140,7 +149,10 @@ def test_o_projection_fp8(oracle, G, P, hq_l, d_model, T, T_pad):
     terms = (tab[rc] @ tab[wc].T) * rs.astype(np.float64)[:, None] * ws.astype(np.float64)[None, :]
     out = torch.empty((T, d_model), dtype=torch.bfloat16, device=G.DEV)
     out.view(torch.uint8).fill_(0x55)
-    B.unpack_o_proj_fp8(_dev_u8(G, recv_codes), _dev_f32(G, rs), _dev_u8(G, wc), _dev_f32(G, ws), out)
+    ws_dev = None
+    if give_workspace:
+        ws_dev = torch.empty(max(B.proj_workspace_bytes(T, d_model, K, fp8=True), 16), dtype=torch.uint8, device=G.DEV)
+    B.unpack_o_proj_fp8(_dev_u8(G, recv_codes), _dev_f32(G, rs), _dev_u8(G, wc), _dev_f32(G, ws), out, workspace=ws_dev)
     torch.cuda.synchronize()
     _check(B.to_host(out), want, terms)
 
