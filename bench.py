@@ -599,7 +599,7 @@ def main() -> int:
         wq8_rot = [wq8] + [wq8.clone() for _ in range(3)]
         wo8_rot = [wo8] + [wo8.clone() for _ in range(3)]
         small_fp8 = {}
-        for Ts in (8, 64, 256):
+        for Ts in (1, 8, 16, 32, 64, 256):
             xq_s, xsc_s = xq[:Ts].contiguous(), xsc[:Ts].contiguous()
             rq_s, rsc_s = rq[:, :Ts].contiguous(), rsc[:Ts].contiguous()
             snd = torch.empty((x3.P, Ts, h3 // x3.P + 2 * (hkv3 // x3.P), D), dtype=bf, device=dev)
@@ -619,7 +619,7 @@ def main() -> int:
                                     wo8.numel())):
                 us = time_in_graph(fn, inner=12) * 1e3
                 row[nm] = {"us": round(us, 2), "weight_bytes": wbytes, "us_to_stream_the_weights_at_peak": round(wbytes / PEAK_HBM_GBPS / 1e3, 2),
-                           "roofline": roof("proj_gemm_kernel<fp8> (k split over workgroups) + proj_stream_finish_kernel", "hbm",
+                           "roofline": roof("proj_stream_kernel<fp8>" if Ts <= 64 else "proj_gemm_kernel<fp8> (k split over workgroups) + proj_stream_finish_kernel", "hbm",
                                             wbytes / (us * 1e-6) / 1e9, PEAK_HBM_GBPS, "GB/s")}
             small_fp8[f"T={Ts}"] = row
             del snd, eo_s, ws_q, ws_o

@@ -344,8 +344,8 @@ int shiftattn_qkv_proj_pack_ws(const void* x, const void* w_qkv, void* send, int
     if (int rc = ensure_device_ready()) return rc;
     const int n_feat = (s.h + 2 * s.h_kv) * 128;
     hipError_t e;
-    if (s.T > 0 && !force_generic() && proj_stream_takes(s.T_pad, n_feat, d_model, workspace_bytes))
-        e = launch_qkv_proj_stream(x, w_qkv, send, d_model, s, workspace, static_cast<hipStream_t>(stream));
+    if (s.T > 0 && !force_generic() && proj_stream_takes(s.T_pad, n_feat, d_model, false, workspace_bytes))
+        e = launch_qkv_proj_stream(x, w_qkv, send, d_model, s, nullptr, nullptr, workspace, static_cast<hipStream_t>(stream));
     else
         e = launch_qkv_proj_pack(x, w_qkv, send, d_model, s, nullptr, nullptr, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "qkv_proj_pack launch");
@@ -371,8 +371,8 @@ int shiftattn_unpack_o_proj_ws(const void* recv, const void* w_o, void* out, int
         return fail(SHIFTATTN_EINVAL, "workspace is NULL or not 16-byte aligned");
     if (int rc = ensure_device_ready()) return rc;
     hipError_t e;
-    if (!force_generic() && proj_stream_takes(s.T, d_model, s.h * 128, workspace_bytes))
-        e = launch_o_proj_stream(recv, w_o, out, d_model, s, workspace, static_cast<hipStream_t>(stream));
+    if (!force_generic() && proj_stream_takes(s.T, d_model, s.h * 128, false, workspace_bytes))
+        e = launch_o_proj_stream(recv, w_o, out, d_model, s, nullptr, nullptr, workspace, static_cast<hipStream_t>(stream));
     else
         e = launch_unpack_o_proj(recv, w_o, out, d_model, s, nullptr, nullptr, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_o_proj launch");
@@ -385,12 +385,13 @@ int shiftattn_unpack_o_proj(const void* recv, const void* w_o, void* out, int32_
 
 size_t shiftattn_proj_workspace_bytes(int32_t rows, int32_t n_features, int32_t k) {
     if (rows < 1 || n_features < 1 || k < 1 || force_generic()) return 0;
-    if (proj_stream_takes(rows, n_features, k, static_cast<size_t>(-1))) return proj_stream_workspace(rows, n_features, k);
+    if (proj_stream_takes(rows, n_features, k, false, static_cast<size_t>(-1))) return proj_stream_workspace(rows, n_features, k, false);
     return proj_gemm_workspace(rows, n_features, k, false);
 }
 
 size_t shiftattn_proj_workspace_bytes_fp8(int32_t rows, int32_t n_features, int32_t k) {
     if (rows < 1 || n_features < 1 || k < 1 || force_generic()) return 0;
+    if (proj_stream_takes(rows, n_features, k, true, static_cast<size_t>(-1))) return proj_stream_workspace(rows, n_features, k, true);
     return proj_gemm_workspace(rows, n_features, k, true);
 }
 
@@ -438,8 +439,13 @@ int shiftattn_qkv_proj_pack_fp8_ws(const void* x_codes, const float* x_scales, c
     if (workspace_bytes > 0 && (!workspace || !aligned16(workspace)))
         return fail(SHIFTATTN_EINVAL, "workspace is NULL or not 16-byte aligned");
     if (int rc = ensure_device_ready()) return rc;
-    hipError_t e = launch_qkv_proj_pack(x_codes, w_codes, send, d_model, s, x_scales, w_scales, force_generic() ? nullptr : workspace,
-                                        workspace_bytes, static_cast<hipStream_t>(stream));
+    const int n_feat = (s.h + 2 * s.h_kv) * 128;
+    hipError_t e;
+    if (s.T > 0 && !force_generic() && proj_stream_takes(s.T_pad, n_feat, d_model, true, workspace_bytes))
+        e = launch_qkv_proj_stream(x_codes, w_codes, send, d_model, s, x_scales, w_scales, workspace, static_cast<hipStream_t>(stream));
+    else
+        e = launch_qkv_proj_pack(x_codes, w_codes, send, d_model, s, x_scales, w_scales, force_generic() ? nullptr : workspace,
+                                 workspace_bytes, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "qkv_proj_pack_fp8 launch");
 }
 
@@ -464,8 +470,12 @@ int shiftattn_unpack_o_proj_fp8_ws(const void* recv_codes, const float* a_scales
     if (workspace_bytes > 0 && (!workspace || !aligned16(workspace)))
         return fail(SHIFTATTN_EINVAL, "workspace is NULL or not 16-byte aligned");
     if (int rc = ensure_device_ready()) return rc;
-    hipError_t e = launch_unpack_o_proj(recv_codes, w_codes, out, d_model, s, a_scales, w_scales, force_generic() ? nullptr : workspace,
-                                        workspace_bytes, static_cast<hipStream_t>(stream));
+    hipError_t e;
+    if (!force_generic() && proj_stream_takes(s.T, d_model, s.h * 128, true, workspace_bytes))
+        e = launch_o_proj_stream(recv_codes, w_codes, out, d_model, s, a_scales, w_scales, workspace, static_cast<hipStream_t>(stream));
+    else
+        e = launch_unpack_o_proj(recv_codes, w_codes, out, d_model, s, a_scales, w_scales, force_generic() ? nullptr : workspace,
+                                 workspace_bytes, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "unpack_o_proj_fp8 launch");
 }
 

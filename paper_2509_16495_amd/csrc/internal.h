@@ -130,12 +130,12 @@ hipError_t launch_unpack_o_proj(const void* recv, const void* w_o, void* out, in
 // bytes of workspace that let the large-batch kernel split k over workgroups (few output tiles); 0: no split
 size_t proj_gemm_workspace(int M_out, int N, int K, bool fp8);
 // proj_stream.hip : the same two products for up to 64 token rows, organised around one pass over the weights
-size_t proj_stream_workspace(int M_out, int N, int K);
-bool proj_stream_takes(int M_out, int N, int K, size_t workspace_bytes);
+size_t proj_stream_workspace(int M_out, int N, int K, bool fp8);
+bool proj_stream_takes(int M_out, int N, int K, bool fp8, size_t workspace_bytes);
 hipError_t launch_qkv_proj_stream(const void* x, const void* w_qkv, void* send, int d_model, const XchgShape& s,
-                                  void* workspace, hipStream_t st);
+                                  const float* x_scales, const float* w_scales, void* workspace, hipStream_t st);
 hipError_t launch_o_proj_stream(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s,
-                                void* workspace, hipStream_t st);
+                                const float* a_scales, const float* w_scales, void* workspace, hipStream_t st);
 hipError_t launch_proj_finish(const float* partial, int kg, int t_rows, void* c, int M, int M_out, int N, int mode,
                               const XchgShape& s, const float* x_scales, const float* w_scales, hipStream_t st);
 // layout_kernels.hip : rows of bf16 values -> FP8 E4M3 codes + one float32 scale per row (amax / 448).  Element k of

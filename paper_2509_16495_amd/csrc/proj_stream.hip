@@ -34,11 +34,12 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kSWaves = 8, kSThreads = 64 * kSWaves;
 constexpr int kSGrid = 256;                        // workgroups: one per compute unit
-constexpr int kStepK = 64;                         // k per step of a wavefront
-constexpr int kStepBytes = 16 * kStepK * 2;        // 16 weight rows x 128 bytes
+constexpr int kStepRowBytes = 128;                 // bytes of a weight row per step of a wavefront: 64 bf16 or 128 FP8 k
+constexpr int kStepBytes = 16 * kStepRowBytes;     // 16 weight rows
 constexpr int kHeadDim = 128;
 #define SHIFTATTN_STREAM_HINT " nt"   // weights are read once: non-temporal
 
@@ -47,7 +48,7 @@ struct StreamParams {
     const unsigned char* __restrict__ x;   // token rows, see mode
     uint16_t* __restrict__ c;              // bf16 result (kg == 1)
     float* __restrict__ partial;           // [kg][16 TB][N] fp32 (kg > 1)
-    const float* __restrict__ xs;          // finish only, FP8 products: one scale per token row ...
+    const float* __restrict__ xs;          // FP8 products: one scale per token row ...
     const float* __restrict__ ws;          // ... and one per output feature (nullptr: none)
     int M, M_out, N, K;                    // M token rows exist, rows M .. M_out - 1 of the result are zeros
     int mode;                              // 0: x dense [M][K], result into the send buffers; 1: x gathered from the
@@ -97,9 +98,14 @@ __device__ inline u32x2 round4(f32x4 v) {
     return __builtin_bit_cast(u32x2, r);
 }
 
-// TB: token blocks of 16; KWB: steps of 64 k in a wavefront's k slice; kStages: steps in a wavefront's ring
-template <int TB, int KWB, int kStages>
+// TB: token blocks of 16; KWB: steps (128 bytes of a weight row: 64 bf16 or 128 FP8 k) in a wavefront's k slice;
+// kStages: steps in a wavefront's ring; kFp8: both operands are FP8 E4M3 codes (one v_mfma_scale_f32_16x16x128_f8f6f4
+// with unit block scales per step and token block instead of two bf16 MFMAs; the token's and the feature's scale
+// multiply the sum before it is rounded - or in the finishing kernel when k is split over workgroups)
+template <int TB, int KWB, int kStages, bool kFp8>
 __global__ __launch_bounds__(kSThreads) void proj_stream_kernel(StreamParams p) {
+    constexpr int kElem = kFp8 ? 1 : 2;
+    constexpr int kStepK = kStepRowBytes / kElem;
     static_assert(TB * KWB <= 16, "the token slice of a wavefront fits 128 registers");
     constexpr int kXLoads = TB * KWB * 2;          // 16-byte loads of token data per lane
     static_assert(2 * (kStages - 1) + kXLoads + 2 <= 62, "outstanding loads fit the counter");
@@ -114,7 +120,7 @@ __global__ __launch_bounds__(kSThreads) void proj_stream_kernel(StreamParams p) 
     const int n_tiles = (row_end - row_begin + 15) >> 4;
     const int total = n_tiles * KWB;    // steps of this wavefront
     const int k0 = (cgrp * kSWaves + wave) * (KWB * kStepK);
-    const size_t k_bytes = static_cast<size_t>(p.K) * 2;
+    const size_t k_bytes = static_cast<size_t>(p.K) * kElem;
     const uint32_t ring = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + wave * (kStages * kStepBytes);
     unsigned char* ring_ptr = lds + wave * (kStages * kStepBytes);
     f32x4* red = reinterpret_cast<f32x4*>(lds + kSWaves * kStages * kStepBytes);   // [wavefront][TB][lane]
@@ -146,7 +152,7 @@ __global__ __launch_bounds__(kSThreads) void proj_stream_kernel(StreamParams p) 
         }
     };
     int rq_g = 0, rq_st = 0, rq_tile = 0, rq_slot = 0;   // the next step to request
-    const unsigned char* rq_base = p.w + static_cast<size_t>(row_begin) * k_bytes + static_cast<size_t>(k0) * 2;
+    const unsigned char* rq_base = p.w + static_cast<size_t>(row_begin) * k_bytes + static_cast<size_t>(k0) * kElem;
     auto request = [&]() {
         const uint32_t dst = ring + rq_slot * kStepBytes;
 #pragma unroll
@@ -156,10 +162,10 @@ __global__ __launch_bounds__(kSThreads) void proj_stream_kernel(StreamParams p) 
         if (++rq_st == KWB) {
             rq_st = 0;
             ++rq_tile;
-            rq_base += 16 * k_bytes - (KWB - 1) * (kStepK * 2);
+            rq_base += 16 * k_bytes - (KWB - 1) * kStepRowBytes;
             if (rq_tile < n_tiles) tile_offsets(rq_tile);
         } else {
-            rq_base += kStepK * 2;
+            rq_base += kStepRowBytes;
         }
     };
     tile_offsets(0);
@@ -174,23 +180,27 @@ __global__ __launch_bounds__(kSThreads) void proj_stream_kernel(StreamParams p) 
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) {
             const int t_src = min(16 * tb + l16, p.M - 1);
-            const int k = k0 + 32 * b + 8 * grp;
+            // the 16 bytes of token t_src this lane multiplies with weight piece (b % 2 ? second : first) of step b / 2:
+            // bf16: k block b (32 k), its k group grp; FP8: step b / 2, the lane's 32 k in two halves
+            const int k = kFp8 ? k0 + 128 * (b >> 1) + 32 * grp + 16 * (b & 1) : k0 + 32 * b + 8 * grp;
             const unsigned char* src;
             if (p.mode == 0) {
-                src = p.x + (static_cast<size_t>(t_src) * p.K + k) * 2;
+                src = p.x + (static_cast<size_t>(t_src) * p.K + k) * kElem;
             } else {
                 const int seg = p.s.hq_l * kHeadDim;   // contiguous k of a token row in one receive buffer
                 const int ps = k / seg, rem = k - ps * seg;
-                src = p.x + ((static_cast<size_t>(ps) * p.s.T_pad + t_src) * seg + rem) * 2;
+                src = p.x + ((static_cast<size_t>(ps) * p.s.T_pad + t_src) * seg + rem) * kElem;
             }
             asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(xr[tb][b]) : "v"(src) : "memory");
         }
     }
 
-    // ---- operand reads: row l16, piece 4 kb + grp at position piece ^ key(row)
+    // ---- operand reads: row l16, piece 4 kb + grp (bf16: k group grp of k block kb) or 2 grp + kb (FP8: the halves of
+    // the lane's 32 k) at position piece ^ key(row)
     int rd[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) rd[kb] = l16 * (kStepK * 2) + (((4 * kb + grp) ^ ((l16 >> 1) & 7)) << 4);
+    for (int kb = 0; kb < 2; ++kb)
+        rd[kb] = l16 * kStepRowBytes + ((((kFp8 ? 2 * grp + kb : 4 * kb + grp)) ^ ((l16 >> 1) & 7)) << 4);
 
     int g = 0, slot = 0;
     // One step: the slot read one step ago is free, so the step kStages - 1 ahead is requested into it; then the wait
@@ -228,11 +238,23 @@ __global__ __launch_bounds__(kSThreads) void proj_stream_kernel(StreamParams p) 
         u32x4 a[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) a[kb] = *reinterpret_cast<const u32x4*>(stage + rd[kb]);
+        if constexpr (kFp8) {
+            const i32x8 a8 = {static_cast<int>(a[0][0]), static_cast<int>(a[0][1]), static_cast<int>(a[0][2]), static_cast<int>(a[0][3]),
+                              static_cast<int>(a[1][0]), static_cast<int>(a[1][1]), static_cast<int>(a[1][2]), static_cast<int>(a[1][3])};
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int tb = 0; tb < TB; ++tb) {
+                const u32x4 lo = xr[tb][2 * st], hi = xr[tb][2 * st + 1];
+                const i32x8 b8 = {static_cast<int>(lo[0]), static_cast<int>(lo[1]), static_cast<int>(lo[2]), static_cast<int>(lo[3]),
+                                  static_cast<int>(hi[0]), static_cast<int>(hi[1]), static_cast<int>(hi[2]), static_cast<int>(hi[3])};
+                acc[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, acc[tb], 0, 0, 0, 127, 0, 127);
+            }
+        } else {
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb)
-                acc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag(a[kb]), frag(xr[tb][2 * st + kb]), acc[tb], 0, 0, 0);
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb)
+                    acc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag(a[kb]), frag(xr[tb][2 * st + kb]), acc[tb], 0, 0, 0);
+        }
         slot = slot + 1 == kStages ? 0 : slot + 1;
         ++g;
     };
@@ -263,6 +285,14 @@ __global__ __launch_bounds__(kSThreads) void proj_stream_kernel(StreamParams p) 
                 if (p.kg > 1) {
                     *reinterpret_cast<f32x4*>(p.partial + (static_cast<size_t>(cgrp) * (16 * TB) + t) * p.N + f) = sum;
                 } else if (t < p.M_out) {
+                    if constexpr (kFp8) {
+                        if (t < p.M) {
+                            const float row_scale = p.xs[t];
+                            const f32x4 col_scale = *reinterpret_cast<const f32x4*>(p.ws + f);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) sum[e] = sum[e] * row_scale * col_scale[e];
+                        }
+                    }
                     store4(p, t, f, t < p.M ? round4(sum) : u32x2{0u, 0u});
                 }
             }
@@ -297,15 +327,16 @@ __global__ __launch_bounds__(256) void proj_stream_finish_kernel(StreamParams p,
 }
 
 struct StreamPlan {
-    int tb, kwb, kg;   // token blocks of 16, k per wavefront in steps of 64, k groups; tb == 0: not served
+    int tb, kwb, kg;   // token blocks of 16, steps per wavefront's k slice, k groups; tb == 0: not served
 };
 
 // The largest k slice per wavefront that fits the registers decides how many workgroups must share a block of features.
-StreamPlan plan_stream(int M_out, int K) {
+StreamPlan plan_stream(int M_out, int K, bool fp8) {
     StreamPlan pl = {0, 0, 0};
-    if (M_out < 1 || M_out > 64 || K % (kSWaves * kStepK) != 0) return pl;
+    const int step_k = kStepRowBytes / (fp8 ? 1 : 2);
+    if (M_out < 1 || M_out > 64 || K % (kSWaves * step_k) != 0) return pl;
     const int tb = M_out <= 16 ? 1 : M_out <= 32 ? 2 : 4;
-    const int per_wave = K / (kSWaves * kStepK);   // steps of 64 k per wavefront if one workgroup covered all of k
+    const int per_wave = K / (kSWaves * step_k);   // steps per wavefront if one workgroup covered all of k
     for (int kwb = 16 / tb; kwb >= 1; kwb /= 2) {
         if (per_wave % kwb != 0) continue;
         const int kg = per_wave / kwb;
@@ -322,15 +353,15 @@ template <int TB>
 constexpr int stream_lds() { return kSWaves * stream_stages<TB>() * kStepBytes + kSWaves * TB * 64 * 16; }
 static_assert(stream_lds<1>() <= 160 * 1024 && stream_lds<2>() <= 160 * 1024 && stream_lds<4>() <= 160 * 1024, "LDS of a compute unit");
 
-template <int TB, int KWB>
+template <int TB, int KWB, bool kFp8>
 hipError_t launch_stream(const StreamParams& p, hipStream_t st) {
-    proj_stream_kernel<TB, KWB, stream_stages<TB>()><<<kSGrid, kSThreads, stream_lds<TB>(), st>>>(p);
+    proj_stream_kernel<TB, KWB, stream_stages<TB>(), kFp8><<<kSGrid, kSThreads, stream_lds<TB>(), st>>>(p);
     return hipGetLastError();
 }
 
-template <int TB, int KWB>
+template <int TB, int KWB, bool kFp8>
 hipError_t init_stream() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_stream_kernel<TB, KWB, stream_stages<TB>()>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_stream_kernel<TB, KWB, stream_stages<TB>(), kFp8>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, stream_lds<TB>());
 }
 
@@ -344,9 +375,15 @@ hipError_t run_stream(StreamParams p, const StreamPlan& pl, void* workspace, hip
     const int blocks = kSGrid / pl.kg;
     p.rows_per_block = ((p.N + blocks - 1) / blocks + 3) / 4 * 4;
     hipError_t e = hipErrorInvalidValue;
-#define SHIFTATTN_STREAM_LAUNCH(tb_, kwb_) if (pl.tb == tb_ && pl.kwb == kwb_) e = launch_stream<tb_, kwb_>(p, st);
-    SHIFTATTN_STREAM_SHAPES(SHIFTATTN_STREAM_LAUNCH)
+    if (p.xs) {
+#define SHIFTATTN_STREAM_LAUNCH(tb_, kwb_) if (pl.tb == tb_ && pl.kwb == kwb_) e = launch_stream<tb_, kwb_, true>(p, st);
+        SHIFTATTN_STREAM_SHAPES(SHIFTATTN_STREAM_LAUNCH)
 #undef SHIFTATTN_STREAM_LAUNCH
+    } else {
+#define SHIFTATTN_STREAM_LAUNCH(tb_, kwb_) if (pl.tb == tb_ && pl.kwb == kwb_) e = launch_stream<tb_, kwb_, false>(p, st);
+        SHIFTATTN_STREAM_SHAPES(SHIFTATTN_STREAM_LAUNCH)
+#undef SHIFTATTN_STREAM_LAUNCH
+    }
     return e;
 }
 
@@ -374,58 +411,65 @@ hipError_t launch_proj_finish(const float* partial, int kg, int t_rows, void* c,
 
 hipError_t proj_stream_init() {
     hipError_t e = hipSuccess;
-#define SHIFTATTN_STREAM_INIT(tb_, kwb_) if (e == hipSuccess) e = init_stream<tb_, kwb_>();
+#define SHIFTATTN_STREAM_INIT(tb_, kwb_)                         \
+    if (e == hipSuccess) e = init_stream<tb_, kwb_, false>(); \
+    if (e == hipSuccess) e = init_stream<tb_, kwb_, true>();
     SHIFTATTN_STREAM_SHAPES(SHIFTATTN_STREAM_INIT)
 #undef SHIFTATTN_STREAM_INIT
     return e;
 }
 
 // bytes of workspace the streaming kernel needs for M_out token rows (0: none, or the shape is not served by it)
-size_t proj_stream_workspace(int M_out, int N, int K) {
-    const StreamPlan pl = plan_stream(M_out, K);
+size_t proj_stream_workspace(int M_out, int N, int K, bool fp8) {
+    const StreamPlan pl = plan_stream(M_out, K, fp8);
     return pl.tb == 0 || pl.kg == 1 ? 0 : static_cast<size_t>(pl.kg) * 16 * pl.tb * N * sizeof(float);
 }
 
-// served: bf16, up to 64 token rows, and either no workspace needed or one of sufficient size given
-bool proj_stream_takes(int M_out, int N, int K, size_t workspace_bytes) {
-    const StreamPlan pl = plan_stream(M_out, K);
-    return pl.tb != 0 && N % 4 == 0 && proj_stream_workspace(M_out, N, K) <= workspace_bytes;
+// served: up to 64 token rows, and either no workspace needed or one of sufficient size given
+bool proj_stream_takes(int M_out, int N, int K, bool fp8, size_t workspace_bytes) {
+    const StreamPlan pl = plan_stream(M_out, K, fp8);
+    return pl.tb != 0 && N % 4 == 0 && proj_stream_workspace(M_out, N, K, fp8) <= workspace_bytes;
 }
 
+// x_scales / w_scales: nullptr for bf16 operands, the row scales of FP8 E4M3 codes otherwise
 hipError_t launch_qkv_proj_stream(const void* x, const void* w_qkv, void* send, int d_model, const XchgShape& s,
-                                  void* workspace, hipStream_t st) {
+                                  const float* x_scales, const float* w_scales, void* workspace, hipStream_t st) {
     StreamParams p = {};
     p.w = static_cast<const unsigned char*>(w_qkv);
     p.x = static_cast<const unsigned char*>(x);
     p.c = static_cast<uint16_t*>(send);
+    p.xs = x_scales;
+    p.ws = w_scales;
     p.M = s.T;
     p.M_out = s.T_pad;
     p.N = (s.h + 2 * s.h_kv) * kHeadDim;
     p.K = d_model;
     p.mode = 0;
     p.s = s;
-    const StreamPlan pl = plan_stream(p.M_out, p.K);
+    const StreamPlan pl = plan_stream(p.M_out, p.K, x_scales != nullptr);
     const hipError_t e = run_stream(p, pl, workspace, st);
     if (e != hipSuccess || pl.kg == 1) return e;
-    return launch_proj_finish(static_cast<const float*>(workspace), pl.kg, 16 * pl.tb, send, p.M, p.M_out, p.N, 0, s, nullptr, nullptr, st);
+    return launch_proj_finish(static_cast<const float*>(workspace), pl.kg, 16 * pl.tb, send, p.M, p.M_out, p.N, 0, s, x_scales, w_scales, st);
 }
 
 hipError_t launch_o_proj_stream(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s,
-                                void* workspace, hipStream_t st) {
+                                const float* a_scales, const float* w_scales, void* workspace, hipStream_t st) {
     StreamParams p = {};
     p.w = static_cast<const unsigned char*>(w_o);
     p.x = static_cast<const unsigned char*>(recv);
     p.c = static_cast<uint16_t*>(out);
+    p.xs = a_scales;
+    p.ws = w_scales;
     p.M = s.T;
     p.M_out = s.T;
     p.N = d_model;
     p.K = s.h * kHeadDim;
     p.mode = 1;
     p.s = s;
-    const StreamPlan pl = plan_stream(p.M_out, p.K);
+    const StreamPlan pl = plan_stream(p.M_out, p.K, a_scales != nullptr);
     const hipError_t e = run_stream(p, pl, workspace, st);
     if (e != hipSuccess || pl.kg == 1) return e;
-    return launch_proj_finish(static_cast<const float*>(workspace), pl.kg, 16 * pl.tb, out, p.M, p.M_out, p.N, 1, s, nullptr, nullptr, st);
+    return launch_proj_finish(static_cast<const float*>(workspace), pl.kg, 16 * pl.tb, out, p.M, p.M_out, p.N, 1, s, a_scales, w_scales, st);
 }
 
 }  // namespace shiftattn

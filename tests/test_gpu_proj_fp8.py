@@ -94,13 +94,28 @@ QKV_CASES = [
     (2, 8, 4, 1024, 600, 600),
     (2, 8, 4, 192, 9, 10),         # three k tiles: fewer than the ring holds
     (8, 64, 8, 192, 0, 8),         # padding rows only
-    (8, 64, 8, 4096, 20, 24),      # few output tiles, long k: with a workspace, k split over workgroups
+    (8, 8, 8, 5120, 20, 24),       # few output tiles, long k no multiple of 1024: with a workspace, k split over workgroups
     (8, 32, 8, 2048, 130, 136),
+    (8, 8, 8, 8192, 8, 8),         # a decode step's few rows: the weight-streaming kernel (one pass over the codes)
+    (8, 8, 8, 4096, 20, 24),       # two token blocks, one k group
+    (8, 8, 8, 4096, 40, 40),       # four token blocks: two k groups with a workspace, the large-batch kernel without
+    (4, 40, 8, 1024, 5, 8),        # 28 features per workgroup, one step per wavefront
+    (8, 32, 4, 2048, 3, 4),        # replication into several send buffers
 ]
 
 
-@pytest.mark.parametrize("give_workspace", [False, True])
-@pytest.mark.parametrize("P,h,h_kv,d_model,T,T_pad", QKV_CASES)
+def _with_and_without_workspace(cases, k_of, rows_of):
+    """Every case with a workspace; without one where that is another path (the oracle's part dominates the big ones)."""
+    out = []
+    for c in cases:
+        out.append(c + (True,))
+        if k_of(c) < 4096 or rows_of(c) > 32:
+            out.append(c + (False,))
+    return out
+
+
+@pytest.mark.parametrize("P,h,h_kv,d_model,T,T_pad,give_workspace",
+                         _with_and_without_workspace(QKV_CASES, lambda c: c[3], lambda c: c[5]))
 def test_qkv_projection_fp8(oracle, G, P, h, h_kv, d_model, T, T_pad, give_workspace):
     import torch
     from paper_2509_16495_amd import binding as B
@@ -127,10 +142,12 @@ def test_qkv_projection_fp8(oracle, G, P, h, h_kv, d_model, T, T_pad, give_works
     assert not np.any(got[:, T:])
 
 
-@pytest.mark.parametrize("give_workspace", [False, True])
-@pytest.mark.parametrize("P,hq_l,d_model,T,T_pad", [(8, 4, 512, 300, 304), (4, 10, 256, 257, 260), (1, 2, 256, 5, 5),
-                                                    (2, 4, 768, 600, 600), (8, 8, 256, 0, 4), (8, 4, 4096, 40, 40),
-                                                    (4, 8, 1024, 9, 12)])
+O_CASES = [(8, 4, 512, 300, 304), (4, 10, 256, 257, 260), (1, 2, 256, 5, 5), (2, 4, 768, 600, 600), (8, 8, 256, 0, 4),
+           (8, 4, 4096, 40, 40), (4, 8, 1024, 9, 12), (8, 4, 2048, 16, 16), (8, 8, 2048, 64, 64), (2, 4, 1024, 1, 1)]
+
+
+@pytest.mark.parametrize("P,hq_l,d_model,T,T_pad,give_workspace",
+                         _with_and_without_workspace(O_CASES, lambda c: c[0] * c[1] * 128, lambda c: c[3]))
 def test_o_projection_fp8(oracle, G, P, hq_l, d_model, T, T_pad, give_workspace):
     import torch
     from paper_2509_16495_amd import binding as B
