@@ -202,8 +202,9 @@ int shiftattn_qkv_proj_pack_fp8(const void *x_codes, const float *x_scales, cons
 int shiftattn_unpack_o_proj_fp8(const void *recv_codes, const float *a_scales, const void *w_codes,
                                 const float *w_scales, void *out, int32_t T, int32_t T_pad, int32_t d_model,
                                 const shiftattn_xchg *xc, void *stream);
-/* The FP8 projections with a workspace: with few output tiles (up to a few hundred token rows) k is split over
- * workgroups, as in the bf16 forms above; the scales are applied once, after the ranges' fp32 sums are added.
+/* The FP8 projections with a workspace, as the bf16 forms above: up to 64 token rows are one pass over the weight
+ * codes (k groups, and with them a workspace, from 33 rows on at d_model = 8192), a few hundred rows split k over
+ * workgroups; the scales are applied once, after the fp32 sums of all of k are added.
  * shiftattn_proj_workspace_bytes_fp8: the size for FP8 operands (it differs from the bf16 size). */
 size_t shiftattn_proj_workspace_bytes_fp8(int32_t rows, int32_t n_features, int32_t k);
 int shiftattn_qkv_proj_pack_fp8_ws(const void *x_codes, const float *x_scales, const void *w_codes,
