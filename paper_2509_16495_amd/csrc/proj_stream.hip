@@ -6,20 +6,22 @@
 //   * 256 workgroups of eight wavefronts, one per compute unit, each owning a contiguous block of output features
 //     (N / 256 rows, so every compute unit reads the same number of weight bytes) and walking it in tiles of 16;
 //   * the eight wavefronts of a workgroup split k: wavefront w multiplies k slice w of every tile.  Its slice of the
-//     token rows (16 TB tokens x 64 KWB k, TB KWB <= 16) stays in 128 registers for the whole kernel in MFMA operand
-//     layout, so the only traffic of the main loop is the weights;
+//     token rows (16 TB tokens x KWB steps of 128 bytes of k: 64 bf16 or 128 FP8 elements; TB KWB <= 16) stays in
+//     128 registers for the whole kernel in MFMA operand layout, so the only traffic of the main loop is the weights;
 //   * weights arrive by direct-to-LDS loads (1 KiB per instruction: eight rows x 128 bytes, whole cache lines, marked
 //     non-temporal: they are used once) into a ring private to the wavefront - no workgroup barrier in the stream, a
 //     wavefront waits for its own loads by count, seven or eight steps of 2 KiB in flight - and are read back as
-//     v_mfma_f32_16x16x32_bf16 A operands; a row of 64 k keeps its eight 16-byte pieces at positions
-//     piece ^ (row / 2) % 8, which makes those reads conflict-free;
+//     MFMA A operands (two v_mfma_f32_16x16x32_bf16 per step and token block, or one
+//     v_mfma_scale_f32_16x16x128_f8f6f4 over FP8 codes); the 128 bytes of a row keep their eight 16-byte pieces at
+//     positions piece ^ (row / 2) % 8, which makes those reads conflict-free;
 //   * the token rows are requested behind the first steps of weights and waited for piecewise inside the first tile,
 //     so the stream is already running while they arrive (every workgroup reads all of them: 64 MB through the L2s at
 //     16 tokens and k = 8192, which is what a 16-token call costs over a 1-token call);
 //   * per tile the eight partial 16 x 16 TB results meet in LDS and are summed in wavefront order (bitwise
-//     reproducible), rounded once to bf16 and stored where the pack / unpack would have put them.
+//     reproducible), multiplied by the token's and the feature's scale when the operands are FP8 codes, rounded once
+//     to bf16 and stored where the pack / unpack would have put them.
 //
-// When the token rows do not fit the registers of eight wavefronts (more than 16 tokens at k = 8192), k is split
+// When the token rows do not fit the registers of eight wavefronts (more than 16 bf16 or 32 FP8 tokens at k = 8192), k is split
 // over `kg` workgroups as well; those write fp32 partial results to a caller-provided workspace and a small second
 // kernel sums them in group order and does the rounding and the layout.
 #include "internal.h"
@@ -44,7 +46,7 @@ constexpr int kHeadDim = 128;
 #define SHIFTATTN_STREAM_HINT " nt"   // weights are read once: non-temporal
 
 struct StreamParams {
-    const unsigned char* __restrict__ w;   // [N][K] bf16
+    const unsigned char* __restrict__ w;   // [N][K] bf16 or FP8 E4M3 codes
     const unsigned char* __restrict__ x;   // token rows, see mode
     uint16_t* __restrict__ c;              // bf16 result (kg == 1)
     float* __restrict__ partial;           // [kg][16 TB][N] fp32 (kg > 1)
