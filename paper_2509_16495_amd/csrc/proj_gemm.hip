@@ -9,18 +9,24 @@
 //                   receive buffer p - the unpack kernel disappears.
 // Weights are stored one row per output feature (K contiguous), as linear layers keep them.
 //
-// Kernel: 256 x 256 output tile per workgroup, K in tiles of 32, four wavefronts (2 along the features
-// x 2 along the tokens, 128 x 128 each: one wavefront per SIMD with its 256 accumulator registers in the
-// AGPR half of the register file), v_mfma_f32_32x32x16_bf16 with the weight rows as A operand and the
-// token rows as B operand, so a lane ends up with runs of four consecutive features of one token (8-byte
-// stores).  The two operand tiles of a k tile (2 x 16 KiB) arrive by direct-to-LDS loads into a ring of
-// four buffers: one is multiplied while up to three are in flight, and the wait in front of the one
-// meeting per k tile counts loads instead of draining them.  A row of 32 k (64 bytes) keeps its four
-// 16-byte pieces at positions piece ^ ((row / 4) % 4), which makes the operand reads (32 consecutive
-// rows, one piece column) conflict-free.
+// Kernel: 256 x 256 output tile per workgroup, four wavefronts (2 along the features x 2 along the tokens, 128 x 128
+// each: one wavefront per SIMD with its 256 accumulator registers in the AGPR half of the register file), the weight
+// rows as A operand and the token rows as B operand, so a lane ends up with runs of four consecutive features of one
+// token (8-byte stores).  k advances in stages of 128 bytes per row (64 bf16 or 128 FP8 elements: whole cache lines),
+// two stage buffers of 64 KiB in LDS filled by direct-to-LDS loads of 1 KiB (eight rows); a row keeps its eight
+// 16-byte pieces at positions piece ^ ((row / 2) % 8), which makes the operand reads (16 or 32 consecutive rows, one
+// piece column) conflict-free.  One barrier per stage.  bf16: v_mfma_f32_16x16x32_bf16; FP8: the 32x32x64 scaled form.
+// What the main loop is built around (all measured on this kernel):
+//   * the chip runs these kernels at its power limit: the clock settles where MFMA rate x energy per MFMA fits, so
+//     the 16x16x32 form (less accumulator traffic per flop) sustains about 15 % more than 32x32x16;
+//   * with one wavefront per SIMD and 16-clock MFMAs the matrix pipe stays fed only if at most one other instruction
+//     sits between two MFMAs: every LDS read, every load (split in two: M0, then the load) and the scalar bookkeeping
+//     has a slot of its own behind an MFMA;
+//   * workgroups on different XCDs start their walk over k at different places (see rot0 below).
 #include "internal.h"
 
 #include <type_traits>
+#include <utility>
 
 namespace shiftattn {
 
@@ -34,20 +40,19 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kTile = 256;                 // rows of either operand per workgroup
-constexpr int kRowBytes = 64;              // bytes of a row per k tile: 32 bf16 or 64 FP8 elements
-constexpr int kOperandBytes = kTile * kRowBytes;   // 16384
+constexpr int kRowBytes = 128;             // bytes of a row per k stage: one cache line, 64 bf16 or 128 FP8 elements
+constexpr int kOperandBytes = kTile * kRowBytes;   // 32768
 constexpr int kStage = 2 * kOperandBytes;  // weights, then tokens
-constexpr int kStages = 4;                 // ring of k tiles in LDS: one being multiplied, the others in flight
+constexpr int kStages = 2;                 // k stages in LDS: one being multiplied, one in flight
 constexpr int kGemmLds = kStages * kStage; // 131072
 constexpr int kWavesN = 2, kWavesM = 2;    // wavefronts along the features / along the tokens
 constexpr int kGemmThreads = 64 * kWavesN * kWavesM;
 constexpr int kNT = kTile / kWavesN / 32;  // 32-feature tiles per wavefront
 constexpr int kMT = kTile / kWavesM / 32;  // 32-token tiles per wavefront
 constexpr int kLoadRows = kTile / (kWavesN * kWavesM);   // rows of either operand that one wavefront loads
-constexpr int kLoadsPerOperand = kLoadRows / 16;          // 16 rows (1 KiB) per instruction
-constexpr int kLoadsPerTile = 2 * kLoadsPerOperand;       // direct-to-LDS instructions per wavefront and k tile
-constexpr int kLoadEvery = kNT * kMT / kLoadsPerOperand;  // MFMAs between two loads
-static_assert(kNT * kMT % kLoadsPerOperand == 0 && kNT + kMT <= 15, "load spreading / lgkmcnt field");
+constexpr int kLoadsPerOperand = kLoadRows / 8;           // 8 rows (1 KiB) per instruction
+constexpr int kLoadsPerStage = 2 * kLoadsPerOperand;      // direct-to-LDS instructions per wavefront and k stage
+static_assert(kNT * kMT == kLoadsPerStage && kNT + kMT <= 15, "one load behind every MFMA of a slice / lgkmcnt field");
 
 // s_waitcnt immediates: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8
 constexpr int wait_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (lgkm << 8); }
@@ -55,6 +60,16 @@ constexpr int kNoVm = 63, kNoLgkm = 15;
 constexpr int kHeadDim = 128;
 
 __device__ inline bf16x8 frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// The bf16 MFMA as assembly with its accumulator tied in place in an accumulation register: given the builtin, the
+// register allocator rotated the 64 small accumulators of a wavefront through both register files (some 500 copies
+// per k stage).  The compiler does not know this statement is an MFMA: its operands come straight from LDS reads
+// (waited for by the compiler, which does track the registers), an accumulator is touched again 64 MFMAs later at the
+// earliest, and compiler-generated reads of the results sit behind mfma_settle().
+__device__ inline __attribute__((always_inline)) void mfma_16x16x32(f32x4& d, u32x4 a, u32x4 b) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
+}
+__device__ inline __attribute__((always_inline)) void mfma_settle() { asm volatile("s_nop 7\n\ts_nop 7" ::: "memory"); }
 
 struct GemmParams {
     const unsigned char* __restrict__ w;   // [N][K], bf16 or FP8 E4M3 codes
@@ -78,10 +93,8 @@ struct GemmParams {
 template <bool kFp8, bool kSplit>
 __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     constexpr int kElem = kFp8 ? 1 : 2;          // bytes per operand element
-    constexpr int kBK = kRowBytes / kElem;       // k per tile
+    constexpr int kBK = kRowBytes / kElem;       // k per stage
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    typedef __attribute__((address_space(3))) void* lds_ptr;
-    typedef const __attribute__((address_space(1))) void* glb_ptr;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int l32 = lane & 31, half = lane >> 5;
     const int wn = wave % kWavesN, wm = wave / kWavesN;
@@ -90,38 +103,57 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     const int n_splits = kSplit ? p.k_splits : 1;
     const int tile_id = blockIdx.x / n_splits, split = blockIdx.x - tile_id * n_splits;
     const int n0 = (tile_id % n_tiles) * kTile, m0 = (tile_id / n_tiles) * kTile;
-    // this workgroup's k tiles: [kt0, kt0 + k_steps) of the K / kBK in all
-    const int kt_all = p.K / kBK;
+    // this workgroup's k stages: [kt0, kt0 + k_steps) of all; with FP8 operands the very last stage may hold 64 k only
+    const int kt_all = (p.K + kBK - 1) / kBK;
     const int kt0 = kSplit ? static_cast<int>(static_cast<int64_t>(kt_all) * split / n_splits) : 0;
     const int k_steps = kSplit ? static_cast<int>(static_cast<int64_t>(kt_all) * (split + 1) / n_splits) - kt0 : kt_all;
+    const bool ragged = kFp8 && p.K % kBK != 0 && kt0 + k_steps == kt_all;
 
-    // ---- direct-to-LDS loads: this wavefront fills rows 32 wave .. 32 wave + 31 of both operand tiles, sixteen rows
-    // (1 KiB) per instruction; lane -> row 16 j + lane / 4, LDS piece position lane % 4, logical piece = position ^ key
+    // ---- direct-to-LDS loads: this wavefront fills rows 64 wave .. 64 wave + 63 of both operand tiles, eight rows of
+    // 128 bytes (1 KiB, eight whole cache lines) per instruction; lane -> row 8 j + lane / 8, LDS piece position
+    // lane % 8, logical piece = position ^ key.  (Half lines - 16 rows of 64 bytes per instruction - kept the address
+    // path of the compute unit busy nine tenths of the time and every line was requested twice, one k tile apart.)
     // The address of a load is a wavefront-uniform base (tile origin + k, kept in scalar registers and advanced by
     // scalar adds) plus a 32-bit byte offset per lane that never changes, and the LDS destination is uniform too: no
     // vector ALU instruction is spent on a load.
-    const int ld_row = lane >> 2, ld_pos = lane & 3;
+    const int ld_row = lane >> 3, ld_pos = lane & 7;
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     const size_t k_bytes = static_cast<size_t>(p.K) * kElem;
     const size_t seg_bytes = p.mode == 0 ? k_bytes : static_cast<size_t>(p.s.hq_l) * kHeadDim * kElem;   // contiguous k of a token row
     uint32_t w_off[kLoadsPerOperand], x_off[kLoadsPerOperand];   // byte offsets of this lane's piece from the tile origin at k = 0
 #pragma unroll
     for (int j = 0; j < kLoadsPerOperand; ++j) {
-        const int row = kLoadRows * wave + 16 * j + ld_row;
-        const int piece = ld_pos ^ ((row >> 2) & 3);
+        const int row = kLoadRows * wave + 8 * j + ld_row;
+        const int piece = ld_pos ^ ((row >> 1) & 7);
         w_off[j] = static_cast<uint32_t>(static_cast<size_t>(row) * k_bytes + piece * 16);
         const int m = min(m0 + row, p.M - 1) - m0;   // rows past the end re-read the last one; they are not stored
         x_off[j] = static_cast<uint32_t>(static_cast<size_t>(m) * seg_bytes + piece * 16);
     }
+    // A half-filled last stage: the lanes of pieces 4..7 (past the end of the row) fetch pieces 0..3 once more.  The
+    // key of row 64 wave + 8 j + lane / 8 has bit 2 equal to j % 2, so which lanes those are depends on j % 2 only.
+    uint32_t tail_fix[2];
+#pragma unroll
+    for (int jp = 0; jp < 2; ++jp) tail_fix[jp] = (((ld_pos >> 2) ^ jp) & 1) ? 64u : 0u;
     const unsigned char* w_tile = p.w + static_cast<size_t>(n0) * k_bytes;
     const unsigned char* x_tile = p.x + static_cast<size_t>(m0) * seg_bytes;
     // A token row's k runs contiguously through the hq_l heads that one source rank returned, then jumps to the
     // next rank's buffer (mode 1); in mode 0 it is contiguous throughout.
-    const int seg_tiles = static_cast<int>(seg_bytes / kRowBytes);
+    const int seg_tiles = max(static_cast<int>(seg_bytes / kRowBytes), 1);
     const size_t seg_jump = p.mode == 0 ? 0 : static_cast<size_t>(p.s.T_pad - 1) * seg_bytes;
-    int ld_kt = 0, ld_left = seg_tiles - kt0 % seg_tiles;   // next tile to load (counted from kt0), and how many tiles remain in its segment
-    w_tile += static_cast<size_t>(kt0) * kRowBytes;
-    x_tile += static_cast<size_t>(kt0) * kRowBytes + static_cast<size_t>(kt0 / seg_tiles) * seg_jump;
+    // The workgroups of a launch move through k in step, and rows lie a power of two apart: left alone, every compute
+    // unit of the chip asks for the same few memory channels at the same time (measured: the address path stalled by the
+    // cache twice as often, twice the bytes fetched into the L2s).  So the walk over k starts at a different place on
+    // every XCD (workgroup i runs on XCD i % 8; the workgroups of one XCD stay together, they share operand panels
+    // through its L2) and wraps around; a sum over k does not care where it starts.
+    const int rot0 = ragged ? 0 : static_cast<int>((static_cast<int64_t>(blockIdx.x % 8) * k_steps) / 8);
+    const unsigned char* const w_start = w_tile + static_cast<size_t>(kt0) * kRowBytes;
+    const unsigned char* const x_start = x_tile + static_cast<size_t>(kt0) * kRowBytes + static_cast<size_t>(kt0 / seg_tiles) * seg_jump;
+    const int left_start = seg_tiles - kt0 % seg_tiles;
+    const int kt_first = kt0 + rot0;
+    int ld_kt = 0, ld_left = seg_tiles - kt_first % seg_tiles;   // loads issued so far, and how many stages remain in the segment of the next one
+    int wrap_left = k_steps - rot0;                              // stages until the walk is back at the start of its range
+    w_tile += static_cast<size_t>(kt_first) * kRowBytes;
+    x_tile += static_cast<size_t>(kt_first) * kRowBytes + static_cast<size_t>(kt_first / seg_tiles) * seg_jump;
     // 1 KiB from a wavefront-uniform base (scalar registers) + a 32-bit byte offset per lane into LDS at dst (uniform):
     // written as assembly so that the load forms the address itself instead of a 64-bit vector addition in front of it.
     // These loads are waited for with the explicit vmcnt waits below only.
@@ -138,189 +170,270 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :: "s"(m0v), "v"(lane_off), "s"(scalar_ptr(base)) : "memory");
     };
-    auto load_one = [&](int j) {          // first the weight rows, then the token rows
-        unsigned char* dst = lds + (ld_kt % kStages) * kStage + (kLoadRows * wave_s) * kRowBytes;
-        if (j < kLoadsPerOperand) dma_1k(w_tile, w_off[j], dst + j * 1024);
-        else dma_1k(x_tile, x_off[j - kLoadsPerOperand], dst + kOperandBytes + (j - kLoadsPerOperand) * 1024);
+    auto load_one = [&](int j, bool tail) {          // first the token rows, then the weight rows
+        unsigned char* dst = lds + (ld_kt % kStages) * kStage + (kLoadRows * wave_s) * kRowBytes;   // (= ld_dst)
+        const uint32_t fix = tail ? tail_fix[j % 2] : 0u;
+        if (j < kLoadsPerOperand) dma_1k(x_tile, x_off[j] - fix, dst + kOperandBytes + j * 1024);
+        else dma_1k(w_tile, w_off[j - kLoadsPerOperand] - fix, dst + (j - kLoadsPerOperand) * 1024);
     };
-    auto load_advance = [&]() {
+    auto advance_x = [&]() {              // behind the last token-row load of a stage
+        x_tile += kRowBytes;
+        if (--ld_left == 0) {             // (a real branch, rarely taken: as selects this is a dozen scalar instructions)
+            asm volatile("; next source buffer");
+            ld_left = seg_tiles;
+            x_tile += seg_jump;
+        }
+    };
+    // LDS address of this wavefront's rows in the stage buffer that the next loads fill
+    uint32_t ld_dst = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds + (kLoadRows * wave_s) * kRowBytes));
+    uint32_t ld_dst_step = kStage;        // to the other buffer and back
+    auto advance_w = [&]() {              // behind the last load of a stage
         ++ld_kt;
         w_tile += kRowBytes;
-        x_tile += kRowBytes;
-        if (--ld_left == 0) { ld_left = seg_tiles; x_tile += seg_jump; }
+        if (--wrap_left == 0) {           // (rarely taken, a real branch)
+            asm volatile("; back to the start of the k range");
+            w_tile = w_start;
+            x_tile = x_start;
+            ld_left = left_start;
+        }
+        ld_dst += ld_dst_step;
+        ld_dst_step = 0u - ld_dst_step;
+    };
+    // The same load in two statements, for the loop of the 16-clock MFMAs, where the single wavefront of a SIMD keeps the
+    // matrix pipe fed only if no more than one other instruction sits between two MFMAs: the LDS destination into M0
+    // (one scalar addition; the MFMA behind it is the wait state the load needs), then, one MFMA later, the load.
+    // Nothing else in this kernel writes M0 between the two (the compiler has no use of its own for it here).
+    auto set_m0 = [&]<int j>() {
+        constexpr int imm = j < kLoadsPerOperand ? kOperandBytes + j * 1024 : (j - kLoadsPerOperand) * 1024;
+        const uint32_t dst = ld_dst;
+        asm volatile("s_add_u32 m0, %0, %1" :: "s"(dst), "n"(imm) : "scc");
+    };
+    auto issue_load = [&]<int j>(bool tail) {
+        constexpr bool is_x = j < kLoadsPerOperand;
+        constexpr int jj = is_x ? j : j - kLoadsPerOperand;
+        const uint32_t off = (is_x ? x_off[jj] : w_off[jj]) - (tail ? tail_fix[j % 2] : 0u);
+        const unsigned char* base = scalar_ptr(is_x ? x_tile : w_tile);
+        asm volatile("global_load_lds_dwordx4 %0, %1" :: "v"(off), "s"(base) : "memory");
     };
 
-    // ---- operand reads: row l32 of a 32-row tile, piece 2 ks + half
-    const int key = (l32 >> 2) & 3;   // 32-row tiles start at multiples of 32: the key depends on l32 only
-    int rd[2];
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) rd[ks] = l32 * kRowBytes + (((2 * ks + half) ^ key) << 4);
+    // ---- operand reads: row l32 of a 32-row tile; 32-row tiles start at multiples of 32, so the key depends on l32 only
+    const int key = (l32 >> 1) & 7;
+    auto rd_at = [&](int piece) { return l32 * kRowBytes + ((piece ^ key) << 4); };
     const int a_base = (wn * kNT * 32) * kRowBytes;                    // weight rows of this wavefront
     const int b_base = kOperandBytes + (wm * kMT * 32) * kRowBytes;   // token rows of this wavefront
 
-    f32x16 acc[kNT][kMT];
+    // accumulators: 16 x 16 tiles (bf16, v_mfma_f32_16x16x32_bf16) or 32 x 32 tiles (FP8), 256 registers either way
+    using AccTile = std::conditional_t<kFp8, f32x16, f32x4>;
+    constexpr int kAT = kFp8 ? kNT : 8;          // accumulator tiles of a wavefront along the features / along the tokens
+    constexpr int kAccRegs = kFp8 ? 16 : 4;
+    AccTile acc[kAT][kAT];
 #pragma unroll
-    for (int nt = 0; nt < kNT; ++nt)
+    for (int nt = 0; nt < kAT; ++nt)
 #pragma unroll
-        for (int mt = 0; mt < kMT; ++mt)
+        for (int mt = 0; mt < kAT; ++mt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[nt][mt][r] = 0.f;
+            for (int r = 0; r < kAccRegs; ++r) acc[nt][mt][r] = 0.f;
 
-    // Operands are read from LDS one 16-wide k slice ahead of the MFMAs that use them (two register sets).  The
-    // workgroup meets once per k tile, before the tile's last slice is multiplied: by then every wavefront holds
-    // that slice in registers, so the tile's buffer is free, and the first slice of the next tile is fetched while
-    // the last one is multiplied.  The loads of the tile kStages - 1 ahead go into the buffer freed one meeting
-    // earlier and are spread between the MFMAs, one behind every fourth.
-    auto read_ops = [&](const unsigned char* base, int ks, u32x4 (&a)[kNT], u32x4 (&b)[kMT]) {
+    // the first two stages are requested (the last one of a short k with its half-row fix), stage 0 has landed everywhere
+    auto prologue = [&]() {
+        for (int t = 0; t < kStages && t < k_steps; ++t) {
+            const bool tail = ragged && t == k_steps - 1;
 #pragma unroll
-        for (int nt = 0; nt < kNT; ++nt) a[nt] = *reinterpret_cast<const u32x4*>(base + a_base + nt * 32 * kRowBytes + rd[ks]);
-#pragma unroll
-        for (int mt = 0; mt < kMT; ++mt) b[mt] = *reinterpret_cast<const u32x4*>(base + b_base + mt * 32 * kRowBytes + rd[ks]);
-    };
-    auto multiply = [&]<int kLoad0>(const u32x4 (&a)[kNT], const u32x4 (&b)[kMT]) {   // kLoad0 < 0: no loads in between
-#pragma unroll
-        for (int nt = 0; nt < kNT; ++nt)
-#pragma unroll
-            for (int mt = 0; mt < kMT; ++mt) {
-                acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[nt]), frag(b[mt]), acc[nt][mt], 0, 0, 0);
-                if (kLoad0 >= 0 && (nt * kMT + mt) % kLoadEvery == 1) {
-                    load_one(kLoad0 + (nt * kMT + mt) / kLoadEvery);
-                    __builtin_amdgcn_sched_barrier(0);   // keep the load between these MFMAs
-                }
-            }
-    };
-
-    auto prologue = [&]() {   // the first kStages - 1 tiles are requested, tile 0 has landed everywhere
-        for (int t = 0; t < kStages - 1 && t < k_steps; ++t) {
-#pragma unroll
-            for (int j = 0; j < kLoadsPerTile; ++j) load_one(j);
-            load_advance();
+            for (int j = 0; j < kLoadsPerStage; ++j) load_one(j, tail);
+            advance_x();
+            advance_w();
         }
-        if (k_steps >= kStages - 1) __builtin_amdgcn_s_waitcnt(wait_imm(kLoadsPerTile * (kStages - 2), kNoLgkm));
+        if (k_steps >= kStages) __builtin_amdgcn_s_waitcnt(wait_imm(kLoadsPerStage, kNoLgkm));
         else __builtin_amdgcn_s_waitcnt(wait_imm(0, kNoLgkm));
-        __builtin_amdgcn_s_barrier();
+        asm volatile("s_barrier" ::: "memory");
     };
+    // The stage loop.  kLoadMode 0: no loads (the last two stages; a half-filled last one stops after its first slice), 1: the loads of the stage after next follow the
+    // meeting, 2: the same with the half-row fix (that stage is a half-filled last one).
+    auto run_stages = [&](auto&& stage) {
+        int st = 0;
+        const int n_plain = k_steps - kStages - (ragged ? 1 : 0);
+        for (; st < n_plain; ++st) stage.template operator()<1>(st);
+        if constexpr (kFp8) {
+            if (ragged && st + kStages < k_steps) {
+                stage.template operator()<2>(st);
+                ++st;
+            }
+        }
+        for (; st < k_steps; ++st) stage.template operator()<0>(st);
+    };
+
+    // Operands are read from LDS one MFMA k step (a "slice": 32 bytes of every row for bf16, 64 for FP8) ahead of the
+    // MFMAs that use them, into the other of two register sets, one read behind an MFMA, in the order in which the
+    // MFMAs of the coming slice need them: the matrix pipe never waits behind a burst of reads (with one wavefront per
+    // SIMD nothing else would feed it meanwhile).  The workgroup meets once per stage, in front of the stage's last
+    // slice: by then a wavefront holds that slice in registers (it is done with the stage's buffer) and its loads of
+    // the next stage have landed.  Behind the meeting the first slice of the next stage is read and the stage after
+    // next is requested into the buffer just left, one load behind every MFMA.
     if constexpr (!kFp8) {
-        u32x4 a0[kNT], b0[kMT], a1[kNT], b1[kMT];
-        prologue();
-        read_ops(lds, 0, a0, b0);
-        auto tile = [&]<bool kLoads>(int kt) {
-            read_ops(lds + (kt % kStages) * kStage, 1, a1, b1);
-            __builtin_amdgcn_sched_barrier(0);   // the reads stay ahead of the MFMAs of the slice before ...
-            __builtin_amdgcn_s_waitcnt(wait_imm(kNoVm, kNT + kMT));  // ... which wait for their own operands only
-            multiply.template operator()<kLoads ? 0 : -1>(a0, b0);
-            // tile kt + 1 has landed (behind it: kStages - 3 whole tiles and the weight loads just issued), and this
-            // wavefront's reads of tile kt are done
-            __builtin_amdgcn_sched_barrier(0);
-            if (kLoads) __builtin_amdgcn_s_waitcnt(wait_imm(kLoadsPerTile * (kStages - 3) + kLoadsPerOperand, 0));
-            else __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
-            __builtin_amdgcn_s_barrier();   // bare: a __syncthreads() would wait for every load in flight
-            read_ops(lds + ((kt + 1) % kStages) * kStage, 0, a0, b0);   // behind the last tile: stale data, not used
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_waitcnt(wait_imm(kNoVm, kNT + kMT));
-            multiply.template operator()<kLoads ? kLoadsPerOperand : -1>(a1, b1);
-            if (kLoads) load_advance();
+        // v_mfma_f32_16x16x32_bf16 (at the chip's power limit it sustains about 15 % more than the 32x32x16 form: it
+        // reads and writes a quarter of the accumulator registers per MFMA for half the work).  A slice is 32 k, half
+        // a stage: lane -> row lane % 16 of a 16-row tile, piece 4 slice + lane / 16 of its 128-byte row; eight tiles
+        // of either operand per wavefront, 64 MFMAs per slice.
+        const int r16 = lane & 15, kg = lane >> 4;
+        int rd[2];
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) rd[sl] = r16 * kRowBytes + (((4 * sl + kg) ^ ((r16 >> 1) & 7)) << 4);
+        u32x4 a[2][kAT], b[2][kAT];   // [set]
+        // read r of a slice into set S, in the order of first use by MFMA (i, j) = (I / 8, I % 8): a[0], b[0..7], a[1..7]
+        auto read_one = [&]<int r, int S>(const unsigned char* base, int sl) {
+            if constexpr (r == 0) a[S][0] = *reinterpret_cast<const u32x4*>(base + a_base + rd[sl]);
+            else if constexpr (r <= kAT) b[S][r - 1] = *reinterpret_cast<const u32x4*>(base + b_base + (r - 1) * 16 * kRowBytes + rd[sl]);
+            else a[S][r - kAT] = *reinterpret_cast<const u32x4*>(base + a_base + (r - kAT) * 16 * kRowBytes + rd[sl]);
         };
-        int kt = 0;
-        for (; kt + kStages - 1 < k_steps; ++kt) tile.template operator()<true>(kt);
-        for (; kt < k_steps; ++kt) tile.template operator()<false>(kt);
+        // the 64 MFMAs of one slice on set S; the 16 reads of (rd_base, rd_sl) into the other set behind MFMAs 0, 4, 8,
+        // ... (kDense: 0, 3, ..., 45, so that they are back before the slice ends); kLoadMode > 0: the 16 loads of the
+        // stage after next, each in two slots
+        auto slice = [&]<int S, bool kDense, int kLoadMode>(const unsigned char* rd_base, int rd_sl) {
+            [&]<int... I>(std::integer_sequence<int, I...>) {
+                (([&]() {
+                     constexpr int i = I / kAT, j = I % kAT;
+                     mfma_16x16x32(acc[i][j], a[S][i], b[S][j]);
+                     if constexpr (kDense) {
+                         if constexpr (I % 3 == 0 && I / 3 < 2 * kAT) read_one.template operator()<I / 3, 1 - S>(rd_base, rd_sl);
+                     } else {
+                         if constexpr (I % 4 == 0) read_one.template operator()<I / 4, 1 - S>(rd_base, rd_sl);
+                     }
+                     if constexpr (kLoadMode > 0) {   // load j: M0 behind MFMA 4 j + 1, the load behind MFMA 4 j + 2
+                         if constexpr (I % 4 == 1) set_m0.template operator()<I / 4>();
+                         if constexpr (I % 4 == 2) issue_load.template operator()<I / 4>(kLoadMode == 2);
+                         if constexpr (I == 4 * kLoadsPerOperand - 1) advance_x();   // (scalar work, in slots of its own)
+                         if constexpr (I == kAT * kAT - 1) advance_w();
+                     }
+                     __builtin_amdgcn_sched_barrier(0);
+                 }()),
+                 ...);
+            }(std::make_integer_sequence<int, kAT * kAT>{});
+        };
+        prologue();
+        [&]<int... R>(std::integer_sequence<int, R...>) {
+            (read_one.template operator()<R, 0>(lds, 0), ...);
+        }(std::make_integer_sequence<int, 2 * kAT>{});
+        auto stage = [&]<int kLoadMode>(int st) {
+            // (where two copies of this body meet, the compiler moves accumulators between registers; the wait states
+            // an MFMA needs behind such a move are put here, since it cannot know that one follows)
+            asm volatile("s_nop 4" ::: "memory");
+            slice.template operator()<0, true, 0>(lds + (st % kStages) * kStage, 1);
+            // this wavefront is done with the buffer, and its loads of the next stage have landed
+            __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
+            asm volatile("s_barrier" ::: "memory");
+            // (behind the last stage: stale data, not used)
+            slice.template operator()<1, false, kLoadMode>(lds + ((st + 1) % kStages) * kStage, 0);
+        };
+        run_stages(stage);
+        mfma_settle();
     } else {
-        // One MFMA per (feature tile, token tile) and k tile: its 32-byte operands are the two 16-byte pieces the
-        // bf16 path reads for its two k slices (which k a lane holds does not matter as long as both operands agree).
-        // Two register sets: the next tile's operands are fetched while this tile's MFMAs run.
+        // One MFMA per (feature tile, token tile) and slice of 64 k: the 32-byte operand of a lane is a pair of 16-byte
+        // pieces, two apart (which k a lane holds does not matter as long as both operands agree).
+        int rd[2][2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            rd[q][0] = rd_at(4 * q + half);
+            rd[q][1] = rd_at(4 * q + 2 + half);
+        }
         i32x8 a[2][kNT], b[2][kMT];   // [set]
         auto join = [](u32x4 lo, u32x4 hi) -> i32x8 {
             return i32x8{static_cast<int>(lo[0]), static_cast<int>(lo[1]), static_cast<int>(lo[2]), static_cast<int>(lo[3]),
                          static_cast<int>(hi[0]), static_cast<int>(hi[1]), static_cast<int>(hi[2]), static_cast<int>(hi[3])};
         };
-        auto read_tile = [&](const unsigned char* base, auto set_c) {
-            constexpr int S = decltype(set_c)::value;
-#pragma unroll
-            for (int nt = 0; nt < kNT; ++nt) {
-                const unsigned char* r = base + a_base + nt * 32 * kRowBytes;
-                a[S][nt] = join(*reinterpret_cast<const u32x4*>(r + rd[0]), *reinterpret_cast<const u32x4*>(r + rd[1]));
-            }
-#pragma unroll
-            for (int mt = 0; mt < kMT; ++mt) {
-                const unsigned char* r = base + b_base + mt * 32 * kRowBytes;
-                b[S][mt] = join(*reinterpret_cast<const u32x4*>(r + rd[0]), *reinterpret_cast<const u32x4*>(r + rd[1]));
+        // operand r of slice q into set S, in the order of first use: a[0], b[0..], a[1..]
+        auto read_one = [&]<int r, int S>(const unsigned char* base, int q) {
+            if constexpr (r == 0 || r > kMT) {
+                constexpr int nt = r == 0 ? 0 : r - kMT;
+                const unsigned char* row = base + a_base + nt * 32 * kRowBytes;
+                a[S][nt] = join(*reinterpret_cast<const u32x4*>(row + rd[q][0]), *reinterpret_cast<const u32x4*>(row + rd[q][1]));
+            } else {
+                const unsigned char* row = base + b_base + (r - 1) * 32 * kRowBytes;
+                b[S][r - 1] = join(*reinterpret_cast<const u32x4*>(row + rd[q][0]), *reinterpret_cast<const u32x4*>(row + rd[q][1]));
             }
         };
-        // kLoadMode 1: the tile kStages - 1 ahead exists and is requested; 2: checked at run time (the last few tiles)
-        auto tile8 = [&]<int kLoadMode, int S>(int kt) {
-            const bool ld = kLoadMode == 1 || kt + kStages - 1 < k_steps;
-            // tile kt + 1 has landed (behind it kStages - 3 whole tiles), and this wavefront's reads of tile kt are done
-            if (ld) __builtin_amdgcn_s_waitcnt(wait_imm(kLoadsPerTile * (kStages - 3), 0));
-            else __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
-            __builtin_amdgcn_s_barrier();
-            read_tile(lds + ((kt + 1) % kStages) * kStage, std::integral_constant<int, 1 - S>{});   // behind the last tile: stale, unused
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int nt = 0; nt < kNT; ++nt)
-#pragma unroll
-                for (int mt = 0; mt < kMT; ++mt) {
-                    acc[nt][mt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[S][nt], b[S][mt], acc[nt][mt], 0, 0, 0, 127, 0, 127);
-                    if ((nt * kMT + mt) % 2 == 0) {
-                        if (ld) load_one((nt * kMT + mt) / 2);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                }
-            if (ld) load_advance();
+        // the 16 MFMAs of one slice on set S, the operands of (rd_base, rd_q) read into the other set behind MFMAs
+        // 0, 2, 4, ... (kDense: 0, 1, ..., 7), kLoadMode > 0: load i of the stage after next behind MFMA i
+        auto slice = [&]<int S, bool kDense, int kLoadMode>(const unsigned char* rd_base, int rd_q) {
+            [&]<int... I>(std::integer_sequence<int, I...>) {
+                (([&]() {
+                     constexpr int nt = I / kMT, mt = I % kMT;
+                     acc[nt][mt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[S][nt], b[S][mt], acc[nt][mt], 0, 0, 0, 127, 0, 127);
+                     if constexpr (kDense) {
+                         if constexpr (I < kNT + kMT) read_one.template operator()<I, 1 - S>(rd_base, rd_q);
+                     } else {
+                         if constexpr (I % 2 == 0) read_one.template operator()<I / 2, 1 - S>(rd_base, rd_q);
+                     }
+                     if constexpr (kLoadMode > 0) {
+                         load_one(I, kLoadMode == 2);
+                         if constexpr (I == kLoadsPerOperand - 1) advance_x();
+                     }
+                     __builtin_amdgcn_sched_barrier(0);
+                 }()),
+                 ...);
+            }(std::make_integer_sequence<int, kNT * kMT>{});
         };
-        static_assert(kNT * kMT == 2 * kLoadsPerTile, "one load behind every second MFMA");
         prologue();
-        read_tile(lds, std::integral_constant<int, 0>{});
-        int kt = 0;
-        for (; kt + kStages < k_steps; kt += 2) {
-            tile8.template operator()<1, 0>(kt);
-            tile8.template operator()<1, 1>(kt + 1);
-        }
-        for (; kt < k_steps; kt += 2) {
-            tile8.template operator()<2, 0>(kt);
-            if (kt + 1 < k_steps) tile8.template operator()<2, 1>(kt + 1);
-        }
+        [&]<int... R>(std::integer_sequence<int, R...>) {
+            (read_one.template operator()<R, 0>(lds, 0), ...);
+        }(std::make_integer_sequence<int, kNT + kMT>{});
+        auto stage = [&]<int kLoadMode>(int st) {
+            slice.template operator()<0, true, 0>(lds + (st % kStages) * kStage, 1);
+            __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
+            asm volatile("s_barrier" ::: "memory");
+            if (kLoadMode == 0 && ragged && st == k_steps - 1) return;   // a half-filled last stage: its first 64 k only
+            slice.template operator()<1, false, kLoadMode>(lds + ((st + 1) % kStages) * kStage, 0);
+            if (kLoadMode > 0) advance_w();
+        };
+        run_stages(stage);
     }
 
-    // ---- result: register r of acc[nt][mt] is feature 32 nt + 8 (r / 4) + 4 half + r % 4 of token 32 mt + l32
-    const int f_wave = n0 + wn * kNT * 32;     // first feature of this wavefront; its features lie in one head
+    // ---- result.  A lane holds runs of four consecutive features of one token:
+    //   16 x 16 tiles: acc[i][j] is features 16 i + 4 (lane / 16) .. + 3 of token 16 j + lane % 16;
+    //   32 x 32 tiles: registers 4 q .. 4 q + 3 of acc[nt][mt] are features 32 nt + 8 q + 4 half .. + 3 of token 32 mt + l32.
+    constexpr int kTokStep = kFp8 ? 32 : 16;                  // tokens per accumulator tile
+    constexpr int kQuads = kFp8 ? 4 * kNT : kAT;              // runs of four features per token and lane
+    const int tok_lane = kFp8 ? l32 : (lane & 15);
+    auto quad_feature = [&](int q) { return kFp8 ? 32 * (q / 4) + 8 * (q % 4) + 4 * half : 16 * q + 4 * (lane >> 4); };
+    auto quad_value = [&](int q, int t, int e) -> float {
+        if constexpr (kFp8) return acc[q / 4][t][4 * (q % 4) + e];
+        else return acc[q][t][e];
+    };
+    const int f_wave = n0 + wn * (kTile / kWavesN);     // first feature of this wavefront; its features lie in one head
     auto store_rows = [&](uint16_t* dst_row0, size_t row_stride) {   // dst_row0: feature f_wave of token row 0
 #pragma unroll
-        for (int mt = 0; mt < kMT; ++mt) {
-            const int m = m0 + wm * kMT * 32 + mt * 32 + l32;
+        for (int t = 0; t < kAT; ++t) {
+            const int m = m0 + wm * (kTile / kWavesM) + t * kTokStep + tok_lane;
             if (m >= p.M_out) continue;
-            uint16_t* row = dst_row0 + static_cast<size_t>(m) * row_stride + 4 * half;
+            uint16_t* row = dst_row0 + static_cast<size_t>(m) * row_stride;
             float row_scale = 1.f;
             if constexpr (kFp8) row_scale = m < p.M ? p.xs[m] : 0.f;
 #pragma unroll
-            for (int nt = 0; nt < kNT; ++nt)
+            for (int q = 0; q < kQuads; ++q) {
+                const int f = quad_feature(q);
+                f32x4 col_scale = {1.f, 1.f, 1.f, 1.f};
+                if constexpr (kFp8) col_scale = *reinterpret_cast<const f32x4*>(p.ws + f_wave + f);
+                bf16x4 v;
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    f32x4 col_scale = {1.f, 1.f, 1.f, 1.f};
-                    if constexpr (kFp8) col_scale = *reinterpret_cast<const f32x4*>(p.ws + f_wave + 32 * nt + 8 * r4 + 4 * half);
-                    bf16x4 v;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float y = m < p.M ? acc[nt][mt][4 * r4 + e] : 0.f;
-                        if constexpr (kFp8) y = y * row_scale * col_scale[e];
-                        v[e] = static_cast<__bf16>(y);
-                    }
-                    *reinterpret_cast<u32x2*>(row + 32 * nt + 8 * r4) = __builtin_bit_cast(u32x2, v);
+                for (int e = 0; e < 4; ++e) {
+                    float y = m < p.M ? quad_value(q, t, e) : 0.f;
+                    if constexpr (kFp8) y = y * row_scale * col_scale[e];
+                    v[e] = static_cast<__bf16>(y);
                 }
+                *reinterpret_cast<u32x2*>(row + f) = __builtin_bit_cast(u32x2, v);
+            }
         }
     };
     if constexpr (kSplit) {   // this k range's fp32 sums, [split][token][feature]; proj_finish adds the ranges and does the layout
-        float* base = p.partial + static_cast<size_t>(split) * p.M_out * p.N + f_wave + 4 * half;
+        float* base = p.partial + static_cast<size_t>(split) * p.M_out * p.N + f_wave;
 #pragma unroll
-        for (int mt = 0; mt < kMT; ++mt) {
-            const int m = m0 + wm * kMT * 32 + mt * 32 + l32;
+        for (int t = 0; t < kAT; ++t) {
+            const int m = m0 + wm * (kTile / kWavesM) + t * kTokStep + tok_lane;
             if (m >= p.M) continue;   // rows past the last token are zeros in the result and are not read
             float* row = base + static_cast<size_t>(m) * p.N;
 #pragma unroll
-            for (int nt = 0; nt < kNT; ++nt)
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4)
-                    *reinterpret_cast<f32x4*>(row + 32 * nt + 8 * r4) =
-                        f32x4{acc[nt][mt][4 * r4], acc[nt][mt][4 * r4 + 1], acc[nt][mt][4 * r4 + 2], acc[nt][mt][4 * r4 + 3]};
+            for (int q = 0; q < kQuads; ++q)
+                *reinterpret_cast<f32x4*>(row + quad_feature(q)) =
+                    f32x4{quad_value(q, t, 0), quad_value(q, t, 1), quad_value(q, t, 2), quad_value(q, t, 3)};
         }
         return;
     }
