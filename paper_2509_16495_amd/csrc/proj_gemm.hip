@@ -34,7 +34,6 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
@@ -47,12 +46,11 @@ constexpr int kStages = 2;                 // k stages in LDS: one being multipl
 constexpr int kGemmLds = kStages * kStage; // 131072
 constexpr int kWavesN = 2, kWavesM = 2;    // wavefronts along the features / along the tokens
 constexpr int kGemmThreads = 64 * kWavesN * kWavesM;
-constexpr int kNT = kTile / kWavesN / 32;  // 32-feature tiles per wavefront
-constexpr int kMT = kTile / kWavesM / 32;  // 32-token tiles per wavefront
+constexpr int kWaveRows = kTile / kWavesN;                // rows of either operand that one wavefront multiplies (128)
+static_assert(kTile / kWavesM == kWaveRows, "square wavefront tiles");
 constexpr int kLoadRows = kTile / (kWavesN * kWavesM);   // rows of either operand that one wavefront loads
 constexpr int kLoadsPerOperand = kLoadRows / 8;           // 8 rows (1 KiB) per instruction
 constexpr int kLoadsPerStage = 2 * kLoadsPerOperand;      // direct-to-LDS instructions per wavefront and k stage
-static_assert(kNT * kMT == kLoadsPerStage && kNT + kMT <= 15, "one load behind every MFMA of a slice / lgkmcnt field");
 
 // s_waitcnt immediates: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8
 constexpr int wait_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (lgkm << 8); }
@@ -96,7 +94,6 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     constexpr int kBK = kRowBytes / kElem;       // k per stage
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int l32 = lane & 31, half = lane >> 5;
     const int wn = wave % kWavesN, wm = wave / kWavesN;
     // feature tiles vary fastest: workgroups that run together share the token rows in L2
     const int n_tiles = p.N / kTile;
@@ -216,23 +213,19 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
         asm volatile("global_load_lds_dwordx4 %0, %1" :: "v"(off), "s"(base) : "memory");
     };
 
-    // ---- operand reads: row l32 of a 32-row tile; 32-row tiles start at multiples of 32, so the key depends on l32 only
-    const int key = (l32 >> 1) & 7;
-    auto rd_at = [&](int piece) { return l32 * kRowBytes + ((piece ^ key) << 4); };
-    const int a_base = (wn * kNT * 32) * kRowBytes;                    // weight rows of this wavefront
-    const int b_base = kOperandBytes + (wm * kMT * 32) * kRowBytes;   // token rows of this wavefront
+    // ---- operand reads: tiles of 16 rows; this wavefront's weight rows and token rows in a stage buffer
+    const int a_base = (wn * kWaveRows) * kRowBytes;
+    const int b_base = kOperandBytes + (wm * kWaveRows) * kRowBytes;
 
-    // accumulators: 16 x 16 tiles (bf16, v_mfma_f32_16x16x32_bf16) or 32 x 32 tiles (FP8), 256 registers either way
-    using AccTile = std::conditional_t<kFp8, f32x16, f32x4>;
-    constexpr int kAT = kFp8 ? kNT : 8;          // accumulator tiles of a wavefront along the features / along the tokens
-    constexpr int kAccRegs = kFp8 ? 16 : 4;
-    AccTile acc[kAT][kAT];
+    // accumulators: 8 x 8 tiles of 16 x 16 per wavefront, 256 registers
+    constexpr int kAT = 8;
+    f32x4 acc[kAT][kAT];
 #pragma unroll
     for (int nt = 0; nt < kAT; ++nt)
 #pragma unroll
         for (int mt = 0; mt < kAT; ++mt)
 #pragma unroll
-            for (int r = 0; r < kAccRegs; ++r) acc[nt][mt][r] = 0.f;
+            for (int r = 0; r < 4; ++r) acc[nt][mt][r] = 0.f;
 
     // the first two stages are requested (the last one of a short k with its half-row fix), stage 0 has landed everywhere
     auto prologue = [&]() {
@@ -247,7 +240,7 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
         else __builtin_amdgcn_s_waitcnt(wait_imm(0, kNoLgkm));
         asm volatile("s_barrier" ::: "memory");
     };
-    // The stage loop.  kLoadMode 0: no loads (the last two stages; a half-filled last one stops after its first slice), 1: the loads of the stage after next follow the
+    // The stage loop.  kLoadMode 0: no loads (the last two stages), 1: the loads of the stage after next follow the
     // meeting, 2: the same with the half-row fix (that stage is a half-filled last one).
     auto run_stages = [&](auto&& stage) {
         int st = 0;
@@ -327,77 +320,93 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
         run_stages(stage);
         mfma_settle();
     } else {
-        // One MFMA per (feature tile, token tile) and slice of 64 k: the 32-byte operand of a lane is a pair of 16-byte
-        // pieces, two apart (which k a lane holds does not matter as long as both operands agree).
-        int rd[2][2];
+        // v_mfma_scale_f32_16x16x128_f8f6f4 with unit block scales: a stage (128 bytes of a row) is one MFMA k step,
+        // 64 MFMAs of 32 clocks; lane -> row lane % 16 of a 16-row tile, pieces 2 (lane / 16) and 2 (lane / 16) + 1 of
+        // its row (which k a lane holds does not matter as long as both operands agree).  Registers hold the eight token
+        // tiles of the stage (b, 64 registers) and eight weight tiles (a, 64): rows i = 0..3 of the MFMA grid fetch
+        // weight tiles 4..7 of the stage, the workgroup meets in front of row 4 (all of the stage's operands are in
+        // registers or on their way, the next stage has landed), rows 4..7 fetch weight tiles 0..3 of the next stage and
+        // request the stage after next, and token tile j of the next stage is fetched right behind MFMA (7, j), the
+        // last one that uses its registers, eight MFMAs ahead of the first one that needs it.
+        const int r16 = lane & 15, kg = lane >> 4;
+        int rd[2];
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            rd[q][0] = rd_at(4 * q + half);
-            rd[q][1] = rd_at(4 * q + 2 + half);
-        }
-        i32x8 a[2][kNT], b[2][kMT];   // [set]
+        for (int h = 0; h < 2; ++h) rd[h] = r16 * kRowBytes + (((2 * kg + h) ^ ((r16 >> 1) & 7)) << 4);
+        i32x8 a[kAT], b[kAT];
+        int unit_scale;   // E8M0 code of 1.0, in a vector register as the instruction wants it
+        asm volatile("v_mov_b32 %0, 127" : "=v"(unit_scale));
         auto join = [](u32x4 lo, u32x4 hi) -> i32x8 {
             return i32x8{static_cast<int>(lo[0]), static_cast<int>(lo[1]), static_cast<int>(lo[2]), static_cast<int>(lo[3]),
                          static_cast<int>(hi[0]), static_cast<int>(hi[1]), static_cast<int>(hi[2]), static_cast<int>(hi[3])};
         };
-        // operand r of slice q into set S, in the order of first use: a[0], b[0..], a[1..]
-        auto read_one = [&]<int r, int S>(const unsigned char* base, int q) {
-            if constexpr (r == 0 || r > kMT) {
-                constexpr int nt = r == 0 ? 0 : r - kMT;
-                const unsigned char* row = base + a_base + nt * 32 * kRowBytes;
-                a[S][nt] = join(*reinterpret_cast<const u32x4*>(row + rd[q][0]), *reinterpret_cast<const u32x4*>(row + rd[q][1]));
-            } else {
-                const unsigned char* row = base + b_base + (r - 1) * 32 * kRowBytes;
-                b[S][r - 1] = join(*reinterpret_cast<const u32x4*>(row + rd[q][0]), *reinterpret_cast<const u32x4*>(row + rd[q][1]));
-            }
+        auto read_a = [&]<int i>(const unsigned char* base) {
+            const unsigned char* row = base + a_base + i * 16 * kRowBytes;
+            a[i] = join(*reinterpret_cast<const u32x4*>(row + rd[0]), *reinterpret_cast<const u32x4*>(row + rd[1]));
         };
-        // the 16 MFMAs of one slice on set S, the operands of (rd_base, rd_q) read into the other set behind MFMAs
-        // 0, 2, 4, ... (kDense: 0, 1, ..., 7), kLoadMode > 0: load i of the stage after next behind MFMA i
-        auto slice = [&]<int S, bool kDense, int kLoadMode>(const unsigned char* rd_base, int rd_q) {
+        auto read_b = [&]<int j>(const unsigned char* base) {
+            const unsigned char* row = base + b_base + j * 16 * kRowBytes;
+            b[j] = join(*reinterpret_cast<const u32x4*>(row + rd[0]), *reinterpret_cast<const u32x4*>(row + rd[1]));
+        };
+        // (assembly with the accumulator tied in place, as for bf16 above)
+        auto mfma = [&](f32x4& d, const i32x8& av, const i32x8& bv) {
+            asm volatile("v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %2, %0, %3, %3 op_sel_hi:[0,0,0]"
+                         : "+a"(d) : "v"(av), "v"(bv), "v"(unit_scale));
+        };
+        prologue();
+        [&]<int... R>(std::integer_sequence<int, R...>) {
+            (read_b.template operator()<R>(lds), ...);
+        }(std::make_integer_sequence<int, kAT>{});
+        [&]<int... R>(std::integer_sequence<int, R...>) {
+            (read_a.template operator()<R>(lds), ...);
+        }(std::make_integer_sequence<int, kAT / 2>{});
+        auto stage = [&]<int kLoadMode>(int st) {
+            const unsigned char* cur = lds + (st % kStages) * kStage;
+            const unsigned char* nxt = lds + ((st + 1) % kStages) * kStage;
+            asm volatile("s_nop 4" ::: "memory");   // (accumulator moves between two copies of this body, see above)
+            if (kLoadMode == 0 && ragged && st == k_steps - 1) {
+                // a half-filled last stage: the upper 64 bytes of its rows repeat the lower ones (see the loads); the
+                // lanes that hold them multiply by zero
+#pragma unroll
+                for (int j = 0; j < kAT; ++j)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) b[j][e] = kg >= 2 ? 0 : b[j][e];
+                asm volatile("s_nop 4" ::: "memory");
+            }
             [&]<int... I>(std::integer_sequence<int, I...>) {
                 (([&]() {
-                     constexpr int nt = I / kMT, mt = I % kMT;
-                     acc[nt][mt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[S][nt], b[S][mt], acc[nt][mt], 0, 0, 0, 127, 0, 127);
-                     if constexpr (kDense) {
-                         if constexpr (I < kNT + kMT) read_one.template operator()<I, 1 - S>(rd_base, rd_q);
-                     } else {
-                         if constexpr (I % 2 == 0) read_one.template operator()<I / 2, 1 - S>(rd_base, rd_q);
+                     constexpr int i = I / kAT, j = I % kAT;
+                     if constexpr (I == kAT * kAT / 2) {
+                         // this wavefront is done with the buffer, and its loads of the next stage have landed
+                         __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
+                         asm volatile("s_barrier" ::: "memory");
                      }
-                     if constexpr (kLoadMode > 0) {
-                         load_one(I, kLoadMode == 2);
-                         if constexpr (I == kLoadsPerOperand - 1) advance_x();
+                     mfma(acc[i][j], a[i], b[j]);
+                     if constexpr (i < kAT / 2 && j == 0) read_a.template operator()<i + kAT / 2>(cur);
+                     if constexpr (i >= kAT / 2 && j == 1) read_a.template operator()<i - kAT / 2>(nxt);   // (behind the last stage: stale, unused)
+                     if constexpr (i == kAT - 1) read_b.template operator()<j>(nxt);
+                     if constexpr (kLoadMode > 0 && i >= kAT / 2) {   // 16 loads in the 32 slots behind the meeting: M0, then the load
+                         constexpr int slot = I - kAT * kAT / 2;
+                         if constexpr (slot % 2 == 0) set_m0.template operator()<slot / 2>();
+                         else issue_load.template operator()<slot / 2>(kLoadMode == 2);
+                         if constexpr (slot == 2 * kLoadsPerOperand - 1) advance_x();
+                         if constexpr (slot == 2 * kLoadsPerStage - 1) advance_w();
                      }
                      __builtin_amdgcn_sched_barrier(0);
                  }()),
                  ...);
-            }(std::make_integer_sequence<int, kNT * kMT>{});
-        };
-        prologue();
-        [&]<int... R>(std::integer_sequence<int, R...>) {
-            (read_one.template operator()<R, 0>(lds, 0), ...);
-        }(std::make_integer_sequence<int, kNT + kMT>{});
-        auto stage = [&]<int kLoadMode>(int st) {
-            slice.template operator()<0, true, 0>(lds + (st % kStages) * kStage, 1);
-            __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
-            asm volatile("s_barrier" ::: "memory");
-            if (kLoadMode == 0 && ragged && st == k_steps - 1) return;   // a half-filled last stage: its first 64 k only
-            slice.template operator()<1, false, kLoadMode>(lds + ((st + 1) % kStages) * kStage, 0);
-            if (kLoadMode > 0) advance_w();
+            }(std::make_integer_sequence<int, kAT * kAT>{});
         };
         run_stages(stage);
+        mfma_settle();
     }
 
-    // ---- result.  A lane holds runs of four consecutive features of one token:
-    //   16 x 16 tiles: acc[i][j] is features 16 i + 4 (lane / 16) .. + 3 of token 16 j + lane % 16;
-    //   32 x 32 tiles: registers 4 q .. 4 q + 3 of acc[nt][mt] are features 32 nt + 8 q + 4 half .. + 3 of token 32 mt + l32.
-    constexpr int kTokStep = kFp8 ? 32 : 16;                  // tokens per accumulator tile
-    constexpr int kQuads = kFp8 ? 4 * kNT : kAT;              // runs of four features per token and lane
-    const int tok_lane = kFp8 ? l32 : (lane & 15);
-    auto quad_feature = [&](int q) { return kFp8 ? 32 * (q / 4) + 8 * (q % 4) + 4 * half : 16 * q + 4 * (lane >> 4); };
-    auto quad_value = [&](int q, int t, int e) -> float {
-        if constexpr (kFp8) return acc[q / 4][t][4 * (q % 4) + e];
-        else return acc[q][t][e];
-    };
+    // ---- result.  A lane holds runs of four consecutive features of one token: acc[i][j] is features
+    // 16 i + 4 (lane / 16) .. + 3 of token 16 j + lane % 16.
+    constexpr int kTokStep = 16;
+    constexpr int kQuads = kAT;
+    const int tok_lane = lane & 15;
+    auto quad_feature = [&](int q) { return 16 * q + 4 * (lane >> 4); };
+    auto quad_value = [&](int q, int t, int e) -> float { return acc[q][t][e]; };
     const int f_wave = n0 + wn * (kTile / kWavesN);     // first feature of this wavefront; its features lie in one head
     auto store_rows = [&](uint16_t* dst_row0, size_t row_stride) {   // dst_row0: feature f_wave of token row 0
 #pragma unroll
