@@ -43,7 +43,9 @@ constexpr int kRowBytes = 128;             // bytes of a row per k stage: one ca
 constexpr int kOperandBytes = kTile * kRowBytes;   // 32768
 constexpr int kStage = 2 * kOperandBytes;  // weights, then tokens
 constexpr int kStages = 2;                 // k stages in LDS: one being multiplied, one in flight
-constexpr int kGemmLds = kStages * kStage; // 131072
+constexpr int kStagingPitch = 272;         // bytes between token rows of a wavefront's result staged in LDS (256 + 16)
+constexpr int kStagingWave = (kTile / 2) * kStagingPitch;   // 128 token rows per wavefront
+constexpr int kGemmLds = 4 * kStagingWave > kStages * kStage ? 4 * kStagingWave : kStages * kStage;   // 139264
 constexpr int kWavesN = 2, kWavesM = 2;    // wavefronts along the features / along the tokens
 constexpr int kGemmThreads = 64 * kWavesN * kWavesM;
 constexpr int kWaveRows = kTile / kWavesN;                // rows of either operand that one wavefront multiplies (128)
@@ -408,12 +410,18 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     auto quad_feature = [&](int q) { return 16 * q + 4 * (lane >> 4); };
     auto quad_value = [&](int q, int t, int e) -> float { return acc[q][t][e]; };
     const int f_wave = n0 + wn * (kTile / kWavesN);     // first feature of this wavefront; its features lie in one head
-    auto store_rows = [&](uint16_t* dst_row0, size_t row_stride) {   // dst_row0: feature f_wave of token row 0
+    // The bf16 result goes through LDS (the stage buffers are free by now): a wavefront lays its 128 tokens x 128
+    // features down as rows of 256 bytes (pitch 272: the 8-byte writes of 16 token rows then spread over all banks),
+    // reads them back 16 bytes per lane and stores whole rows - 256 contiguous bytes per token instead of the 8-byte
+    // pieces the accumulator layout would give (those cost 4 % of the kernel).  A wavefront reads only what it wrote
+    // itself, so the workgroup does not meet; what other wavefronts may still be reading there is discarded anyway
+    // (the last stage's look-ahead reads).
+    unsigned char* stg = lds + wave * kStagingWave;
+    auto stage_result = [&]() {
 #pragma unroll
         for (int t = 0; t < kAT; ++t) {
-            const int m = m0 + wm * (kTile / kWavesM) + t * kTokStep + tok_lane;
-            if (m >= p.M_out) continue;
-            uint16_t* row = dst_row0 + static_cast<size_t>(m) * row_stride;
+            const int tok = t * kTokStep + tok_lane;
+            const int m = m0 + wm * kWaveRows + tok;
             float row_scale = 1.f;
             if constexpr (kFp8) row_scale = m < p.M ? p.xs[m] : 0.f;
 #pragma unroll
@@ -424,12 +432,22 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
                 bf16x4 v;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float y = m < p.M ? quad_value(q, t, e) : 0.f;
+                    float y = m < p.M ? quad_value(q, t, e) : 0.f;   // rows M .. M_out - 1 of the result are zeros
                     if constexpr (kFp8) y = y * row_scale * col_scale[e];
                     v[e] = static_cast<__bf16>(y);
                 }
-                *reinterpret_cast<u32x2*>(row + f) = __builtin_bit_cast(u32x2, v);
+                *reinterpret_cast<u32x2*>(stg + tok * kStagingPitch + f * 2) = __builtin_bit_cast(u32x2, v);
             }
+        }
+    };
+    auto store_rows = [&](uint16_t* dst_row0, size_t row_stride) {   // dst_row0: feature f_wave of token row 0
+#pragma unroll 8
+        for (int r = 0; r < kWaveRows / 4; ++r) {
+            const int tok = 4 * r + (lane >> 4);
+            const int m = m0 + wm * kWaveRows + tok;
+            if (m >= p.M_out) continue;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + tok * kStagingPitch + (lane & 15) * 16);
+            *reinterpret_cast<u32x4*>(dst_row0 + static_cast<size_t>(m) * row_stride + (lane & 15) * 8) = v;
         }
     };
     if constexpr (kSplit) {   // this k range's fp32 sums, [split][token][feature]; proj_finish adds the ranges and does the layout
@@ -446,6 +464,7 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
         }
         return;
     }
+    stage_result();
     if (p.mode == 1) {
         store_rows(p.c + f_wave, static_cast<size_t>(p.N));
         return;
