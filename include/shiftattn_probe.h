@@ -7,10 +7,11 @@
  * (a hipStream_t as void*) and returns SHIFTATTN_OK or a negative code of shiftattn.h; the caller
  * times it.  All buffer pointers are device pointers, 16-byte aligned.
  *
- * ceiling_mfma_bf16: every wavefront of a chip-filling grid issues iters x 16 independent
- *   32x32x16 bf16 MFMAs on the operand values found in `operands` (2 KiB = 128 lanes x 8 bf16;
- *   random values give the clock real data gives).  *flops (host) receives the flops of the
- *   launch.  sink: 4 bytes, never written in practice.
+ * ceiling_mfma_bf16: every wavefront of a chip-filling grid issues iters x 32 independent
+ *   16x16x32 bf16 MFMAs (the form that sustains the higher rate at the chip's power limit) on the
+ *   operand values found in `operands` (2 KiB = 128 lanes x 8 bf16; random values give the clock
+ *   real data gives).  *flops (host) receives the flops of the launch.  sink: 4 bytes, never
+ *   written in practice.
  * ceiling_hbm_read: streams `bytes` (rounded down to 16 KiB) of `src` through every wavefront
  *   with 16-byte non-temporal loads.  *bytes_read (host) receives the bytes requested.
  * ceiling_hbm_copy: copies `bytes` (rounded down to 16 KiB) from src to dst with 16-byte

@@ -2,9 +2,11 @@
 // against, under the conditions those kernels run in.  The datasheet peaks (2.5 PFLOP/s dense bf16
 // MFMA, 8 TB/s HBM) assume the top clock and ideal access streams; these two kernels give the rates
 // a benchmark report can put beside them:
-//   * an MFMA-only loop: every SIMD of the chip issues independent 32x32x16 bf16 MFMAs on operands
-//     taken from memory (with random operand values the shader clock settles well below its
-//     maximum, so this is lower than the same loop on constants), and
+//   * an MFMA-only loop: every SIMD of the chip issues independent 16x16x32 bf16 MFMAs on operands
+//     taken from memory.  The chip runs such a loop at its power limit: the shader clock settles well
+//     below its maximum, lower for random operand values than for constants, and lower for the 32x32x16
+//     form (which moves four times the accumulator registers per instruction for twice the work, and
+//     sustains about 13 % less) - so this is the higher of the two rates a kernel can be held against, and
 //   * a streaming read: every wavefront reads 16 KiB pieces of a large buffer with 16-byte
 //     non-temporal loads, one KiB per instruction, the request shape of the decode kernel.
 #include "internal.h"
@@ -14,32 +16,33 @@ namespace shiftattn {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kProbeWorkgroups = 256;  // one per compute unit
 constexpr int kProbeThreads = 512;     // two wavefronts per SIMD
-constexpr int kProbeUnroll = 16;
+constexpr int kProbeUnroll = 32;
+constexpr int kProbeAcc = 16;          // independent accumulators per wavefront
 
 __global__ __launch_bounds__(kProbeThreads) void mfma_ceiling_kernel(const u32x4* __restrict__ operands,
                                                                      float* __restrict__ sink, int iters) {
     const int lane = threadIdx.x & 63;
     const bf16x8 a = __builtin_bit_cast(bf16x8, operands[lane]);
     const bf16x8 b = __builtin_bit_cast(bf16x8, operands[64 + lane]);
-    f32x16 acc[4];
+    f32x4 acc[kProbeAcc];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < kProbeAcc; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+        for (int r = 0; r < 4; ++r) acc[i][r] = 0.f;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int m = 0; m < kProbeUnroll; ++m)
-            acc[m % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[m % 4], 0, 0, 0);
+            acc[m % kProbeAcc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[m % kProbeAcc], 0, 0, 0);
     }
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < kProbeAcc; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s += acc[i][r];
+        for (int r = 0; r < 4; ++r) s += acc[i][r];
     if (s == 12345.678f) sink[0] = s;  // keeps the loop alive; practically never true
 }
 
@@ -106,7 +109,7 @@ hipError_t launch_hbm_copy_ceiling(const void* src, void* dst, size_t bytes, int
 hipError_t launch_mfma_ceiling(const void* operands, void* sink, int iters, int64_t* flops, hipStream_t st) {
     mfma_ceiling_kernel<<<kProbeWorkgroups, kProbeThreads, 0, st>>>(static_cast<const u32x4*>(operands),
                                                                      static_cast<float*>(sink), iters);
-    *flops = static_cast<int64_t>(kProbeWorkgroups) * (kProbeThreads / 64) * iters * kProbeUnroll * (2LL * 32 * 32 * 16);
+    *flops = static_cast<int64_t>(kProbeWorkgroups) * (kProbeThreads / 64) * iters * kProbeUnroll * (2LL * 16 * 16 * 32);
     return hipGetLastError();
 }
 
