@@ -83,6 +83,7 @@ struct GemmParams {
     int mode;
     int k_splits;                     // workgroups that share an output tile, each with a range of k tiles (bf16 only)
     float* __restrict__ partial;      // k_splits > 1: fp32 partial results [k_splits][M_out][N] instead of c
+    int items;                        // work items of the launch: output tiles x k ranges
     XchgShape s;
 };
 
@@ -90,17 +91,22 @@ struct GemmParams {
 // accumulation); the result is multiplied by the token's and the feature's scale before it is rounded to bf16.
 // kSplit: the workgroup covers one of p.k_splits ranges of k and leaves fp32 sums in p.partial (for FP8 operands: before
 // the scales, which the finishing kernel applies)
+// one output tile (and k range): work item `item` of the launch
 template <bool kFp8, bool kSplit>
-__global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
+__device__ __attribute__((always_inline)) void proj_gemm_tile(const GemmParams& p, const int item) {
     constexpr int kElem = kFp8 ? 1 : 2;          // bytes per operand element
     constexpr int kBK = kRowBytes / kElem;       // k per stage
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    // (an opaque copy of the thread index per work item, and another one for the epilogue below: as invariants of the
+    // persistent loop, everything derived from it would be computed once and kept in registers through the main loop)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int wave = tid >> 6, lane = tid & 63;
     const int wn = wave % kWavesN, wm = wave / kWavesN;
     // feature tiles vary fastest: workgroups that run together share the token rows in L2
     const int n_tiles = p.N / kTile;
     const int n_splits = kSplit ? p.k_splits : 1;
-    const int tile_id = blockIdx.x / n_splits, split = blockIdx.x - tile_id * n_splits;
+    const int tile_id = item / n_splits, split = item - tile_id * n_splits;
     const int n0 = (tile_id % n_tiles) * kTile, m0 = (tile_id / n_tiles) * kTile;
     // this workgroup's k stages: [kt0, kt0 + k_steps) of all; with FP8 operands the very last stage may hold 64 k only
     const int kt_all = (p.K + kBK - 1) / kBK;
@@ -404,10 +410,13 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
 
     // ---- result.  A lane holds runs of four consecutive features of one token: acc[i][j] is features
     // 16 i + 4 (lane / 16) .. + 3 of token 16 j + lane % 16.
+    int tid_e = threadIdx.x;
+    asm volatile("" : "+v"(tid_e));
+    const int lane_e = tid_e & 63;
     constexpr int kTokStep = 16;
     constexpr int kQuads = kAT;
-    const int tok_lane = lane & 15;
-    auto quad_feature = [&](int q) { return 16 * q + 4 * (lane >> 4); };
+    const int tok_lane = lane_e & 15;
+    auto quad_feature = [&](int q) { return 16 * q + 4 * (lane_e >> 4); };
     auto quad_value = [&](int q, int t, int e) -> float { return acc[q][t][e]; };
     const int f_wave = n0 + wn * (kTile / kWavesN);     // first feature of this wavefront; its features lie in one head
     // The bf16 result goes through LDS (the stage buffers are free by now): a wavefront lays its 128 tokens x 128
@@ -443,11 +452,11 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     auto store_rows = [&](uint16_t* dst_row0, size_t row_stride) {   // dst_row0: feature f_wave of token row 0
 #pragma unroll 8
         for (int r = 0; r < kWaveRows / 4; ++r) {
-            const int tok = 4 * r + (lane >> 4);
+            const int tok = 4 * r + (lane_e >> 4);
             const int m = m0 + wm * kWaveRows + tok;
             if (m >= p.M_out) continue;
-            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + tok * kStagingPitch + (lane & 15) * 16);
-            *reinterpret_cast<u32x4*>(dst_row0 + static_cast<size_t>(m) * row_stride + (lane & 15) * 8) = v;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + tok * kStagingPitch + (lane_e & 15) * 16);
+            *reinterpret_cast<u32x4*>(dst_row0 + static_cast<size_t>(m) * row_stride + (lane_e & 15) * 8) = v;
         }
     };
     if constexpr (kSplit) {   // this k range's fp32 sums, [split][token][feature]; proj_finish adds the ranges and does the layout
@@ -493,16 +502,37 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
     }
 }
 
+// The grid is persistent: one workgroup per compute unit walks the launch's work items (output tile, k range) with
+// stride gridDim.x, so a compute unit goes from one tile to the next without waiting for a workgroup to be scheduled
+// (ten rounds of tiles at the 70B shape).  Item i runs on the XCD workgroup i % gridDim.x was placed on; with a grid
+// that is a multiple of 8 an XCD keeps seeing neighbouring tiles, which share operand panels through its L2.
+template <bool kFp8, bool kSplit>
+__global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
+    for (int item = blockIdx.x; item < p.items; item += gridDim.x) {
+        proj_gemm_tile<kFp8, kSplit>(p, item);
+        // the next item's loads go where other wavefronts may still be reading their staged result rows
+        __builtin_amdgcn_s_waitcnt(wait_imm(kNoVm, 0));
+        asm volatile("s_barrier" ::: "memory");
+    }
+}
+
 template <bool kFp8>
 hipError_t launch(const GemmParams& p, hipStream_t st) {
-    const int64_t wgs = static_cast<int64_t>(p.N / kTile) * ((p.M_out + kTile - 1) / kTile) * p.k_splits;
-    if (wgs == 0) return hipSuccess;
-    if (wgs > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const int64_t items = static_cast<int64_t>(p.N / kTile) * ((p.M_out + kTile - 1) / kTile) * p.k_splits;
+    if (items == 0) return hipSuccess;
+    if (items > 0x7FFFFFFF) return hipErrorInvalidValue;
+    GemmParams q = p;
+    q.items = static_cast<int>(items);
+    int cus = 0, device = 0;   // one workgroup fits a compute unit (registers, LDS)
+    hipError_t e = hipGetDevice(&device);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
+    if (e != hipSuccess) return e;
+    const unsigned grid = static_cast<unsigned>(items < cus ? items : cus);
     if (p.k_splits > 1) {
-        proj_gemm_kernel<kFp8, true><<<static_cast<unsigned>(wgs), kGemmThreads, kGemmLds, st>>>(p);
+        proj_gemm_kernel<kFp8, true><<<grid, kGemmThreads, kGemmLds, st>>>(q);
         return hipGetLastError();
     }
-    proj_gemm_kernel<kFp8, false><<<static_cast<unsigned>(wgs), kGemmThreads, kGemmLds, st>>>(p);
+    proj_gemm_kernel<kFp8, false><<<grid, kGemmThreads, kGemmLds, st>>>(q);
     return hipGetLastError();
 }
 
