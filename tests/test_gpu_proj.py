@@ -38,6 +38,7 @@ QKV_CASES = [
     (1, 2, 1, 64, 5, 5),           # one k step, one tile
     (2, 8, 4, 1024, 600, 600),     # three token tiles
     (8, 64, 8, 192, 0, 8),         # padding rows only
+    (8, 64, 8, 128, 1800, 1800),   # 320 tiles: more than one per compute unit (the grid walks them), two k stages
 ]
 
 
@@ -59,7 +60,9 @@ def test_qkv_projection_into_send_buffers(oracle, G, P, h, h_kv, d_model, T, T_p
 
 
 @pytest.mark.parametrize("P,hq_l,d_model,T,T_pad", [(8, 4, 512, 300, 304), (4, 10, 256, 257, 260), (1, 2, 256, 5, 5),
-                                                    (2, 4, 768, 600, 600), (8, 8, 256, 0, 4)])
+                                                    (2, 4, 768, 600, 600), (8, 8, 256, 0, 4),
+                                                    # eight tiles, one per XCD: every start of the k walk, most of them inside a source buffer's segment
+                                                    (2, 3, 512, 1024, 1024)])
 def test_o_projection_out_of_receive_buffers(oracle, G, P, hq_l, d_model, T, T_pad):
     import torch
     from paper_2509_16495_amd import binding as B
