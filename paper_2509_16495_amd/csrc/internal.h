@@ -127,7 +127,7 @@ hipError_t launch_qkv_proj_pack(const void* x, const void* w_qkv, void* send, in
 hipError_t launch_unpack_o_proj(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s,
                                 const float* a_scales, const float* w_scales, void* workspace, size_t workspace_bytes,
                                 hipStream_t st);
-// bytes of workspace that let the large-batch kernel split k over workgroups (few output tiles); 0: no split
+// bytes of workspace that let the large-batch kernel split k over workgroups for its last (or only) round of tiles; 0: no split
 size_t proj_gemm_workspace(int M_out, int N, int K, bool fp8);
 // proj_stream.hip : the same two products for up to 64 token rows, organised around one pass over the weights
 size_t proj_stream_workspace(int M_out, int N, int K, bool fp8);
@@ -136,8 +136,10 @@ hipError_t launch_qkv_proj_stream(const void* x, const void* w_qkv, void* send, 
                                   const float* x_scales, const float* w_scales, void* workspace, hipStream_t st);
 hipError_t launch_o_proj_stream(const void* recv, const void* w_o, void* out, int d_model, const XchgShape& s,
                                 const float* a_scales, const float* w_scales, void* workspace, hipStream_t st);
+// (row_base: the partial results start at this token row of the result; rows below it are not touched)
 hipError_t launch_proj_finish(const float* partial, int kg, int t_rows, void* c, int M, int M_out, int N, int mode,
-                              const XchgShape& s, const float* x_scales, const float* w_scales, hipStream_t st);
+                              const XchgShape& s, const float* x_scales, const float* w_scales, hipStream_t st,
+                              int row_base = 0);
 // layout_kernels.hip : rows of bf16 values -> FP8 E4M3 codes + one float32 scale per row (amax / 448).  Element k of
 // row t lies at (k / seg_len) * seg_stride + t * row_stride + k % seg_len, in `x` and in `codes` alike.
 hipError_t launch_quantize_rows_fp8(const void* x, void* codes, float* scales, int rows, int cols, int seg_len,

@@ -84,6 +84,8 @@ struct GemmParams {
     int k_splits;                     // workgroups that share an output tile, each with a range of k tiles (bf16 only)
     float* __restrict__ partial;      // k_splits > 1: fp32 partial results [k_splits][M_out][N] instead of c
     int items;                        // work items of the launch: output tiles x k ranges
+    int m_base;                       // first token row of the launch's tiles (a multiple of the tile height)
+    int m_tiles;                      // token tiles of the launch
     XchgShape s;
 };
 
@@ -107,7 +109,7 @@ __device__ __attribute__((always_inline)) void proj_gemm_tile(const GemmParams& 
     const int n_tiles = p.N / kTile;
     const int n_splits = kSplit ? p.k_splits : 1;
     const int tile_id = item / n_splits, split = item - tile_id * n_splits;
-    const int n0 = (tile_id % n_tiles) * kTile, m0 = (tile_id / n_tiles) * kTile;
+    const int n0 = (tile_id % n_tiles) * kTile, m0 = p.m_base + (tile_id / n_tiles) * kTile;
     // this workgroup's k stages: [kt0, kt0 + k_steps) of all; with FP8 operands the very last stage may hold 64 k only
     const int kt_all = (p.K + kBK - 1) / kBK;
     const int kt0 = kSplit ? static_cast<int>(static_cast<int64_t>(kt_all) * split / n_splits) : 0;
@@ -460,12 +462,12 @@ __device__ __attribute__((always_inline)) void proj_gemm_tile(const GemmParams& 
         }
     };
     if constexpr (kSplit) {   // this k range's fp32 sums, [split][token][feature]; proj_finish adds the ranges and does the layout
-        float* base = p.partial + static_cast<size_t>(split) * p.M_out * p.N + f_wave;
+        float* base = p.partial + static_cast<size_t>(split) * (p.M_out - p.m_base) * p.N + f_wave;   // [split][row - m_base][feature]
 #pragma unroll
         for (int t = 0; t < kAT; ++t) {
             const int m = m0 + wm * (kTile / kWavesM) + t * kTokStep + tok_lane;
             if (m >= p.M) continue;   // rows past the last token are zeros in the result and are not read
-            float* row = base + static_cast<size_t>(m) * p.N;
+            float* row = base + static_cast<size_t>(m - p.m_base) * p.N;
 #pragma unroll
             for (int q = 0; q < kQuads; ++q)
                 *reinterpret_cast<f32x4*>(row + quad_feature(q)) =
@@ -518,7 +520,7 @@ __global__ __launch_bounds__(kGemmThreads) void proj_gemm_kernel(GemmParams p) {
 
 template <bool kFp8>
 hipError_t launch(const GemmParams& p, hipStream_t st) {
-    const int64_t items = static_cast<int64_t>(p.N / kTile) * ((p.M_out + kTile - 1) / kTile) * p.k_splits;
+    const int64_t items = static_cast<int64_t>(p.N / kTile) * p.m_tiles * p.k_splits;
     if (items == 0) return hipSuccess;
     if (items > 0x7FFFFFFF) return hipErrorInvalidValue;
     GemmParams q = p;
@@ -536,29 +538,36 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
     return hipGetLastError();
 }
 
-// Few output tiles (up to about a thousand token rows): k is split over workgroups when a rough model of the launch
-// says so - a workgroup walks its k range at about 6.5 TFLOP/s (12.5 over FP8 operands), workgroups beyond one per compute unit queue up in
-// rounds, and every range adds fp32 partial results that are written and read back.  Ranges are at least 16 k tiles
-// long.  1: no split (enough tiles or a short k).
-int k_splits_for(int M_out, int N, int K, bool fp8) {
-    const int64_t tiles = static_cast<int64_t>(N / kTile) * ((M_out + kTile - 1) / kTile);
-    if (tiles == 0 || tiles >= 512) return 1;
+// How a product is laid over the 256 compute units.  The grid walks whole output tiles; when their number is no
+// multiple of 256 (or below it) the last round would leave most of the chip idle, so the trailing token tiles can
+// instead be split over k: `unsplit_tiles` leading token tiles (256 rows each) are done whole, the rest in `splits`
+// ranges of k whose fp32 sums go to the caller's workspace and are added by the finishing kernel.  Chosen by a rough
+// model of the launches - a workgroup walks all of k of a tile at about 6.5 TFLOP/s (12.5 over FP8 operands),
+// work items beyond one per compute unit queue up in rounds, every range adds fp32 partial results that are written and
+// read back.  Ranges are at least 8 k stages long.  splits == 1: everything whole.
+struct GemmPlan {
+    int unsplit_tiles, splits;
+};
+GemmPlan plan_gemm(int M_out, int N, int K, bool fp8) {
+    const int n_tiles = N / kTile, m_tiles = (M_out + kTile - 1) / kTile;
+    GemmPlan best = {m_tiles, 1};
+    if (n_tiles == 0 || m_tiles == 0) return best;
     const double walk = 2.0 * kTile * kTile * static_cast<double>(K) / (fp8 ? 12.5e12 : 6.5e12);   // one workgroup over all of k
-    const double partial = 2.0 * M_out * static_cast<double>(N) * sizeof(float) / 4.0e12;
-    auto model = [&](int sp) {
-        const double load = static_cast<double>(tiles) * sp / 256.0;
-        const double whole = static_cast<double>(static_cast<long>(load + 0.999999));
-        const double rounds = load <= 1.0 ? 1.0 : (whole < load + 0.5 ? whole : load + 0.5);
-        return rounds / sp * walk + (sp > 1 ? sp * partial + 5.0e-6 : 0.0);
-    };
+    auto rounds = [](int64_t items) { return static_cast<double>((items + 255) / 256); };
     const int by_length = K / (fp8 ? 64 : 32) / 16;
-    int best = 1;
-    double t_best = model(1);
-    for (int sp = 2; sp <= 16 && sp <= by_length; ++sp) {
-        const double t = model(sp);
-        if (t < 0.97 * t_best) {
-            t_best = t;
-            best = sp;
+    double t_best = rounds(static_cast<int64_t>(n_tiles) * m_tiles) * walk;
+    const double t_whole = t_best;
+    for (int ma = 0; ma < m_tiles; ++ma) {
+        const int64_t tiles_b = static_cast<int64_t>(n_tiles) * (m_tiles - ma);
+        const double rows_b = static_cast<double>(M_out - ma * kTile);
+        const double partial = 2.0 * rows_b * N * sizeof(float) / 3.2e12;   // written once, read once
+        const double t_a = ma > 0 ? rounds(static_cast<int64_t>(n_tiles) * ma) * walk + 3.0e-6 : 0.0;
+        for (int sp = 2; sp <= 16 && sp <= by_length; ++sp) {
+            const double t = t_a + rounds(tiles_b * sp) / sp * walk + sp * partial + 5.0e-6;
+            if (t < t_best && t < 0.97 * t_whole) {
+                t_best = t;
+                best = {ma, sp};
+            }
         }
     }
     return best;
@@ -589,22 +598,34 @@ bool unpack_o_proj_supported(const XchgShape& s, int d_model, int elem) {
 }
 
 size_t proj_gemm_workspace(int M_out, int N, int K, bool fp8) {
-    const int sp = k_splits_for(M_out, N, K, fp8);
-    return sp == 1 ? 0 : static_cast<size_t>(sp) * M_out * N * sizeof(float);
+    const GemmPlan pl = plan_gemm(M_out, N, K, fp8);
+    return pl.splits == 1 ? 0 : static_cast<size_t>(pl.splits) * (M_out - pl.unsplit_tiles * kTile) * N * sizeof(float);
 }
 
-// runs the product with its k split when that pays and the workspace holds the partial results
+// runs the product as planned when the workspace holds the partial results, else in whole tiles
 static hipError_t run_gemm(GemmParams& p, void* workspace, size_t workspace_bytes, hipStream_t st) {
+    const bool fp8 = p.xs != nullptr;
+    const int m_tiles = (p.M_out + kTile - 1) / kTile;
     p.k_splits = 1;
     p.partial = nullptr;
-    const bool fp8 = p.xs != nullptr;
+    p.m_base = 0;
+    p.m_tiles = m_tiles;
+    const GemmPlan pl = plan_gemm(p.M_out, p.N, p.K, fp8);
     const size_t need = proj_gemm_workspace(p.M_out, p.N, p.K, fp8);
     if (need == 0 || need > workspace_bytes || !workspace) return fp8 ? launch<true>(p, st) : launch<false>(p, st);
-    p.k_splits = k_splits_for(p.M_out, p.N, p.K, fp8);
+    if (pl.unsplit_tiles > 0) {
+        p.m_tiles = pl.unsplit_tiles;
+        const hipError_t e = fp8 ? launch<true>(p, st) : launch<false>(p, st);
+        if (e != hipSuccess) return e;
+    }
+    p.m_base = pl.unsplit_tiles * kTile;
+    p.m_tiles = m_tiles - pl.unsplit_tiles;
+    p.k_splits = pl.splits;
     p.partial = static_cast<float*>(workspace);
     const hipError_t e = fp8 ? launch<true>(p, st) : launch<false>(p, st);
     if (e != hipSuccess) return e;
-    return launch_proj_finish(p.partial, p.k_splits, p.M_out, p.c, p.M, p.M_out, p.N, p.mode, p.s, p.xs, p.ws, st);
+    return launch_proj_finish(p.partial, p.k_splits, p.M_out - p.m_base, p.c, p.M, p.M_out, p.N, p.mode, p.s, p.xs, p.ws, st,
+                              p.m_base);
 }
 
 hipError_t launch_qkv_proj_pack(const void* x, const void* w_qkv, void* send, int d_model, const XchgShape& s,

@@ -305,16 +305,18 @@ __global__ __launch_bounds__(kSThreads) void proj_stream_kernel(StreamParams p) 
 }
 
 // kg > 1: result[t][f .. f + 3] = sum over the k groups in group order, rounded once
-__global__ __launch_bounds__(256) void proj_stream_finish_kernel(StreamParams p, int t_rows) {
+// (row_base: partial row r is row row_base + r of the result)
+__global__ __launch_bounds__(256) void proj_stream_finish_kernel(StreamParams p, int t_rows, int row_base) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     const int quads = p.N / 4;
-    if (i >= static_cast<int64_t>(p.M_out) * quads) return;
-    const int t = static_cast<int>(i / quads), f = static_cast<int>(i % quads) * 4;
+    if (i >= static_cast<int64_t>(p.M_out - row_base) * quads) return;
+    const int r = static_cast<int>(i / quads), f = static_cast<int>(i % quads) * 4;
+    const int t = row_base + r;
     f32x4 sum = {0.f, 0.f, 0.f, 0.f};
     if (t < p.M) {
-        sum = *reinterpret_cast<const f32x4*>(p.partial + static_cast<size_t>(t) * p.N + f);
+        sum = *reinterpret_cast<const f32x4*>(p.partial + static_cast<size_t>(r) * p.N + f);
         for (int c = 1; c < p.kg; ++c) {
-            const f32x4 v = *reinterpret_cast<const f32x4*>(p.partial + (static_cast<size_t>(c) * t_rows + t) * p.N + f);
+            const f32x4 v = *reinterpret_cast<const f32x4*>(p.partial + (static_cast<size_t>(c) * t_rows + r) * p.N + f);
 #pragma unroll
             for (int e = 0; e < 4; ++e) sum[e] += v[e];
         }
@@ -393,7 +395,7 @@ hipError_t run_stream(StreamParams p, const StreamPlan& pl, void* workspace, hip
 
 // result = sum over kg partial results [kg][t_rows][N] (fp32) in group order, rounded once, stored with the layout of `mode`
 hipError_t launch_proj_finish(const float* partial, int kg, int t_rows, void* c, int M, int M_out, int N, int mode,
-                              const XchgShape& s, const float* x_scales, const float* w_scales, hipStream_t st) {
+                              const XchgShape& s, const float* x_scales, const float* w_scales, hipStream_t st, int row_base) {
     StreamParams p = {};
     p.xs = x_scales;
     p.ws = w_scales;
@@ -405,9 +407,9 @@ hipError_t launch_proj_finish(const float* partial, int kg, int t_rows, void* c,
     p.mode = mode;
     p.kg = kg;
     p.s = s;
-    const int64_t items = static_cast<int64_t>(M_out) * (N / 4);
-    if (items == 0) return hipSuccess;
-    proj_stream_finish_kernel<<<static_cast<unsigned>((items + 255) / 256), 256, 0, st>>>(p, t_rows);
+    const int64_t items = static_cast<int64_t>(M_out - row_base) * (N / 4);
+    if (items <= 0) return hipSuccess;
+    proj_stream_finish_kernel<<<static_cast<unsigned>((items + 255) / 256), 256, 0, st>>>(p, t_rows, row_base);
     return hipGetLastError();
 }
 

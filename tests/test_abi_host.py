@@ -91,6 +91,8 @@ def test_launch_plans_follow_the_shape_of_the_batch(B):
     assert [B.proj_workspace_bytes(t, n, k) // (n * 4) for t in (1, 16, 17, 32, 33, 64)] == [0, 0, 2 * 32, 2 * 32, 4 * 64, 4 * 64]
     assert B.proj_workspace_bytes(65, n, k) == 6 * 65 * n * 4 and B.proj_workspace_bytes(512, n, k) == 3 * 512 * n * 4
     assert B.proj_workspace_bytes(1024, n, k) == 0 and B.proj_workspace_bytes(16384, n, k) == 0
+    # 2048 rows are 320 tiles: six token tiles whole (240 tiles), the last 512 rows in three k ranges (240 work items)
+    assert B.proj_workspace_bytes(2048, n, k) == 3 * 512 * n * 4
     assert B.proj_workspace_bytes(8, 6144, 4096) == 0 and B.proj_workspace_bytes(0, n, k) == 0
 
 

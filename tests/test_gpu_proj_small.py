@@ -127,7 +127,9 @@ def test_projection_workspace_sizes_and_a_short_workspace():
     assert B.proj_workspace_bytes(17, 10240, 8192) == 2 * 32 * 10240 * 4
     assert B.proj_workspace_bytes(64, 10240, 8192) == 4 * 64 * 10240 * 4
     assert B.proj_workspace_bytes(65, 10240, 8192) == 6 * 65 * 10240 * 4       # 40 output tiles: six k ranges each
-    assert B.proj_workspace_bytes(256, 8192, 8192) == 5 * 256 * 8192 * 4
+    assert B.proj_workspace_bytes(256, 8192, 8192) == 6 * 256 * 8192 * 4
+    assert B.proj_workspace_bytes(2048, 10240, 8192) == 3 * 512 * 10240 * 4    # 320 tiles: 240 whole, the last 512 rows in three k ranges
+    assert B.proj_workspace_bytes(2048, 8192, 8192) == 0                       # 256 tiles: one round of the chip
     assert B.proj_workspace_bytes(16384, 10240, 8192) == 0                     # enough tiles without a split
     assert B.proj_workspace_bytes(64, 6144, 4096) == 2 * 64 * 6144 * 4
     assert B.proj_workspace_bytes(8, 10240, 5120) == 6 * 8 * 10240 * 4          # not served by the streaming kernel: split large-batch kernel
