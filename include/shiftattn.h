@@ -159,8 +159,9 @@ int shiftattn_unpack_o_proj(const void *recv, const void *w_o, void *out, int32_
 /* ---- The same two projections with a workspace (Algorithm 2: the few-token steps below the threshold) ----
  * With up to 64 token rows (T_pad for qkv_proj_pack, T for unpack_o_proj) the product is one pass over the
  * weight matrix; from 17 rows on (at d_model = 8192) that pass is split over k between workgroups.  With a few
- * hundred rows the large-batch kernel has too few output tiles to fill the chip and splits k as well.  Either
- * way the fp32 partial results need device memory:
+ * hundred rows the large-batch kernel has too few output tiles to fill the chip and splits k as well, and with
+ * a few thousand (a prefill chunk) it does so for the last token rows when the tiles are no multiple of the
+ * chip's compute units.  Either way the fp32 partial results need device memory:
  *   shiftattn_proj_workspace_bytes(rows, n_features, k): bytes for a product of `rows` token rows with a
  *     [n_features][k] weight matrix (qkv: n_features = (h + 2 h_kv) * D, k = d_model; o: n_features =
  *     d_model, k = h * D); 0 when none is needed.
