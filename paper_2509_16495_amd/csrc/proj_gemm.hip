@@ -15,7 +15,7 @@
 // token (8-byte stores).  k advances in stages of 128 bytes per row (64 bf16 or 128 FP8 elements: whole cache lines),
 // two stage buffers of 64 KiB in LDS filled by direct-to-LDS loads of 1 KiB (eight rows); a row keeps its eight
 // 16-byte pieces at positions piece ^ ((row / 2) % 8), which makes the operand reads (16 or 32 consecutive rows, one
-// piece column) conflict-free.  One barrier per stage.  bf16: v_mfma_f32_16x16x32_bf16; FP8: the 32x32x64 scaled form.
+// piece column) conflict-free.  One barrier per stage.  bf16: v_mfma_f32_16x16x32_bf16; FP8: v_mfma_scale_f32_16x16x128_f8f6f4.
 // What the main loop is built around (all measured on this kernel):
 //   * the chip runs these kernels at its power limit: the clock settles where MFMA rate x energy per MFMA fits, so
 //     the 16x16x32 form (less accumulator traffic per flop) sustains about 15 % more than 32x32x16;
@@ -81,19 +81,18 @@ struct GemmParams {
     // mode 0 (qkv_proj_pack): x dense [M][K]; result columns scattered to send buffers (XchgShape below)
     // mode 1 (unpack_o_proj): x gathered from recv [P][T_pad][hq_l][128] (k = (p hq_l + j) 128 + e); result dense [M][N]
     int mode;
-    int k_splits;                     // workgroups that share an output tile, each with a range of k tiles (bf16 only)
-    float* __restrict__ partial;      // k_splits > 1: fp32 partial results [k_splits][M_out][N] instead of c
+    int k_splits;                     // workgroups that share an output tile, each with a range of k stages
+    float* __restrict__ partial;      // k_splits > 1: fp32 partial results [k_splits][M_out - m_base][N] instead of c
     int items;                        // work items of the launch: output tiles x k ranges
     int m_base;                       // first token row of the launch's tiles (a multiple of the tile height)
     int m_tiles;                      // token tiles of the launch
     XchgShape s;
 };
 
-// kFp8: both operands are FP8 E4M3 codes (v_mfma_scale_f32_32x32x64_f8f6f4 with unit block scales, fp32
+// kFp8: both operands are FP8 E4M3 codes (v_mfma_scale_f32_16x16x128_f8f6f4 with unit block scales, fp32
 // accumulation); the result is multiplied by the token's and the feature's scale before it is rounded to bf16.
 // kSplit: the workgroup covers one of p.k_splits ranges of k and leaves fp32 sums in p.partial (for FP8 operands: before
-// the scales, which the finishing kernel applies)
-// one output tile (and k range): work item `item` of the launch
+// the scales, which the finishing kernel applies).  One call is one output tile (and k range): work item `item` of the launch.
 template <bool kFp8, bool kSplit>
 __device__ __attribute__((always_inline)) void proj_gemm_tile(const GemmParams& p, const int item) {
     constexpr int kElem = kFp8 ? 1 : 2;          // bytes per operand element
