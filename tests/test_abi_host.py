@@ -94,6 +94,20 @@ def test_launch_plans_follow_the_shape_of_the_batch(B):
     # 2048 rows are 320 tiles: six token tiles whole (240 tiles), the last 512 rows in three k ranges (240 work items)
     assert B.proj_workspace_bytes(2048, n, k) == 3 * 512 * n * 4
     assert B.proj_workspace_bytes(8, 6144, 4096) == 0 and B.proj_workspace_bytes(0, n, k) == 0
+    # whatever the plan, the workspace is whole fp32 rows of the result: at most 16 ranges of at most all rows, rows of
+    # whole leading tiles excluded in steps of 256, and nothing when the tiles are a whole number of rounds of the chip
+    for feats, kk in ((10240, 8192), (8192, 8192), (6144, 4096), (2560, 5120), (256, 64)):
+        for rows in (65, 100, 255, 256, 257, 511, 777, 1024, 1500, 2048, 2300, 4096, 5000, 8192, 16384, 20000):
+            for fp8 in (False, True):
+                need = B.proj_workspace_bytes(rows, feats, kk, fp8=fp8)
+                assert need % (feats * 4) == 0
+                q = need // (feats * 4)   # ranges x rows they cover
+                assert q <= 16 * rows
+                if q:
+                    covered = [r for r in range(rows, 0, -256) if q % r == 0 and 2 <= q // r <= 16]
+                    assert covered, (rows, feats, kk, q)
+                if (feats // 256) * (-(-rows // 256)) % 256 == 0:
+                    assert need == 0, (rows, feats, kk)
 
 
 def test_struct_layouts_match_header(B):
