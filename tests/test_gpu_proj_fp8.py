@@ -101,6 +101,7 @@ QKV_CASES = [
     (8, 8, 8, 4096, 40, 40),       # four token blocks: two k groups with a workspace, the large-batch kernel without
     (4, 40, 8, 1024, 5, 8),        # 28 features per workgroup, one step per wavefront
     (8, 32, 4, 2048, 3, 4),        # replication into several send buffers
+    (2, 4, 2, 2112, 100, 100),     # k split over two workgroups with a half-filled last stage in the second range
 ]
 
 
