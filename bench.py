@@ -433,6 +433,13 @@ def main() -> int:
         result["decode_kv_read_fp8"]["replayed_from_graph"] = {"ms": round(ms_g, 5), "GB/s": round(c4.kv_bytes() / 2 / (ms_g * 1e-3) / 1e9, 1),
                                                                "frac": round(c4.kv_bytes() / 2 / (ms_g * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4)}
         log(f"[bench] decode cfg4, FP8 cache: {ms * 1e3:.1f} us, {gbps:.0f} GB/s of KV ({gbps / PEAK_HBM_GBPS:.1%} of HBM peak); replayed from a graph {ms_g * 1e3:.1f} us")
+        if cpu:
+            sub = W.sub_case(c4, range(0, c4.num_seqs, 8))
+            t0 = time.perf_counter()
+            O.attention_case(sub, O.cache_for_case(sub, fp8_scales=(k_scale, v_scale)), k_scale=k_scale, v_scale=v_scale)
+            dt = time.perf_counter() - t0
+            result["decode_kv_read_fp8"]["cpu_baseline"] = cpu_obj(dt, sub.kv_bytes() / 2 / 1e9, "GB/s",
+                                                                   "every 8th sequence of the batch (32 of 256), all heads, cache build included")
         del cache4, cache4q, w4
 
         # ---- small decode batches (the shift configuration's regime, Algorithm 2: few tokens per step) ----------------
@@ -532,6 +539,21 @@ def main() -> int:
                           "roofline": roof("proj_gemm_kernel", "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s", traffic_key=nm + "_70b")}
             log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%} of bf16 MFMA peak); "
                 f"library GEMM + separate layout kernel {ms_ref * 1e3:.1f} us")
+        n_cpu_rows = 2048   # token rows of these products that the oracle is timed on
+        if cpu:
+            x_h, wq_h, wo_h = B.to_host(xe[:n_cpu_rows]), B.to_host(wq), B.to_host(wo)
+            recv_h = B.to_host(recv3[:, :n_cpu_rows].contiguous())
+            t0 = time.perf_counter()
+            O.qkv_proj_pack(x_h, wq_h, x3.P, h3, hkv3, D, n_cpu_rows, "bf16")
+            dt = time.perf_counter() - t0
+            result["qkv_proj_pack"]["cpu_baseline"] = cpu_obj(dt, 2.0 * n_cpu_rows * d_model * wq.shape[0] / 1e12, "TFLOP/s",
+                                                              f"the first {n_cpu_rows} token rows, all features")
+            t0 = time.perf_counter()
+            O.unpack_o_proj(recv_h, wo_h, n_cpu_rows, "bf16")
+            dt = time.perf_counter() - t0
+            result["unpack_o_proj"]["cpu_baseline"] = cpu_obj(dt, 2.0 * n_cpu_rows * d_model * h3 * D / 1e12, "TFLOP/s",
+                                                              f"the first {n_cpu_rows} token rows, all features")
+            del x_h, recv_h
         xq, xsc = torch.empty(xe.shape, dtype=torch.uint8, device=dev), torch.empty(x3.T, dtype=torch.float32, device=dev)
         wq8, wsc = torch.empty(wq.shape, dtype=torch.uint8, device=dev), torch.empty(wq.shape[0], dtype=torch.float32, device=dev)
         rq, rsc = torch.empty(recv3.shape, dtype=torch.uint8, device=dev), torch.empty(x3.T, dtype=torch.float32, device=dev)
@@ -556,6 +578,21 @@ def main() -> int:
                           "roofline": roof("proj_gemm_kernel<fp8>", "mfma", tf, PEAK_FP8_TFLOPS, "TFLOP/s", traffic_key=nm + "_70b")}
             log(f"[bench] {nm} cfg3: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_FP8_TFLOPS:.1%} of the fp8 MFMA peak); "
                 f"quantising the activations {ms_q * 1e3:.1f} us ({q_bytes / (ms_q * 1e-3) / 1e9:.0f} GB/s)")
+        if cpu:
+            xq_h, xsc_h = B.to_host(xq[:n_cpu_rows]), B.to_host(xsc[:n_cpu_rows])
+            rq_h, rsc_h = B.to_host(rq[:, :n_cpu_rows].contiguous()), B.to_host(rsc[:n_cpu_rows])
+            wq8_h, wsc_h, wo8_h, wosc_h = B.to_host(wq8), B.to_host(wsc), B.to_host(wo8), B.to_host(wosc)
+            t0 = time.perf_counter()
+            O.qkv_proj_pack_fp8(xq_h, xsc_h, wq8_h, wsc_h, x3.P, h3, hkv3, D, n_cpu_rows)
+            dt = time.perf_counter() - t0
+            result["qkv_proj_pack_fp8"]["cpu_baseline"] = cpu_obj(dt, 2.0 * n_cpu_rows * d_model * wq.shape[0] / 1e12, "TFLOP/s",
+                                                                  f"the first {n_cpu_rows} token rows, all features")
+            t0 = time.perf_counter()
+            O.unpack_o_proj_fp8(rq_h, rsc_h, wo8_h, wosc_h, n_cpu_rows)
+            dt = time.perf_counter() - t0
+            result["unpack_o_proj_fp8"]["cpu_baseline"] = cpu_obj(dt, 2.0 * n_cpu_rows * d_model * h3 * D / 1e12, "TFLOP/s",
+                                                                  f"the first {n_cpu_rows} token rows, all features")
+            del xq_h, rq_h, wq8_h, wo8_h
 
         # ---- the same projections at the token counts of a decode step (Algorithm 2: below the threshold) ---------
         # three copies of each weight matrix in rotation (504 / 403 MB), so that no pass is served from the 256 MB cache in
