@@ -19,13 +19,16 @@
 // with bits 2 and 3 of the K row index swapped in the MFMA row assignment, so that the keys a lane holds are runs
 // of eight consecutive tokens (one 16-byte piece of a dimension-major V row).
 //
-// Softmax against the maximum of the tiles before.  The exponentials of a tile are taken against the column's
-// reference maximum as it stood when the tile began, so they do not wait for the tile's own maximum and spread
-// evenly over the MFMA slots; the tile's maximum is collected on the side.  If it exceeds the reference by more
-// than 2^8 (in exp2 units) for any column of the wavefront - the first tile of a pass, and rarely after - the
-// wavefront takes a slow path at the end of the tile: new reference, O and the running sum rescaled, the tile's
-// P recomputed from the S^T values it still holds.  P thus never exceeds 2^8, which bf16 and the fp32 sums hold
-// without loss.
+// Softmax against a reference that lags.  The exponentials of a tile are taken against the column's reference maximum
+// as it stood when the tile began, so they do not wait for the tile's own maximum and spread evenly over the MFMA
+// slots.  The first attempt at a pass takes the reference from the column's first visible key tile and then follows
+// no maximum at all in its steady-state iterations (one vector instruction per two logits less): softmax does not
+// care which reference it is shifted by as long as nothing overflows, real logits stay within 2^100 of their first
+// tile's maximum, and P up to 2^100 is held by bf16 and the fp32 sums without loss.  A running sum that leaves that
+// range flags the pass; it is then run again with the tile's maximum collected on the side and checked against the
+// reference (slack 2^32): a column that has no sums yet takes a new reference and recomputes the tile's P from the
+// S^T values it still holds, one that has sums flags the pass once more, and the third attempt starts from references
+// within the slack of every column's true maximum.  O^T is never rescaled inside the loop.
 //
 // Pipeline of iteration j: S^T of tile j+1 (16 MFMAs), softmax of tile j, O^T += V^T P^T of tile j-1 (16 MFMAs).
 // LDS holds a ring of three stages of K (32 keys) + V^T (32 keys), tile t in stage t%3.  During iteration j
@@ -69,6 +72,12 @@ constexpr int kLdsBytes = kRingBytes + kCols * kPitch + kFlagBytes;  // 118800
 // inside what bf16 and the fp32 sums hold (their relative precision does not depend on magnitude); O^T overflows only
 // for |V| beyond 2^70.
 constexpr float kRefSlack = 32.0f;
+// The first attempt at a pass does not follow the maximum at all behind its first key tile (see prefill64_kernel): a
+// column's reference is the maximum of its first visible tile, P may then reach 2^kLazySlack (still far inside bf16 and
+// fp32 range; O^T overflows only for |V| beyond 2^27), and a running sum beyond that bound sends the pass to the
+// attempts that do follow the maximum.
+constexpr float kLazySlack = 100.0f;
+constexpr float kLazySumBound = 0x1p100f;
 
 __device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -228,7 +237,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             :: "s"(m0v), "v"(off[0]), "v"(off[1]), "v"(off[2]), "v"(off[3]), "s"(src) : "memory");
     };
 
-    const float thr = kRefSlack / p.c;
+    const float thr_tracked = kRefSlack / p.c, thr_lazy = kLazySlack / p.c;
 
     for (int pass = 0; pass < n_pass; ++pass) {
         const int tile = pass == 0 ? hi_tile : rank;
@@ -299,6 +308,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         // the reference covers (reference + slack), running sum
         float m_used[2] = {-INFINITY, -INFINITY}, mc[2] = {0.f, 0.f}, bound[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
         bool redo = false;          // uniform: a column of this wavefront needed a rescaling the key loop does not do
+        float thr = thr_lazy;       // how far a logit may exceed the reference (of the current attempt)
 
         // Ring of three LDS stages: K of tile t and V^T of tile t live in stage t % 3.  Iteration j reads K of tile
         // j + 1 and V^T of tile j - 1 and loads K of tile j + 3 and V^T of tile j + 1, so everything an iteration reads
@@ -334,8 +344,11 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         };
 
         // One iteration on tile j.  PAR = parity of j: selects the register sets at compile time.
-        auto body = [&](auto par_c, auto has_a_c, auto has_c_c, auto guard_c, int j) SHIFTATTN_INLINE {
+        // TRACK: the tile's maximum is collected and checked against the reference (off only in the steady-state bodies
+        // of a pass's first attempt, which check the running sums instead)
+        auto body = [&](auto par_c, auto has_a_c, auto has_c_c, auto guard_c, auto track_c, int j) SHIFTATTN_INLINE {
             constexpr int PAR = decltype(par_c)::value;
+            constexpr bool TRACK = decltype(track_c)::value != 0;
             constexpr bool GUARD = decltype(guard_c)::value != 0;  // outside the steady-state loop
             constexpr bool HAS_A = decltype(has_a_c)::value != 0;
             constexpr bool HAS_C = decltype(has_c_c)::value != 0;
@@ -409,6 +422,8 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
                     t[0] = static_cast<__bf16>(e_last2);
                     t[1] = static_cast<__bf16>(e_last);
                     p_cur[cb][r >> 3][(r & 7) >> 1] = __builtin_bit_cast(uint32_t, t);
+                    // (pinned to this slot: left free, the packing drifts together and the slots lose their balance)
+                    if constexpr (!TRACK) asm volatile("" : "+v"(p_cur[cb][r >> 3]));
                 }
             };
             auto chunk = [&](auto vc) SHIFTATTN_INLINE {
@@ -416,7 +431,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
                 constexpr int cb = v / 16, r = v % 16;
                 const float e = __builtin_amdgcn_exp2f(fmaf(s_cur[cb][r], p.c, -mc[cb]));
                 if constexpr (v >= 1) finish_prev(IC<v>{});
-                if constexpr (r % 2 == 1) {
+                if constexpr (TRACK && r % 2 == 1) {
                     mx[cb] = fmaxf(fmaxf(mx[cb], s_cur[cb][r - 1]), s_cur[cb][r]);
                     asm volatile("" : "+v"(mx[cb]));
                 }
@@ -491,6 +506,10 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             }
 
             // ---- the tile's maximum against what the reference covers: rarely, a new reference ------------------
+            if constexpr (!TRACK) {
+                // no maximum was taken: a sum that has left the range the reference was meant to keep it in flags the pass
+                if (__builtin_expect(__builtin_amdgcn_ballot_w64(l_run[0] > kLazySumBound || l_run[1] > kLazySumBound) != 0, 0)) redo = true;
+            } else
             if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx[0] > bound[0] || mx[1] > bound[1]) != 0, 0)) {
                 // A column that meets its first visible keys has no sums yet (O^T = 0, l = 0): its reference is set and
                 // the tile's P recomputed, nothing else.  A column that already holds sums would need them rescaled;
@@ -532,11 +551,20 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             st2 = st_new;
         };
 
-        // Second attempt only if some wavefront flagged the first (see the end of an iteration): it starts from the
-        // reference the first ended with, which is within the slack of every column's true maximum, so nothing is
-        // flagged again.
-        for (int attempt = 0; attempt < 2; ++attempt) {
+        // Up to three attempts at the pass.  The first follows no maximum behind the first key tile (its steady-state
+        // bodies save the instruction per two logits that would collect it; real logits stay within 2^100 of their
+        // first tile's maximum).  If some wavefront flags it (see the end of an iteration), the second starts over and
+        // follows the maximum tile by tile; it can end flagged itself (a column outgrew its reference after it had sums),
+        // and then holds, for every column, a reference within the slack of the true maximum: the third attempt starts
+        // from that and is not flagged.
+        for (int attempt = 0; attempt < 3; ++attempt) {
         redo = false;
+        const bool lazy = attempt == 0;
+        thr = lazy ? thr_lazy : thr_tracked;
+        if (attempt == 1) {   // forget the first attempt's references
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) m_used[cb] = -INFINITY, mc[cb] = 0.f, bound[cb] = -INFINITY;
+        }
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
             l_run[cb] = 0.f;
@@ -575,20 +603,27 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             k_cur[0] += kStageBytes;  // on to stage 2: iteration 1's first K operand
             mfma_settle();
             if (n == 1) {
-                body(IC<0>{}, IC<0>{}, IC<0>{}, IC<1>{}, 0);
+                body(IC<0>{}, IC<0>{}, IC<0>{}, IC<1>{}, IC<1>{}, 0);
             } else {
-                body(IC<0>{}, IC<1>{}, IC<0>{}, IC<1>{}, 0);
+                body(IC<0>{}, IC<1>{}, IC<0>{}, IC<1>{}, IC<1>{}, 0);
                 int j = 1;  // stays odd: the steady-state loop takes two tiles per trip so that the register sets of
                             // even and odd tiles are fixed at compile time
-                for (; j + 2 < n; j += 2) {
-                    body(IC<1>{}, IC<1>{}, IC<1>{}, IC<0>{}, j);
-                    body(IC<0>{}, IC<1>{}, IC<1>{}, IC<0>{}, j + 1);
+                if (lazy) {
+                    for (; j + 2 < n; j += 2) {
+                        body(IC<1>{}, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{}, j);
+                        body(IC<0>{}, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{}, j + 1);
+                    }
+                } else {
+                    for (; j + 2 < n; j += 2) {
+                        body(IC<1>{}, IC<1>{}, IC<1>{}, IC<0>{}, IC<1>{}, j);
+                        body(IC<0>{}, IC<1>{}, IC<1>{}, IC<0>{}, IC<1>{}, j + 1);
+                    }
                 }
                 if (j + 1 < n) {
-                    body(IC<1>{}, IC<1>{}, IC<1>{}, IC<1>{}, j);
-                    body(IC<0>{}, IC<0>{}, IC<1>{}, IC<1>{}, j + 1);
+                    body(IC<1>{}, IC<1>{}, IC<1>{}, IC<1>{}, IC<1>{}, j);
+                    body(IC<0>{}, IC<0>{}, IC<1>{}, IC<1>{}, IC<1>{}, j + 1);
                 } else {
-                    body(IC<1>{}, IC<0>{}, IC<1>{}, IC<1>{}, j);
+                    body(IC<1>{}, IC<0>{}, IC<1>{}, IC<1>{}, IC<1>{}, j);
                 }
             }
             // epilogue: O^T += V^T P^T of the last tile (tile n - 1, in stage (n - 1) % 3 = st2 by now)
@@ -616,7 +651,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             else last_c(IC<0>{});
             mfma_settle();
         }
-        if (attempt == 1) break;
+        if (attempt == 2) break;
         int* flags = reinterpret_cast<int*>(lds + kRingBytes + kCols * kPitch);
         if (lane == 0) flags[wave] = redo ? 1 : 0;
         __syncthreads();  // also: every wavefront is done with the ring

@@ -99,17 +99,20 @@ def _with_late_outliers(case, rows, key_positions, beta):
     return case
 
 
-@pytest.mark.parametrize("tile", [128, 256])
-def test_prefill_reference_maximum_jumps_late(oracle, G, opts, tile):
+@pytest.mark.parametrize("tile,beta", [(128, 3.0), (256, 3.0), (256, 9.0)])
+def test_prefill_reference_maximum_jumps_late(oracle, G, opts, tile, beta):
     """Logits that exceed a column's running maximum by far more than the kernels let their reference lag, long after the
     column has begun to accumulate: the 128-column kernel rescales in place, the 256-column kernel runs the pass again
-    from the final reference.  Also a jump inside the very first key tile and one in the last, partial tile."""
+    from the final reference.  Also a jump inside the very first key tile and one in the last, partial tile.  beta = 3:
+    about 50 powers of two above everything before (the 256-column kernel's first attempt, which follows no maximum behind
+    the first tile, still holds it); beta = 9: about 150 (its running sums leave the fp32 range it allows itself, the
+    pass is run again following the maximum, and once more from the final reference)."""
     opts(tile=tile)
     case = W.make_attn_case("t", 93, "bf16", [(300, 1500)], 8, 1, 128)
     first_new = 1200
     rows = [5, 5, 120, 299, 17]
     keys = [700, 1100, 3, first_new + 299, 40]       # visible to their rows: key <= 1200 + row
-    case = _with_late_outliers(case, rows, keys, beta=3.0)
+    case = _with_late_outliers(case, rows, keys, beta=beta)
     want = oracle.attention_case(case, oracle.cache_for_case(case))
     got = G.prefill_case(case, G.cache_for_case(case))
     _check(got, want)
