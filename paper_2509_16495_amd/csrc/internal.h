@@ -78,14 +78,16 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
 
 // prefill_mfma64.hip : the same operation on 256-column workgroup tiles, one 64-column wavefront per SIMD; bf16 cache
 struct Prefill64Plan {
-    int tile_tokens, pair_ranks, n_splits;
+    int tile_tokens, pair_ranks, n_splits;  // pair_ranks: workgroups per (sequence, KV head, key range)
+    bool paired;                            // a workgroup takes two tiles of a sequence (heaviest with lightest)
     long workgroups;
     double model_seconds;  // launch_model_seconds of this plan
 };
 // Rough duration of a prefill launch, used only to choose between plans: `wgs` workgroups (one per compute unit at a
-// time) of `cols` columns each walk max_seq_len keys cut into `splits` ranges; ranges beyond one cost a merge pass.
-inline double launch_model_seconds(long wgs, int splits, int cols, int total_q, int max_seq_len, int hq_l) {
-    const double unit = 4.0 * 128 * cols * static_cast<double>(max_seq_len) / 3.9e12;  // one workgroup, all keys, at 1 PFLOP/s per chip
+// time) of `cols` columns each walk `walks` x max_seq_len keys cut into `splits` ranges; ranges beyond one cost a merge
+// pass.
+inline double launch_model_seconds(long wgs, int splits, int cols, int total_q, int max_seq_len, int hq_l, double walks) {
+    const double unit = walks * 4.0 * 128 * cols * static_cast<double>(max_seq_len) / 3.9e12;  // one workgroup at 1 PFLOP/s per chip
     const double merge = 2.0 * total_q * hq_l * 130 * 4 / 4.0e12;                     // partials written and read back, per range
     const double load = static_cast<double>(wgs) * splits / 256.0;
     // equal workgroups are dispatched as compute units fall free: whole rounds while they are few, half a round of tail
@@ -93,6 +95,12 @@ inline double launch_model_seconds(long wgs, int splits, int cols, int total_q, 
     const double whole = static_cast<double>(static_cast<long>(load + 0.999999));
     const double rounds = load <= 1.0 ? 1.0 : (whole < load + 0.5 ? whole : load + 0.5);
     return rounds / splits * unit + (splits > 1 ? splits * merge + 5.0e-6 : 0.0);
+}
+// Keys a workgroup walks when it takes a sequence's tiles in pairs (heaviest with lightest), in units of the context: one
+// walk for a prefill from nothing (tile i sees i + 1 tiles' worth of keys, its partner the rest), two for a short chunk
+// behind a long context (both tiles see nearly all of it).
+inline double paired_walks(int max_q_len, int max_seq_len) {
+    return max_seq_len > 0 ? 2.0 - static_cast<double>(max_q_len < max_seq_len ? max_q_len : max_seq_len) / max_seq_len : 1.0;
 }
 bool prefill_mfma64_supported(const AttnShape& a);
 Prefill64Plan prefill_mfma64_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const AttnShape& a,

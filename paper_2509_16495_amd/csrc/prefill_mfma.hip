@@ -665,9 +665,10 @@ Plan make_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const 
         splits = forced;
     } else {
         const int by_len = max_seq_len / (16 * kKvTile);  // at least 16 key tiles per range
-        double best = launch_model_seconds(wgs, 1, 128, total_q, max_seq_len, a.hq_l);
+        const double walks = paired_walks(max_q_len, max_seq_len);
+        double best = launch_model_seconds(wgs, 1, 128, total_q, max_seq_len, a.hq_l, walks);
         for (int cand = 2; cand <= 16 && cand <= by_len; ++cand) {
-            const double t = launch_model_seconds(wgs, cand, 128, total_q, max_seq_len, a.hq_l);
+            const double t = launch_model_seconds(wgs, cand, 128, total_q, max_seq_len, a.hq_l, walks);
             if (t < best * 0.97) {  // a further range must pay for itself
                 best = t;
                 splits = cand;
@@ -732,7 +733,8 @@ Choice choose(int num_seqs, int total_q, int max_q_len, int max_seq_len, const A
     const int forced = option_prefill_tile();
     if (forced == 128) return c;
     const long wgs_n = static_cast<long>(c.narrow.pair_ranks) * num_seqs * c.narrow.head_slots;
-    const double t_narrow = 1.12 * launch_model_seconds(wgs_n, c.narrow.n_splits, 128, total_q, max_seq_len, a.hq_l);
+    const double t_narrow = 1.12 * launch_model_seconds(wgs_n, c.narrow.n_splits, 128, total_q, max_seq_len, a.hq_l,
+                                                         paired_walks(max_q_len, max_seq_len));
     c.wide = forced == 256 || c.w.model_seconds < 0.97 * t_narrow;
     return c;
 }

@@ -39,8 +39,8 @@
 // wavefront per SIMD every instruction of the iteration - barrier, loads, address updates, the check of the maximum -
 // takes issue time the MFMAs cannot hide behind another wavefront, so all of it is kept to a few instructions.
 //
-// Scheduling: tiles of a sequence are processed in pairs (heaviest with lightest) by one workgroup; long contexts
-// under short chunks are split into key ranges merged by launch_combine.
+// Scheduling: tiles of a sequence are processed in pairs (heaviest with lightest) by one workgroup; a short chunk on a
+// long context is taken one tile per workgroup, its keys split into ranges merged by launch_combine.
 #include "internal.h"
 
 #include <utility>
@@ -164,6 +164,7 @@ struct Prefill64Params {
     int num_seqs, total_q, hq_l, hkv_l, G;
     int tile_tokens;  // kCols / G
     int n_splits;     // key ranges per tile
+    int paired;       // tiles of a sequence taken two per workgroup (see prefill_mfma64_plan)
     int max_blocks;
     float c;          // softmax_scale * log2(e) (times k_scale for a cache widened from FP8)
     float out_scale;  // multiplies the normalised output: v_scale of an FP8 cache, else 1
@@ -191,9 +192,10 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
     const int tile_tokens = p.tile_tokens;
     const int cols_used = tile_tokens * p.G;
     const int n_tiles = (q_len + tile_tokens - 1) / tile_tokens;
-    const int hi_tile = n_tiles - 1 - rank;
-    if (rank > hi_tile) return;  // uniform
-    const int n_pass = (hi_tile == rank) ? 1 : 2;
+    // paired: the workgroup takes tile n_tiles - 1 - rank and then tile rank (heaviest with lightest); else tile rank alone
+    const int hi_tile = p.paired ? n_tiles - 1 - rank : rank;
+    if (p.paired ? rank > hi_tile : rank >= n_tiles) return;  // uniform
+    const int n_pass = (!p.paired || hi_tile == rank) ? 1 : 2;
     const_i32_ptr table = (const_i32_ptr)(p.block_table + static_cast<size_t>(s) * p.max_blocks);
     // Inside the key loop the block id of the coming iteration is fetched by a *vector* load: a scalar load shares its
     // counter with the LDS operand reads and returns out of order with them, so while one is outstanding every wait for
@@ -286,7 +288,6 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             const int tok_r = min(tok0 + cw_r / p.G, q_len - 1);
             q_ptr[cb] = p.q + static_cast<size_t>(q_begin + tok_r) * p.q_stride + (g * p.G + cw_r % p.G) * kD + half * 8;
         }
-        load_q_to_acc(qf[0], qf[1], q_ptr[0], q_ptr[1]);
         const int w_tok_first = tok0 + (wave * 64) / p.G;
         const int w_pos_min =
             __builtin_amdgcn_readfirstlane((wave * 64 < cols_used && w_tok_first < q_len) ? ctx - q_len + w_tok_first : -1);
@@ -551,6 +552,19 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             st2 = st_new;
         };
 
+        // prologue loads: K of the first three tiles and V^T of the first (two cache blocks per wavefront)
+        auto issue_prologue = [&]() SHIFTATTN_INLINE {
+            const int id_p = table[min(2 * (kt_begin + (wave >> 1)) + ld_blk, last_block)];
+            dma_4k(uniform_ptr(block_base(id_p)), k_ld, lds + (wave >> 1) * kStageBytes + ld_blk * kBlockBytes);
+            // the loads "iteration -1" would have issued: K of tile 2 into stage 2, V^T of tile 0 into stage 0
+            const int id_q = table[load_block_index(-1)];
+            dma_4k(uniform_ptr(block_base(id_q)), ld_off, lds + (is_k ? 2 * kStageBytes : 0) + ld_dst);
+            id_vec = table_v[load_block_index(0) + lane_zero];
+        };
+        // The first attempt's go out in front of the fetch of Q^T, whose wait then covers both.
+        if (n > 0) issue_prologue();
+        load_q_to_acc(qf[0], qf[1], q_ptr[0], q_ptr[1]);
+
         // Up to three attempts at the pass.  The first follows no maximum behind the first key tile (its steady-state
         // bodies save the instruction per two logits that would collect it; real logits stay within 2^100 of their
         // first tile's maximum).  If some wavefront flags it (see the end of an iteration), the second starts over and
@@ -574,16 +588,8 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
                 for (int r = 0; r < 16; ++r) oacc[cb][mt][r] = 0.f;
         }
         if (n > 0) {
-            // prologue: K of the first three tiles and V^T of the first (two cache blocks per wavefront), S^T of the
-            // first tile
-            {
-                const int id_p = table[min(2 * (kt_begin + (wave >> 1)) + ld_blk, last_block)];
-                dma_4k(uniform_ptr(block_base(id_p)), k_ld, lds + (wave >> 1) * kStageBytes + ld_blk * kBlockBytes);
-                // the loads "iteration -1" would have issued: K of tile 2 into stage 2, V^T of tile 0 into stage 0
-                const int id_q = table[load_block_index(-1)];
-                dma_4k(uniform_ptr(block_base(id_q)), ld_off, lds + (is_k ? 2 * kStageBytes : 0) + ld_dst);
-                id_vec = table_v[load_block_index(0) + lane_zero];
-            }
+            // prologue: the loads (already on their way in the first attempt), S^T of the first tile
+            if (attempt > 0) issue_prologue();
             st0 = 0, st1 = kStageBytes, st2 = 2 * kStageBytes;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) k_cur[ks] = k_rd[ks] + kStageBytes;   // iteration 0 reads K of tile 1
@@ -726,7 +732,11 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
                 }
             }
         }
-        __syncthreads();  // the next pass reuses the ring
+        // The next pass reuses the ring, the flags and the staging tile: every wavefront must have left this pass's last
+        // LDS reads behind.  A bare barrier: __syncthreads() would also wait for the output stores just issued (several
+        // microseconds until the last is acknowledged); nothing in the next pass depends on them, and its first loads
+        // overlap them.
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     }
 }
 
@@ -742,21 +752,27 @@ Prefill64Plan prefill_mfma64_plan(int num_seqs, int total_q, int max_q_len, int 
     const int G = a.hq_l / a.hkv_l;
     pl.tile_tokens = kCols / G;
     const int tiles = (max_q_len + pl.tile_tokens - 1) / pl.tile_tokens;
-    pl.pair_ranks = (tiles + 1) / 2;
+    // Causal tiles differ in work (tile i sees i + 1 tiles' worth of keys), so a workgroup takes the heaviest tile left
+    // together with the lightest.  A short chunk behind a long context has no such imbalance to level - its tiles all walk
+    // the context - and pairing would only make every workgroup pay set-up, first tile and write-out twice: there each
+    // workgroup takes one tile, and the key ranges (below) fill the chip.
+    pl.paired = !(static_cast<long>(max_seq_len) >= 16L * max_q_len);
+    pl.pair_ranks = pl.paired ? (tiles + 1) / 2 : tiles;
     // Key ranges per column tile: the count that minimises a simple model of the launch (launch_model_seconds) - a
     // workgroup's time falls with the number of ranges, workgroups beyond one per compute unit queue up, and every range
     // adds a partial result per (token, head) that the merge kernel writes and reads back.  A long prefill that fills the
     // chip takes 1; a short chunk on a long context takes as many as fill it.
     const long wgs = static_cast<long>(pl.pair_ranks) * num_seqs * a.hkv_l;
+    const double walks = pl.paired ? paired_walks(max_q_len, max_seq_len) : 1.0;
     int splits = 1;
     if (forced_splits > 0) {
         splits = forced_splits;
-        pl.model_seconds = launch_model_seconds(wgs, splits, kCols, total_q, max_seq_len, a.hq_l);
+        pl.model_seconds = launch_model_seconds(wgs, splits, kCols, total_q, max_seq_len, a.hq_l, walks);
     } else {
         const int by_len = max_seq_len / (32 * kKv);  // at least 32 key tiles per range
-        pl.model_seconds = launch_model_seconds(wgs, 1, kCols, total_q, max_seq_len, a.hq_l);
+        pl.model_seconds = launch_model_seconds(wgs, 1, kCols, total_q, max_seq_len, a.hq_l, walks);
         for (int cand = 2; cand <= 16 && cand <= by_len; ++cand) {
-            const double t = launch_model_seconds(wgs, cand, kCols, total_q, max_seq_len, a.hq_l);
+            const double t = launch_model_seconds(wgs, cand, kCols, total_q, max_seq_len, a.hq_l, walks);
             if (t < pl.model_seconds * 0.97) {  // a further range must pay for itself
                 pl.model_seconds = t;
                 splits = cand;
@@ -802,6 +818,7 @@ hipError_t launch_prefill_mfma64(const void* q, const void* cache, const int32_t
     p.G = a.hq_l / a.hkv_l;
     p.tile_tokens = pl.tile_tokens;
     p.n_splits = pl.n_splits;
+    p.paired = pl.paired ? 1 : 0;
     p.max_blocks = max_blocks;
     p.c = c;
     p.out_scale = out_scale;

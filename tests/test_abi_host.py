@@ -75,7 +75,7 @@ def test_launch_plans_follow_the_shape_of_the_batch(B):
 
     assert ranges(4, 16384, 4096, 4096, 4) == 0         # 256 equal workgroups of 128-column tiles: one round, no split
     assert ranges(1, 16384, 16384, 16384, 8) == 0       # 256 pairs of 256-column tiles
-    assert ranges(1, 2048, 2048, 133120, 8) == 8        # 32 pairs: eight ranges fill the chip
+    assert ranges(1, 2048, 2048, 133120, 8) == 4        # 64 tiles, one per workgroup (nothing to level by pairing): four ranges fill the chip
     assert ranges(1, 16384, 16384, 16384, 5) == 3       # 161 pairs: three ranges make two full rounds
     assert ranges(4, 16384, 4096, 4096, 5) == 0         # short contexts: the merge would cost more than the ragged round
     try:

@@ -55,6 +55,10 @@ SHAPES = [
     ([(700, 700)], 8, 1),                                    # 22 wide tiles: pairs, a middle tile on its own
     ([(513, 1100), (31, 31), (257, 257)], 8, 1),             # several sequences of unequal tile counts
     ([(40, 4000)], 7, 1),                                    # 36 tokens per wide tile, long cached context
+    # short chunks behind long contexts (longest context >= 16 x longest chunk): the wide kernel takes one tile per
+    # workgroup instead of pairs; sequences of 4, 1, 3 and 0 tiles, one of them a prefill from nothing
+    ([(100, 2100), (31, 31), (70, 1200), (0, 5)], 8, 1),
+    ([(65, 1100), (64, 1040)], 8, 2),
 ]
 
 
