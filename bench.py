@@ -81,6 +81,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--settle-scale", type=float, default=1.0,
+                    help="scales the load applied before every timed region (0: none; counter runs do not need it)")
     ap.add_argument("--no-extras", action="store_true", help="only the headline step")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also run a plain 1-GiB elementwise copy a few times (reference for scaling FETCH_SIZE / WRITE_SIZE)")
@@ -115,10 +117,11 @@ def main() -> int:
         for its first 15-20 ms of load (the shader clock under the power limit settles over some tens of launches: a
         16384-token prefill launch takes 610 us right after a pause and 472 us from the 40th launch on); a serving
         engine runs in the settled state, so that is the state every figure here is taken in."""
-        t0 = time.perf_counter()
-        while (time.perf_counter() - t0) * 1e3 < ms:
+        t0, calls = time.perf_counter(), 0
+        while (time.perf_counter() - t0) * 1e3 < ms * args.settle_scale and calls < 256:   # (launch-bound kernels: 256 calls do)
             for _ in range(4):
                 fn()
+            calls += 4
             torch.cuda.synchronize()
 
     def time_events(fn, reps, warm=3):
@@ -317,7 +320,7 @@ def main() -> int:
     phases["unified_call_alone"] = {"ms": round(ms, 5), "rate": round(step_flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s"}
     ck_ms = phases["chunk_prefill"]["ms"]
     achieved = pre5.flops() / (ck_ms * 1e-3) / 1e12
-    roofline = roof("prefill64_kernel (bf16 MFMA chunked prefill over 8 key ranges; the call's combine_splits_kernel, about 1.5 % of it, is "
+    roofline = roof("prefill64_kernel (bf16 MFMA chunked prefill, one 256-column tile per workgroup over 4 key ranges; the call's combine_splits_kernel, about 1.5 % of it, is "
                     "inside the timed interval)", "mfma", achieved, PEAK_BF16_TFLOPS, "TFLOP/s",
                     traffic_key="chunk_prefill_long_context", flops_per_launch=pre5.flops(), median_launch_ms=round(ck_ms, 5))
     dd_ms = phases["decodes"]["ms"]
@@ -337,7 +340,7 @@ def main() -> int:
         "decode_in_step": {"kv_bytes": dec5.kv_bytes(), "ms": round(dd_ms, 5),
                            "roofline": roof("decode_flat_kernel + combine_flat_kernel", "hbm", dd_gbps, PEAK_HBM_GBPS, "GB/s", traffic_key="decode_64_long_contexts")},
         "ms_per_step_graph_replay": round(ms_per_step_graph, 5),
-        "timing_state": {"settle_ms": SETTLE_MS, "ms_per_step_first_steps_after_a_pause": round(ms_per_step_after_idle, 5),
+        "timing_state": {"settle_ms": SETTLE_MS * args.settle_scale, "ms_per_step_first_steps_after_a_pause": round(ms_per_step_after_idle, 5),
                          "note": "every timed region starts after settle_ms (3x for the step) of the same work back to back: the "
                                  "chip's clock under the power limit takes 15-20 ms of load to settle, and matrix-heavy kernels run "
                                  "up to 25 % slower until then; the figure for the first steps after a 0.2 s pause is given beside it"},
