@@ -318,6 +318,18 @@ def main() -> int:
     phases["all_parts_as_separate_calls"] = {"ms": round(ms, 5), "rate": round(step_flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s"}
     ms = time_events(do_mixed, reps)
     phases["unified_call_alone"] = {"ms": round(ms, 5), "rate": round(step_flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s"}
+    # how the chip settles: the chunk's attention call, 200 launches in a row after a pause, medians of ten
+    torch.cuda.synchronize()
+    time.sleep(0.5)
+    sev = [torch.cuda.Event(enable_timing=True) for _ in range(201)]
+    sev[0].record()
+    for i in range(200):
+        do_chunk_only()
+        sev[i + 1].record()
+    torch.cuda.synchronize()
+    s_us = [sev[i].elapsed_time(sev[i + 1]) * 1e3 for i in range(200)]
+    settling = [round(float(np.median(s_us[i:i + 10])), 1) for i in range(0, 200, 10)]
+    log("[bench] chunk attention call, us per launch after a 0.5 s pause (medians of 10 launches): " + " ".join(f"{v:.0f}" for v in settling))
     ck_ms = phases["chunk_prefill"]["ms"]
     achieved = pre5.flops() / (ck_ms * 1e-3) / 1e12
     roofline = roof("prefill64_kernel (bf16 MFMA chunked prefill, one 256-column tile per workgroup over 4 key ranges; the call's combine_splits_kernel, about 1.5 % of it, is "
@@ -343,7 +355,8 @@ def main() -> int:
         "timing_state": {"settle_ms": SETTLE_MS * args.settle_scale, "ms_per_step_first_steps_after_a_pause": round(ms_per_step_after_idle, 5),
                          "note": "every timed region starts after settle_ms (3x for the step) of the same work back to back: the "
                                  "chip's clock under the power limit takes 15-20 ms of load to settle, and matrix-heavy kernels run "
-                                 "up to 25 % slower until then; the figure for the first steps after a 0.2 s pause is given beside it"},
+                                 "up to 25 % slower until then; the figure for the first steps after a 0.2 s pause is given beside it",
+                         "chunk_prefill_us_per_launch_after_a_pause_medians_of_10": settling},
         "phases": phases,
         "traffic_note": "HBM bytes per launch (FETCH_SIZE + WRITE_SIZE) from the profiled runs in profiles/hbm_traffic.md; null when "
                         "that table was not measured on this tree's kernel sources",
