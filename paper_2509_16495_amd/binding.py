@@ -93,6 +93,7 @@ def lib() -> ctypes.CDLL:
         L.shiftattn_use_base_config.argtypes = [i32, i32]
         L.shiftattn_use_base_config.restype = i32
         L.shiftattn_ceiling_mfma_bf16.argtypes = [vp, vp, i32, ctypes.POINTER(ctypes.c_int64), vp]
+        L.shiftattn_ceiling_mfma_bf16_fresh.argtypes = [vp, vp, i32, ctypes.POINTER(ctypes.c_int64), vp]
         L.shiftattn_ceiling_hbm_read.argtypes = [vp, sz, vp, ctypes.POINTER(ctypes.c_int64), vp]
         L.shiftattn_ceiling_hbm_copy.argtypes = [vp, vp, sz, ctypes.POINTER(ctypes.c_int64), vp]
         L.shiftattn_set_option.argtypes = [i32, i32]
@@ -171,6 +172,14 @@ def ceiling_mfma_bf16(operands: torch.Tensor, sink: torch.Tensor, iters: int) ->
     assert operands.numel() * operands.element_size() >= 2048 and operands.is_contiguous()
     flops = ctypes.c_int64(0)
     _check(lib().shiftattn_ceiling_mfma_bf16(_ptr(operands), _ptr(sink), iters, ctypes.byref(flops), _stream()))
+    return flops.value
+
+
+def ceiling_mfma_bf16_fresh(operands: torch.Tensor, sink: torch.Tensor, iters: int) -> int:
+    """Enqueue the MFMA-only probe whose operands change from one MFMA to the next; returns the flops of the launch."""
+    assert operands.numel() * operands.element_size() >= 16384 and operands.is_contiguous()
+    flops = ctypes.c_int64(0)
+    _check(lib().shiftattn_ceiling_mfma_bf16_fresh(_ptr(operands), _ptr(sink), iters, ctypes.byref(flops), _stream()))
     return flops.value
 
 

@@ -291,6 +291,14 @@ int shiftattn_ceiling_mfma_bf16(const void* operands, void* sink, int32_t iters,
     return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "ceiling_mfma launch");
 }
 
+int shiftattn_ceiling_mfma_bf16_fresh(const void* operands, void* sink, int32_t iters, int64_t* flops, void* stream) {
+    if (!operands || !sink || !flops) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
+    if (!aligned16(operands)) return fail(SHIFTATTN_EINVAL, "operands must be 16-byte aligned");
+    if (iters < 1 || iters > (1 << 24)) return fail(SHIFTATTN_EINVAL, "iters = %d", iters);
+    hipError_t e = launch_mfma_ceiling_fresh(operands, sink, iters, flops, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SHIFTATTN_OK : hip_fail(e, "ceiling_mfma_fresh launch");
+}
+
 int shiftattn_ceiling_hbm_read(const void* src, size_t bytes, void* sink, int64_t* bytes_read, void* stream) {
     if (!src || !sink || !bytes_read) return fail(SHIFTATTN_EINVAL, "a required pointer is NULL");
     if (!aligned16(src)) return fail(SHIFTATTN_EINVAL, "src must be 16-byte aligned");

@@ -6,7 +6,8 @@
 //     taken from memory.  The chip runs such a loop at its power limit: the shader clock settles well
 //     below its maximum, lower for random operand values than for constants, and lower for the 32x32x16
 //     form (which moves four times the accumulator registers per instruction for twice the work, and
-//     sustains about 13 % less) - so this is the higher of the two rates a kernel can be held against, and
+//     sustains about 13 % less) - so this is the higher of the two rates a kernel can be held against; a second loop
+//     gives every MFMA operands that differ from the one before, which is what a product of real matrices does, and
 //   * a streaming read: every wavefront reads 16 KiB pieces of a large buffer with 16-byte
 //     non-temporal loads, one KiB per instruction, the request shape of the decode kernel.
 #include "internal.h"
@@ -37,6 +38,38 @@ __global__ __launch_bounds__(kProbeThreads) void mfma_ceiling_kernel(const u32x4
 #pragma unroll
         for (int m = 0; m < kProbeUnroll; ++m)
             acc[m % kProbeAcc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[m % kProbeAcc], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < kProbeAcc; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s += acc[i][r];
+    if (s == 12345.678f) sink[0] = s;  // keeps the loop alive; practically never true
+}
+
+// The same loop with operands that change from one MFMA to the next, as they do in a product of real matrices: eight A
+// and eight B fragments per lane, MFMA m takes A fragment m % 8 and B fragment (m / 8) % 8 (the order of an 8 x 8 block of
+// output tiles).  Inputs that toggle cost power the constant operands of the loop above do not, and the chip gives that
+// up in clock: this is the rate a GEMM-shaped kernel can be held against.
+constexpr int kFreshUnroll = 64;
+__global__ __launch_bounds__(kProbeThreads) void mfma_ceiling_fresh_kernel(const u32x4* __restrict__ operands,
+                                                                           float* __restrict__ sink, int iters) {
+    const int lane = threadIdx.x & 63;
+    bf16x8 a[8], b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = __builtin_bit_cast(bf16x8, operands[i * 64 + lane]);
+        b[i] = __builtin_bit_cast(bf16x8, operands[(8 + i) * 64 + lane]);
+    }
+    f32x4 acc[kProbeAcc];
+#pragma unroll
+    for (int i = 0; i < kProbeAcc; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[i][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int m = 0; m < kFreshUnroll; ++m)
+            acc[m % kProbeAcc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m % 8], b[(m / 8) % 8], acc[m % kProbeAcc], 0, 0, 0);
     }
     float s = 0.f;
 #pragma unroll
@@ -110,6 +143,13 @@ hipError_t launch_mfma_ceiling(const void* operands, void* sink, int iters, int6
     mfma_ceiling_kernel<<<kProbeWorkgroups, kProbeThreads, 0, st>>>(static_cast<const u32x4*>(operands),
                                                                      static_cast<float*>(sink), iters);
     *flops = static_cast<int64_t>(kProbeWorkgroups) * (kProbeThreads / 64) * iters * kProbeUnroll * (2LL * 16 * 16 * 32);
+    return hipGetLastError();
+}
+
+hipError_t launch_mfma_ceiling_fresh(const void* operands, void* sink, int iters, int64_t* flops, hipStream_t st) {
+    mfma_ceiling_fresh_kernel<<<kProbeWorkgroups, kProbeThreads, 0, st>>>(static_cast<const u32x4*>(operands),
+                                                                           static_cast<float*>(sink), iters);
+    *flops = static_cast<int64_t>(kProbeWorkgroups) * (kProbeThreads / 64) * iters * kFreshUnroll * (2LL * 16 * 16 * 32);
     return hipGetLastError();
 }
 

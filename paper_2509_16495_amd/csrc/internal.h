@@ -155,6 +155,7 @@ hipError_t launch_quantize_rows_fp8(const void* x, void* codes, float* scales, i
 
 // ceilings.hip : attainable-rate probes for benchmark reports
 hipError_t launch_mfma_ceiling(const void* operands, void* sink, int iters, int64_t* flops, hipStream_t st);
+hipError_t launch_mfma_ceiling_fresh(const void* operands, void* sink, int iters, int64_t* flops, hipStream_t st);
 hipError_t launch_hbm_read_ceiling(const void* src, size_t bytes, void* sink, int64_t* bytes_read, hipStream_t st);
 hipError_t launch_hbm_copy_ceiling(const void* src, void* dst, size_t bytes, int64_t* bytes_copied, hipStream_t st);
 
