@@ -333,9 +333,11 @@ int32_t shiftattn_use_base_config(int32_t n_tokens, int32_t threshold);
  *   SHIFTATTN_OPT_PREFILL_TILE   128 | 256: which prefill kernel takes bf16 / head_dim 128 launches
  *   SHIFTATTN_OPT_PREFILL_SPLITS 1 .. 64: key ranges per column tile of those kernels
  *   SHIFTATTN_OPT_GENERIC_ONLY   1: every attention call runs the general kernel (any type / head_dim)
+ *   SHIFTATTN_OPT_PREFILL_PAIRING 1 | 2: the 256-column prefill kernel takes a sequence's column tiles two per
+ *                                workgroup, heaviest with lightest (1), or one per workgroup, heaviest first (2)
  *   set returns EINVAL for an unknown option or value; get returns -1 for an unknown option. */
 enum { SHIFTATTN_OPT_PREFILL_TILE = 0, SHIFTATTN_OPT_PREFILL_SPLITS = 1, SHIFTATTN_OPT_GENERIC_ONLY = 2,
-       SHIFTATTN_OPT_COUNT = 3 };
+       SHIFTATTN_OPT_PREFILL_PAIRING = 3, SHIFTATTN_OPT_COUNT = 4 };
 int shiftattn_init(void);
 int shiftattn_set_option(int32_t option, int32_t value);
 int32_t shiftattn_get_option(int32_t option);

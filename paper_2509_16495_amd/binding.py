@@ -104,7 +104,7 @@ def lib() -> ctypes.CDLL:
     return _lib
 
 
-OPT_PREFILL_TILE, OPT_PREFILL_SPLITS, OPT_GENERIC_ONLY = 0, 1, 2
+OPT_PREFILL_TILE, OPT_PREFILL_SPLITS, OPT_GENERIC_ONLY, OPT_PREFILL_PAIRING = 0, 1, 2, 3
 
 
 def init() -> None:

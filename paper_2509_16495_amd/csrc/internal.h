@@ -122,6 +122,7 @@ hipError_t proj_stream_init();
 // Process-wide tuning switches (api.hip: shiftattn_set_option); 0 = decided per call
 int option_prefill_tile();    // 0, 128 or 256
 int option_prefill_splits();  // 0 or the number of key ranges
+int option_prefill_pairing(); // 0, 1 (tiles in pairs) or 2 (one tile per workgroup)
 
 // proj_gemm.hip : the projections in front of the first exchange and behind the second (bf16, head_dim 128)
 bool qkv_proj_pack_supported(const XchgShape& s, int d_model, int elem);

@@ -192,9 +192,11 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
     const int tile_tokens = p.tile_tokens;
     const int cols_used = tile_tokens * p.G;
     const int n_tiles = (q_len + tile_tokens - 1) / tile_tokens;
-    // paired: the workgroup takes tile n_tiles - 1 - rank and then tile rank (heaviest with lightest); else tile rank alone
-    const int hi_tile = p.paired ? n_tiles - 1 - rank : rank;
-    if (p.paired ? rank > hi_tile : rank >= n_tiles) return;  // uniform
+    // paired: the workgroup takes tile n_tiles - 1 - rank and then tile rank (heaviest with lightest); else the former
+    // alone - workgroups start in the order of their index, so the heaviest tiles of all sequences go first and the light
+    // ones fill the compute units that fall free
+    const int hi_tile = n_tiles - 1 - rank;
+    if (p.paired ? rank > hi_tile : hi_tile < 0) return;  // uniform
     const int n_pass = (!p.paired || hi_tile == rank) ? 1 : 2;
     const_i32_ptr table = (const_i32_ptr)(p.block_table + static_cast<size_t>(s) * p.max_blocks);
     // Inside the key loop the block id of the coming iteration is fetched by a *vector* load: a scalar load shares its
@@ -752,33 +754,61 @@ Prefill64Plan prefill_mfma64_plan(int num_seqs, int total_q, int max_q_len, int 
     const int G = a.hq_l / a.hkv_l;
     pl.tile_tokens = kCols / G;
     const int tiles = (max_q_len + pl.tile_tokens - 1) / pl.tile_tokens;
-    // Causal tiles differ in work (tile i sees i + 1 tiles' worth of keys), so a workgroup takes the heaviest tile left
-    // together with the lightest.  A short chunk behind a long context has no such imbalance to level - its tiles all walk
-    // the context - and pairing would only make every workgroup pay set-up, first tile and write-out twice: there each
-    // workgroup takes one tile, and the key ranges (below) fill the chip.
-    pl.paired = !(static_cast<long>(max_seq_len) >= 16L * max_q_len);
-    pl.pair_ranks = pl.paired ? (tiles + 1) / 2 : tiles;
-    // Key ranges per column tile: the count that minimises a simple model of the launch (launch_model_seconds) - a
-    // workgroup's time falls with the number of ranges, workgroups beyond one per compute unit queue up, and every range
-    // adds a partial result per (token, head) that the merge kernel writes and reads back.  A long prefill that fills the
-    // chip takes 1; a short chunk on a long context takes as many as fill it.
-    const long wgs = static_cast<long>(pl.pair_ranks) * num_seqs * a.hkv_l;
-    const double walks = pl.paired ? paired_walks(max_q_len, max_seq_len) : 1.0;
-    int splits = 1;
-    if (forced_splits > 0) {
-        splits = forced_splits;
-        pl.model_seconds = launch_model_seconds(wgs, splits, kCols, total_q, max_seq_len, a.hq_l, walks);
-    } else {
-        const int by_len = max_seq_len / (32 * kKv);  // at least 32 key tiles per range
-        pl.model_seconds = launch_model_seconds(wgs, 1, kCols, total_q, max_seq_len, a.hq_l, walks);
-        for (int cand = 2; cand <= 16 && cand <= by_len; ++cand) {
-            const double t = launch_model_seconds(wgs, cand, kCols, total_q, max_seq_len, a.hq_l, walks);
-            if (t < pl.model_seconds * 0.97) {  // a further range must pay for itself
-                pl.model_seconds = t;
-                splits = cand;
-            }
-        }
-    }
+    // Causal tiles differ in work (tile i sees i + 1 tiles' worth of keys).  Two ways to level it: a workgroup takes the
+    // heaviest tile left together with the lightest (equal workgroups, one round when the pairs fit the chip), or one
+    // tile per workgroup, heaviest first, the light ones filling the compute units that fall free (any number of tiles
+    // levels out, but a tile is never shorter than its keys: it wants key ranges when the heaviest outweighs a compute
+    // unit's share).  A short chunk behind a long context has nothing to level - its tiles all walk the context - and
+    // pairing only makes every workgroup pay set-up, first tile and write-out twice.  Both are priced with the same rough
+    // model (plus kPassSeconds per pass a compute unit makes) over the key ranges per tile - a workgroup's time falls with
+    // the ranges, every range adds a partial result per (token, head) that the merge kernel writes and reads back - and
+    // the cheaper plan is taken.
+    constexpr double kPassSeconds = 15e-6;  // set-up, Q fetch, first and last tiles, write-out: what a pass costs around its loop
+    const long seq_heads = static_cast<long>(num_seqs) * a.hkv_l;
+    const int by_len = max_seq_len / (32 * kKv);  // at least 32 key tiles per range
+    struct Cand {
+        int splits;
+        double seconds, with_passes;
+    };
+    auto best_of = [&](auto model) {  // model(splits) -> {seconds, passes per compute unit}
+        Cand best = {0, 0.0, 0.0};
+        auto take = [&](int sp) {
+            const auto [t, passes] = model(sp);
+            const Cand c = {sp, t, t + passes * kPassSeconds};
+            if (best.splits == 0 || c.with_passes < best.with_passes * 0.97) best = c;  // a further range must pay for itself
+        };
+        if (forced_splits > 0) take(forced_splits);
+        else
+            for (int cand = 1; cand <= 16 && (cand == 1 || cand <= by_len); ++cand) take(cand);
+        return best;
+    };
+    const int pair_ranks = (tiles + 1) / 2;
+    const Cand paired = best_of([&](int sp) {
+        const long wgs = pair_ranks * seq_heads;
+        const double rounds = static_cast<double>((wgs * sp + 255) / 256);
+        return std::pair<double, double>(
+            launch_model_seconds(wgs, sp, kCols, total_q, max_seq_len, a.hq_l, paired_walks(max_q_len, max_seq_len)), 2.0 * rounds);
+    });
+    const Cand single = best_of([&](int sp) {
+        // tile i of a sequence walks (S - Q + (i + 1) tile_tokens) / S of the longest context S
+        const double S = max_seq_len > 0 ? max_seq_len : 1, Q = max_q_len < max_seq_len ? max_q_len : max_seq_len;
+        const double unit = 4.0 * 128 * kCols * S / 3.9e12, merge = 2.0 * total_q * a.hq_l * 130 * 4 / 4.0e12;
+        const double base = (S - Q) / S, step = pl.tile_tokens / S;
+        // (the batch counted as total_q / max_q_len sequences of the longest chunk: the lengths themselves are on the device)
+        const double seqs = max_q_len > 0 && total_q < static_cast<double>(num_seqs) * max_q_len ? static_cast<double>(total_q) / max_q_len
+                                                                                                  : static_cast<double>(num_seqs);
+        const double total = (tiles * base + step * tiles * (tiles + 1) / 2.0) * seqs * a.hkv_l;
+        const double heaviest = (base + step * tiles < 1.0 ? base + step * tiles : 1.0) / sp;
+        const long items = static_cast<long>(tiles * seqs * a.hkv_l * sp + 0.5);
+        const double share = 1.03 * total / 256.0;  // a compute unit's share of all the work, filled by ever lighter tiles
+        const double span = items <= 256 ? heaviest : (heaviest > share ? heaviest : share);
+        return std::pair<double, double>(span * unit + (sp > 1 ? sp * merge + 5.0e-6 : 0.0), static_cast<double>((items + 255) / 256));
+    });
+    const int forced_pairing = option_prefill_pairing();
+    pl.paired = forced_pairing == 1 || (forced_pairing == 0 && paired.with_passes <= single.with_passes);
+    pl.pair_ranks = pl.paired ? pair_ranks : tiles;
+    int splits = pl.paired ? paired.splits : single.splits;
+    pl.model_seconds = pl.paired ? paired.seconds : single.seconds;
     if (splits < 1) splits = 1;
     if (splits > 64) splits = 64;
     pl.n_splits = splits;

@@ -43,8 +43,9 @@ def test_every_declared_symbol_is_exported(B):
 def test_options_and_their_bounds(B):
     """The tuning switches: defaults are 0, values are range-checked, unknown options refused."""
     L = B.lib()
-    for opt in (B.OPT_PREFILL_TILE, B.OPT_PREFILL_SPLITS, B.OPT_GENERIC_ONLY):
+    for opt in (B.OPT_PREFILL_TILE, B.OPT_PREFILL_SPLITS, B.OPT_GENERIC_ONLY, B.OPT_PREFILL_PAIRING):
         assert B.get_option(opt) == 0
+    assert L.shiftattn_set_option(B.OPT_PREFILL_PAIRING, 3) == B.EINVAL and L.shiftattn_set_option(B.OPT_PREFILL_PAIRING, -1) == B.EINVAL
     assert L.shiftattn_set_option(B.OPT_PREFILL_TILE, 64) == B.EINVAL
     assert L.shiftattn_set_option(B.OPT_PREFILL_SPLITS, 65) == B.EINVAL and L.shiftattn_set_option(B.OPT_PREFILL_SPLITS, -1) == B.EINVAL
     assert L.shiftattn_set_option(B.OPT_GENERIC_ONLY, 2) == B.EINVAL
@@ -58,7 +59,7 @@ def test_options_and_their_bounds(B):
         B.set_option(B.OPT_GENERIC_ONLY, 1)
         assert B.prefill_workspace_bytes(1, 2048, 2048, 133120, a) == 0 and B.decode_workspace_bytes(4, 64, a) == 0
     finally:
-        for opt in (B.OPT_PREFILL_TILE, B.OPT_PREFILL_SPLITS, B.OPT_GENERIC_ONLY):
+        for opt in (B.OPT_PREFILL_TILE, B.OPT_PREFILL_SPLITS, B.OPT_GENERIC_ONLY, B.OPT_PREFILL_PAIRING):
             B.set_option(opt, 0)
     assert B.prefill_workspace_bytes(1, 2048, 2048, 133120, a) == auto
 
@@ -76,15 +77,21 @@ def test_launch_plans_follow_the_shape_of_the_batch(B):
     assert ranges(4, 16384, 4096, 4096, 4) == 0         # 256 equal workgroups of 128-column tiles: one round, no split
     assert ranges(1, 16384, 16384, 16384, 8) == 0       # 256 pairs of 256-column tiles
     assert ranges(1, 2048, 2048, 133120, 8) == 4        # 64 tiles, one per workgroup (nothing to level by pairing): four ranges fill the chip
-    assert ranges(1, 16384, 16384, 16384, 5) == 3       # 161 pairs: three ranges make two full rounds
+    assert ranges(1, 16384, 16384, 16384, 5) == 2       # 322 tiles, one per workgroup, heaviest first: two ranges bring the heaviest under a compute unit's share
     assert ranges(4, 16384, 4096, 4096, 5) == 0         # short contexts: the merge would cost more than the ragged round
     try:
         B.set_option(B.OPT_PREFILL_TILE, 128)
         assert ranges(1, 2048, 2048, 133120, 8) == 4    # 64 pairs of 128-column tiles
         B.set_option(B.OPT_PREFILL_TILE, 256)
         assert ranges(4, 16384, 4096, 4096, 4) == 2     # 128 pairs of 256-column tiles
+        B.set_option(B.OPT_PREFILL_PAIRING, 1)
+        assert ranges(1, 2048, 2048, 133120, 8) == 8    # in pairs the chunk is 32 workgroups: eight ranges fill the chip
+        assert ranges(1, 16384, 16384, 16384, 5) == 3   # 161 pairs: three ranges make two full rounds
+        B.set_option(B.OPT_PREFILL_PAIRING, 2)
+        assert ranges(1, 16384, 16384, 16384, 8) == 0   # 512 tiles, heaviest first: the light ones level the chip out
     finally:
         B.set_option(B.OPT_PREFILL_TILE, 0)
+        B.set_option(B.OPT_PREFILL_PAIRING, 0)
     # projections: k groups of the streaming kernel (token slice of a wavefront <= 128 registers), k ranges of the
     # large-batch kernel while its tiles are few, nothing once they fill the chip
     n, k = 10240, 8192

@@ -24,13 +24,15 @@ def opts():
     """Sets tuning switches for one test and puts them back to 'decided per call'."""
     from paper_2509_16495_amd import binding as B
 
-    def set_(tile=0, splits=0):
+    def set_(tile=0, splits=0, pairing=0):
         B.set_option(B.OPT_PREFILL_TILE, tile)
         B.set_option(B.OPT_PREFILL_SPLITS, splits)
+        B.set_option(B.OPT_PREFILL_PAIRING, pairing)
 
     yield set_
     B.set_option(B.OPT_PREFILL_TILE, 0)
     B.set_option(B.OPT_PREFILL_SPLITS, 0)
+    B.set_option(B.OPT_PREFILL_PAIRING, 0)
 
 
 def _check(got_bits, want):
@@ -72,6 +74,19 @@ def test_prefill_kernel_forced(oracle, G, opts, tile, splits, seqs, hq_l, hkv_l)
     case = W.make_attn_case("t", 91, "bf16", seqs, hq_l, hkv_l, 128)
     want = oracle.attention_case(case, oracle.cache_for_case(case))
     got = G.prefill_case(case, G.cache_for_case(case, fill_byte=0xFF))   # unwritten slots hold NaN patterns
+    _check(got, want)
+
+
+@pytest.mark.parametrize("pairing", [1, 2])
+@pytest.mark.parametrize("splits", [0, 2])
+@pytest.mark.parametrize("seqs,hq_l,hkv_l", SHAPES)
+def test_wide_prefill_kernel_tiles_in_pairs_and_one_per_workgroup(oracle, G, opts, pairing, splits, seqs, hq_l, hkv_l):
+    """The 256-column kernel with its tiles forced two per workgroup (heaviest with lightest) and one per workgroup
+    (heaviest first), whatever the planner would choose for the shape."""
+    opts(tile=256, splits=splits, pairing=pairing)
+    case = W.make_attn_case("t", 93, "bf16", seqs, hq_l, hkv_l, 128)
+    want = oracle.attention_case(case, oracle.cache_for_case(case))
+    got = G.prefill_case(case, G.cache_for_case(case, fill_byte=0xFF))
     _check(got, want)
 
 
