@@ -732,16 +732,21 @@ def main() -> int:
         # ---- configs[2]: 70B-shaped prefill; and the same length with 5 query heads per KV head (Table 4, Llama-17B-16E at P=8)
         for key, case, label in (("prefill_70b", W.config3_attn(), "configs[2]: 8q/1kv, D=128, one 16384-token causal prefill"),
                                  ("prefill_5q_per_kv", W.make_attn_case("g5_16k", 35, "bf16", [(16384, 16384)], 5, 1, D),
-                                  "40q/8kv model on 8 ranks: 5q/1kv, D=128, one 16384-token causal prefill (not a BASELINE config)")):
+                                  "40q/8kv model on 8 ranks: 5q/1kv, D=128, one 16384-token causal prefill (not a BASELINE config)"),
+                                 ("prefill_unequal_prompts", W.make_attn_case("mix3", 36, "bf16", [(12000, 12000), (7000, 7000), (3000, 3000)], 8, 1, D),
+                                  "8q/1kv, D=128, three prompts of 12000 + 7000 + 3000 tokens prefilled in one batch (not a BASELINE config)")):
             cch = torch.zeros((case.num_blocks, 1, 2, 16 * D), dtype=bf, device=dev)
             B.kv_write(B.to_device(case.k_ctx, "bf16", dev), B.to_device(case.v_ctx, "bf16", dev), ti(case.slots, np.int64), cch)
             q3 = B.to_device(case.q, "bf16", dev)
             t3, cu3, s3 = ti(case.block_table, np.int32), ti(case.cu_seqlens_q, np.int32), ti(case.ctx_lens, np.int32)
             o3 = torch.empty_like(q3)
-            ms = time_events(lambda: B.prefill(q3, cch, t3, cu3, s3, case.total_q, case.total_q, o3, case.softmax_scale), reps)
+            mq3, mc3 = int(case.q_lens.max()), int(case.ctx_lens.max())
+            ms = time_events(lambda: B.prefill(q3, cch, t3, cu3, s3, mq3, mc3, o3, case.softmax_scale), reps)
             tf = case.flops() / (ms * 1e-3) / 1e12
+            kname = ("prefill64_kernel (256-column tiles in pairs)" if key == "prefill_70b" else
+                     "prefill64_kernel (256-column tiles one per workgroup, heaviest first" + (", 2 key ranges)" if key == "prefill_5q_per_kv" else ")"))
             result[key] = {"workload": label, "flops": case.flops(), "ms": round(ms, 5),
-                           "roofline": roof("prefill64_kernel (256-column tiles)" if key == "prefill_70b" else "prefill_kernel (128-column tiles)", "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s", traffic_key=key)}
+                           "roofline": roof(kname, "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s", traffic_key=key)}
             log(f"[bench] {key}: {ms * 1e3:.1f} us, {tf:.1f} TFLOP/s ({tf / PEAK_BF16_TFLOPS:.1%} of bf16 MFMA peak)")
             if cpu:
                 rows = sample_rows(case, step=256, edge=32)
