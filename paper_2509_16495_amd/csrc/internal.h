@@ -80,8 +80,10 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
 struct Prefill64Plan {
     int tile_tokens, pair_ranks, n_splits;  // pair_ranks: workgroups per (sequence, KV head, key range)
     bool paired;                            // a workgroup takes two tiles of a sequence (heaviest with lightest)
+    bool rotate;                            // rotate_sequences_over_dies() of the batch
     long workgroups;
     double model_seconds;  // launch_model_seconds of this plan
+    double model_with_passes;  // the same plus what the passes of a compute unit cost around their key loops
 };
 // Rough duration of a prefill launch, used only to choose between plans: `wgs` workgroups (one per compute unit at a
 // time) of `cols` columns each walk `walks` x max_seq_len keys cut into `splits` ranges; ranges beyond one cost a merge
@@ -101,6 +103,23 @@ inline double launch_model_seconds(long wgs, int splits, int cols, int total_q, 
 // behind a long context (both tiles see nearly all of it).
 inline double paired_walks(int max_q_len, int max_seq_len) {
     return max_seq_len > 0 ? 2.0 - static_cast<double>(max_q_len < max_seq_len ? max_q_len : max_seq_len) / max_seq_len : 1.0;
+}
+// The batch counted in sequences of its longest chunk (the lengths themselves are on the device; the host knows their
+// sum and their maximum): what the workgroups of a launch planned for the longest amount to when many are light or empty.
+inline double longest_chunk_equivalents(int num_seqs, int total_q, int max_q_len) {
+    return max_q_len > 0 && total_q < static_cast<double>(num_seqs) * max_q_len ? static_cast<double>(total_q) / max_q_len
+                                                                                : static_cast<double>(num_seqs);
+}
+// Workgroup i of a launch runs on die i % 8.  The prefill kernels number their workgroups (tile rank, key range) x
+// (sequence, head), so when the (sequence, head) count is a multiple of eight every workgroup of a sequence lands on the
+// same die: good while the sequences are alike (a die's L2 holds the K/V of its sequences only), and a 32-CU bottleneck
+// for a long prompt among short ones (measured: one 4096-token prompt with seven of 700 tokens took twice the time of
+// the long prompt alone).  Batches whose chunks are far from equal, and whose (sequence, head) count is a multiple of
+// four (a sequence then sees one or two dies), therefore rotate the (sequence, head) index by the (tile rank, key range)
+// index; other counts spread by themselves, and rotating them only costs L2 hits.
+inline bool rotate_sequences_over_dies(int num_seqs, int heads, int total_q, int max_q_len) {
+    return num_seqs > 1 && (static_cast<long>(num_seqs) * heads) % 4 == 0 &&
+           longest_chunk_equivalents(num_seqs, total_q, max_q_len) < 0.75 * num_seqs;
 }
 bool prefill_mfma64_supported(const AttnShape& a);
 Prefill64Plan prefill_mfma64_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const AttnShape& a,

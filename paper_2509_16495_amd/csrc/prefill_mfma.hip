@@ -94,6 +94,7 @@ struct PrefillParams {
     int gs_log2;      // log2 of heads stacked per token in the column index
     int head_slots;   // hq_l >> gs_log2
     int n_splits;     // key ranges per tile
+    int rotate;       // the (sequence, head slot) index is rotated by the (pair rank, key range) index (see internal.h)
     int max_blocks;
     float c;          // softmax_scale * log2(e) (times k_scale for a cache widened from FP8)
     float out_scale;  // multiplies the normalised output: v_scale of an FP8 cache, else 1
@@ -115,6 +116,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
     item -= rank * (n_sh * p.n_splits);
     const int split = item / n_sh;
     item -= split * n_sh;
+    if (p.rotate) item = (item + n_sh - static_cast<int>((blockIdx.x / n_sh) % n_sh)) % n_sh;
     const int s = item / p.head_slots;
     const int hs = item - s * p.head_slots;
 
@@ -641,8 +643,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillParams p) {
     }
 }
 
+constexpr double kPassSeconds = 7e-6;  // what a pass of this kernel costs around its key loop (Q, first tiles, merge of the groups, write-out)
+
 struct Plan {
     int gs_log2, head_slots, tile_tokens, pair_ranks, n_splits;
+    bool rotate;
 };
 
 Plan make_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const AttnShape& a) {
@@ -666,9 +671,14 @@ Plan make_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const 
     } else {
         const int by_len = max_seq_len / (16 * kKvTile);  // at least 16 key tiles per range
         const double walks = paired_walks(max_q_len, max_seq_len);
-        double best = launch_model_seconds(wgs, 1, 128, total_q, max_seq_len, a.hq_l, walks);
+        // (with what the passes cost around their key loops: two per round of pairs, about 7 us each)
+        auto priced = [&](int sp) {
+            return launch_model_seconds(wgs, sp, 128, total_q, max_seq_len, a.hq_l, walks) +
+                   2.0 * static_cast<double>((wgs * sp + 255) / 256) * kPassSeconds;
+        };
+        double best = priced(1);
         for (int cand = 2; cand <= 16 && cand <= by_len; ++cand) {
-            const double t = launch_model_seconds(wgs, cand, 128, total_q, max_seq_len, a.hq_l, walks);
+            const double t = priced(cand);
             if (t < best * 0.97) {  // a further range must pay for itself
                 best = t;
                 splits = cand;
@@ -678,6 +688,7 @@ Plan make_plan(int num_seqs, int total_q, int max_q_len, int max_seq_len, const 
     if (splits < 1) splits = 1;
     if (splits > 64) splits = 64;
     pl.n_splits = splits;
+    pl.rotate = rotate_sequences_over_dies(num_seqs, pl.head_slots, total_q, max_q_len);
     return pl;
 }
 
@@ -732,10 +743,14 @@ Choice choose(int num_seqs, int total_q, int max_q_len, int max_seq_len, const A
     c.w = prefill_mfma64_plan(num_seqs, total_q, max_q_len, max_seq_len, a, option_prefill_splits());
     const int forced = option_prefill_tile();
     if (forced == 128) return c;
-    const long wgs_n = static_cast<long>(c.narrow.pair_ranks) * num_seqs * c.narrow.head_slots;
+    // Both priced with what their passes cost around the key loop (two passes per round of pairs here; the wide kernel's,
+    // about 15 us each, are in its plan); the 12 % are this kernel's slower loop.  The workgroups that weigh are counted
+    // as for the wide kernel: those of sequences shorter than the longest are light or leave at once.
+    const long wgs_n = static_cast<long>(c.narrow.pair_ranks * longest_chunk_equivalents(num_seqs, total_q, max_q_len) * c.narrow.head_slots + 0.999);
+    const double rounds_n = static_cast<double>((wgs_n * c.narrow.n_splits + 255) / 256);
     const double t_narrow = 1.12 * launch_model_seconds(wgs_n, c.narrow.n_splits, 128, total_q, max_seq_len, a.hq_l,
-                                                         paired_walks(max_q_len, max_seq_len));
-    c.wide = forced == 256 || c.w.model_seconds < 0.97 * t_narrow;
+                                                         paired_walks(max_q_len, max_seq_len)) + 2.0 * rounds_n * kPassSeconds;
+    c.wide = forced == 256 || c.w.model_with_passes < 0.97 * t_narrow;
     return c;
 }
 
@@ -805,6 +820,7 @@ hipError_t launch_prefill_mfma(const void* q, const void* cache, const int32_t* 
     p.gs_log2 = pl.gs_log2;
     p.head_slots = pl.head_slots;
     p.n_splits = pl.n_splits;
+    p.rotate = pl.rotate ? 1 : 0;
     p.max_blocks = max_blocks;
     p.c = c;
     p.out_scale = a.v_scale;

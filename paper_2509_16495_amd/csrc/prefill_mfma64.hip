@@ -165,6 +165,7 @@ struct Prefill64Params {
     int tile_tokens;  // kCols / G
     int n_splits;     // key ranges per tile
     int paired;       // tiles of a sequence taken two per workgroup (see prefill_mfma64_plan)
+    int rotate;       // the (sequence, KV head) index is rotated by the (tile rank, key range) index (see internal.h)
     int max_blocks;
     float c;          // softmax_scale * log2(e) (times k_scale for a cache widened from FP8)
     float out_scale;  // multiplies the normalised output: v_scale of an FP8 cache, else 1
@@ -183,6 +184,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
     item -= rank * (n_sg * p.n_splits);
     const int split = item / n_sg;
     item -= split * n_sg;
+    if (p.rotate) item = (item + n_sg - static_cast<int>((blockIdx.x / n_sg) % n_sg)) % n_sg;
     const int s = item / p.hkv_l;
     const int g = item - s * p.hkv_l;
 
@@ -764,7 +766,7 @@ Prefill64Plan prefill_mfma64_plan(int num_seqs, int total_q, int max_q_len, int 
     // the ranges, every range adds a partial result per (token, head) that the merge kernel writes and reads back - and
     // the cheaper plan is taken.
     constexpr double kPassSeconds = 15e-6;  // set-up, Q fetch, first and last tiles, write-out: what a pass costs around its loop
-    const long seq_heads = static_cast<long>(num_seqs) * a.hkv_l;
+    const double seqs_equiv = longest_chunk_equivalents(num_seqs, total_q, max_q_len);
     const int by_len = max_seq_len / (32 * kKv);  // at least 32 key tiles per range
     struct Cand {
         int splits;
@@ -784,7 +786,7 @@ Prefill64Plan prefill_mfma64_plan(int num_seqs, int total_q, int max_q_len, int 
     };
     const int pair_ranks = (tiles + 1) / 2;
     const Cand paired = best_of([&](int sp) {
-        const long wgs = pair_ranks * seq_heads;
+        const long wgs = static_cast<long>(pair_ranks) * num_seqs * a.hkv_l;
         const double rounds = static_cast<double>((wgs * sp + 255) / 256);
         return std::pair<double, double>(
             launch_model_seconds(wgs, sp, kCols, total_q, max_seq_len, a.hq_l, paired_walks(max_q_len, max_seq_len)), 2.0 * rounds);
@@ -794,9 +796,7 @@ Prefill64Plan prefill_mfma64_plan(int num_seqs, int total_q, int max_q_len, int 
         const double S = max_seq_len > 0 ? max_seq_len : 1, Q = max_q_len < max_seq_len ? max_q_len : max_seq_len;
         const double unit = 4.0 * 128 * kCols * S / 3.9e12, merge = 2.0 * total_q * a.hq_l * 130 * 4 / 4.0e12;
         const double base = (S - Q) / S, step = pl.tile_tokens / S;
-        // (the batch counted as total_q / max_q_len sequences of the longest chunk: the lengths themselves are on the device)
-        const double seqs = max_q_len > 0 && total_q < static_cast<double>(num_seqs) * max_q_len ? static_cast<double>(total_q) / max_q_len
-                                                                                                  : static_cast<double>(num_seqs);
+        const double seqs = seqs_equiv;
         const double total = (tiles * base + step * tiles * (tiles + 1) / 2.0) * seqs * a.hkv_l;
         const double heaviest = (base + step * tiles < 1.0 ? base + step * tiles : 1.0) / sp;
         const long items = static_cast<long>(tiles * seqs * a.hkv_l * sp + 0.5);
@@ -809,9 +809,11 @@ Prefill64Plan prefill_mfma64_plan(int num_seqs, int total_q, int max_q_len, int 
     pl.pair_ranks = pl.paired ? pair_ranks : tiles;
     int splits = pl.paired ? paired.splits : single.splits;
     pl.model_seconds = pl.paired ? paired.seconds : single.seconds;
+    pl.model_with_passes = pl.paired ? paired.with_passes : single.with_passes;
     if (splits < 1) splits = 1;
     if (splits > 64) splits = 64;
     pl.n_splits = splits;
+    pl.rotate = rotate_sequences_over_dies(num_seqs, a.hkv_l, total_q, max_q_len);
     pl.workgroups = static_cast<long>(pl.pair_ranks) * splits * num_seqs * a.hkv_l;
     return pl;
 }
@@ -849,6 +851,7 @@ hipError_t launch_prefill_mfma64(const void* q, const void* cache, const int32_t
     p.tile_tokens = pl.tile_tokens;
     p.n_splits = pl.n_splits;
     p.paired = pl.paired ? 1 : 0;
+    p.rotate = pl.rotate ? 1 : 0;
     p.max_blocks = max_blocks;
     p.c = c;
     p.out_scale = out_scale;
