@@ -328,7 +328,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             return min(2 * (kt_begin + j + (is_k ? 3 : 1)) + ld_blk, last_block);
         };
         int id_vec = 0;  // block id of the coming iteration's loads, in a vector register until they are issued
-        const int ld_limit = __builtin_amdgcn_readfirstlane(is_k ? n - 3 : n);  // iterations in which this wavefront loads
+        // iterations in which this wavefront loads: K of tiles 3 .. n - 1, V^T of tiles 1 .. n - 1 (a load beyond the last tile
+        // would be waited for, with its whole latency, in front of the last product)
+        const int ld_limit = n - __builtin_amdgcn_readfirstlane(is_k ? 3 : 1);
 
         // zero the V^T entries of keys at or past the context in the given stage (tile kt)
         auto clear_ragged_v = [&](int kt, int stage_off) SHIFTATTN_INLINE {
