@@ -335,9 +335,14 @@ int32_t shiftattn_use_base_config(int32_t n_tokens, int32_t threshold);
  *   SHIFTATTN_OPT_GENERIC_ONLY   1: every attention call runs the general kernel (any type / head_dim)
  *   SHIFTATTN_OPT_PREFILL_PAIRING 1 | 2: the 256-column prefill kernel takes a sequence's column tiles two per
  *                                workgroup, heaviest with lightest (1), or one per workgroup, heaviest first (2)
+ *   SHIFTATTN_OPT_PREFILL_EXACT_SCALE 1: the 256-column prefill kernel never rounds Q a second time.  By default its
+ *                                first attempt at a tile multiplies Q by the softmax scale and rounds it to bf16 again
+ *                                (one vector instruction per logit less; logits move by up to 2^-9 of their value, and a
+ *                                tile whose softmax sums leave [2^-40, 2^40] is redone on Q as given); with 1 every
+ *                                tile is computed on Q as given, the scale applied in fp32
  *   set returns EINVAL for an unknown option or value; get returns -1 for an unknown option. */
 enum { SHIFTATTN_OPT_PREFILL_TILE = 0, SHIFTATTN_OPT_PREFILL_SPLITS = 1, SHIFTATTN_OPT_GENERIC_ONLY = 2,
-       SHIFTATTN_OPT_PREFILL_PAIRING = 3, SHIFTATTN_OPT_COUNT = 4 };
+       SHIFTATTN_OPT_PREFILL_PAIRING = 3, SHIFTATTN_OPT_PREFILL_EXACT_SCALE = 4, SHIFTATTN_OPT_COUNT = 5 };
 int shiftattn_init(void);
 int shiftattn_set_option(int32_t option, int32_t value);
 int32_t shiftattn_get_option(int32_t option);

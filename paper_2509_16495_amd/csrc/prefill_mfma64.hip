@@ -76,8 +76,7 @@ constexpr float kRefSlack = 32.0f;
 // column's reference is the maximum of its first visible tile, P may then reach 2^kLazySlack (still far inside bf16 and
 // fp32 range; O^T overflows only for |V| beyond 2^27), and a running sum beyond that bound sends the pass to the
 // attempts that do follow the maximum.
-constexpr float kLazySlack = 100.0f;
-constexpr float kLazySumBound = 0x1p100f;
+constexpr float kFreeSumLo = 0x1p-40f, kFreeSumHi = 0x1p40f;
 
 __device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -166,6 +165,7 @@ struct Prefill64Params {
     int n_splits;     // key ranges per tile
     int paired;       // tiles of a sequence taken two per workgroup (see prefill_mfma64_plan)
     int rotate;       // the (sequence, KV head) index is rotated by the (tile rank, key range) index (see internal.h)
+    int exact_scale;  // every attempt works on Q^T as given (no attempt on the scaled, re-rounded Q^T)
     int max_blocks;
     float c;          // softmax_scale * log2(e) (times k_scale for a cache widened from FP8)
     float out_scale;  // multiplies the normalised output: v_scale of an FP8 cache, else 1
@@ -243,7 +243,6 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             :: "s"(m0v), "v"(off[0]), "v"(off[1]), "v"(off[2]), "v"(off[3]), "s"(src) : "memory");
     };
 
-    const float thr_tracked = kRefSlack / p.c, thr_lazy = kLazySlack / p.c;
 
     for (int pass = 0; pass < n_pass; ++pass) {
         const int tile = pass == 0 ? hi_tile : rank;
@@ -279,19 +278,45 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         for (int x = 0; x < 4; ++x) ld_off[x] = is_k ? k_ld[x] : v_ld;
         int pos_col[2];
         bf16x8 qf[2][8];
-        const uint16_t* q_ptr[2];
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
             const int cw = wave * 64 + cb * 32 + l32;
             const int tok = tok0 + cw / p.G;
             const bool valid = cw < cols_used && tok < q_len;
             pos_col[cb] = valid ? ctx - q_len + tok : -1;
-            // a column beyond the tile's or the sequence's end reads the row of the nearest real one: every one of its
-            // logits is masked (position -1) or its results are dropped, and columns do not mix
-            const int cw_r = min(cw, cols_used - 1);
-            const int tok_r = min(tok0 + cw_r / p.G, q_len - 1);
-            q_ptr[cb] = p.q + static_cast<size_t>(q_begin + tok_r) * p.q_stride + (g * p.G + cw_r % p.G) * kD + half * 8;
         }
+        // Q^T of this lane's columns into the accumulation registers.  with_scale: multiplied by the softmax scale (times
+        // log2 e, times k_scale of a cache widened from FP8) and rounded to bf16 again, for the attempt that follows no
+        // reference: its logits then leave the MFMAs in exp2 units and its loop spends no instruction on scaling them.
+        // (the addresses are formed here and not kept: a second fetch is rare)
+        auto fetch_q = [&](bool with_scale) SHIFTATTN_INLINE {
+            int lane_q = lane;
+            asm volatile("" : "+v"(lane_q));
+            const uint16_t* q_ptr[2];
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+                const int cw = wave * 64 + cb * 32 + (lane_q & 31);
+                // a column beyond the tile's or the sequence's end reads the row of the nearest real one: every one of
+                // its logits is masked (position -1) or its results are dropped, and columns do not mix
+                const int cw_r = min(cw, cols_used - 1);
+                const int tok_r = min(tok0 + cw_r / p.G, q_len - 1);
+                q_ptr[cb] = p.q + static_cast<size_t>(q_begin + tok_r) * p.q_stride + (g * p.G + cw_r % p.G) * kD + (lane_q >> 5) * 8;
+            }
+            load_q_to_acc(qf[0], qf[1], q_ptr[0], q_ptr[1]);
+            if (with_scale) {
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                    for (int ks = 0; ks < 8; ++ks) {
+                        bf16x8 v = qf[cb][ks];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = static_cast<__bf16>(static_cast<float>(v[e]) * p.c);
+                        qf[cb][ks] = v;
+                        // (the scaled value is made to look born in accumulation registers, as the loaded one was)
+                        asm volatile("" : "+a"(qf[cb][ks]));
+                    }
+            }
+        };
         const int w_tok_first = tok0 + (wave * 64) / p.G;
         const int w_pos_min =
             __builtin_amdgcn_readfirstlane((wave * 64 < cols_used && w_tok_first < q_len) ? ctx - q_len + w_tok_first : -1);
@@ -313,7 +338,8 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         // the reference covers (reference + slack), running sum
         float m_used[2] = {-INFINITY, -INFINITY}, mc[2] = {0.f, 0.f}, bound[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
         bool redo = false;          // uniform: a column of this wavefront needed a rescaling the key loop does not do
-        float thr = thr_lazy;       // how far a logit may exceed the reference (of the current attempt)
+        float m_rep[2] = {-INFINITY, -INFINITY};
+        const float thr = kRefSlack / p.c;  // how far a logit may exceed the reference (attempts that follow the maximum)
 
         // Ring of three LDS stages: K of tile t and V^T of tile t live in stage t % 3.  Iteration j reads K of tile
         // j + 1 and V^T of tile j - 1 and loads K of tile j + 3 and V^T of tile j + 1, so everything an iteration reads
@@ -402,6 +428,8 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             if constexpr (!HAS_C) v_cur += d_next;
 
             if (key0 + kKv - 1 > w_pos_min) {  // tile crosses the diagonal of this wavefront: uniform
+                // (a real branch: the selects below take their inputs from a statement that cannot be moved out of it)
+                asm volatile("; keys beyond a column's position" : "+v"(s_cur[0]), "+v"(s_cur[1]));
 #pragma unroll
                 for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
@@ -421,9 +449,17 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             auto finish_prev = [&](auto vc) SHIFTATTN_INLINE {  // finishes logit v - 1
                 constexpr int v = decltype(vc)::value;
                 constexpr int pv = v - 1, cb = pv / 16, r = pv % 16;
-                // (the empty asm statement pins the sum, and with it the exponential it adds, to this slot)
-                l_run[cb] += e_last;
-                asm volatile("" : "+v"(l_run[cb]));
+                // The row sum runs one logit further behind (logit v - 2): the first vector instruction behind a slot's MFMA
+                // then never reads the exponential issued last, which would cost a wait state.
+                // (the empty asm statement pins the sum to this slot)
+                if constexpr (pv >= 1) {
+                    l_run[(pv - 1) / 16] += e_last2;
+                    asm volatile("" : "+v"(l_run[(pv - 1) / 16]));
+                }
+                if constexpr (pv == 31) {
+                    l_run[1] += e_last;
+                    asm volatile("" : "+v"(l_run[1]));
+                }
                 if constexpr (r % 2 == 1) {
                     bf16x2 t;
                     t[0] = static_cast<__bf16>(e_last2);
@@ -436,7 +472,8 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             auto chunk = [&](auto vc) SHIFTATTN_INLINE {
                 constexpr int v = decltype(vc)::value;
                 constexpr int cb = v / 16, r = v % 16;
-                const float e = __builtin_amdgcn_exp2f(fmaf(s_cur[cb][r], p.c, -mc[cb]));
+                // (no reference followed: Q^T carries the scale, the logit arrives in exp2 units)
+                const float e = TRACK ? __builtin_amdgcn_exp2f(fmaf(s_cur[cb][r], p.c, -mc[cb])) : __builtin_amdgcn_exp2f(s_cur[cb][r]);
                 if constexpr (v >= 1) finish_prev(IC<v>{});
                 if constexpr (TRACK && r % 2 == 1) {
                     mx[cb] = fmaxf(fmaxf(mx[cb], s_cur[cb][r - 1]), s_cur[cb][r]);
@@ -513,10 +550,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             }
 
             // ---- the tile's maximum against what the reference covers: rarely, a new reference ------------------
-            if constexpr (!TRACK) {
-                // no maximum was taken: a sum that has left the range the reference was meant to keep it in flags the pass
-                if (__builtin_expect(__builtin_amdgcn_ballot_w64(l_run[0] > kLazySumBound || l_run[1] > kLazySumBound) != 0, 0)) redo = true;
-            } else
+            if constexpr (TRACK)
             if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx[0] > bound[0] || mx[1] > bound[1]) != 0, 0)) {
                 // A column that meets its first visible keys has no sums yet (O^T = 0, l = 0): its reference is set and
                 // the tile's P recomputed, nothing else.  A column that already holds sums would need them rescaled;
@@ -569,7 +603,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         };
         // The first attempt's go out in front of the fetch of Q^T, whose wait then covers both.
         if (n > 0) issue_prologue();
-        load_q_to_acc(qf[0], qf[1], q_ptr[0], q_ptr[1]);
+        fetch_q(!p.exact_scale);
 
         // Up to three attempts at the pass.  The first follows no maximum behind the first key tile (its steady-state
         // bodies save the instruction per two logits that would collect it; real logits stay within 2^100 of their
@@ -577,14 +611,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         // follows the maximum tile by tile; it can end flagged itself (a column outgrew its reference after it had sums),
         // and then holds, for every column, a reference within the slack of the true maximum: the third attempt starts
         // from that and is not flagged.
-        for (int attempt = 0; attempt < 3; ++attempt) {
+        const int first_attempt = p.exact_scale ? 1 : 0;
+        for (int attempt = first_attempt; attempt < 3; ++attempt) {
         redo = false;
-        const bool lazy = attempt == 0;
-        thr = lazy ? thr_lazy : thr_tracked;
-        if (attempt == 1) {   // forget the first attempt's references
-#pragma unroll
-            for (int cb = 0; cb < 2; ++cb) m_used[cb] = -INFINITY, mc[cb] = 0.f, bound[cb] = -INFINITY;
-        }
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
             l_run[cb] = 0.f;
@@ -593,9 +622,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[cb][mt][r] = 0.f;
         }
-        if (n > 0) {
+        auto key_loop = [&](auto track_c) SHIFTATTN_INLINE {
             // prologue: the loads (already on their way in the first attempt), S^T of the first tile
-            if (attempt > 0) issue_prologue();
+            if (attempt > first_attempt) issue_prologue();
             st0 = 0, st1 = kStageBytes, st2 = 2 * kStageBytes;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) k_cur[ks] = k_rd[ks] + kStageBytes;   // iteration 0 reads K of tile 1
@@ -615,27 +644,20 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             k_cur[0] += kStageBytes;  // on to stage 2: iteration 1's first K operand
             mfma_settle();
             if (n == 1) {
-                body(IC<0>{}, IC<0>{}, IC<0>{}, IC<1>{}, IC<1>{}, 0);
+                body(IC<0>{}, IC<0>{}, IC<0>{}, IC<1>{}, track_c, 0);
             } else {
-                body(IC<0>{}, IC<1>{}, IC<0>{}, IC<1>{}, IC<1>{}, 0);
+                body(IC<0>{}, IC<1>{}, IC<0>{}, IC<1>{}, track_c, 0);
                 int j = 1;  // stays odd: the steady-state loop takes two tiles per trip so that the register sets of
                             // even and odd tiles are fixed at compile time
-                if (lazy) {
-                    for (; j + 2 < n; j += 2) {
-                        body(IC<1>{}, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{}, j);
-                        body(IC<0>{}, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{}, j + 1);
-                    }
-                } else {
-                    for (; j + 2 < n; j += 2) {
-                        body(IC<1>{}, IC<1>{}, IC<1>{}, IC<0>{}, IC<1>{}, j);
-                        body(IC<0>{}, IC<1>{}, IC<1>{}, IC<0>{}, IC<1>{}, j + 1);
-                    }
+                for (; j + 2 < n; j += 2) {
+                    body(IC<1>{}, IC<1>{}, IC<1>{}, IC<0>{}, track_c, j);
+                    body(IC<0>{}, IC<1>{}, IC<1>{}, IC<0>{}, track_c, j + 1);
                 }
                 if (j + 1 < n) {
-                    body(IC<1>{}, IC<1>{}, IC<1>{}, IC<1>{}, IC<1>{}, j);
-                    body(IC<0>{}, IC<0>{}, IC<1>{}, IC<1>{}, IC<1>{}, j + 1);
+                    body(IC<1>{}, IC<1>{}, IC<1>{}, IC<1>{}, track_c, j);
+                    body(IC<0>{}, IC<0>{}, IC<1>{}, IC<1>{}, track_c, j + 1);
                 } else {
-                    body(IC<1>{}, IC<0>{}, IC<1>{}, IC<1>{}, IC<1>{}, j);
+                    body(IC<1>{}, IC<0>{}, IC<1>{}, IC<1>{}, track_c, j);
                 }
             }
             // epilogue: O^T += V^T P^T of the last tile (tile n - 1, in stage (n - 1) % 3 = st2 by now)
@@ -662,6 +684,27 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             if (lp) last_c(IC<1>{});
             else last_c(IC<0>{});
             mfma_settle();
+        };
+        if (n > 0) {
+            if (attempt == 0) key_loop(IC<0>{});
+            else key_loop(IC<1>{});
+        }
+        if (attempt == 0) {
+            // No reference was used (P = exp2 of the logit itself).  That is exact as long as nothing left the range
+            // bf16 and the fp32 sums hold without loss: a column that sees keys of this range must end with a sum inside
+            // [2^-60, 2^100] (its largest P then lies within a factor "number of keys" of the sum, far from bf16's
+            // denormals and from overflow; an infinity or a NaN fails the test as well).  Otherwise the pass is flagged.
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+                const float l_tot = l_run[cb] + __shfl_xor(l_run[cb], 32);
+                const bool sees = n > 0 && pos_col[cb] >= kt_begin * kKv;
+                if (sees && !(l_tot >= kFreeSumLo && l_tot <= kFreeSumHi)) redo = true;
+                m_rep[cb] = sees ? 0.f : -INFINITY;   // what a partial result reports as its reference (exp2 units)
+            }
+            redo = __builtin_amdgcn_ballot_w64(redo) != 0;
+        } else {
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) m_rep[cb] = m_used[cb] * p.c;
         }
         if (attempt == 2) break;
         int* flags = reinterpret_cast<int*>(lds + kRingBytes + kCols * kPitch);
@@ -669,6 +712,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         __syncthreads();  // also: every wavefront is done with the ring
         const int any_redo = flags[0] | flags[1] | flags[2] | flags[3];
         if (__builtin_expect(__builtin_amdgcn_readfirstlane(any_redo) == 0, 1)) break;
+        if (attempt == 0) fetch_q(false);   // the attempts that follow the maximum work on Q^T as given, scale in the loop
         }
 
         // ---- results of the pass ----------------------------------------------------------------------------
@@ -732,7 +776,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
                             *reinterpret_cast<f32x4*>(op + 32 * mt + 8 * r4) = v;
                         }
                     if (half_m == 0) {
-                        p.ml_part[prow * 2] = m_used[cb] * p.c;  // -inf when this key range held no visible key
+                        p.ml_part[prow * 2] = m_rep[cb];  // exp2 units; -inf when this key range held no visible key
                         p.ml_part[prow * 2 + 1] = l_tot;
                     }
                 }
@@ -854,6 +898,7 @@ hipError_t launch_prefill_mfma64(const void* q, const void* cache, const int32_t
     p.n_splits = pl.n_splits;
     p.paired = pl.paired ? 1 : 0;
     p.rotate = pl.rotate ? 1 : 0;
+    p.exact_scale = option_prefill_exact_scale() ? 1 : 0;
     p.max_blocks = max_blocks;
     p.c = c;
     p.out_scale = out_scale;

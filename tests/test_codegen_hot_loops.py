@@ -48,10 +48,11 @@ def _blocks_of(source, kernel_substr, tmp_path):
 def test_prefill64_steady_state_loop_has_no_spills(tmp_path):
     blocks = _blocks_of("prefill_mfma64.hip", "prefill64_kernel", tmp_path)
     heavy = [i for i, b in enumerate(blocks) if b[1] >= 24]      # bodies of an iteration: 32 MFMAs, a few of them in a block in front
-    assert len(heavy) >= 4, [tuple(b) for b in blocks if b[1]]
-    # the two bodies of the first attempt's loop (no maximum followed) are the shortest of them
-    lazy = sorted(heavy, key=lambda i: blocks[i][3])[:2]
-    for i in lazy:
+    # the steady-state bodies (two of the attempt that follows no reference, two of those that follow the maximum) are the
+    # short ones; the bodies next to a pass's ends carry wait states in front of every MFMA and are far longer
+    steady = [i for i in heavy if blocks[i][3] < 300]
+    assert len(steady) >= 4, [tuple(b) for b in blocks if b[1]]
+    for i in steady:
         body = blocks[i]
         assert body[2] == 0, ("spill traffic in a steady-state body", tuple(body))
         front = blocks[i - 1]                                   # barrier, refill of the ring and the body's first MFMAs
