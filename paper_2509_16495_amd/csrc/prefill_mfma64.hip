@@ -19,16 +19,18 @@
 // with bits 2 and 3 of the K row index swapped in the MFMA row assignment, so that the keys a lane holds are runs
 // of eight consecutive tokens (one 16-byte piece of a dimension-major V row).
 //
-// Softmax against a reference that lags.  The exponentials of a tile are taken against the column's reference maximum
-// as it stood when the tile began, so they do not wait for the tile's own maximum and spread evenly over the MFMA
-// slots.  The first attempt at a pass takes the reference from the column's first visible key tile and then follows
-// no maximum at all in its steady-state iterations (one vector instruction per two logits less): softmax does not
-// care which reference it is shifted by as long as nothing overflows, real logits stay within 2^100 of their first
-// tile's maximum, and P up to 2^100 is held by bf16 and the fp32 sums without loss.  A running sum that leaves that
-// range flags the pass; it is then run again with the tile's maximum collected on the side and checked against the
-// reference (slack 2^32): a column that has no sums yet takes a new reference and recomputes the tile's P from the
-// S^T values it still holds, one that has sums flags the pass once more, and the third attempt starts from references
-// within the slack of every column's true maximum.  O^T is never rescaled inside the loop.
+// Softmax without a reference, and against one that lags.  Softmax does not care which reference its exponentials are
+// shifted by as long as nothing leaves the range of bf16 and the fp32 sums.  The first attempt at a pass uses none: Q^T
+// takes the softmax scale when it is fetched (rounded to bf16 again: a logit moves by at most 2^-9 of its value), the
+// logits leave the MFMAs in exp2 units, and P is the exp2 of the logit itself - two vector instructions per logit
+// (exponential, row sum) and one per two (packing) is all the loop spends on the softmax.  A column that sees keys must
+// end the pass with a sum inside [2^-40, 2^40]; otherwise the pass is flagged, Q^T fetched again as given, and the pass
+// run again the careful way, the scale applied in fp32: the exponentials of a tile are taken against the column's
+// reference maximum as it stood when the tile began (so they do not wait for the tile's own maximum and spread evenly
+// over the MFMA slots), the tile's maximum is collected on the side and checked against the reference (slack 2^32): a
+// column that has no sums yet takes a new reference and recomputes the tile's P from the S^T values it still holds, one
+// that has sums flags the pass once more, and the third attempt starts from references within the slack of every
+// column's true maximum.  O^T is never rescaled inside the loop.  (A process-wide switch sends every pass the careful way.)
 //
 // Pipeline of iteration j: S^T of tile j+1 (16 MFMAs), softmax of tile j, O^T += V^T P^T of tile j-1 (16 MFMAs).
 // LDS holds a ring of three stages of K (32 keys) + V^T (32 keys), tile t in stage t%3.  During iteration j
@@ -72,10 +74,10 @@ constexpr int kLdsBytes = kRingBytes + kCols * kPitch + kFlagBytes;  // 118800
 // inside what bf16 and the fp32 sums hold (their relative precision does not depend on magnitude); O^T overflows only
 // for |V| beyond 2^70.
 constexpr float kRefSlack = 32.0f;
-// The first attempt at a pass does not follow the maximum at all behind its first key tile (see prefill64_kernel): a
-// column's reference is the maximum of its first visible tile, P may then reach 2^kLazySlack (still far inside bf16 and
-// fp32 range; O^T overflows only for |V| beyond 2^27), and a running sum beyond that bound sends the pass to the
-// attempts that do follow the maximum.
+// The first attempt at a pass uses no reference (see the top of the file): the sum of a column that sees keys must end
+// inside this range - its largest P then lies within a factor "number of keys" of the sum, far from bf16's denormals and
+// from overflow (O^T overflows only for |V| beyond 2^87), and every logit that matters lies within 40 + log2(keys) of
+// zero, which bounds what the second rounding of Q^T can move (2^-9 of the logit).  An infinity or a NaN fails the test.
 constexpr float kFreeSumLo = 0x1p-40f, kFreeSumHi = 0x1p40f;
 
 __device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
