@@ -242,6 +242,11 @@ int shiftattn_kv_write(const void *k_new, const void *v_new, const int64_t *slot
  * out (device, out)         : [total_q][hq_l][D], row stride a->out_stride
  * workspace (device)        : at least shiftattn_prefill_workspace_bytes(...) bytes, 16-byte
  *                             aligned; may be NULL when that is 0.  Contents are scratch.
+ * Arithmetic of the bf16 path: logits and outputs accumulate in fp32, the softmax runs in fp32, the
+ * probabilities are rounded to bf16 before the second product, the output once at the end.  Launches
+ * with many columns additionally round Q times the softmax scale to bf16 once per tile (a logit
+ * moves by at most 2^-9 of its value; tiles with extreme logits are recomputed without it);
+ * SHIFTATTN_OPT_PREFILL_EXACT_SCALE switches that off.
  * num_seqs == 0 or total_q == 0 is a valid no-op. */
 int shiftattn_prefill(const void *q, const void *k_new, const void *v_new, const int64_t *slot_mapping,
                       void *kv_cache, const int32_t *block_table, const int32_t *cu_seqlens_q,
