@@ -337,6 +337,15 @@ def main() -> int:
                     traffic_key="chunk_prefill_long_context", flops_per_launch=pre5.flops(), median_launch_ms=round(ck_ms, 5))
     dd_ms = phases["decodes"]["ms"]
     dd_gbps = dec5.kv_bytes() / (dd_ms * 1e-3) / 1e9
+    # the chunk's attention with the opt-in switch that lets Q carry the softmax scale (one more rounding of Q to bf16; off
+    # by default and in everything else this run measures)
+    B.set_option(B.OPT_PREFILL_SCALED_Q, 1)
+    try:
+        sq_ms = time_events(do_chunk_only, reps)
+    finally:
+        B.set_option(B.OPT_PREFILL_SCALED_Q, 0)
+    sq_tf = pre5.flops() / (sq_ms * 1e-3) / 1e12
+    log(f"[bench] chunk attention alone: with SHIFTATTN_OPT_PREFILL_SCALED_Q {sq_ms * 1e3:.1f} us, {sq_tf:.1f} TFLOP/s ({sq_tf / PEAK_BF16_TFLOPS:.1%} of peak)")
 
     result = {
         "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -352,6 +361,12 @@ def main() -> int:
         "decode_in_step": {"kv_bytes": dec5.kv_bytes(), "ms": round(dd_ms, 5),
                            "roofline": roof("decode_flat_kernel + combine_flat_kernel", "hbm", dd_gbps, PEAK_HBM_GBPS, "GB/s", traffic_key="decode_64_long_contexts")},
         "ms_per_step_graph_replay": round(ms_per_step_graph, 5),
+        "chunk_prefill_with_scaled_q": {
+            "ms": round(sq_ms, 5), "roofline": roof("prefill64_kernel, SHIFTATTN_OPT_PREFILL_SCALED_Q = 1", "mfma", sq_tf, PEAK_BF16_TFLOPS, "TFLOP/s"),
+            "note": "opt-in, not the path the step above runs: Q is multiplied by the softmax scale per tile and rounded to bf16 again, the "
+                    "loop then spends no instruction on scaling logits; a logit moves by up to 2^-9 of its value and outputs of magnitude "
+                    "2 and more can land one bf16 step from the correctly rounded value; timed alone in a loop (the chunk's K/V then stay "
+                    "in the cache in front of HBM, which makes it 2-3 % faster than inside the step)"},
         "timing_state": {"settle_ms": SETTLE_MS * args.settle_scale, "ms_per_step_first_steps_after_a_pause": round(ms_per_step_after_idle, 5),
                          "note": "every timed region starts after settle_ms (3x for the step) of the same work back to back: the "
                                  "chip's clock under the power limit takes 15-20 ms of load to settle, and matrix-heavy kernels run "

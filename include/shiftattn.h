@@ -242,11 +242,9 @@ int shiftattn_kv_write(const void *k_new, const void *v_new, const int64_t *slot
  * out (device, out)         : [total_q][hq_l][D], row stride a->out_stride
  * workspace (device)        : at least shiftattn_prefill_workspace_bytes(...) bytes, 16-byte
  *                             aligned; may be NULL when that is 0.  Contents are scratch.
- * Arithmetic of the bf16 path: logits and outputs accumulate in fp32, the softmax runs in fp32, the
- * probabilities are rounded to bf16 before the second product, the output once at the end.  Launches
- * with many columns additionally round Q times the softmax scale to bf16 once per tile (a logit
- * moves by at most 2^-9 of its value; tiles with extreme logits are recomputed without it);
- * SHIFTATTN_OPT_PREFILL_EXACT_SCALE switches that off.
+ * Arithmetic of the bf16 path: logits and outputs accumulate in fp32, the softmax (scale included)
+ * runs in fp32, the probabilities are rounded to bf16 before the second product, the output once
+ * at the end.  (SHIFTATTN_OPT_PREFILL_SCALED_Q trades one more rounding of Q for speed.)
  * num_seqs == 0 or total_q == 0 is a valid no-op. */
 int shiftattn_prefill(const void *q, const void *k_new, const void *v_new, const int64_t *slot_mapping,
                       void *kv_cache, const int32_t *block_table, const int32_t *cu_seqlens_q,
@@ -340,14 +338,15 @@ int32_t shiftattn_use_base_config(int32_t n_tokens, int32_t threshold);
  *   SHIFTATTN_OPT_GENERIC_ONLY   1: every attention call runs the general kernel (any type / head_dim)
  *   SHIFTATTN_OPT_PREFILL_PAIRING 1 | 2: the 256-column prefill kernel takes a sequence's column tiles two per
  *                                workgroup, heaviest with lightest (1), or one per workgroup, heaviest first (2)
- *   SHIFTATTN_OPT_PREFILL_EXACT_SCALE 1: the 256-column prefill kernel never rounds Q a second time.  By default its
- *                                first attempt at a tile multiplies Q by the softmax scale and rounds it to bf16 again
- *                                (one vector instruction per logit less; logits move by up to 2^-9 of their value, and a
- *                                tile whose softmax sums leave [2^-40, 2^40] is redone on Q as given); with 1 every
- *                                tile is computed on Q as given, the scale applied in fp32
+ *   SHIFTATTN_OPT_PREFILL_SCALED_Q 1: the 256-column prefill kernel multiplies Q by the softmax scale when a tile
+ *                                fetches it and rounds it to bf16 again, so that its loop spends no instruction
+ *                                on scaling logits (about 5 % faster).  A logit then moves by up to 2^-9 of its
+ *                                value: outputs of magnitude 2 and more can land one bf16 step from the correctly
+ *                                rounded value.  Tiles whose softmax sums leave [2^-40, 2^40] are recomputed on Q
+ *                                as given.  Off by default: the scale is applied to the fp32 logits
  *   set returns EINVAL for an unknown option or value; get returns -1 for an unknown option. */
 enum { SHIFTATTN_OPT_PREFILL_TILE = 0, SHIFTATTN_OPT_PREFILL_SPLITS = 1, SHIFTATTN_OPT_GENERIC_ONLY = 2,
-       SHIFTATTN_OPT_PREFILL_PAIRING = 3, SHIFTATTN_OPT_PREFILL_EXACT_SCALE = 4, SHIFTATTN_OPT_COUNT = 5 };
+       SHIFTATTN_OPT_PREFILL_PAIRING = 3, SHIFTATTN_OPT_PREFILL_SCALED_Q = 4, SHIFTATTN_OPT_COUNT = 5 };
 int shiftattn_init(void);
 int shiftattn_set_option(int32_t option, int32_t value);
 int32_t shiftattn_get_option(int32_t option);

@@ -104,7 +104,7 @@ def lib() -> ctypes.CDLL:
     return _lib
 
 
-OPT_PREFILL_TILE, OPT_PREFILL_SPLITS, OPT_GENERIC_ONLY, OPT_PREFILL_PAIRING, OPT_PREFILL_EXACT_SCALE = 0, 1, 2, 3, 4
+OPT_PREFILL_TILE, OPT_PREFILL_SPLITS, OPT_GENERIC_ONLY, OPT_PREFILL_PAIRING, OPT_PREFILL_SCALED_Q = 0, 1, 2, 3, 4
 
 
 def init() -> None:

@@ -227,7 +227,7 @@ namespace shiftattn {
 int option_prefill_tile() { return g_options[SHIFTATTN_OPT_PREFILL_TILE].load(std::memory_order_relaxed); }
 int option_prefill_splits() { return g_options[SHIFTATTN_OPT_PREFILL_SPLITS].load(std::memory_order_relaxed); }
 int option_prefill_pairing() { return g_options[SHIFTATTN_OPT_PREFILL_PAIRING].load(std::memory_order_relaxed); }
-int option_prefill_exact_scale() { return g_options[SHIFTATTN_OPT_PREFILL_EXACT_SCALE].load(std::memory_order_relaxed); }
+int option_prefill_scaled_q() { return g_options[SHIFTATTN_OPT_PREFILL_SCALED_Q].load(std::memory_order_relaxed); }
 }  // namespace shiftattn
 
 extern "C" {
@@ -255,8 +255,8 @@ int shiftattn_set_option(int32_t option, int32_t value) {
         case SHIFTATTN_OPT_PREFILL_PAIRING:
             if (value < 0 || value > 2) return fail(SHIFTATTN_EINVAL, "SHIFTATTN_OPT_PREFILL_PAIRING takes 0, 1 or 2, not %d", value);
             break;
-        case SHIFTATTN_OPT_PREFILL_EXACT_SCALE:
-            if (value != 0 && value != 1) return fail(SHIFTATTN_EINVAL, "SHIFTATTN_OPT_PREFILL_EXACT_SCALE takes 0 or 1, not %d", value);
+        case SHIFTATTN_OPT_PREFILL_SCALED_Q:
+            if (value != 0 && value != 1) return fail(SHIFTATTN_EINVAL, "SHIFTATTN_OPT_PREFILL_SCALED_Q takes 0 or 1, not %d", value);
             break;
         default:
             return fail(SHIFTATTN_EINVAL, "unknown option %d", option);

@@ -142,7 +142,7 @@ hipError_t proj_stream_init();
 int option_prefill_tile();    // 0, 128 or 256
 int option_prefill_splits();  // 0 or the number of key ranges
 int option_prefill_pairing(); // 0, 1 (tiles in pairs) or 2 (one tile per workgroup)
-int option_prefill_exact_scale();  // 1: the 256-column kernel works on Q as given in every attempt
+int option_prefill_scaled_q();     // 1: the 256-column kernel's first attempt works on Q times the scale, re-rounded
 
 // proj_gemm.hip : the projections in front of the first exchange and behind the second (bf16, head_dim 128)
 bool qkv_proj_pack_supported(const XchgShape& s, int d_model, int elem);

@@ -167,7 +167,7 @@ struct Prefill64Params {
     int n_splits;     // key ranges per tile
     int paired;       // tiles of a sequence taken two per workgroup (see prefill_mfma64_plan)
     int rotate;       // the (sequence, KV head) index is rotated by the (tile rank, key range) index (see internal.h)
-    int exact_scale;  // every attempt works on Q^T as given (no attempt on the scaled, re-rounded Q^T)
+    int scaled_q;     // the first attempt at a pass works on Q^T times the softmax scale, rounded to bf16 again
     int max_blocks;
     float c;          // softmax_scale * log2(e) (times k_scale for a cache widened from FP8)
     float out_scale;  // multiplies the normalised output: v_scale of an FP8 cache, else 1
@@ -383,7 +383,10 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         // of a pass's first attempt, which check the running sums instead)
         auto body = [&](auto par_c, auto has_a_c, auto has_c_c, auto guard_c, auto track_c, int j) SHIFTATTN_INLINE {
             constexpr int PAR = decltype(par_c)::value;
-            constexpr bool TRACK = decltype(track_c)::value != 0;
+            // track_c: 1 = the maximum is followed (TRACK); 0 and 2 = no reference at all, on logits that arrive in exp2
+            // units (Q^T carries the scale) or that take the scale here in fp32
+            constexpr bool TRACK = decltype(track_c)::value == 1;
+            constexpr bool SCALE_HERE = decltype(track_c)::value == 2;
             constexpr bool GUARD = decltype(guard_c)::value != 0;  // outside the steady-state loop
             constexpr bool HAS_A = decltype(has_a_c)::value != 0;
             constexpr bool HAS_C = decltype(has_c_c)::value != 0;
@@ -475,7 +478,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
                 constexpr int v = decltype(vc)::value;
                 constexpr int cb = v / 16, r = v % 16;
                 // (no reference followed: Q^T carries the scale, the logit arrives in exp2 units)
-                const float e = TRACK ? __builtin_amdgcn_exp2f(fmaf(s_cur[cb][r], p.c, -mc[cb])) : __builtin_amdgcn_exp2f(s_cur[cb][r]);
+                const float e = TRACK        ? __builtin_amdgcn_exp2f(fmaf(s_cur[cb][r], p.c, -mc[cb]))
+                                : SCALE_HERE ? __builtin_amdgcn_exp2f(s_cur[cb][r] * p.c)
+                                             : __builtin_amdgcn_exp2f(s_cur[cb][r]);
                 if constexpr (v >= 1) finish_prev(IC<v>{});
                 if constexpr (TRACK && r % 2 == 1) {
                     mx[cb] = fmaxf(fmaxf(mx[cb], s_cur[cb][r - 1]), s_cur[cb][r]);
@@ -605,7 +610,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         };
         // The first attempt's go out in front of the fetch of Q^T, whose wait then covers both.
         if (n > 0) issue_prologue();
-        fetch_q(!p.exact_scale);
+        fetch_q(p.scaled_q != 0);
 
         // Up to three attempts at the pass.  The first follows no maximum behind the first key tile (its steady-state
         // bodies save the instruction per two logits that would collect it; real logits stay within 2^100 of their
@@ -613,8 +618,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         // follows the maximum tile by tile; it can end flagged itself (a column outgrew its reference after it had sums),
         // and then holds, for every column, a reference within the slack of the true maximum: the third attempt starts
         // from that and is not flagged.
-        const int first_attempt = p.exact_scale ? 1 : 0;
-        for (int attempt = first_attempt; attempt < 3; ++attempt) {
+        for (int attempt = 0; attempt < 3; ++attempt) {
         redo = false;
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
@@ -626,7 +630,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         }
         auto key_loop = [&](auto track_c) SHIFTATTN_INLINE {
             // prologue: the loads (already on their way in the first attempt), S^T of the first tile
-            if (attempt > first_attempt) issue_prologue();
+            if (attempt > 0) issue_prologue();
             st0 = 0, st1 = kStageBytes, st2 = 2 * kStageBytes;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) k_cur[ks] = k_rd[ks] + kStageBytes;   // iteration 0 reads K of tile 1
@@ -688,8 +692,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             mfma_settle();
         };
         if (n > 0) {
-            if (attempt == 0) key_loop(IC<0>{});
-            else key_loop(IC<1>{});
+            if (attempt > 0) key_loop(IC<1>{});
+            else if (p.scaled_q) key_loop(IC<0>{});
+            else key_loop(IC<2>{});
         }
         if (attempt == 0) {
             // No reference was used (P = exp2 of the logit itself).  That is exact as long as nothing left the range
@@ -714,7 +719,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         __syncthreads();  // also: every wavefront is done with the ring
         const int any_redo = flags[0] | flags[1] | flags[2] | flags[3];
         if (__builtin_expect(__builtin_amdgcn_readfirstlane(any_redo) == 0, 1)) break;
-        if (attempt == 0) fetch_q(false);   // the attempts that follow the maximum work on Q^T as given, scale in the loop
+        if (attempt == 0 && p.scaled_q) fetch_q(false);   // the attempts that follow the maximum work on Q^T as given
         }
 
         // ---- results of the pass ----------------------------------------------------------------------------
@@ -900,7 +905,7 @@ hipError_t launch_prefill_mfma64(const void* q, const void* cache, const int32_t
     p.n_splits = pl.n_splits;
     p.paired = pl.paired ? 1 : 0;
     p.rotate = pl.rotate ? 1 : 0;
-    p.exact_scale = option_prefill_exact_scale() ? 1 : 0;
+    p.scaled_q = option_prefill_scaled_q() ? 1 : 0;
     p.max_blocks = max_blocks;
     p.c = c;
     p.out_scale = out_scale;

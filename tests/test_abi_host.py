@@ -43,9 +43,9 @@ def test_every_declared_symbol_is_exported(B):
 def test_options_and_their_bounds(B):
     """The tuning switches: defaults are 0, values are range-checked, unknown options refused."""
     L = B.lib()
-    for opt in (B.OPT_PREFILL_TILE, B.OPT_PREFILL_SPLITS, B.OPT_GENERIC_ONLY, B.OPT_PREFILL_PAIRING, B.OPT_PREFILL_EXACT_SCALE):
+    for opt in (B.OPT_PREFILL_TILE, B.OPT_PREFILL_SPLITS, B.OPT_GENERIC_ONLY, B.OPT_PREFILL_PAIRING, B.OPT_PREFILL_SCALED_Q):
         assert B.get_option(opt) == 0
-    assert L.shiftattn_set_option(B.OPT_PREFILL_EXACT_SCALE, 2) == B.EINVAL
+    assert L.shiftattn_set_option(B.OPT_PREFILL_SCALED_Q, 2) == B.EINVAL
     assert L.shiftattn_set_option(B.OPT_PREFILL_PAIRING, 3) == B.EINVAL and L.shiftattn_set_option(B.OPT_PREFILL_PAIRING, -1) == B.EINVAL
     assert L.shiftattn_set_option(B.OPT_PREFILL_TILE, 64) == B.EINVAL
     assert L.shiftattn_set_option(B.OPT_PREFILL_SPLITS, 65) == B.EINVAL and L.shiftattn_set_option(B.OPT_PREFILL_SPLITS, -1) == B.EINVAL
@@ -60,7 +60,7 @@ def test_options_and_their_bounds(B):
         B.set_option(B.OPT_GENERIC_ONLY, 1)
         assert B.prefill_workspace_bytes(1, 2048, 2048, 133120, a) == 0 and B.decode_workspace_bytes(4, 64, a) == 0
     finally:
-        for opt in (B.OPT_PREFILL_TILE, B.OPT_PREFILL_SPLITS, B.OPT_GENERIC_ONLY, B.OPT_PREFILL_PAIRING, B.OPT_PREFILL_EXACT_SCALE):
+        for opt in (B.OPT_PREFILL_TILE, B.OPT_PREFILL_SPLITS, B.OPT_GENERIC_ONLY, B.OPT_PREFILL_PAIRING, B.OPT_PREFILL_SCALED_Q):
             B.set_option(opt, 0)
     assert B.prefill_workspace_bytes(1, 2048, 2048, 133120, a) == auto
 
