@@ -20,17 +20,19 @@
 // of eight consecutive tokens (one 16-byte piece of a dimension-major V row).
 //
 // Softmax without a reference, and against one that lags.  Softmax does not care which reference its exponentials are
-// shifted by as long as nothing leaves the range of bf16 and the fp32 sums.  The first attempt at a pass uses none: Q^T
-// takes the softmax scale when it is fetched (rounded to bf16 again: a logit moves by at most 2^-9 of its value), the
-// logits leave the MFMAs in exp2 units, and P is the exp2 of the logit itself - two vector instructions per logit
-// (exponential, row sum) and one per two (packing) is all the loop spends on the softmax.  A column that sees keys must
-// end the pass with a sum inside [2^-40, 2^40]; otherwise the pass is flagged, Q^T fetched again as given, and the pass
-// run again the careful way, the scale applied in fp32: the exponentials of a tile are taken against the column's
-// reference maximum as it stood when the tile began (so they do not wait for the tile's own maximum and spread evenly
-// over the MFMA slots), the tile's maximum is collected on the side and checked against the reference (slack 2^32): a
-// column that has no sums yet takes a new reference and recomputes the tile's P from the S^T values it still holds, one
-// that has sums flags the pass once more, and the third attempt starts from references within the slack of every
-// column's true maximum.  O^T is never rescaled inside the loop.  (A process-wide switch sends every pass the careful way.)
+// shifted by as long as nothing leaves the range of bf16 and the fp32 sums.  The first attempt at a pass uses none: P is
+// exp2(scale x logit) - a multiplication, an exponential and the row sum per logit, one packing per two, is all the loop
+// spends on the softmax.  A column that sees keys must end the pass with a sum inside [2^-40, 2^40]; otherwise the pass
+// is flagged and run again the careful way: the exponentials of a tile are taken against the column's reference
+// maximum as it stood when the tile began (so they do not wait for the tile's own maximum and spread evenly over the
+// MFMA slots), the tile's maximum is collected on the side and checked against the reference (slack 2^32): a column
+// that has no sums yet takes a new reference and recomputes the tile's P from the S^T values it still holds, one that
+// has sums flags the pass once more, and the third attempt starts from references within the slack of every column's
+// true maximum.  O^T is never rescaled inside the loop.
+// A process-wide switch (off by default) takes the multiplication out of the first attempt as well: Q^T is multiplied
+// by the scale when the tile fetches it and rounded to bf16 again, so the logits leave the MFMAs in exp2 units.  A logit
+// then moves by up to 2^-9 of its value, which can put an output of magnitude 2 or more one bf16 step from the correctly
+// rounded value; a pass that is flagged fetches Q^T again as given.
 //
 // Pipeline of iteration j: S^T of tile j+1 (16 MFMAs), softmax of tile j, O^T += V^T P^T of tile j-1 (16 MFMAs).
 // LDS holds a ring of three stages of K (32 keys) + V^T (32 keys), tile t in stage t%3.  During iteration j
@@ -77,7 +79,7 @@ constexpr float kRefSlack = 32.0f;
 // The first attempt at a pass uses no reference (see the top of the file): the sum of a column that sees keys must end
 // inside this range - its largest P then lies within a factor "number of keys" of the sum, far from bf16's denormals and
 // from overflow (O^T overflows only for |V| beyond 2^87), and every logit that matters lies within 40 + log2(keys) of
-// zero, which bounds what the second rounding of Q^T can move (2^-9 of the logit).  An infinity or a NaN fails the test.
+// zero (which also bounds what a second rounding of Q^T can move).  An infinity or a NaN fails the test.
 constexpr float kFreeSumLo = 0x1p-40f, kFreeSumHi = 0x1p40f;
 
 __device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
