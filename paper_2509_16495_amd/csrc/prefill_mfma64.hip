@@ -19,20 +19,23 @@
 // with bits 2 and 3 of the K row index swapped in the MFMA row assignment, so that the keys a lane holds are runs
 // of eight consecutive tokens (one 16-byte piece of a dimension-major V row).
 //
-// Softmax without a reference, and against one that lags.  Softmax does not care which reference its exponentials are
-// shifted by as long as nothing leaves the range of bf16 and the fp32 sums.  The first attempt at a pass uses none: P is
-// exp2(scale x logit) - a multiplication, an exponential and the row sum per logit, one packing per two, is all the loop
-// spends on the softmax.  A column that sees keys must end the pass with a sum inside [2^-40, 2^40]; otherwise the pass
-// is flagged and run again the careful way: the exponentials of a tile are taken against the column's reference
-// maximum as it stood when the tile began (so they do not wait for the tile's own maximum and spread evenly over the
-// MFMA slots), the tile's maximum is collected on the side and checked against the reference (slack 2^32): a column
-// that has no sums yet takes a new reference and recomputes the tile's P from the S^T values it still holds, one that
-// has sums flags the pass once more, and the third attempt starts from references within the slack of every column's
-// true maximum.  O^T is never rescaled inside the loop.
-// A process-wide switch (off by default) takes the multiplication out of the first attempt as well: Q^T is multiplied
-// by the scale when the tile fetches it and rounded to bf16 again, so the logits leave the MFMAs in exp2 units.  A logit
-// then moves by up to 2^-9 of its value, which can put an output of magnitude 2 or more one bf16 step from the correctly
-// rounded value; a pass that is flagged fetches Q^T again as given.
+// Softmax against a reference that lags.  Softmax does not care which reference its exponentials are shifted by as long
+// as nothing leaves the range of bf16 and the fp32 sums.  The first attempt at a pass takes the reference from the
+// column's first visible key tile (whose maximum then gets P = 1 exactly: a row with few keys, all in that tile, comes
+// out as exactly as the careful way would give it) and follows no maximum behind it: a fused multiply-add, an
+// exponential and the row sum per logit, one packing per two, is all the loop spends on the softmax.  Real logits stay
+// within 2^100 of their first tile's maximum, and P up to 2^100 is held by bf16 and the fp32 sums without loss; a column
+// whose sum ends beyond that flags the pass, which is then run again the careful way: the exponentials of a tile are
+// taken against the column's reference maximum as it stood when the tile began (so they do not wait for the tile's own
+// maximum and spread evenly over the MFMA slots), the tile's maximum is collected on the side and checked against the
+// reference (slack 2^32): a column that has no sums yet takes a new reference and recomputes the tile's P from the S^T
+// values it still holds, one that has sums flags the pass once more, and the third attempt starts from references
+// within the slack of every column's true maximum.  O^T is never rescaled inside the loop.
+// A process-wide switch (off by default) makes the first attempt cheaper still: Q^T is multiplied by the softmax scale
+// when the tile fetches it and rounded to bf16 again, the logits leave the MFMAs in exp2 units, and P is the exp2 of
+// the logit itself, with no reference at all (sums must end inside [2^-40, 2^40]).  A logit then moves by up to 2^-9 of
+// its value and the largest P is no longer exactly 1, which can put an output of magnitude 2 or more one bf16 step from
+// the correctly rounded value; a pass that is flagged fetches Q^T again as given.
 //
 // Pipeline of iteration j: S^T of tile j+1 (16 MFMAs), softmax of tile j, O^T += V^T P^T of tile j-1 (16 MFMAs).
 // LDS holds a ring of three stages of K (32 keys) + V^T (32 keys), tile t in stage t%3.  During iteration j
@@ -81,6 +84,10 @@ constexpr float kRefSlack = 32.0f;
 // from overflow (O^T overflows only for |V| beyond 2^87), and every logit that matters lies within 40 + log2(keys) of
 // zero (which also bounds what a second rounding of Q^T can move).  An infinity or a NaN fails the test.
 constexpr float kFreeSumLo = 0x1p-40f, kFreeSumHi = 0x1p40f;
+// The default first attempt keeps the reference the column's first key tile left and follows no maximum behind it: P may
+// then reach 2^100 (still far inside bf16 and fp32 range; O^T overflows only for |V| beyond 2^27), and a sum beyond that
+// sends the pass to the attempts that do follow the maximum.
+constexpr float kKeepSumBound = 0x1p100f;
 
 __device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -385,10 +392,10 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         // of a pass's first attempt, which check the running sums instead)
         auto body = [&](auto par_c, auto has_a_c, auto has_c_c, auto guard_c, auto track_c, int j) SHIFTATTN_INLINE {
             constexpr int PAR = decltype(par_c)::value;
-            // track_c: 1 = the maximum is followed (TRACK); 0 and 2 = no reference at all, on logits that arrive in exp2
-            // units (Q^T carries the scale) or that take the scale here in fp32
+            // track_c: 1 = the maximum is followed (TRACK); 2 = the reference the column's first key tile left is kept and no
+            // maximum followed (KEEP); 0 = no reference at all, on logits that arrive in exp2 units (Q^T carries the scale)
             constexpr bool TRACK = decltype(track_c)::value == 1;
-            constexpr bool SCALE_HERE = decltype(track_c)::value == 2;
+            constexpr bool KEEP = decltype(track_c)::value == 2;
             constexpr bool GUARD = decltype(guard_c)::value != 0;  // outside the steady-state loop
             constexpr bool HAS_A = decltype(has_a_c)::value != 0;
             constexpr bool HAS_C = decltype(has_c_c)::value != 0;
@@ -481,7 +488,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
                 constexpr int cb = v / 16, r = v % 16;
                 // (no reference followed: Q^T carries the scale, the logit arrives in exp2 units)
                 const float e = TRACK        ? __builtin_amdgcn_exp2f(fmaf(s_cur[cb][r], p.c, -mc[cb]))
-                                : SCALE_HERE ? __builtin_amdgcn_exp2f(s_cur[cb][r] * p.c)
+                                : KEEP       ? __builtin_amdgcn_exp2f(fmaf(s_cur[cb][r], p.c, -mc[cb]))
                                              : __builtin_amdgcn_exp2f(s_cur[cb][r]);
                 if constexpr (v >= 1) finish_prev(IC<v>{});
                 if constexpr (TRACK && r % 2 == 1) {
@@ -651,10 +658,12 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             pre_a = lds_read16(k_cur[0]);
             k_cur[0] += kStageBytes;  // on to stage 2: iteration 1's first K operand
             mfma_settle();
+            // (the attempt that keeps its first tile's reference takes it here, from a tile that follows the maximum)
+            constexpr int kFirst = decltype(track_c)::value == 2 ? 1 : decltype(track_c)::value;
             if (n == 1) {
-                body(IC<0>{}, IC<0>{}, IC<0>{}, IC<1>{}, track_c, 0);
+                body(IC<0>{}, IC<0>{}, IC<0>{}, IC<1>{}, IC<kFirst>{}, 0);
             } else {
-                body(IC<0>{}, IC<1>{}, IC<0>{}, IC<1>{}, track_c, 0);
+                body(IC<0>{}, IC<1>{}, IC<0>{}, IC<1>{}, IC<kFirst>{}, 0);
                 int j = 1;  // stays odd: the steady-state loop takes two tiles per trip so that the register sets of
                             // even and odd tiles are fixed at compile time
                 for (; j + 2 < n; j += 2) {
@@ -699,16 +708,22 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
             else key_loop(IC<2>{});
         }
         if (attempt == 0) {
-            // No reference was used (P = exp2 of the logit itself).  That is exact as long as nothing left the range
-            // bf16 and the fp32 sums hold without loss: a column that sees keys of this range must end with a sum inside
-            // [2^-60, 2^100] (its largest P then lies within a factor "number of keys" of the sum, far from bf16's
-            // denormals and from overflow; an infinity or a NaN fails the test as well).  Otherwise the pass is flagged.
+            // The first attempt followed no maximum.  That is exact as long as nothing left the range bf16 and the fp32 sums
+            // hold without loss.  With the first tile's reference kept: a column's sum must not exceed 2^100 (P then stays
+            // below it; what underflows is negligible beside the first tile's keys).  With no reference at all: a column that
+            // sees keys of this range must end with a sum inside [2^-40, 2^40].  An infinity or a NaN fails either test; the
+            // pass is then flagged.
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) {
                 const float l_tot = l_run[cb] + __shfl_xor(l_run[cb], 32);
-                const bool sees = n > 0 && pos_col[cb] >= kt_begin * kKv;
-                if (sees && !(l_tot >= kFreeSumLo && l_tot <= kFreeSumHi)) redo = true;
-                m_rep[cb] = sees ? 0.f : -INFINITY;   // what a partial result reports as its reference (exp2 units)
+                if (p.scaled_q) {
+                    const bool sees = n > 0 && pos_col[cb] >= kt_begin * kKv;
+                    if (sees && !(l_tot >= kFreeSumLo && l_tot <= kFreeSumHi)) redo = true;
+                    m_rep[cb] = sees ? 0.f : -INFINITY;   // what a partial result reports as its reference (exp2 units)
+                } else {
+                    if (!(l_tot <= kKeepSumBound)) redo = true;
+                    m_rep[cb] = m_used[cb] * p.c;
+                }
             }
             redo = __builtin_amdgcn_ballot_w64(redo) != 0;
         } else {
@@ -721,7 +736,11 @@ __global__ __launch_bounds__(kThreads, 1) void prefill64_kernel(Prefill64Params 
         __syncthreads();  // also: every wavefront is done with the ring
         const int any_redo = flags[0] | flags[1] | flags[2] | flags[3];
         if (__builtin_expect(__builtin_amdgcn_readfirstlane(any_redo) == 0, 1)) break;
-        if (attempt == 0 && p.scaled_q) fetch_q(false);   // the attempts that follow the maximum work on Q^T as given
+        if (attempt == 0) {   // the attempts that follow the maximum start without references, on Q^T as given
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) m_used[cb] = -INFINITY, mc[cb] = 0.f, bound[cb] = -INFINITY;
+            if (p.scaled_q) fetch_q(false);
+        }
         }
 
         // ---- results of the pass ----------------------------------------------------------------------------
