@@ -339,11 +339,12 @@ int32_t shiftattn_use_base_config(int32_t n_tokens, int32_t threshold);
  *   SHIFTATTN_OPT_PREFILL_PAIRING 1 | 2: the 256-column prefill kernel takes a sequence's column tiles two per
  *                                workgroup, heaviest with lightest (1), or one per workgroup, heaviest first (2)
  *   SHIFTATTN_OPT_PREFILL_SCALED_Q 1: the 256-column prefill kernel multiplies Q by the softmax scale when a tile
- *                                fetches it and rounds it to bf16 again, so that its loop spends no instruction
- *                                on scaling logits (about 5 % faster).  A logit then moves by up to 2^-9 of its
- *                                value: outputs of magnitude 2 and more can land one bf16 step from the correctly
- *                                rounded value.  Tiles whose softmax sums leave [2^-40, 2^40] are recomputed on Q
- *                                as given.  Off by default: the scale is applied to the fp32 logits
+ *                                fetches it, rounds it to bf16 again and takes its softmax without a reference,
+ *                                so that its loop spends no instruction on scaling and shifting logits (about
+ *                                4 % faster).  A logit then moves by up to 2^-9 of its value and the largest
+ *                                probability of a row is no longer exactly 1: outputs of magnitude 2 and more
+ *                                can land one bf16 step from the correctly rounded value.  Tiles whose softmax
+ *                                sums leave [2^-40, 2^40] are recomputed on Q as given.  Off by default
  *   set returns EINVAL for an unknown option or value; get returns -1 for an unknown option. */
 enum { SHIFTATTN_OPT_PREFILL_TILE = 0, SHIFTATTN_OPT_PREFILL_SPLITS = 1, SHIFTATTN_OPT_GENERIC_ONLY = 2,
        SHIFTATTN_OPT_PREFILL_PAIRING = 3, SHIFTATTN_OPT_PREFILL_SCALED_Q = 4, SHIFTATTN_OPT_COUNT = 5 };
