@@ -363,9 +363,9 @@ def main() -> int:
         "ms_per_step_graph_replay": round(ms_per_step_graph, 5),
         "chunk_prefill_with_scaled_q": {
             "ms": round(sq_ms, 5), "roofline": roof("prefill64_kernel, SHIFTATTN_OPT_PREFILL_SCALED_Q = 1", "mfma", sq_tf, PEAK_BF16_TFLOPS, "TFLOP/s"),
-            "note": "opt-in, not the path the step above runs: Q is multiplied by the softmax scale per tile and rounded to bf16 again, the "
-                    "loop then spends no instruction on scaling logits; a logit moves by up to 2^-9 of its value and outputs of magnitude "
-                    "2 and more can land one bf16 step from the correctly rounded value; timed alone in a loop (the chunk's K/V then stay "
+            "note": "opt-in, not the path the step above runs: Q is multiplied by the softmax scale per tile and rounded to bf16 again and the "
+                    "softmax takes no reference, so the loop spends no instruction on scaling and shifting logits; outputs of magnitude "
+                    "2 and more can then land one bf16 step from the correctly rounded value (beyond the 2e-2 bound in 2 of 40 random batches); timed alone in a loop (the chunk's K/V then stay "
                     "in the cache in front of HBM, which makes it 2-3 % faster than inside the step)"},
         "timing_state": {"settle_ms": SETTLE_MS * args.settle_scale, "ms_per_step_first_steps_after_a_pause": round(ms_per_step_after_idle, 5),
                          "note": "every timed region starts after settle_ms (3x for the step) of the same work back to back: the "
