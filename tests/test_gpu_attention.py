@@ -123,6 +123,22 @@ def test_decode_bf16_small(oracle, G, hq_l, hkv_l):
     _check(got, want, "bf16")
 
 
+def test_decode_random_batches(oracle, G):
+    """Thirty decode batches of random shape (1-40 sequences, contexts of 1-5000 tokens, 4 / 5 / 8 / 16 query heads per KV
+    head), N(0,1) data: every output element within the bound (short contexts give single V rows of magnitude up to 4,
+    where one bf16 step is 0.031)."""
+    rng = np.random.default_rng(321)
+    for it in range(30):
+        n = int(rng.integers(1, 41))
+        seqs = [(1, int(rng.integers(1, 5001)) if rng.integers(0, 4) else int(rng.integers(1, 40))) for _ in range(n)]
+        hq = int(rng.choice([4, 5, 8, 16]))
+        case = W.make_attn_case("dsweep", 2000 + it, "bf16", seqs, hq, 1, 128)
+        want = oracle.attention_case(case, oracle.cache_for_case(case))
+        got = W.to_f64(G.decode_case(case, G.cache_for_case(case)), "bf16")
+        err = np.abs(got - want)
+        assert err.max() <= 2e-2 and err.mean() <= 1e-3, (it, err.max(), err.mean())
+
+
 def test_decode_many_sequences_and_long_contexts(oracle, G):
     """The flat decomposition at the edges of its range: as many (sequence, KV head) pairs as it
     indexes, one more than that (a second run of the kernel takes the rest), a context long enough that the
